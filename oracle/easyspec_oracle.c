@@ -1,0 +1,445 @@
+/*
+ * EasySpec CPU oracle.  TEST INFRASTRUCTURE ONLY: a plain, slow, double-precision
+ * implementation of the draft model's layer-sequential step (paper Alg. 1), the
+ * layer-parallel fuzzy step (paper Alg. 2), bonus calibration (paper Sec. 3.2) and greedy
+ * acceptance (paper Alg. 3 at temperature 0).  Only the tests, the smoke check and the
+ * benchmark's cpu_baseline leg may call it; it shares no code with the HIP library.
+ *
+ * Arithmetic: every vector and accumulator is a double.  Parameters are read from the
+ * caller's arrays (float32, or bf16 bit patterns widened on the fly).  When cfg.bf16 == 1
+ * the storage rounding points of a bf16 model apply: the KV cache holds bf16 values, and
+ * every vector that enters a weight contraction (normed hidden state, attention output,
+ * SiLU(gate)*up, final normed hidden state) is rounded to bf16 first.  With cfg.bf16 == 0
+ * nothing is rounded except the KV cache, which holds float32.
+ *
+ * Model function (pre-norm decoder; the paper names only "attention layers", "MLP layers"
+ * and the normalisation before attention, App. E.1; the rest follows the benchmark shapes):
+ *   RMSNorm(x; g) = x * rsqrt(mean(x^2) + eps) * g
+ *   Attn_i(h) at position p = Wo * GQA(RoPE(Wq n + bq, p), K-cache incl. RoPE(Wk n + bk, p),
+ *                                      V-cache incl. Wv n + bv),  n = RMSNorm(h; g_attn_i)
+ *   MLP_i(h)  = Wd (SiLU(Wg y) * (Wu y)),  y = RMSNorm(h; g_mlp_i)
+ *   logits    = Wlm RMSNorm(h_L; g_final)
+ *
+ * Parity pins (tests/test_oracle_*.py): sequential step against an independent library
+ * decoder; Alg. 2 with all sets of size one == Alg. 1 bit for bit; calibration == token by
+ * token sequential decoding bit for bit; greedy speculative decoding == vanilla greedy
+ * decoding.  The numeric value of a fuzzy step with sets larger than one is fixed by no
+ * number in the paper (its similarity table needs trained weights): that part is pinned
+ * by a second composition of the same library blocks and by structural invariants only.
+ *
+ * OpenMP splits output rows only, so results do not depend on the thread count.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+typedef struct {
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  int32_t qkv_bias; /* 1: bq, bk, bv present */
+  int32_t bf16;     /* 1: matrices are bf16 bit patterns and the bf16 rounding points apply */
+  int32_t max_ctx;  /* KV slots per layer */
+  double rms_eps, rope_theta;
+} eso_config;
+
+typedef struct {
+  const void *wq, *wk, *wv, *wo, *wg, *wu, *wd; /* row-major [out][in], model dtype */
+  const float *bq, *bk, *bv;                    /* NULL without bias */
+  const float *g_attn, *g_mlp;
+} eso_layer;
+
+typedef struct {
+  eso_config cfg;
+  eso_layer *layers;
+  const void *embed, *lm_head; /* [vocab][d_model] */
+  const float *g_final;
+} eso_model;
+
+typedef struct {
+  const eso_model *m;
+  float *K, *V; /* [layer][kv_head][slot][head_dim] */
+  int32_t precise; /* slots [0, precise) hold values written by calibration */
+  int32_t fuzzy;   /* slots [precise, precise+fuzzy) hold values written by fuzzy steps */
+  double *attn_tap; /* optional [n_layers][d_model]: Attnoutput_i of the last single-token step */
+} eso_seq;
+
+/* ---------------------------------------------------------------- storage formats */
+
+static float bf16_bits_to_float(uint16_t b) {
+  uint32_t u = (uint32_t)b << 16;
+  float f;
+  memcpy(&f, &u, 4);
+  return f;
+}
+
+/* Round to the nearest bf16 value, ties to even (finite inputs). */
+double eso_bf16_round(double x) {
+  float f = (float)x;
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  u &= 0xFFFF0000u;
+  memcpy(&f, &u, 4);
+  return (double)f;
+}
+
+static double weight_at(const void *w, int bf16, size_t idx) {
+  return bf16 ? (double)bf16_bits_to_float(((const uint16_t *)w)[idx]) : (double)((const float *)w)[idx];
+}
+
+static double act_round(const eso_config *c, double x) { return c->bf16 ? eso_bf16_round(x) : x; }
+static float kv_store(const eso_config *c, double x) { return c->bf16 ? (float)eso_bf16_round(x) : (float)x; }
+
+/* ---------------------------------------------------------------- primitives */
+
+/* y[r] = sum_j W[r][j] x[j] (+ b[r]) */
+void eso_matvec(const void *w, int bf16, const float *bias, int rows, int cols, const double *x, double *y) {
+#pragma omp parallel for schedule(static)
+  for (int r = 0; r < rows; ++r) {
+    double acc = 0.0;
+    size_t base = (size_t)r * (size_t)cols;
+    for (int j = 0; j < cols; ++j) acc += weight_at(w, bf16, base + (size_t)j) * x[j];
+    y[r] = bias ? acc + (double)bias[r] : acc;
+  }
+}
+
+/* y = x * rsqrt(mean(x^2) + eps) * g */
+void eso_rmsnorm(const double *x, const float *g, int n, double eps, double *y) {
+  double ss = 0.0;
+  for (int j = 0; j < n; ++j) ss += x[j] * x[j];
+  double r = 1.0 / sqrt(ss / (double)n + eps);
+  for (int j = 0; j < n; ++j) y[j] = x[j] * r * (double)g[j];
+}
+
+/* Rotary embedding of one head vector at position pos: element i pairs with i + hd/2,
+ * angle = pos * theta^(-2i/hd). */
+void eso_rope(double *x, int hd, int pos, double theta) {
+  int half = hd / 2;
+  for (int i = 0; i < half; ++i) {
+    double ang = (double)pos * pow(theta, -2.0 * (double)i / (double)hd);
+    double c = cos(ang), s = sin(ang);
+    double a = x[i], b = x[i + half];
+    x[i] = a * c - b * s;
+    x[i + half] = b * c + a * s;
+  }
+}
+
+double eso_silu(double z) { return z / (1.0 + exp(-z)); }
+
+/* in-place softmax over n scores */
+void eso_softmax(double *s, int n) {
+  double mx = s[0];
+  for (int t = 1; t < n; ++t)
+    if (s[t] > mx) mx = s[t];
+  double sum = 0.0;
+  for (int t = 0; t < n; ++t) {
+    s[t] = exp(s[t] - mx);
+    sum += s[t];
+  }
+  for (int t = 0; t < n; ++t) s[t] /= sum;
+}
+
+/* index of the largest entry, lowest index on ties; optionally the gap to the runner-up */
+int32_t eso_argmax(const double *x, int n, double *margin) {
+  int best = 0;
+  for (int j = 1; j < n; ++j)
+    if (x[j] > x[best]) best = j;
+  if (margin) {
+    double second = -INFINITY;
+    for (int j = 0; j < n; ++j)
+      if (j != best && x[j] > second) second = x[j];
+    *margin = x[best] - second;
+  }
+  return best;
+}
+
+/* ---------------------------------------------------------------- model / sequence objects */
+
+eso_model *eso_model_create(const eso_config *cfg) {
+  if (!cfg || cfg->n_layers < 1 || cfg->n_q_heads % cfg->n_kv_heads || cfg->head_dim % 2) return NULL;
+  eso_model *m = (eso_model *)calloc(1, sizeof(eso_model));
+  m->cfg = *cfg;
+  m->layers = (eso_layer *)calloc((size_t)cfg->n_layers, sizeof(eso_layer));
+  return m;
+}
+
+void eso_model_set_layer(eso_model *m, int i, const void *wq, const void *wk, const void *wv, const void *wo,
+                         const void *wg, const void *wu, const void *wd, const float *bq, const float *bk,
+                         const float *bv, const float *g_attn, const float *g_mlp) {
+  eso_layer *l = &m->layers[i];
+  l->wq = wq; l->wk = wk; l->wv = wv; l->wo = wo; l->wg = wg; l->wu = wu; l->wd = wd;
+  l->bq = bq; l->bk = bk; l->bv = bv; l->g_attn = g_attn; l->g_mlp = g_mlp;
+}
+
+void eso_model_set_top(eso_model *m, const void *embed, const float *g_final, const void *lm_head) {
+  m->embed = embed; m->g_final = g_final; m->lm_head = lm_head;
+}
+
+void eso_model_destroy(eso_model *m) {
+  if (!m) return;
+  free(m->layers);
+  free(m);
+}
+
+static size_t kv_elems(const eso_config *c) {
+  return (size_t)c->n_layers * (size_t)c->n_kv_heads * (size_t)c->max_ctx * (size_t)c->head_dim;
+}
+
+eso_seq *eso_seq_create(const eso_model *m) {
+  eso_seq *s = (eso_seq *)calloc(1, sizeof(eso_seq));
+  s->m = m;
+  s->K = (float *)calloc(kv_elems(&m->cfg), sizeof(float));
+  s->V = (float *)calloc(kv_elems(&m->cfg), sizeof(float));
+  return s;
+}
+
+void eso_seq_destroy(eso_seq *s) {
+  if (!s) return;
+  free(s->K); free(s->V); free(s->attn_tap); free(s);
+}
+
+float *eso_seq_k(eso_seq *s) { return s->K; }
+float *eso_seq_v(eso_seq *s) { return s->V; }
+int32_t eso_seq_precise(const eso_seq *s) { return s->precise; }
+int32_t eso_seq_fuzzy(const eso_seq *s) { return s->fuzzy; }
+void eso_seq_set_lens(eso_seq *s, int32_t precise, int32_t fuzzy) { s->precise = precise; s->fuzzy = fuzzy; }
+double *eso_seq_enable_attn_tap(eso_seq *s) {
+  if (!s->attn_tap) s->attn_tap = (double *)calloc((size_t)s->m->cfg.n_layers * (size_t)s->m->cfg.d_model, sizeof(double));
+  return s->attn_tap;
+}
+
+static float *kv_row(const eso_seq *s, float *base, int layer, int kvh, int slot) {
+  const eso_config *c = &s->m->cfg;
+  return base + (((size_t)layer * c->n_kv_heads + kvh) * (size_t)c->max_ctx + (size_t)slot) * (size_t)c->head_dim;
+}
+
+/* ---------------------------------------------------------------- the three blocks */
+
+/* Attnoutput = Attn_layer(h) for the token at position pos; stores that token's k, v in
+ * cache slot pos (values computed from THIS h, whatever h is) and attends to slots 0..pos. */
+static void attn_block(eso_seq *s, int layer, const double *h, int pos, double *out) {
+  const eso_config *c = &s->m->cfg;
+  const eso_layer *l = &s->m->layers[layer];
+  int d = c->d_model, hd = c->head_dim, nq = c->n_q_heads, nkv = c->n_kv_heads, grp = nq / nkv;
+  double *n = (double *)malloc(sizeof(double) * (size_t)d);
+  double *q = (double *)malloc(sizeof(double) * (size_t)nq * hd);
+  double *k = (double *)malloc(sizeof(double) * (size_t)nkv * hd);
+  double *v = (double *)malloc(sizeof(double) * (size_t)nkv * hd);
+  double *o = (double *)malloc(sizeof(double) * (size_t)nq * hd);
+  double *sc = (double *)malloc(sizeof(double) * (size_t)(pos + 1));
+
+  eso_rmsnorm(h, l->g_attn, d, c->rms_eps, n);
+  for (int j = 0; j < d; ++j) n[j] = act_round(c, n[j]);
+  eso_matvec(l->wq, c->bf16, l->bq, nq * hd, d, n, q);
+  eso_matvec(l->wk, c->bf16, l->bk, nkv * hd, d, n, k);
+  eso_matvec(l->wv, c->bf16, l->bv, nkv * hd, d, n, v);
+  for (int a = 0; a < nq; ++a) eso_rope(q + (size_t)a * hd, hd, pos, c->rope_theta);
+  for (int g = 0; g < nkv; ++g) {
+    eso_rope(k + (size_t)g * hd, hd, pos, c->rope_theta);
+    float *kr = kv_row(s, s->K, layer, g, pos), *vr = kv_row(s, s->V, layer, g, pos);
+    for (int e = 0; e < hd; ++e) {
+      kr[e] = kv_store(c, k[(size_t)g * hd + e]);
+      vr[e] = kv_store(c, v[(size_t)g * hd + e]);
+    }
+  }
+  double scale = 1.0 / sqrt((double)hd);
+  for (int a = 0; a < nq; ++a) {
+    int g = a / grp; /* query head a reads KV head a / (Hq/Hkv) */
+    const double *qa = q + (size_t)a * hd;
+    for (int t = 0; t <= pos; ++t) {
+      const float *kr = kv_row(s, s->K, layer, g, t);
+      double dot = 0.0;
+      for (int e = 0; e < hd; ++e) dot += qa[e] * (double)kr[e];
+      sc[t] = dot * scale;
+    }
+    eso_softmax(sc, pos + 1);
+    for (int e = 0; e < hd; ++e) {
+      double acc = 0.0;
+      for (int t = 0; t <= pos; ++t) acc += sc[t] * (double)kv_row(s, s->V, layer, g, t)[e];
+      o[(size_t)a * hd + e] = act_round(c, acc);
+    }
+  }
+  eso_matvec(l->wo, c->bf16, NULL, d, nq * hd, o, out);
+  free(n); free(q); free(k); free(v); free(o); free(sc);
+}
+
+/* MLPoutput = MLP_layer(h) */
+static void mlp_block(const eso_model *m, int layer, const double *h, double *out) {
+  const eso_config *c = &m->cfg;
+  const eso_layer *l = &m->layers[layer];
+  int d = c->d_model, f = c->d_ffn;
+  double *y = (double *)malloc(sizeof(double) * (size_t)d);
+  double *g = (double *)malloc(sizeof(double) * (size_t)f);
+  double *u = (double *)malloc(sizeof(double) * (size_t)f);
+  eso_rmsnorm(h, l->g_mlp, d, c->rms_eps, y);
+  for (int j = 0; j < d; ++j) y[j] = act_round(c, y[j]);
+  eso_matvec(l->wg, c->bf16, NULL, f, d, y, g);
+  eso_matvec(l->wu, c->bf16, NULL, f, d, y, u);
+  for (int j = 0; j < f; ++j) g[j] = act_round(c, eso_silu(g[j]) * u[j]);
+  eso_matvec(l->wd, c->bf16, NULL, d, f, g, out);
+  free(y); free(g); free(u);
+}
+
+static void embed_row(const eso_model *m, int32_t token, double *h) {
+  int d = m->cfg.d_model;
+  for (int j = 0; j < d; ++j) h[j] = weight_at(m->embed, m->cfg.bf16, (size_t)token * d + j);
+}
+
+static void head(const eso_model *m, const double *h, double *logits) {
+  const eso_config *c = &m->cfg;
+  double *x = (double *)malloc(sizeof(double) * (size_t)c->d_model);
+  eso_rmsnorm(h, m->g_final, c->d_model, c->rms_eps, x);
+  for (int j = 0; j < c->d_model; ++j) x[j] = act_round(c, x[j]);
+  eso_matvec(m->lm_head, c->bf16, NULL, c->vocab, c->d_model, x, logits);
+  free(x);
+}
+
+/* ---------------------------------------------------------------- paper Alg. 1 */
+
+/* One layer-sequential forward of one token at position precise (requires fuzzy == 0);
+ * the slot it writes is precise.  Returns 0, or -1 on a bad state. */
+int eso_sequential_step(eso_seq *s, int32_t token, double *logits, double *hidden_out) {
+  const eso_config *c = &s->m->cfg;
+  if (s->fuzzy != 0 || s->precise + 1 > c->max_ctx || token < 0 || token >= c->vocab) return -1;
+  int d = c->d_model, pos = s->precise;
+  double *h = (double *)malloc(sizeof(double) * (size_t)d), *a = (double *)malloc(sizeof(double) * (size_t)d);
+  double *mo = (double *)malloc(sizeof(double) * (size_t)d);
+  embed_row(s->m, token, h);
+  for (int i = 0; i < c->n_layers; ++i) {
+    attn_block(s, i, h, pos, a);                       /* Attnoutput_i = Attn_i(h_i) */
+    if (s->attn_tap) memcpy(s->attn_tap + (size_t)i * d, a, sizeof(double) * (size_t)d);
+    for (int j = 0; j < d; ++j) h[j] = h[j] + a[j];    /* h'_i = h_i + Attnoutput_i */
+    mlp_block(s->m, i, h, mo);                         /* MLPoutput_i = MLP_i(h'_i) */
+    for (int j = 0; j < d; ++j) h[j] = h[j] + mo[j];   /* h_{i+1} = h'_i + MLPoutput_i */
+  }
+  if (hidden_out) memcpy(hidden_out, h, sizeof(double) * (size_t)d);
+  if (logits) head(s->m, h, logits);
+  s->precise += 1;
+  free(h); free(a); free(mo);
+  return 0;
+}
+
+/* ---------------------------------------------------------------- paper Alg. 2 */
+
+/* One layer-parallel fuzzy forward of one token.  bounds[0]=0 < ... < bounds[n_sets]=L;
+ * set j = layers [bounds[j], bounds[j+1]).  Every attention layer of a set reads the hidden
+ * state that enters the set; the MLPs stay sequential.  Writes slot precise+fuzzy in every
+ * layer and counts it as fuzzy. */
+int eso_fuzzy_step(eso_seq *s, const int32_t *bounds, int32_t n_sets, int32_t token, double *logits,
+                   double *hidden_out) {
+  const eso_config *c = &s->m->cfg;
+  if (n_sets < 1 || bounds[0] != 0 || bounds[n_sets] != c->n_layers) return -1;
+  for (int j = 0; j < n_sets; ++j)
+    if (bounds[j + 1] <= bounds[j]) return -1;
+  if (s->precise + s->fuzzy + 1 > c->max_ctx || token < 0 || token >= c->vocab) return -1;
+  int d = c->d_model, pos = s->precise + s->fuzzy;
+  double *h = (double *)malloc(sizeof(double) * (size_t)d), *h1 = (double *)malloc(sizeof(double) * (size_t)d);
+  double *a = (double *)malloc(sizeof(double) * (size_t)d * (size_t)c->n_layers);
+  double *mo = (double *)malloc(sizeof(double) * (size_t)d);
+  embed_row(s->m, token, h);
+  for (int j = 0; j < n_sets; ++j) {
+    int lo = bounds[j], hi = bounds[j + 1];
+    memcpy(h1, h, sizeof(double) * (size_t)d);                                 /* h_1 = h */
+    for (int i = lo; i < hi; ++i) attn_block(s, i, h1, pos, a + (size_t)i * d); /* Attn_i(h_1), parallel */
+    for (int i = lo; i < hi; ++i) {
+      const double *ai = a + (size_t)i * d;
+      for (int e = 0; e < d; ++e) h[e] = h[e] + ai[e];  /* h'_i = h_i + Attnoutput_i */
+      mlp_block(s->m, i, h, mo);                        /* MLPoutput_i = MLP_i(h'_i) */
+      for (int e = 0; e < d; ++e) h[e] = h[e] + mo[e];  /* h_{i+1} = h'_i + MLPoutput_i */
+    }
+  }
+  if (s->attn_tap) memcpy(s->attn_tap, a, sizeof(double) * (size_t)d * (size_t)c->n_layers);
+  if (hidden_out) memcpy(hidden_out, h, sizeof(double) * (size_t)d);
+  if (logits) head(s->m, h, logits);
+  s->fuzzy += 1;
+  free(h); free(h1); free(a); free(mo);
+  return 0;
+}
+
+/* ---------------------------------------------------------------- bonus calibration (Sec. 3.2) */
+
+/* Drop every fuzzy slot, then run ONE token-parallel, layer-sequential forward over the
+ * n tokens (accepted tokens followed by the bonus token) at positions precise..precise+n-1.
+ * Their k, v overwrite those slots and count as precise.  logits_all: [n][vocab] or NULL;
+ * hidden_all: [n][d_model] or NULL.  The last row's logits give the next draft token. */
+int eso_calibrate(eso_seq *s, const int32_t *tokens, int32_t n, double *logits_all, double *hidden_all) {
+  const eso_config *c = &s->m->cfg;
+  if (n < 1 || s->precise + n > c->max_ctx) return -1;
+  for (int r = 0; r < n; ++r)
+    if (tokens[r] < 0 || tokens[r] >= c->vocab) return -1;
+  s->fuzzy = 0;
+  int d = c->d_model, p0 = s->precise;
+  double *H = (double *)malloc(sizeof(double) * (size_t)n * d);
+  double *a = (double *)malloc(sizeof(double) * (size_t)d), *mo = (double *)malloc(sizeof(double) * (size_t)d);
+  for (int r = 0; r < n; ++r) embed_row(s->m, tokens[r], H + (size_t)r * d);
+  for (int i = 0; i < c->n_layers; ++i) {
+    /* rows in increasing position: row r stores its k, v before it attends, so it sees rows <= r */
+    for (int r = 0; r < n; ++r) {
+      double *h = H + (size_t)r * d;
+      attn_block(s, i, h, p0 + r, a);
+      for (int e = 0; e < d; ++e) h[e] = h[e] + a[e];
+    }
+    for (int r = 0; r < n; ++r) {
+      double *h = H + (size_t)r * d;
+      mlp_block(s->m, i, h, mo);
+      for (int e = 0; e < d; ++e) h[e] = h[e] + mo[e];
+    }
+  }
+  if (hidden_all) memcpy(hidden_all, H, sizeof(double) * (size_t)n * d);
+  if (logits_all)
+    for (int r = 0; r < n; ++r) head(s->m, H + (size_t)r * d, logits_all + (size_t)r * c->vocab);
+  s->precise += n;
+  free(H); free(a); free(mo);
+  return 0;
+}
+
+/* Logits of the last calibrated row only (what a drafter needs): same forward as
+ * eso_calibrate but the head runs on one row. */
+int eso_calibrate_last(eso_seq *s, const int32_t *tokens, int32_t n, double *logits_last) {
+  const eso_config *c = &s->m->cfg;
+  double *hid = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1) * c->d_model);
+  int rc = eso_calibrate(s, tokens, n, NULL, hid);
+  if (rc == 0 && logits_last) head(s->m, hid + (size_t)(n - 1) * c->d_model, logits_last);
+  free(hid);
+  return rc;
+}
+
+/* ---------------------------------------------------------------- Alg. 3 at temperature 0 */
+
+/* With one-hot draft and target distributions a drafted token is accepted exactly when it
+ * equals the target model's argmax at that position; the bonus token is the target's argmax
+ * at the first rejected position, or at position gamma when everything was accepted.
+ * draft: [gamma]; target: [gamma+1]. */
+void eso_greedy_accept(const int32_t *draft, const int32_t *target, int32_t gamma, int32_t *accept_len,
+                       int32_t *bonus) {
+  int m = 0;
+  while (m < gamma && draft[m] == target[m]) ++m;
+  *accept_len = m;
+  *bonus = target[m];
+}
+
+/* ---------------------------------------------------------------- layer-parallel strategy (Sec. 3.1.1) */
+
+/* policy 0 ("aligned", the rule in the text): first and last layer alone; the layers between
+ * are cut at multiples of N: 1..N-1, N..2N-1, ..., the last set stopping before layer L-1.
+ * policy 1 ("packed", the 16-layer row of the strategy table): first and last layer alone;
+ * sets of N consecutive layers starting at layer 1, the last one truncated before layer L-1.
+ * bounds must hold L+1 entries.  Returns 0 or -1. */
+int eso_default_groups(int32_t L, int32_t N, int32_t policy, int32_t *bounds, int32_t *n_sets) {
+  if (L < 1 || N < 1 || (policy != 0 && policy != 1)) return -1;
+  int n = 0;
+  bounds[n++] = 0;
+  if (L == 1) { bounds[n] = 1; *n_sets = 1; return 0; }
+  bounds[n++] = 1; /* layer 0 alone */
+  int last = L - 1; /* layer L-1 alone */
+  int cur = 1;
+  while (cur < last) {
+    int next = (policy == 0) ? ((cur / N) + 1) * N : cur + N;
+    if (next > last) next = last;
+    bounds[n++] = next;
+    cur = next;
+  }
+  bounds[n] = L;
+  *n_sets = n;
+  return 0;
+}
