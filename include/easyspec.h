@@ -1,0 +1,177 @@
+/*
+ * easyspec.h — C ABI of the MI355X (gfx950) EasySpec draft-model hot path.
+ *
+ * What the library computes (EasySpec, arXiv 2502.02493):
+ *   - easyspec_draft_step     one layer-parallel "fuzzy" forward of the draft model
+ *                             (paper Alg. 2; the layer-parallel strategy of Sec. 3.1.1)
+ *   - easyspec_calibrate      bonus calibration: drop the fuzzy KV entries, refill the cache
+ *                             with precise values by one token-parallel, layer-sequential
+ *                             forward (paper Sec. 3.2, Alg. 1)
+ *   - easyspec_greedy_accept  acceptance of drafted tokens at temperature 0 (paper Alg. 3)
+ *
+ * Model function: pre-norm decoder with RMSNorm, rotary embedding (pairs i, i + head_dim/2),
+ * grouped-query attention (query head j reads KV head j / (n_q_heads/n_kv_heads)), SwiGLU MLP,
+ * untied LM head.  Storage dtype (weights and KV cache) is fp32 or bf16; the residual stream,
+ * queries, softmax and all accumulators are fp32.
+ *
+ * Conventions
+ *   - Every function returns EASYSPEC_OK (0) or a negative error code.  Arguments are checked
+ *     on the host before anything is launched: a failed call leaves lengths and device memory
+ *     unchanged.  easyspec_last_error() returns a message for the last failure.
+ *   - "dev" pointers are device memory owned by the caller; they must stay valid until the
+ *     context's stream has passed the call.  "host" pointers are ordinary host memory.
+ *     "host|dev" pointers may be either.  The library never frees caller memory.
+ *   - Calls are asynchronous on the stream given at creation unless stated otherwise.
+ *   - A context is not thread-safe; use one thread per context.
+ *   - The library has no CPU fallback: without a usable HIP device easyspec_create fails.
+ */
+#ifndef EASYSPEC_H
+#define EASYSPEC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EASYSPEC_OK 0
+#define EASYSPEC_EINVAL (-1)    /* bad argument or unsupported shape */
+#define EASYSPEC_ECAPACITY (-2) /* a sequence would exceed max_ctx, or too many tokens */
+#define EASYSPEC_ESTATE (-3)    /* call not valid in the current state (no weights, no live sequence, ...) */
+#define EASYSPEC_EHIP (-4)      /* a HIP runtime call failed; message in easyspec_last_error */
+
+#define EASYSPEC_DTYPE_F32 0
+#define EASYSPEC_DTYPE_BF16 1
+
+#define EASYSPEC_POLICY_ALIGNED 0 /* the rule in the text of Sec. 3.1.1 */
+#define EASYSPEC_POLICY_PACKED 1  /* the 16-layer row of the strategy table of Sec. 3.1.1 */
+
+#define EASYSPEC_MAX_BATCH 16        /* sequences per context */
+#define EASYSPEC_MAX_CALIB_TOKENS 16 /* tokens of one sequence per calibration call */
+#define EASYSPEC_MAX_SET 8           /* layers per layer-parallel set */
+
+typedef struct easyspec_config {
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  float rms_eps, rope_theta;
+  int32_t qkv_bias;         /* 0/1: q, k, v projections carry a bias */
+  int32_t dtype;            /* EASYSPEC_DTYPE_*: storage type of matrices, embedding and KV cache */
+  int32_t max_batch;        /* 1..EASYSPEC_MAX_BATCH sequences */
+  int32_t max_ctx;          /* KV slots per sequence (precise + fuzzy) */
+  int32_t max_calib_tokens; /* 1..EASYSPEC_MAX_CALIB_TOKENS */
+} easyspec_config;
+/* Shape limits: head_dim is 64 or 128; d_model, n_q_heads*head_dim and d_ffn are multiples
+ * of 32; n_q_heads/n_kv_heads is 1, 2, 4, 7 or 8. */
+
+typedef struct easyspec_layer_weights {
+  /* row-major [out][in] matrices in the storage dtype (bf16 = raw 16-bit patterns) */
+  const void *wq; /* [n_q_heads*head_dim][d_model]  */
+  const void *wk; /* [n_kv_heads*head_dim][d_model] */
+  const void *wv; /* [n_kv_heads*head_dim][d_model] */
+  const void *wo; /* [d_model][n_q_heads*head_dim]  */
+  const void *wg; /* [d_ffn][d_model]  gate */
+  const void *wu; /* [d_ffn][d_model]  up   */
+  const void *wd; /* [d_model][d_ffn]  down */
+  /* fp32 vectors */
+  const float *bq, *bk, *bv; /* biases, NULL unless qkv_bias */
+  const float *g_attn;       /* [d_model] gain of the norm before attention */
+  const float *g_mlp;        /* [d_model] gain of the norm before the MLP */
+} easyspec_layer_weights;
+
+typedef struct easyspec_weights {
+  const easyspec_layer_weights *layers; /* host array of n_layers entries */
+  const void *embed;                    /* [vocab][d_model] storage dtype */
+  const void *lm_head;                  /* [vocab][d_model] storage dtype */
+  const float *g_final;                 /* [d_model] fp32 */
+} easyspec_weights;
+
+typedef struct easyspec_ctx easyspec_ctx; /* opaque: owns its weight copy, KV cache and workspaces */
+
+/* Create a context on the current HIP device.  hip_stream: a hipStream_t (NULL = the default
+ * stream) on which every later call is ordered.  Allocates the packed weight arrays, the KV
+ * cache ([layer][sequence][kv_head][slot][head_dim], K and V apart) and the workspaces; the
+ * rotary table is computed on the host in double precision.  Starts with every layer in a set
+ * of its own (plain sequential order, paper Alg. 1).  *out is NULL on failure. */
+int easyspec_create(const easyspec_config *cfg, void *hip_stream, easyspec_ctx **out);
+
+/* Frees everything the context owns (synchronises its stream first).  NULL is allowed. */
+void easyspec_destroy(easyspec_ctx *ctx);
+
+/* Copy the parameters into the context, repacked into the library's streaming layout: per
+ * operation one layer-major array, so that the layers of any set are one contiguous range.
+ * Every pointer inside src is host|dev; the caller keeps src.  Synchronous. */
+int easyspec_load_weights(easyspec_ctx *ctx, const easyspec_weights *src);
+
+/* Layer-parallel strategy (Sec. 3.1.1: "a change in the configuration is enough").
+ * bounds (host): bounds[0] = 0 < bounds[1] < ... < bounds[n_sets] = n_layers; set j is the
+ * layers [bounds[j], bounds[j+1]), at most EASYSPEC_MAX_SET of them.  Only fuzzy steps use it. */
+int easyspec_set_groups(easyspec_ctx *ctx, const int32_t *bounds, int32_t n_sets);
+
+/* Boundaries of the paper's strategy for layer-parallel size N: first and last layer alone,
+ * the layers between cut into N-sets (policy: see EASYSPEC_POLICY_*).  bounds (host) must hold
+ * n_layers + 1 entries; *n_sets receives the number of sets.  Pure host function. */
+int easyspec_default_groups(int32_t n_layers, int32_t N, int32_t policy, int32_t *bounds, int32_t *n_sets);
+
+/* One fuzzy forward (Alg. 2) for every live sequence (precise length > 0), one token each.
+ *   tokens_in  dev [max_batch]  token fed to sequence b (ignored for idle sequences)
+ *   tokens_out dev [max_batch]  argmax of the logits, lowest index on ties (idle: untouched)
+ *   logits_out dev [max_batch][vocab] fp32, or NULL
+ * For each set, every attention layer of the set reads the hidden state entering the set and
+ * stores the k, v it computes from it in slot precise+fuzzy; the MLPs run in layer order.
+ * Afterwards fuzzy[b] += 1.  EASYSPEC_ESTATE if no sequence is live, EASYSPEC_ECAPACITY if a
+ * live sequence is full. */
+int easyspec_draft_step(easyspec_ctx *ctx, const int32_t *tokens_in, int32_t *tokens_out, float *logits_out);
+
+/* Bonus calibration (Sec. 3.2) of the sequences with n_tokens[b] > 0; also the prompt prefill
+ * (repeat in chunks of max_calib_tokens).
+ *   tokens         dev  [max_batch][max_calib_tokens]  accepted tokens followed by the bonus token
+ *   n_tokens       host [max_batch]  0 = leave sequence b alone, else 1..max_calib_tokens
+ *   next_token_out dev  [max_batch]  argmax after the last token of b (untouched if n_tokens[b]=0)
+ *   logits_out     dev  fp32 or NULL: logits_rows = 0 -> [max_batch][vocab] (last token of each);
+ *                  logits_rows = 1 -> [max_batch][max_calib_tokens][vocab] (every token)
+ * For each such sequence: fuzzy[b] = 0 (all fuzzy slots dropped, accepted or not); layers run
+ * in order over the n tokens at positions precise[b] .. precise[b]+n-1, causal among themselves;
+ * their k, v overwrite those slots; precise[b] += n. */
+int easyspec_calibrate(easyspec_ctx *ctx, const int32_t *tokens, const int32_t *n_tokens,
+                       int32_t *next_token_out, float *logits_out, int32_t logits_rows);
+
+/* Greedy acceptance (Alg. 3 with one-hot distributions): accept_len[b] = number of leading
+ * positions where draft equals target_argmax; bonus[b] = target_argmax[b][accept_len[b]].
+ *   draft [batch][gamma], target_argmax [batch][gamma+1], accept_len [batch], bonus [batch]
+ * hip_stream == NULL: all four are host arrays and the call is a host loop.  Otherwise all four
+ * are dev arrays and one small kernel is launched on that hipStream_t. */
+int easyspec_greedy_accept(const int32_t *draft, const int32_t *target_argmax, int32_t batch, int32_t gamma,
+                           int32_t *accept_len, int32_t *bonus, void *hip_stream);
+
+/* Host copies of the per-sequence lengths; each of precise, fuzzy: host [max_batch] or NULL. */
+int easyspec_get_lens(const easyspec_ctx *ctx, int32_t *precise, int32_t *fuzzy);
+
+/* Shorten sequence b to new_precise_len precise slots and no fuzzy ones (base-model rollback
+ * after verification; 0 makes the sequence idle).  Host state only. */
+int easyspec_truncate(easyspec_ctx *ctx, int32_t b, int32_t new_precise_len);
+
+/* Replace the cache of sequence b by n_slots precise entries.  k, v: host|dev
+ * [n_layers][n_kv_heads][n_slots][head_dim] in the storage dtype.  Synchronous. */
+int easyspec_kv_import(easyspec_ctx *ctx, int32_t b, const void *k, const void *v, int32_t n_slots);
+
+/* Copy slots [0, n_slots) of sequence b out (same layout as import; fuzzy slots included if
+ * n_slots reaches them).  Synchronous. */
+int easyspec_kv_export(easyspec_ctx *ctx, int32_t b, void *k, void *v, int32_t n_slots);
+
+/* Final residual-stream rows (before the last norm) of the most recent forward, in the order
+ * the forward processed them (draft step: live sequences by index; calibration: sequences by
+ * index, tokens in order).  out: dev fp32 [n_rows][d_model]; *n_rows (host) receives the count.
+ * For parity checks of hidden states. */
+int easyspec_get_hidden(easyspec_ctx *ctx, float *out, int32_t max_rows, int32_t *n_rows);
+
+/* Algorithmic HBM bytes of one draft step in the current state: layer weights + LM head + the
+ * KV slots each live sequence reads.  Pure host arithmetic, for roofline reports. */
+int64_t easyspec_step_bytes(const easyspec_ctx *ctx);
+
+/* Message of the last failed call on ctx (ctx == NULL: of the last failed easyspec_create or
+ * context-free call on this thread).  Never NULL. */
+const char *easyspec_last_error(const easyspec_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EASYSPEC_H */

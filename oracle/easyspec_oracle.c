@@ -8,9 +8,12 @@
  * Arithmetic: every vector and accumulator is a double.  Parameters are read from the
  * caller's arrays (float32, or bf16 bit patterns widened on the fly).  When cfg.bf16 == 1
  * the storage rounding points of a bf16 model apply: the KV cache holds bf16 values, and
- * every vector that enters a weight contraction (normed hidden state, attention output,
- * SiLU(gate)*up, final normed hidden state) is rounded to bf16 first.  With cfg.bf16 == 0
- * nothing is rounded except the KV cache, which holds float32.
+ * every vector that enters a weight contraction (gained hidden state, attention output,
+ * SiLU(gate)*up) is rounded to bf16 first.  With cfg.bf16 == 0 nothing is rounded except the
+ * KV cache, which holds float32.  The paper fixes no precision, so the placement of these
+ * roundings is a reading; one of them concerns RMSNorm: the normalised input of a contraction
+ * is carried as the vector x*g (rounded) and the scalar rsqrt(mean(x^2)+eps), and the scalar
+ * multiplies the contraction's result.  Without rounding this is the same function.
  *
  * Model function (pre-norm decoder; the paper names only "attention layers", "MLP layers"
  * and the normalisation before attention, App. E.1; the rest follows the benchmark shapes):
@@ -92,23 +95,32 @@ static float kv_store(const eso_config *c, double x) { return c->bf16 ? (float)e
 
 /* ---------------------------------------------------------------- primitives */
 
-/* y[r] = sum_j W[r][j] x[j] (+ b[r]) */
-void eso_matvec(const void *w, int bf16, const float *bias, int rows, int cols, const double *x, double *y) {
+/* y[r] = scale * sum_j W[r][j] x[j] (+ b[r]) */
+void eso_matvec(const void *w, int bf16, const float *bias, double scale, int rows, int cols, const double *x,
+                double *y) {
 #pragma omp parallel for schedule(static)
   for (int r = 0; r < rows; ++r) {
     double acc = 0.0;
     size_t base = (size_t)r * (size_t)cols;
     for (int j = 0; j < cols; ++j) acc += weight_at(w, bf16, base + (size_t)j) * x[j];
+    acc *= scale;
     y[r] = bias ? acc + (double)bias[r] : acc;
   }
 }
 
-/* y = x * rsqrt(mean(x^2) + eps) * g */
-void eso_rmsnorm(const double *x, const float *g, int n, double eps, double *y) {
+/* RMSNorm(x; g) = x * rsqrt(mean(x^2) + eps) * g, returned in two parts:
+ * xg[j] = x[j] * g[j] and the scalar rsqrt(mean(x^2) + eps). */
+double eso_rmsnorm_split(const double *x, const float *g, int n, double eps, double *xg) {
   double ss = 0.0;
   for (int j = 0; j < n; ++j) ss += x[j] * x[j];
-  double r = 1.0 / sqrt(ss / (double)n + eps);
-  for (int j = 0; j < n; ++j) y[j] = x[j] * r * (double)g[j];
+  for (int j = 0; j < n; ++j) xg[j] = x[j] * (double)g[j];
+  return 1.0 / sqrt(ss / (double)n + eps);
+}
+
+/* the two parts multiplied out */
+void eso_rmsnorm(const double *x, const float *g, int n, double eps, double *y) {
+  double r = eso_rmsnorm_split(x, g, n, eps, y);
+  for (int j = 0; j < n; ++j) y[j] *= r;
 }
 
 /* Rotary embedding of one head vector at position pos: element i pairs with i + hd/2,
@@ -228,11 +240,11 @@ static void attn_block(eso_seq *s, int layer, const double *h, int pos, double *
   double *o = (double *)malloc(sizeof(double) * (size_t)nq * hd);
   double *sc = (double *)malloc(sizeof(double) * (size_t)(pos + 1));
 
-  eso_rmsnorm(h, l->g_attn, d, c->rms_eps, n);
+  double rs = eso_rmsnorm_split(h, l->g_attn, d, c->rms_eps, n);
   for (int j = 0; j < d; ++j) n[j] = act_round(c, n[j]);
-  eso_matvec(l->wq, c->bf16, l->bq, nq * hd, d, n, q);
-  eso_matvec(l->wk, c->bf16, l->bk, nkv * hd, d, n, k);
-  eso_matvec(l->wv, c->bf16, l->bv, nkv * hd, d, n, v);
+  eso_matvec(l->wq, c->bf16, l->bq, rs, nq * hd, d, n, q);
+  eso_matvec(l->wk, c->bf16, l->bk, rs, nkv * hd, d, n, k);
+  eso_matvec(l->wv, c->bf16, l->bv, rs, nkv * hd, d, n, v);
   for (int a = 0; a < nq; ++a) eso_rope(q + (size_t)a * hd, hd, pos, c->rope_theta);
   for (int g = 0; g < nkv; ++g) {
     eso_rope(k + (size_t)g * hd, hd, pos, c->rope_theta);
@@ -259,7 +271,7 @@ static void attn_block(eso_seq *s, int layer, const double *h, int pos, double *
       o[(size_t)a * hd + e] = act_round(c, acc);
     }
   }
-  eso_matvec(l->wo, c->bf16, NULL, d, nq * hd, o, out);
+  eso_matvec(l->wo, c->bf16, NULL, 1.0, d, nq * hd, o, out);
   free(n); free(q); free(k); free(v); free(o); free(sc);
 }
 
@@ -271,12 +283,12 @@ static void mlp_block(const eso_model *m, int layer, const double *h, double *ou
   double *y = (double *)malloc(sizeof(double) * (size_t)d);
   double *g = (double *)malloc(sizeof(double) * (size_t)f);
   double *u = (double *)malloc(sizeof(double) * (size_t)f);
-  eso_rmsnorm(h, l->g_mlp, d, c->rms_eps, y);
+  double rs = eso_rmsnorm_split(h, l->g_mlp, d, c->rms_eps, y);
   for (int j = 0; j < d; ++j) y[j] = act_round(c, y[j]);
-  eso_matvec(l->wg, c->bf16, NULL, f, d, y, g);
-  eso_matvec(l->wu, c->bf16, NULL, f, d, y, u);
+  eso_matvec(l->wg, c->bf16, NULL, rs, f, d, y, g);
+  eso_matvec(l->wu, c->bf16, NULL, rs, f, d, y, u);
   for (int j = 0; j < f; ++j) g[j] = act_round(c, eso_silu(g[j]) * u[j]);
-  eso_matvec(l->wd, c->bf16, NULL, d, f, g, out);
+  eso_matvec(l->wd, c->bf16, NULL, 1.0, d, f, g, out);
   free(y); free(g); free(u);
 }
 
@@ -288,9 +300,9 @@ static void embed_row(const eso_model *m, int32_t token, double *h) {
 static void head(const eso_model *m, const double *h, double *logits) {
   const eso_config *c = &m->cfg;
   double *x = (double *)malloc(sizeof(double) * (size_t)c->d_model);
-  eso_rmsnorm(h, m->g_final, c->d_model, c->rms_eps, x);
+  double rs = eso_rmsnorm_split(h, m->g_final, c->d_model, c->rms_eps, x);
   for (int j = 0; j < c->d_model; ++j) x[j] = act_round(c, x[j]);
-  eso_matvec(m->lm_head, c->bf16, NULL, c->vocab, c->d_model, x, logits);
+  eso_matvec(m->lm_head, c->bf16, NULL, rs, c->vocab, c->d_model, x, logits);
   free(x);
 }
 

@@ -44,7 +44,7 @@ def lib():
         vp, i32, dp, fp, ip = C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_float), C.POINTER(C.c_int32)
         L.eso_bf16_round.restype = C.c_double
         L.eso_bf16_round.argtypes = [C.c_double]
-        L.eso_matvec.argtypes = [vp, C.c_int, vp, C.c_int, C.c_int, dp, dp]
+        L.eso_matvec.argtypes = [vp, C.c_int, vp, C.c_double, C.c_int, C.c_int, dp, dp]
         L.eso_rmsnorm.argtypes = [dp, fp, C.c_int, C.c_double, dp]
         L.eso_rope.argtypes = [dp, C.c_int, C.c_int, C.c_double]
         L.eso_silu.restype = C.c_double
@@ -99,13 +99,13 @@ def bf16_round(x: float) -> float:
     return lib().eso_bf16_round(float(x))
 
 
-def matvec(w: np.ndarray, x: np.ndarray, bias: np.ndarray | None = None) -> np.ndarray:
-    """w: [rows, cols] float32 or uint16 (bf16 bits)."""
+def matvec(w: np.ndarray, x: np.ndarray, bias: np.ndarray | None = None, scale: float = 1.0) -> np.ndarray:
+    """scale * (w @ x) + bias;  w: [rows, cols] float32 or uint16 (bf16 bits)."""
     w = np.ascontiguousarray(w)
     x = np.ascontiguousarray(x, dtype=np.float64)
     y = np.empty(w.shape[0], dtype=np.float64)
     b = None if bias is None else np.ascontiguousarray(bias, dtype=np.float32)
-    lib().eso_matvec(_vp(w), int(w.dtype == np.uint16), _vp(b), w.shape[0], w.shape[1], _dp(x), _dp(y))
+    lib().eso_matvec(_vp(w), int(w.dtype == np.uint16), _vp(b), float(scale), w.shape[0], w.shape[1], _dp(x), _dp(y))
     return y
 
 

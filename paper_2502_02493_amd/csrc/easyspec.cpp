@@ -1,0 +1,519 @@
+// Host side of the EasySpec C ABI (include/easyspec.h): argument checks, the per-sequence
+// precise / fuzzy length state machine, weight repacking, and the launch sequence of one
+// forward pass.  All arithmetic of the method runs in the kernels of kernels.hip.
+#include "../../include/easyspec.h"
+
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "kernels.h"
+
+using namespace es;
+
+struct easyspec_ctx {
+  easyspec_config cfg;
+  Shape s;
+  Buffers b;
+  hipStream_t stream;
+  bool weights_loaded;
+  std::vector<int32_t> precise, fuzzy;
+  std::vector<int32_t> bounds;  // current layer-parallel strategy
+  std::vector<int32_t> single;  // every layer alone (Alg. 1 order)
+  std::vector<void*> allocs;
+  int32_t last_rows;
+  std::string err;
+};
+
+static thread_local std::string g_err;
+
+static int fail(easyspec_ctx* ctx, int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (ctx) ctx->err = buf;
+  else g_err = buf;
+  return code;
+}
+
+#define HIPCHK(ctx, call)                                                                           \
+  do {                                                                                              \
+    hipError_t e_ = (call);                                                                         \
+    if (e_ != hipSuccess) return fail(ctx, EASYSPEC_EHIP, "%s: %s", #call, hipGetErrorString(e_)); \
+  } while (0)
+
+static size_t esize(const Shape& s) { return s.dtype == EASYSPEC_DTYPE_BF16 ? 2 : 4; }
+static size_t packed_bytes(const Shape& s, int rows, int K) { return (size_t)((rows + 15) / 16) * 16 * (size_t)K * esize(s); }
+
+static int dev_alloc(easyspec_ctx* ctx, void** p, size_t bytes) {
+  *p = nullptr;
+  if (bytes == 0) bytes = 16;
+  HIPCHK(ctx, hipMalloc(p, bytes));
+  ctx->allocs.push_back(*p);
+  return EASYSPEC_OK;
+}
+
+#define ALLOC(ctx, ptr, bytes)                                       \
+  do {                                                               \
+    int rc_ = dev_alloc(ctx, (void**)&(ptr), (size_t)(bytes));       \
+    if (rc_ != EASYSPEC_OK) return rc_;                              \
+  } while (0)
+
+static int check_config(const easyspec_config* c) {
+  if (!c) return fail(nullptr, EASYSPEC_EINVAL, "config is NULL");
+  if (c->n_layers < 1 || c->d_model < 32 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->d_ffn < 32 || c->vocab < 1)
+    return fail(nullptr, EASYSPEC_EINVAL, "non-positive model dimension");
+  if (c->dtype != EASYSPEC_DTYPE_F32 && c->dtype != EASYSPEC_DTYPE_BF16) return fail(nullptr, EASYSPEC_EINVAL, "unknown dtype %d", c->dtype);
+  if (c->head_dim != 64 && c->head_dim != 128) return fail(nullptr, EASYSPEC_EINVAL, "head_dim must be 64 or 128, got %d", c->head_dim);
+  if (c->d_model % 32 || c->d_ffn % 32 || (c->n_q_heads * c->head_dim) % 32)
+    return fail(nullptr, EASYSPEC_EINVAL, "d_model, d_ffn and n_q_heads*head_dim must be multiples of 32");
+  if (c->n_q_heads % c->n_kv_heads) return fail(nullptr, EASYSPEC_EINVAL, "n_q_heads must be a multiple of n_kv_heads");
+  const int g = c->n_q_heads / c->n_kv_heads;
+  if (g != 1 && g != 2 && g != 4 && g != 7 && g != 8)
+    return fail(nullptr, EASYSPEC_EINVAL, "n_q_heads/n_kv_heads = %d is not one of 1, 2, 4, 7, 8", g);
+  if (c->max_batch < 1 || c->max_batch > EASYSPEC_MAX_BATCH) return fail(nullptr, EASYSPEC_EINVAL, "max_batch must be 1..%d", EASYSPEC_MAX_BATCH);
+  if (c->max_calib_tokens < 1 || c->max_calib_tokens > EASYSPEC_MAX_CALIB_TOKENS)
+    return fail(nullptr, EASYSPEC_EINVAL, "max_calib_tokens must be 1..%d", EASYSPEC_MAX_CALIB_TOKENS);
+  if (c->max_ctx < 1 || c->max_ctx > kMaxChunks * 1024) return fail(nullptr, EASYSPEC_EINVAL, "max_ctx must be 1..%d", kMaxChunks * 1024);
+  if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return fail(nullptr, EASYSPEC_EINVAL, "bad rms_eps or rope_theta");
+  return EASYSPEC_OK;
+}
+
+extern "C" int easyspec_create(const easyspec_config* cfg, void* hip_stream, easyspec_ctx** out) {
+  if (!out) return fail(nullptr, EASYSPEC_EINVAL, "out is NULL");
+  *out = nullptr;
+  int rc = check_config(cfg);
+  if (rc != EASYSPEC_OK) return rc;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1)
+    return fail(nullptr, EASYSPEC_EHIP, "no HIP device available (this library has no CPU path)");
+
+  easyspec_ctx* ctx = new easyspec_ctx();
+  ctx->cfg = *cfg;
+  ctx->stream = (hipStream_t)hip_stream;
+  ctx->weights_loaded = false;
+  ctx->last_rows = 0;
+  Shape& s = ctx->s;
+  s.dtype = cfg->dtype; s.L = cfg->n_layers; s.d = cfg->d_model; s.Hq = cfg->n_q_heads; s.Hkv = cfg->n_kv_heads;
+  s.hd = cfg->head_dim; s.F = cfg->d_ffn; s.V = cfg->vocab; s.HQ = s.Hq * s.hd; s.RQKV = (s.Hq + 2 * s.Hkv) * s.hd;
+  s.B = cfg->max_batch; s.max_ctx = cfg->max_ctx; s.eps = cfg->rms_eps; s.has_bias = cfg->qkv_bias ? 1 : 0;
+  ctx->precise.assign(s.B, 0);
+  ctx->fuzzy.assign(s.B, 0);
+  for (int i = 0; i <= s.L; ++i) ctx->single.push_back(i);
+  ctx->bounds = ctx->single;
+
+  auto body = [&]() -> int {
+    Buffers& b = ctx->b;
+    memset(&b, 0, sizeof b);
+    const size_t es_ = esize(s);
+    ALLOC(ctx, b.wqkv, (size_t)s.L * packed_bytes(s, s.RQKV, s.d));
+    ALLOC(ctx, b.wo, (size_t)s.L * packed_bytes(s, s.d, s.HQ));
+    ALLOC(ctx, b.wg, (size_t)s.L * packed_bytes(s, s.F, s.d));
+    ALLOC(ctx, b.wu, (size_t)s.L * packed_bytes(s, s.F, s.d));
+    ALLOC(ctx, b.wd, (size_t)s.L * packed_bytes(s, s.d, s.F));
+    ALLOC(ctx, b.wlm, packed_bytes(s, s.V, s.d));
+    ALLOC(ctx, b.embed, (size_t)s.V * s.d * es_);
+    if (s.has_bias) ALLOC(ctx, b.bqkv, (size_t)s.L * s.RQKV * sizeof(float));
+    ALLOC(ctx, b.g_attn, (size_t)s.L * s.d * sizeof(float));
+    ALLOC(ctx, b.g_mlp, (size_t)s.L * s.d * sizeof(float));
+    ALLOC(ctx, b.g_final, (size_t)s.d * sizeof(float));
+    ALLOC(ctx, b.rope, (size_t)s.max_ctx * (s.hd / 2) * sizeof(float2));
+    const size_t kv_bytes = (size_t)s.L * s.B * s.Hkv * s.max_ctx * s.hd * es_;
+    ALLOC(ctx, b.kc, kv_bytes);
+    ALLOC(ctx, b.vc, kv_bytes);
+    ALLOC(ctx, b.H, (size_t)kMaxCols * s.d * sizeof(float));
+    ALLOC(ctx, b.ssp, (size_t)kMaxCols * (s.d / 16) * sizeof(float));
+    ALLOC(ctx, b.XA, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.d * es_);
+    ALLOC(ctx, b.XM, (size_t)kMaxCols * s.d * es_);
+    ALLOC(ctx, b.Q, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.HQ * sizeof(float));
+    ALLOC(ctx, b.AO, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.HQ * es_);
+    ALLOC(ctx, b.A, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.d * sizeof(float));
+    ALLOC(ctx, b.ACT, (size_t)kMaxCols * s.F * es_);
+    const size_t prow = (size_t)EASYSPEC_MAX_SET * kMaxCols * s.Hq;
+    ALLOC(ctx, b.PO, prow * kMaxChunks * s.hd * sizeof(float));
+    ALLOC(ctx, b.PM, prow * kMaxChunks * sizeof(float));
+    ALLOC(ctx, b.PL, prow * kMaxChunks * sizeof(float));
+    const size_t nblk = (size_t)(s.V + 15) / 16;
+    ALLOC(ctx, b.amax_val, kMaxCols * nblk * sizeof(float));
+    ALLOC(ctx, b.amax_idx, kMaxCols * nblk * sizeof(int32_t));
+    HIPCHK(ctx, hipMemsetAsync(b.kc, 0, kv_bytes, ctx->stream));
+    HIPCHK(ctx, hipMemsetAsync(b.vc, 0, kv_bytes, ctx->stream));
+
+    // rotary table in double precision: angle(pos, i) = pos * theta^(-2 i / hd)
+    const int half = s.hd / 2;
+    std::vector<float2> tab((size_t)s.max_ctx * half);
+    std::vector<double> freq(half);
+    for (int i = 0; i < half; ++i) freq[i] = pow((double)cfg->rope_theta, -2.0 * (double)i / (double)s.hd);
+    for (int p = 0; p < s.max_ctx; ++p)
+      for (int i = 0; i < half; ++i) {
+        const double ang = (double)p * freq[i];
+        tab[(size_t)p * half + i] = make_float2((float)cos(ang), (float)sin(ang));
+      }
+    HIPCHK(ctx, hipMemcpy(b.rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice));
+    HIPCHK(ctx, hipStreamSynchronize(ctx->stream));
+    return EASYSPEC_OK;
+  };
+  rc = body();
+  if (rc != EASYSPEC_OK) {
+    g_err = ctx->err;
+    for (void* p : ctx->allocs) (void)hipFree(p);
+    delete ctx;
+    return rc;
+  }
+  *out = ctx;
+  return EASYSPEC_OK;
+}
+
+extern "C" void easyspec_destroy(easyspec_ctx* ctx) {
+  if (!ctx) return;
+  (void)hipStreamSynchronize(ctx->stream);
+  for (void* p : ctx->allocs) (void)hipFree(p);
+  delete ctx;
+}
+
+extern "C" const char* easyspec_last_error(const easyspec_ctx* ctx) { return ctx ? ctx->err.c_str() : g_err.c_str(); }
+
+// ---------------------------------------------------------------------------------------------
+// weights
+// ---------------------------------------------------------------------------------------------
+
+extern "C" int easyspec_load_weights(easyspec_ctx* ctx, const easyspec_weights* w) {
+  if (!ctx) return fail(nullptr, EASYSPEC_EINVAL, "ctx is NULL");
+  if (!w || !w->layers || !w->embed || !w->lm_head || !w->g_final) return fail(ctx, EASYSPEC_EINVAL, "weights: NULL pointer");
+  const Shape& s = ctx->s;
+  for (int l = 0; l < s.L; ++l) {
+    const easyspec_layer_weights& lw = w->layers[l];
+    if (!lw.wq || !lw.wk || !lw.wv || !lw.wo || !lw.wg || !lw.wu || !lw.wd || !lw.g_attn || !lw.g_mlp)
+      return fail(ctx, EASYSPEC_EINVAL, "weights: NULL pointer in layer %d", l);
+    if (s.has_bias && (!lw.bq || !lw.bk || !lw.bv)) return fail(ctx, EASYSPEC_EINVAL, "weights: missing bias in layer %d", l);
+  }
+  const size_t es_ = esize(s);
+  const Buffers& b = ctx->b;
+  // staging for one row-major matrix (largest: LM head, gate/up, or stacked QKV)
+  size_t stage_elems = (size_t)s.V * s.d;
+  if ((size_t)s.F * s.d > stage_elems) stage_elems = (size_t)s.F * s.d;
+  if ((size_t)s.RQKV * s.d > stage_elems) stage_elems = (size_t)s.RQKV * s.d;
+  void* stage = nullptr;
+  HIPCHK(ctx, hipMalloc(&stage, stage_elems * es_));
+  auto body = [&]() -> int {
+    hipStream_t st = ctx->stream;
+    auto put = [&](const void* src, size_t elems, size_t off_elems) -> hipError_t {
+      return hipMemcpyAsync((char*)stage + off_elems * es_, src, elems * es_, hipMemcpyDefault, st);
+    };
+    auto pack = [&](void* dst_base, size_t layer, int rows, int K) -> hipError_t {
+      launch_repack(s.dtype, stage, (char*)dst_base + layer * packed_bytes(s, rows, K), rows, K, st);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+      return hipStreamSynchronize(st);  // staging is reused
+    };
+    for (int l = 0; l < s.L; ++l) {
+      const easyspec_layer_weights& lw = w->layers[l];
+      HIPCHK(ctx, put(lw.wq, (size_t)s.HQ * s.d, 0));
+      HIPCHK(ctx, put(lw.wk, (size_t)s.Hkv * s.hd * s.d, (size_t)s.HQ * s.d));
+      HIPCHK(ctx, put(lw.wv, (size_t)s.Hkv * s.hd * s.d, (size_t)(s.HQ + s.Hkv * s.hd) * s.d));
+      HIPCHK(ctx, pack(b.wqkv, l, s.RQKV, s.d));
+      HIPCHK(ctx, put(lw.wo, (size_t)s.d * s.HQ, 0));
+      HIPCHK(ctx, pack(b.wo, l, s.d, s.HQ));
+      HIPCHK(ctx, put(lw.wg, (size_t)s.F * s.d, 0));
+      HIPCHK(ctx, pack(b.wg, l, s.F, s.d));
+      HIPCHK(ctx, put(lw.wu, (size_t)s.F * s.d, 0));
+      HIPCHK(ctx, pack(b.wu, l, s.F, s.d));
+      HIPCHK(ctx, put(lw.wd, (size_t)s.d * s.F, 0));
+      HIPCHK(ctx, pack(b.wd, l, s.d, s.F));
+      if (s.has_bias) {
+        float* dst = b.bqkv + (size_t)l * s.RQKV;
+        HIPCHK(ctx, hipMemcpyAsync(dst, lw.bq, (size_t)s.HQ * 4, hipMemcpyDefault, st));
+        HIPCHK(ctx, hipMemcpyAsync(dst + s.HQ, lw.bk, (size_t)s.Hkv * s.hd * 4, hipMemcpyDefault, st));
+        HIPCHK(ctx, hipMemcpyAsync(dst + s.HQ + s.Hkv * s.hd, lw.bv, (size_t)s.Hkv * s.hd * 4, hipMemcpyDefault, st));
+      }
+      HIPCHK(ctx, hipMemcpyAsync(b.g_attn + (size_t)l * s.d, lw.g_attn, (size_t)s.d * 4, hipMemcpyDefault, st));
+      HIPCHK(ctx, hipMemcpyAsync(b.g_mlp + (size_t)l * s.d, lw.g_mlp, (size_t)s.d * 4, hipMemcpyDefault, st));
+    }
+    HIPCHK(ctx, put(w->lm_head, (size_t)s.V * s.d, 0));
+    HIPCHK(ctx, pack(b.wlm, 0, s.V, s.d));
+    HIPCHK(ctx, hipMemcpyAsync(b.embed, w->embed, (size_t)s.V * s.d * es_, hipMemcpyDefault, st));
+    HIPCHK(ctx, hipMemcpyAsync(b.g_final, w->g_final, (size_t)s.d * 4, hipMemcpyDefault, st));
+    HIPCHK(ctx, hipStreamSynchronize(st));
+    return EASYSPEC_OK;
+  };
+  const int rc = body();
+  (void)hipFree(stage);
+  if (rc == EASYSPEC_OK) ctx->weights_loaded = true;
+  return rc;
+}
+
+// ---------------------------------------------------------------------------------------------
+// layer-parallel strategy
+// ---------------------------------------------------------------------------------------------
+
+extern "C" int easyspec_default_groups(int32_t L, int32_t N, int32_t policy, int32_t* bounds, int32_t* n_sets) {
+  if (L < 1 || N < 1 || !bounds || !n_sets) return fail(nullptr, EASYSPEC_EINVAL, "default_groups: bad arguments");
+  if (policy != EASYSPEC_POLICY_ALIGNED && policy != EASYSPEC_POLICY_PACKED) return fail(nullptr, EASYSPEC_EINVAL, "default_groups: unknown policy %d", policy);
+  std::vector<int32_t> b;
+  b.push_back(0);
+  if (L >= 2) {
+    // layers 1 .. L-2 are cut into N-sets; layer 0 and layer L-1 stay alone
+    const int32_t stop = L - 1;
+    int32_t lo = 1;
+    b.push_back(lo);
+    while (lo < stop) {
+      int32_t hi = policy == EASYSPEC_POLICY_ALIGNED ? (lo / N + 1) * N : lo + N;
+      if (hi > stop) hi = stop;
+      b.push_back(hi);
+      lo = hi;
+    }
+  }
+  b.push_back(L);
+  for (size_t i = 0; i < b.size(); ++i) bounds[i] = b[i];
+  *n_sets = (int32_t)b.size() - 1;
+  return EASYSPEC_OK;
+}
+
+extern "C" int easyspec_set_groups(easyspec_ctx* ctx, const int32_t* bounds, int32_t n_sets) {
+  if (!ctx) return fail(nullptr, EASYSPEC_EINVAL, "ctx is NULL");
+  if (!bounds || n_sets < 1 || n_sets > ctx->s.L) return fail(ctx, EASYSPEC_EINVAL, "set_groups: bad n_sets");
+  if (bounds[0] != 0 || bounds[n_sets] != ctx->s.L) return fail(ctx, EASYSPEC_EINVAL, "set_groups: bounds must run from 0 to n_layers");
+  for (int j = 0; j < n_sets; ++j) {
+    const int k = bounds[j + 1] - bounds[j];
+    if (k < 1) return fail(ctx, EASYSPEC_EINVAL, "set_groups: bounds must increase");
+    if (k > EASYSPEC_MAX_SET) return fail(ctx, EASYSPEC_EINVAL, "set_groups: set of %d layers exceeds %d", k, EASYSPEC_MAX_SET);
+  }
+  ctx->bounds.assign(bounds, bounds + n_sets + 1);
+  return EASYSPEC_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// one forward pass over the columns `c` (launch sequence of Alg. 1 / Alg. 2)
+// ---------------------------------------------------------------------------------------------
+
+static void pick_chunk(const Shape& s, const Cols& c, int n_set_max, int* chunk, int* n_chunks) {
+  int max_len = 1;
+  for (int i = 0; i < c.n; ++i)
+    if (c.pos[i] + 1 > max_len) max_len = c.pos[i] + 1;
+  int ch = 64;
+  auto nch = [&](int ch_) { return (max_len + ch_ - 1) / ch_; };
+  while (ch < 1024 && (nch(ch) > kMaxChunks || (long)nch(ch) * s.Hkv * n_set_max * c.n > 1024)) ch *= 2;
+  *chunk = ch;
+  *n_chunks = nch(ch);
+}
+
+static int forward(easyspec_ctx* ctx, const Cols& c, const int32_t* tokens, const std::vector<int32_t>& bounds,
+                   float* logits_out, int32_t* tokens_out) {
+  const Shape& s = ctx->s;
+  const Buffers& b = ctx->b;
+  hipStream_t st = ctx->stream;
+  const int n_sets = (int)bounds.size() - 1;
+  launch_embed(s, b, c, tokens, 0, bounds[1] - bounds[0], st);
+  for (int j = 0; j < n_sets; ++j) {
+    const int lo = bounds[j], hi = bounds[j + 1], k = hi - lo;
+    int chunk, n_chunks;
+    pick_chunk(s, c, k, &chunk, &n_chunks);
+    // every attention layer of the set reads the hidden state that enters the set
+    launch_qkv(s, b, c, lo, k, st);
+    launch_attn(s, b, c, lo, k, chunk, n_chunks, st);
+    launch_oproj(s, b, c, lo, k, st);
+    // the MLPs run in layer order on the running residual
+    for (int i = lo; i < hi; ++i) {
+      launch_gateup(s, b, c, i, st);
+      if (i + 1 < hi) {
+        launch_down(s, b, c, i, i + 1 - lo, b.g_mlp + (size_t)(i + 1) * s.d, 1, b.XM, st);
+      } else if (hi < s.L) {
+        launch_down(s, b, c, i, -1, b.g_attn + (size_t)hi * s.d, bounds[j + 2] - hi, b.XA, st);
+      } else {
+        launch_down(s, b, c, i, -1, b.g_final, 1, b.XA, st);
+      }
+    }
+  }
+  launch_head(s, b, c, logits_out, tokens_out, st);
+  HIPCHK(ctx, hipGetLastError());
+  ctx->last_rows = c.n;
+  return EASYSPEC_OK;
+}
+
+extern "C" int easyspec_draft_step(easyspec_ctx* ctx, const int32_t* tokens_in, int32_t* tokens_out, float* logits_out) {
+  if (!ctx) return fail(nullptr, EASYSPEC_EINVAL, "ctx is NULL");
+  if (!ctx->weights_loaded) return fail(ctx, EASYSPEC_ESTATE, "draft_step: no weights loaded");
+  if (!tokens_in || !tokens_out) return fail(ctx, EASYSPEC_EINVAL, "draft_step: NULL token array");
+  const Shape& s = ctx->s;
+  Cols c;
+  memset(&c, 0, sizeof c);
+  for (int b = 0; b < s.B; ++b) {
+    if (ctx->precise[b] == 0) continue;
+    const int pos = ctx->precise[b] + ctx->fuzzy[b];
+    if (pos + 1 > s.max_ctx) return fail(ctx, EASYSPEC_ECAPACITY, "draft_step: sequence %d is full (%d slots)", b, s.max_ctx);
+    c.seq[c.n] = b; c.pos[c.n] = pos; c.tok_idx[c.n] = b; c.logit_row[c.n] = b; c.out_idx[c.n] = b;
+    ++c.n;
+  }
+  if (c.n == 0) return fail(ctx, EASYSPEC_ESTATE, "draft_step: no live sequence (calibrate a prompt first)");
+  const int rc = forward(ctx, c, tokens_in, ctx->bounds, logits_out, tokens_out);
+  if (rc != EASYSPEC_OK) return rc;
+  for (int i = 0; i < c.n; ++i) ctx->fuzzy[c.seq[i]] += 1;
+  return EASYSPEC_OK;
+}
+
+extern "C" int easyspec_calibrate(easyspec_ctx* ctx, const int32_t* tokens, const int32_t* n_tokens, int32_t* next_token_out,
+                                  float* logits_out, int32_t logits_rows) {
+  if (!ctx) return fail(nullptr, EASYSPEC_EINVAL, "ctx is NULL");
+  if (!ctx->weights_loaded) return fail(ctx, EASYSPEC_ESTATE, "calibrate: no weights loaded");
+  if (!tokens || !n_tokens || !next_token_out) return fail(ctx, EASYSPEC_EINVAL, "calibrate: NULL argument");
+  if (logits_rows != 0 && logits_rows != 1) return fail(ctx, EASYSPEC_EINVAL, "calibrate: logits_rows must be 0 or 1");
+  const Shape& s = ctx->s;
+  const int mc = ctx->cfg.max_calib_tokens;
+  int total = 0;
+  for (int b = 0; b < s.B; ++b) {
+    const int n = n_tokens[b];
+    if (n < 0 || n > mc) return fail(ctx, EASYSPEC_ECAPACITY, "calibrate: n_tokens[%d] = %d outside 0..%d", b, n, mc);
+    if (n > 0 && ctx->precise[b] + n > s.max_ctx)
+      return fail(ctx, EASYSPEC_ECAPACITY, "calibrate: sequence %d would hold %d > %d slots", b, ctx->precise[b] + n, s.max_ctx);
+    total += n;
+  }
+  if (total == 0) return fail(ctx, EASYSPEC_EINVAL, "calibrate: no tokens");
+  // passes of at most 16 columns; a sequence's tokens stay together
+  int b = 0;
+  while (b < s.B) {
+    Cols c;
+    memset(&c, 0, sizeof c);
+    while (b < s.B && c.n + n_tokens[b] <= kMaxCols) {
+      const int n = n_tokens[b];
+      for (int r = 0; r < n; ++r) {
+        const bool last = r == n - 1;
+        c.seq[c.n] = b;
+        c.pos[c.n] = ctx->precise[b] + r;  // fuzzy slots are dropped: positions restart at the precise length
+        c.tok_idx[c.n] = b * mc + r;
+        c.logit_row[c.n] = logits_rows ? b * mc + r : (last ? b : -1);
+        c.out_idx[c.n] = last ? b : -1;
+        ++c.n;
+      }
+      ++b;
+    }
+    if (c.n == 0) continue;
+    const int rc = forward(ctx, c, tokens, ctx->single, logits_out, next_token_out);
+    if (rc != EASYSPEC_OK) return rc;
+  }
+  for (int q = 0; q < s.B; ++q)
+    if (n_tokens[q] > 0) {
+      ctx->fuzzy[q] = 0;
+      ctx->precise[q] += n_tokens[q];
+    }
+  return EASYSPEC_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// acceptance, lengths, cache access
+// ---------------------------------------------------------------------------------------------
+
+extern "C" int easyspec_greedy_accept(const int32_t* draft, const int32_t* target, int32_t batch, int32_t gamma,
+                                      int32_t* accept_len, int32_t* bonus, void* hip_stream) {
+  if (!draft || !target || !accept_len || !bonus) return fail(nullptr, EASYSPEC_EINVAL, "greedy_accept: NULL argument");
+  if (batch < 1 || gamma < 0) return fail(nullptr, EASYSPEC_EINVAL, "greedy_accept: batch must be >= 1 and gamma >= 0");
+  if (hip_stream) {
+    launch_accept(draft, target, batch, gamma, accept_len, bonus, (hipStream_t)hip_stream);
+    HIPCHK(nullptr, hipGetLastError());
+    return EASYSPEC_OK;
+  }
+  for (int b = 0; b < batch; ++b) {
+    const int32_t* d = draft + (size_t)b * gamma;
+    const int32_t* t = target + (size_t)b * (gamma + 1);
+    int m = 0;
+    while (m < gamma && d[m] == t[m]) ++m;
+    accept_len[b] = m;
+    bonus[b] = t[m];
+  }
+  return EASYSPEC_OK;
+}
+
+extern "C" int easyspec_get_lens(const easyspec_ctx* ctx, int32_t* precise, int32_t* fuzzy) {
+  if (!ctx) return fail(nullptr, EASYSPEC_EINVAL, "ctx is NULL");
+  for (int b = 0; b < ctx->s.B; ++b) {
+    if (precise) precise[b] = ctx->precise[b];
+    if (fuzzy) fuzzy[b] = ctx->fuzzy[b];
+  }
+  return EASYSPEC_OK;
+}
+
+extern "C" int easyspec_truncate(easyspec_ctx* ctx, int32_t b, int32_t new_len) {
+  if (!ctx) return fail(nullptr, EASYSPEC_EINVAL, "ctx is NULL");
+  if (b < 0 || b >= ctx->s.B) return fail(ctx, EASYSPEC_EINVAL, "truncate: sequence %d out of range", b);
+  if (new_len < 0 || new_len > ctx->precise[b]) return fail(ctx, EASYSPEC_EINVAL, "truncate: length %d outside 0..%d", new_len, ctx->precise[b]);
+  ctx->precise[b] = new_len;
+  ctx->fuzzy[b] = 0;
+  return EASYSPEC_OK;
+}
+
+static int kv_xfer(easyspec_ctx* ctx, int32_t b, void* k, void* v, int32_t n, int to_cache) {
+  const Shape& s = ctx->s;
+  const size_t bytes = (size_t)s.L * s.Hkv * n * s.hd * esize(s);
+  if (bytes == 0) return EASYSPEC_OK;
+  void *dk = nullptr, *dv = nullptr;
+  HIPCHK(ctx, hipMalloc(&dk, bytes));
+  if (hipMalloc(&dv, bytes) != hipSuccess) {
+    (void)hipFree(dk);
+    return fail(ctx, EASYSPEC_EHIP, "kv transfer: out of device memory");
+  }
+  auto body = [&]() -> int {
+    hipStream_t st = ctx->stream;
+    if (to_cache) {
+      HIPCHK(ctx, hipMemcpyAsync(dk, k, bytes, hipMemcpyDefault, st));
+      HIPCHK(ctx, hipMemcpyAsync(dv, v, bytes, hipMemcpyDefault, st));
+    }
+    launch_kv_copy(s, ctx->b, b, dk, dv, n, to_cache, st);
+    HIPCHK(ctx, hipGetLastError());
+    if (!to_cache) {
+      HIPCHK(ctx, hipMemcpyAsync(k, dk, bytes, hipMemcpyDefault, st));
+      HIPCHK(ctx, hipMemcpyAsync(v, dv, bytes, hipMemcpyDefault, st));
+    }
+    HIPCHK(ctx, hipStreamSynchronize(st));
+    return EASYSPEC_OK;
+  };
+  const int rc = body();
+  (void)hipFree(dk);
+  (void)hipFree(dv);
+  return rc;
+}
+
+extern "C" int easyspec_kv_import(easyspec_ctx* ctx, int32_t b, const void* k, const void* v, int32_t n_slots) {
+  if (!ctx) return fail(nullptr, EASYSPEC_EINVAL, "ctx is NULL");
+  if (b < 0 || b >= ctx->s.B) return fail(ctx, EASYSPEC_EINVAL, "kv_import: sequence %d out of range", b);
+  if (n_slots < 0 || n_slots > ctx->s.max_ctx) return fail(ctx, EASYSPEC_ECAPACITY, "kv_import: %d slots exceed max_ctx %d", n_slots, ctx->s.max_ctx);
+  if (n_slots > 0 && (!k || !v)) return fail(ctx, EASYSPEC_EINVAL, "kv_import: NULL argument");
+  const int rc = kv_xfer(ctx, b, const_cast<void*>(k), const_cast<void*>(v), n_slots, 1);
+  if (rc != EASYSPEC_OK) return rc;
+  ctx->precise[b] = n_slots;
+  ctx->fuzzy[b] = 0;
+  return EASYSPEC_OK;
+}
+
+extern "C" int easyspec_kv_export(easyspec_ctx* ctx, int32_t b, void* k, void* v, int32_t n_slots) {
+  if (!ctx) return fail(nullptr, EASYSPEC_EINVAL, "ctx is NULL");
+  if (b < 0 || b >= ctx->s.B) return fail(ctx, EASYSPEC_EINVAL, "kv_export: sequence %d out of range", b);
+  if (n_slots < 0 || n_slots > ctx->s.max_ctx) return fail(ctx, EASYSPEC_ECAPACITY, "kv_export: %d slots exceed max_ctx %d", n_slots, ctx->s.max_ctx);
+  if (n_slots > 0 && (!k || !v)) return fail(ctx, EASYSPEC_EINVAL, "kv_export: NULL argument");
+  return kv_xfer(ctx, b, k, v, n_slots, 0);
+}
+
+extern "C" int easyspec_get_hidden(easyspec_ctx* ctx, float* out, int32_t max_rows, int32_t* n_rows) {
+  if (!ctx) return fail(nullptr, EASYSPEC_EINVAL, "ctx is NULL");
+  if (!out || !n_rows) return fail(ctx, EASYSPEC_EINVAL, "get_hidden: NULL argument");
+  if (ctx->last_rows == 0) return fail(ctx, EASYSPEC_ESTATE, "get_hidden: no forward has run");
+  if (max_rows < ctx->last_rows) return fail(ctx, EASYSPEC_ECAPACITY, "get_hidden: %d rows needed", ctx->last_rows);
+  HIPCHK(ctx, hipMemcpyAsync(out, ctx->b.H, (size_t)ctx->last_rows * ctx->s.d * sizeof(float), hipMemcpyDeviceToDevice, ctx->stream));
+  *n_rows = ctx->last_rows;
+  return EASYSPEC_OK;
+}
+
+extern "C" int64_t easyspec_step_bytes(const easyspec_ctx* ctx) {
+  if (!ctx) return 0;
+  const Shape& s = ctx->s;
+  const int64_t e = (int64_t)esize(s);
+  const int64_t per_layer = ((int64_t)s.RQKV * s.d + (int64_t)s.d * s.HQ + 3ll * s.F * s.d) * e;
+  int64_t bytes = per_layer * s.L + (int64_t)s.V * s.d * e;
+  for (int b = 0; b < s.B; ++b)
+    if (ctx->precise[b] > 0) bytes += (int64_t)(ctx->precise[b] + ctx->fuzzy[b] + 1) * s.L * 2 * s.Hkv * s.hd * e;
+  return bytes;
+}

@@ -1,0 +1,80 @@
+// Internal interface between the host state machine (easyspec.cpp) and the gfx950 kernels
+// (kernels.hip).  Plain structs and launch functions; no device code in this header.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace es {
+
+constexpr int kMaxCols = 16;  // token columns of one forward pass (= one MFMA N tile)
+constexpr int kMaxChunks = 64;  // split-KV chunks per (column, head)
+
+// Which (sequence, position, token) each column of a forward pass stands for.
+struct Cols {
+  int32_t n;
+  int32_t seq[kMaxCols];
+  int32_t pos[kMaxCols];        // slot the column writes; it attends to slots 0..pos
+  int32_t tok_idx[kMaxCols];    // index into the caller's token array
+  int32_t logit_row[kMaxCols];  // row of logits_out to write, or -1
+  int32_t out_idx[kMaxCols];    // index of tokens_out to write, or -1
+};
+
+struct Shape {
+  int32_t dtype;  // 0 fp32, 1 bf16
+  int32_t L, d, Hq, Hkv, hd, F, V;
+  int32_t HQ;     // Hq*hd
+  int32_t RQKV;   // (Hq + 2 Hkv) * hd
+  int32_t B, max_ctx;
+  float eps;
+  int32_t has_bias;
+};
+
+// Device buffers of a context.  "T" = storage dtype.  Packed matrices are arrays of 1 KB tiles
+// (16 rows x 16 bytes per lane-group, see kernels.hip) ordered [layer][row tile][k tile].
+struct Buffers {
+  // weights
+  void *wqkv, *wo, *wg, *wu, *wd, *wlm;  // packed tiles
+  void *embed;                           // plain [V][d] T
+  float *bqkv;                           // [L][RQKV] or null
+  float *g_attn, *g_mlp, *g_final;       // [L][d], [L][d], [d]
+  float2 *rope;                          // [max_ctx][hd/2] (cos, sin)
+  // cache
+  void *kc, *vc;  // [L][B][Hkv][max_ctx][hd] T
+  // workspaces (per forward pass; column-major activations [.][kMaxCols][width])
+  float *H;     // [16][d]      residual stream
+  float *ssp;   // [16][d/16]   per-row-tile partial sums of squares of the vector to be normed next
+  void *XA;     // [MAX_SET][16][d] T   H * g_attn(layer) for the layers of the coming set (or g_final)
+  void *XM;     // [16][d] T            H' * g_mlp(layer)
+  float *Q;     // [MAX_SET][16][HQ]    rotated queries
+  void *AO;     // [MAX_SET][16][HQ] T  attention output (rounded to T)
+  float *A;     // [MAX_SET][16][d]     Attnoutput_i
+  void *ACT;    // [16][F] T            SiLU(gate)*up
+  float *PO;    // [MAX_SET*16*Hq][kMaxChunks][hd]  split-KV partial outputs
+  float *PM, *PL;  // [MAX_SET*16*Hq][kMaxChunks]   partial max / sum
+  float *amax_val; // [16][n_head_blocks]
+  int32_t *amax_idx;
+};
+
+// Launch wrappers (all asynchronous on `st`).
+void launch_repack(int dtype, const void* src, void* dst, int rows, int K, hipStream_t st);
+void launch_embed(const Shape& s, const Buffers& b, const Cols& c, const int32_t* tokens, int layer0, int n_set,
+                  hipStream_t st);
+void launch_qkv(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st);
+void launch_attn(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, int chunk, int n_chunks,
+                 hipStream_t st);
+// O projection of the set's layers; the first layer's result goes straight into the residual.
+void launch_oproj(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st);
+void launch_gateup(const Shape& s, const Buffers& b, const Cols& c, int layer, hipStream_t st);
+// Down projection + residual.  a_next: Attnoutput of the next layer of the same set to add, or
+// -1.  The normed-input vectors for what comes next are written with gains
+// gain[0..n_gain) (stride d) into xout (stride 16*d elements of T).
+void launch_down(const Shape& s, const Buffers& b, const Cols& c, int layer, int a_next, const float* gain,
+                 int n_gain, void* xout, hipStream_t st);
+void launch_head(const Shape& s, const Buffers& b, const Cols& c, float* logits_out, int32_t* tokens_out,
+                 hipStream_t st);
+void launch_accept(const int32_t* draft, const int32_t* target, int batch, int gamma, int32_t* accept_len,
+                   int32_t* bonus, hipStream_t st);
+void launch_kv_copy(const Shape& s, const Buffers& b, int seq, void* k_user, void* v_user, int n_slots,
+                    int to_cache, hipStream_t st);
+
+}  // namespace es

@@ -1,0 +1,860 @@
+// gfx950 (CDNA4, wave64) kernels of the EasySpec draft hot path.
+//
+// Every weight contraction of the model is the same shape of work: a matrix that is far larger
+// than any cache is streamed from HBM exactly once and multiplied with at most 16 token
+// columns (1 per live sequence in a fuzzy draft step, paper Alg. 2; the accepted tokens plus
+// the bonus token in calibration, paper Sec. 3.2).  All of them therefore share one core:
+//
+//   * Weights are repacked at load time into 1 KB tiles of 16 rows x KT columns (KT = 32 bf16
+//     or 16 fp32).  Inside a tile, lane l of a wavefront owns 16 contiguous bytes: row l%16,
+//     columns (l/16)*EPL .. +EPL-1.  That is exactly the A-operand register layout of the
+//     16x16 MFMA instructions, so one fully coalesced 1 KB wave load feeds one MFMA with no
+//     shuffling, and a row tile's K sweep is one contiguous ascending address stream.
+//   * The token columns are the MFMA's N dimension (B operand, 16 bytes per lane read from a
+//     small L2-resident activation array, only lanes of live columns load).
+//   * The waves of a workgroup split K between them (interleaved, so the workgroup reads
+//     consecutive KBs), partial accumulators are summed through LDS in a fixed order, and wave
+//     0 runs the epilogue that the operation needs (bias + rotary + cache write, residual
+//     update + next norm input, SiLU*up, logits + argmax).
+//
+// RMSNorm is split so that no kernel has to normalise before it can start streaming: the
+// producer of a residual vector h writes T(h * gain) for the consumer's gain and the partial
+// sums of squares of h per 16-row tile; the consumer multiplies its accumulators by
+// rsqrt(mean(h^2) + eps).  Both sides of the parity tests use this order of roundings.
+#include "kernels.h"
+
+namespace es {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+struct bf16_t {
+  uint16_t bits;
+};
+
+template <typename T>
+struct Tr;
+template <>
+struct Tr<float> {
+  static constexpr int EPL = 4, KT = 16;
+};
+template <>
+struct Tr<bf16_t> {
+  static constexpr int EPL = 8, KT = 32;
+};
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
+__device__ __forceinline__ uint32_t float_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);  // round to nearest, ties to even
+  return u >> 16;
+}
+
+template <typename T>
+__device__ __forceinline__ float load1(const T* p);
+template <>
+__device__ __forceinline__ float load1<float>(const float* p) {
+  return *p;
+}
+template <>
+__device__ __forceinline__ float load1<bf16_t>(const bf16_t* p) {
+  return bf16_bits_to_float(p->bits);
+}
+
+template <typename T>
+__device__ __forceinline__ void store1(T* p, float v);
+template <>
+__device__ __forceinline__ void store1<float>(float* p, float v) {
+  *p = v;
+}
+template <>
+__device__ __forceinline__ void store1<bf16_t>(bf16_t* p, float v) {
+  p->bits = (uint16_t)float_to_bf16_bits(v);
+}
+
+// four consecutive elements, p aligned to 4 elements
+template <typename T>
+__device__ __forceinline__ void store4(T* p, float a, float b, float c, float d);
+template <>
+__device__ __forceinline__ void store4<float>(float* p, float a, float b, float c, float d) {
+  f32x4 v = {a, b, c, d};
+  *reinterpret_cast<f32x4*>(p) = v;
+}
+template <>
+__device__ __forceinline__ void store4<bf16_t>(bf16_t* p, float a, float b, float c, float d) {
+  u32x2 v = {float_to_bf16_bits(a) | (float_to_bf16_bits(b) << 16), float_to_bf16_bits(c) | (float_to_bf16_bits(d) << 16)};
+  *reinterpret_cast<u32x2*>(p) = v;
+}
+
+// unpack the EPL elements of one 16-byte fragment
+template <typename T>
+__device__ __forceinline__ void unpack(const u32x4& r, float (&out)[Tr<T>::EPL]);
+template <>
+__device__ __forceinline__ void unpack<float>(const u32x4& r, float (&out)[4]) {
+  out[0] = __uint_as_float(r.x); out[1] = __uint_as_float(r.y); out[2] = __uint_as_float(r.z); out[3] = __uint_as_float(r.w);
+}
+template <>
+__device__ __forceinline__ void unpack<bf16_t>(const u32x4& r, float (&out)[8]) {
+  out[0] = __uint_as_float(r.x << 16); out[1] = __uint_as_float(r.x & 0xFFFF0000u);
+  out[2] = __uint_as_float(r.y << 16); out[3] = __uint_as_float(r.y & 0xFFFF0000u);
+  out[4] = __uint_as_float(r.z << 16); out[5] = __uint_as_float(r.z & 0xFFFF0000u);
+  out[6] = __uint_as_float(r.w << 16); out[7] = __uint_as_float(r.w & 0xFFFF0000u);
+}
+
+// One k-tile of multiply-accumulate: acc[16 rows x 16 cols] += A[16 x KT] * B[KT x 16].
+template <typename T>
+__device__ __forceinline__ void mma(f32x4& acc, const u32x4& a, const u32x4& b);
+template <>
+__device__ __forceinline__ void mma<bf16_t>(f32x4& acc, const u32x4& a, const u32x4& b) {
+  acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+}
+template <>
+__device__ __forceinline__ void mma<float>(f32x4& acc, const u32x4& a, const u32x4& b) {
+  // four K=4 steps; step e contracts element e of every lane's fragment (same k on both sides)
+  acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+}
+
+// ------------------------------------------------------------------------------------------
+// The shared core.  w[r]: first tile of row tile r (tiles of one row tile are consecutive,
+// 64 u32x4 each).  x: activations [col][K] in T.  The calling wave accumulates k-tiles
+// wave, wave+NW, ... into acc.
+// ------------------------------------------------------------------------------------------
+template <typename T, int RT>
+__device__ __forceinline__ void gemm_accumulate(const u32x4* const (&w)[RT], const T* __restrict__ x, int K, int ncols,
+                                                f32x4 (&acc)[RT]) {
+  constexpr int EPL = Tr<T>::EPL, KT = Tr<T>::KT;
+  constexpr int U = 8 / RT;  // k-tiles in flight per wave (8 KB of weights)
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, NW = blockDim.x >> 6;
+  const int col = lane & 15, kg = lane >> 4;
+  const int nkt = K / KT;
+  const bool colok = col < ncols;
+  const u32x4* xp = reinterpret_cast<const u32x4*>(x + (size_t)(colok ? col : 0) * K + kg * EPL);
+  const u32x4* wp[RT];
+#pragma unroll
+  for (int r = 0; r < RT; ++r) wp[r] = w[r] + lane;
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  int kt = wave;
+  for (; kt + (U - 1) * NW < nkt; kt += U * NW) {
+    u32x4 a[RT][U], b[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int r = 0; r < RT; ++r) a[r][u] = __builtin_nontemporal_load(wp[r] + (size_t)(kt + u * NW) * 64);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) b[u] = colok ? xp[(size_t)(kt + u * NW) * 4] : zero;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int r = 0; r < RT; ++r) mma<T>(acc[r], a[r][u], b[u]);
+    }
+  }
+  for (; kt < nkt; kt += NW) {
+    u32x4 b = colok ? xp[(size_t)kt * 4] : zero;
+#pragma unroll
+    for (int r = 0; r < RT; ++r) {
+      u32x4 a = __builtin_nontemporal_load(wp[r] + (size_t)kt * 64);
+      mma<T>(acc[r], a, b);
+    }
+  }
+}
+
+// Sum the waves' partial accumulators through LDS in wave order; true for the wave that holds
+// the total (wave 0).  red: (NW-1)*RT*64 f32x4.
+template <int RT>
+__device__ __forceinline__ bool reduce_waves(f32x4 (&acc)[RT], f32x4* red) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, NW = blockDim.x >> 6;
+  if (NW == 1) return true;
+  if (wave > 0) {
+#pragma unroll
+    for (int r = 0; r < RT; ++r) red[((wave - 1) * RT + r) * 64 + lane] = acc[r];
+  }
+  __syncthreads();
+  if (wave == 0) {
+    for (int w = 1; w < NW; ++w) {
+#pragma unroll
+      for (int r = 0; r < RT; ++r) acc[r] += red[((w - 1) * RT + r) * 64 + lane];
+    }
+  }
+  return wave == 0;
+}
+
+// rstd[col] = rsqrt(sum_t ssp[col][t] / d + eps), summed in a fixed order.  Ends with a barrier.
+__device__ __forceinline__ void compute_rstd(const float* __restrict__ ssp, int ntile, int ncols, float inv_d, float eps,
+                                             float* s_rstd) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, NW = blockDim.x >> 6;
+  for (int col = wave; col < ncols; col += NW) {
+    float s = 0.f;
+    for (int t = lane; t < ntile; t += 64) s += ssp[col * ntile + t];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    if (lane == 0) s_rstd[col] = 1.0f / sqrtf(s * inv_d + eps);
+  }
+  __syncthreads();
+}
+
+extern __shared__ f32x4 dyn_red[];
+
+// ------------------------------------------------------------------------------------------
+// QKV projection of the k layers of a set + bias + rotary + KV-cache write.
+// Unit of work: two row tiles of one head, rows e and e + hd/2, so that the rotation pairs
+// sit in the same lane.  grid = k * (Hq + 2 Hkv) * (hd/32).
+// ------------------------------------------------------------------------------------------
+struct QkvArgs {
+  const u32x4* w;  // layer layer0
+  size_t w_layer_stride;
+  const void* x;  // XA [k][16][d]
+  const float* ssp;
+  const float* bias;  // layer layer0, or null
+  const float2* rope;
+  float* q;
+  void* kc;
+  void* vc;
+  int layer0, d, Hq, Hkv, hd, B, max_ctx;
+  float inv_d, eps;
+};
+
+template <typename T>
+__global__ __launch_bounds__(1024) void qkv_kernel(QkvArgs a, Cols c) {
+  __shared__ float s_rstd[kMaxCols];
+  const int KT = Tr<T>::KT;
+  const int nkt = a.d / KT;
+  const int pairs = a.hd / 32;
+  const int units = (a.Hq + 2 * a.Hkv) * pairs;
+  const int li = blockIdx.x / units, u = blockIdx.x % units;
+  const int head = u / pairs, p = u % pairs;
+  const int rt0 = head * (a.hd / 16) + p, rt1 = rt0 + pairs;
+  const u32x4* wl = a.w + (size_t)li * a.w_layer_stride;
+  const u32x4* const w[2] = {wl + (size_t)rt0 * nkt * 64, wl + (size_t)rt1 * nkt * 64};
+  const T* x = reinterpret_cast<const T*>(a.x) + (size_t)li * kMaxCols * a.d;
+  f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+  gemm_accumulate<T, 2>(w, x, a.d, c.n, acc);
+  compute_rstd(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, s_rstd);
+  if (!reduce_waves<2>(acc, dyn_red)) return;
+
+  const int lane = threadIdx.x & 63, col = lane & 15;
+  if (col >= c.n) return;
+  const float r = s_rstd[col];
+  const int pos = c.pos[col], seq = c.seq[col];
+  const int e0 = p * 16 + (lane >> 4) * 4;  // element inside the head, < hd/2
+  const int half = a.hd / 2;
+  const int RQKV = (a.Hq + 2 * a.Hkv) * a.hd;
+  float lo[4], hi[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    float v0 = acc[0][i] * r, v1 = acc[1][i] * r;
+    if (a.bias) {
+      v0 += a.bias[(size_t)li * RQKV + head * a.hd + e0 + i];
+      v1 += a.bias[(size_t)li * RQKV + head * a.hd + e0 + i + half];
+    }
+    if (head < a.Hq + a.Hkv) {
+      const float2 cs = a.rope[(size_t)pos * half + e0 + i];
+      lo[i] = v0 * cs.x - v1 * cs.y;
+      hi[i] = v1 * cs.x + v0 * cs.y;
+    } else {
+      lo[i] = v0;
+      hi[i] = v1;
+    }
+  }
+  if (head < a.Hq) {
+    float* q = a.q + ((size_t)li * kMaxCols + col) * (a.Hq * a.hd) + head * a.hd + e0;
+    store4<float>(q, lo[0], lo[1], lo[2], lo[3]);
+    store4<float>(q + half, hi[0], hi[1], hi[2], hi[3]);
+  } else {
+    const bool is_k = head < a.Hq + a.Hkv;
+    const int kvh = is_k ? head - a.Hq : head - a.Hq - a.Hkv;
+    T* base = reinterpret_cast<T*>(is_k ? a.kc : a.vc);
+    T* row = base + ((((size_t)(a.layer0 + li) * a.B + seq) * a.Hkv + kvh) * a.max_ctx + pos) * a.hd + e0;
+    store4<T>(row, lo[0], lo[1], lo[2], lo[3]);
+    store4<T>(row + half, hi[0], hi[1], hi[2], hi[3]);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Projection back into the residual stream: the O projections of a set's layers in one
+// launch (k > 1), or one down projection (k = 1).  Layer 0 of the launch updates the
+// residual: h = H + acc (+ Attnoutput of the next layer), writes H, the sum of squares of h
+// and T(h * gain_j) for the consumer(s) that come next; the other layers only store their
+// Attnoutput for later.  grid = k * d/16.
+// ------------------------------------------------------------------------------------------
+struct ProjArgs {
+  const u32x4* w;
+  size_t w_layer_stride;
+  const void* x;  // [k][16][K] T
+  int K, d;
+  float* H;
+  float* A;      // [MAX_SET][16][d]
+  int a_add;     // slot of A to add to the residual after acc, or -1
+  const float* gain;
+  int n_gain;
+  void* xout;    // [n_gain][16][d] T
+  float* ssp;
+};
+
+template <typename T>
+__global__ __launch_bounds__(1024) void proj_resid_kernel(ProjArgs a, Cols c) {
+  const int KT = Tr<T>::KT;
+  const int nkt = a.K / KT;
+  const int ntile = a.d / 16;
+  const int li = blockIdx.x / ntile, t = blockIdx.x % ntile;
+  const u32x4* const w[1] = {a.w + (size_t)li * a.w_layer_stride + (size_t)t * nkt * 64};
+  const T* x = reinterpret_cast<const T*>(a.x) + (size_t)li * kMaxCols * a.K;
+  f32x4 acc[1] = {{0.f, 0.f, 0.f, 0.f}};
+  gemm_accumulate<T, 1>(w, x, a.K, c.n, acc);
+  if (!reduce_waves<1>(acc, dyn_red)) return;
+
+  const int lane = threadIdx.x & 63, col = lane & 15;
+  const bool ok = col < c.n;
+  const int r0 = t * 16 + (lane >> 4) * 4;
+  if (li > 0) {
+    if (ok) store4<float>(a.A + ((size_t)li * kMaxCols + col) * a.d + r0, acc[0][0], acc[0][1], acc[0][2], acc[0][3]);
+    return;
+  }
+  float ss = 0.f;
+  if (ok) {
+    float* hp = a.H + (size_t)col * a.d + r0;
+    f32x4 h = *reinterpret_cast<const f32x4*>(hp);
+    h += acc[0];
+    if (a.a_add >= 0) h += *reinterpret_cast<const f32x4*>(a.A + ((size_t)a.a_add * kMaxCols + col) * a.d + r0);
+    *reinterpret_cast<f32x4*>(hp) = h;
+    for (int j = 0; j < a.n_gain; ++j) {
+      const f32x4 g = *reinterpret_cast<const f32x4*>(a.gain + (size_t)j * a.d + r0);
+      T* xo = reinterpret_cast<T*>(a.xout) + ((size_t)j * kMaxCols + col) * a.d + r0;
+      store4<T>(xo, h[0] * g[0], h[1] * g[1], h[2] * g[2], h[3] * g[3]);
+    }
+    ss = h[0] * h[0] + h[1] * h[1] + h[2] * h[2] + h[3] * h[3];
+  }
+  ss += __shfl_xor(ss, 16, 64);
+  ss += __shfl_xor(ss, 32, 64);
+  if (ok && lane < 16) a.ssp[col * ntile + t] = ss;
+}
+
+// ------------------------------------------------------------------------------------------
+// Gate and up projections + SiLU(gate) * up.  grid = F/16.
+// ------------------------------------------------------------------------------------------
+struct GateUpArgs {
+  const u32x4* wg;
+  const u32x4* wu;
+  const void* x;  // XM [16][d]
+  const float* ssp;
+  void* act;  // [16][F] T
+  int d, F;
+  float inv_d, eps;
+};
+
+template <typename T>
+__global__ __launch_bounds__(1024) void gateup_kernel(GateUpArgs a, Cols c) {
+  __shared__ float s_rstd[kMaxCols];
+  const int nkt = a.d / Tr<T>::KT;
+  const int t = blockIdx.x;
+  const u32x4* const w[2] = {a.wg + (size_t)t * nkt * 64, a.wu + (size_t)t * nkt * 64};
+  f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+  gemm_accumulate<T, 2>(w, reinterpret_cast<const T*>(a.x), a.d, c.n, acc);
+  compute_rstd(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, s_rstd);
+  if (!reduce_waves<2>(acc, dyn_red)) return;
+  const int lane = threadIdx.x & 63, col = lane & 15;
+  if (col >= c.n) return;
+  const float r = s_rstd[col];
+  float o[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float g = acc[0][i] * r, u = acc[1][i] * r;
+    o[i] = (g / (1.0f + expf(-g))) * u;
+  }
+  T* dst = reinterpret_cast<T*>(a.act) + (size_t)col * a.F + t * 16 + (lane >> 4) * 4;
+  store4<T>(dst, o[0], o[1], o[2], o[3]);
+}
+
+// ------------------------------------------------------------------------------------------
+// LM head: logits + per-workgroup argmax candidates (lowest index wins ties).  grid = ceil(V/16).
+// ------------------------------------------------------------------------------------------
+struct HeadArgs {
+  const u32x4* w;
+  const void* x;  // XA slot 0: T(h * g_final)
+  const float* ssp;
+  float* logits;  // or null
+  float* cand_val;
+  int32_t* cand_idx;
+  int d, V, nblk;
+  float inv_d, eps;
+};
+
+__device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
+
+template <typename T>
+__global__ __launch_bounds__(1024) void head_kernel(HeadArgs a, Cols c) {
+  __shared__ float s_rstd[kMaxCols];
+  const int nkt = a.d / Tr<T>::KT;
+  const int t = blockIdx.x;
+  const u32x4* const w[1] = {a.w + (size_t)t * nkt * 64};
+  f32x4 acc[1] = {{0.f, 0.f, 0.f, 0.f}};
+  gemm_accumulate<T, 1>(w, reinterpret_cast<const T*>(a.x), a.d, c.n, acc);
+  compute_rstd(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, s_rstd);
+  if (!reduce_waves<1>(acc, dyn_red)) return;
+  const int lane = threadIdx.x & 63, col = lane & 15;
+  const bool ok = col < c.n;
+  const float r = ok ? s_rstd[col] : 0.f;
+  const int r0 = t * 16 + (lane >> 4) * 4;
+  float bv = -INFINITY;
+  int bi = 0x7FFFFFFF;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = r0 + i;
+    const float v = acc[0][i] * r;
+    if (ok && row < a.V) {
+      if (a.logits && c.logit_row[col] >= 0) a.logits[(size_t)c.logit_row[col] * a.V + row] = v;
+      if (better(v, row, bv, bi)) { bv = v; bi = row; }
+    }
+  }
+#pragma unroll
+  for (int off = 16; off <= 32; off <<= 1) {
+    const float ov = __shfl_xor(bv, off, 64);
+    const int oi = __shfl_xor(bi, off, 64);
+    if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+  }
+  if (ok && lane < 16) {
+    a.cand_val[(size_t)col * a.nblk + t] = bv;
+    a.cand_idx[(size_t)col * a.nblk + t] = bi;
+  }
+}
+
+__global__ __launch_bounds__(256) void argmax_final_kernel(const float* cand_val, const int32_t* cand_idx, int nblk,
+                                                           int32_t* tokens_out, Cols c) {
+  __shared__ float sv[256];
+  __shared__ int si[256];
+  const int col = blockIdx.x, tid = threadIdx.x;
+  float bv = -INFINITY;
+  int bi = 0x7FFFFFFF;
+  for (int j = tid; j < nblk; j += 256) {
+    const float v = cand_val[(size_t)col * nblk + j];
+    const int i = cand_idx[(size_t)col * nblk + j];
+    if (better(v, i, bv, bi)) { bv = v; bi = i; }
+  }
+  sv[tid] = bv;
+  si[tid] = bi;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (tid < s && better(sv[tid + s], si[tid + s], sv[tid], si[tid])) { sv[tid] = sv[tid + s]; si[tid] = si[tid + s]; }
+    __syncthreads();
+  }
+  if (tid == 0 && c.out_idx[col] >= 0) tokens_out[c.out_idx[col]] = si[0];
+}
+
+// ------------------------------------------------------------------------------------------
+// Embedding gather: H = E[token]; sum of squares; T(H * g_attn) for the layers of the first set.
+// grid = columns.
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ E, const int32_t* __restrict__ tokens,
+                                                    const float* __restrict__ gain, int n_gain, int d, int V, float* H,
+                                                    T* xa, float* ssp, Cols c) {
+  __shared__ float red[4];
+  const int col = blockIdx.x, tid = threadIdx.x;
+  const int tok = min(max(tokens[c.tok_idx[col]], 0), V - 1);  // ids outside the vocabulary are clamped
+  float ss = 0.f;
+  for (int j = tid; j < d; j += 256) {
+    const float h = load1<T>(E + (size_t)tok * d + j);
+    H[(size_t)col * d + j] = h;
+    for (int i = 0; i < n_gain; ++i) store1<T>(xa + ((size_t)i * kMaxCols + col) * d + j, h * gain[(size_t)i * d + j]);
+    ss += h * h;
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+  if ((tid & 63) == 0) red[tid >> 6] = ss;
+  __syncthreads();
+  const int ntile = d / 16;
+  for (int t = tid; t < ntile; t += 256) ssp[col * ntile + t] = (t == 0) ? ((red[0] + red[1]) + (red[2] + red[3])) : 0.f;
+}
+
+// ------------------------------------------------------------------------------------------
+// Decode attention over the KV caches of a set's layers, split along the context.
+// One workgroup = (context chunk, KV head, layer x column); it serves the G query heads that
+// share the KV head.  A K or V row (hd elements) is spread over LPS lanes, 16 bytes each, so a
+// wave load covers 64/LPS consecutive slots (1 KB, coalesced).  Scores of the chunk are kept
+// in LDS, so the softmax inside a chunk needs no rescaling; chunks are merged afterwards.
+// ------------------------------------------------------------------------------------------
+struct AttnArgs {
+  const float* Q;
+  const void* kc;
+  const void* vc;
+  float* PO;
+  float* PM;
+  float* PL;
+  void* AO;
+  int layer0, Hq, Hkv, B, max_ctx, CH;
+  float scale;
+};
+
+extern __shared__ float dyn_f[];
+
+template <typename T, int HD, int G>
+__global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a, Cols c) {
+  constexpr int EPL = Tr<T>::EPL, LPS = HD / EPL, SPW = 64 / LPS, SPB = 4 * SPW;
+  const int chunk = blockIdx.x, kvh = blockIdx.y;
+  const int li = blockIdx.z / c.n, col = blockIdx.z % c.n;
+  const int n_slots = c.pos[col] + 1;
+  const int s0 = chunk * a.CH;
+  if (s0 >= n_slots) return;
+  const int s1 = min(s0 + a.CH, n_slots);
+  const int n = s1 - s0;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int sub = lane / LPS, e0 = (lane % LPS) * EPL;
+
+  float* sc = dyn_f;                   // [G][CH]
+  float* red = dyn_f + G * a.CH;       // [4][G*HD] (reused for [4][G] scalars before that)
+  const size_t rowbase = (((size_t)(a.layer0 + li) * a.B + c.seq[col]) * a.Hkv + kvh) * (size_t)a.max_ctx;
+  const T* kb = reinterpret_cast<const T*>(a.kc) + rowbase * HD + e0;
+  const T* vb = reinterpret_cast<const T*>(a.vc) + rowbase * HD + e0;
+  const int HQ = a.Hq * HD;
+
+  // ---- scores
+  {
+    float q[G][EPL];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const float* qp = a.Q + ((size_t)li * kMaxCols + col) * HQ + (kvh * G + g) * HD + e0;
+#pragma unroll
+      for (int j = 0; j < EPL; ++j) q[g][j] = qp[j];
+    }
+    for (int sb = s0 + wave * SPW; sb < s1; sb += SPB) {
+      const int s = sb + sub;
+      const bool valid = s < s1;
+      float kv[EPL];
+      if (valid) {
+        const u32x4 raw = *reinterpret_cast<const u32x4*>(kb + (size_t)s * HD);
+        unpack<T>(raw, kv);
+      } else {
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) kv[j] = 0.f;
+      }
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float dot = 0.f;
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) dot += q[g][j] * kv[j];
+#pragma unroll
+        for (int off = 1; off < LPS; off <<= 1) dot += __shfl_xor(dot, off, 64);
+        if (valid && (lane % LPS) == 0) sc[g * a.CH + (s - s0)] = dot * a.scale;
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- chunk max, exponentials, chunk sum (per head)
+  float mx[G], sum[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float m = -INFINITY;
+    for (int j = tid; j < n; j += 256) m = fmaxf(m, sc[g * a.CH + j]);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+    if (lane == 0) red[wave * G + g] = m;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int g = 0; g < G; ++g) mx[g] = fmaxf(fmaxf(red[g], red[G + g]), fmaxf(red[2 * G + g], red[3 * G + g]));
+  __syncthreads();
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float s = 0.f;
+    for (int j = tid; j < n; j += 256) {
+      const float p = expf(sc[g * a.CH + j] - mx[g]);
+      sc[g * a.CH + j] = p;
+      s += p;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    if (lane == 0) red[wave * G + g] = s;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int g = 0; g < G; ++g) sum[g] = (red[g] + red[G + g]) + (red[2 * G + g] + red[3 * G + g]);
+  __syncthreads();
+
+  // ---- P * V
+  float acc[G][EPL];
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int j = 0; j < EPL; ++j) acc[g][j] = 0.f;
+  for (int sb = s0 + wave * SPW; sb < s1; sb += SPB) {
+    const int s = sb + sub;
+    if (s < s1) {
+      float v[EPL];
+      const u32x4 raw = *reinterpret_cast<const u32x4*>(vb + (size_t)s * HD);
+      unpack<T>(raw, v);
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float p = sc[g * a.CH + (s - s0)];
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) acc[g][j] += p * v[j];
+      }
+    }
+  }
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int j = 0; j < EPL; ++j) {
+      float v = acc[g][j];
+#pragma unroll
+      for (int off = LPS; off < 64; off <<= 1) v += __shfl_xor(v, off, 64);
+      if (sub == 0) red[(wave * G + g) * HD + e0 + j] = v;
+    }
+  __syncthreads();
+  for (int idx = tid; idx < G * HD; idx += 256) {
+    const int g = idx / HD, e = idx % HD;
+    const float v = (red[(0 * G + g) * HD + e] + red[(1 * G + g) * HD + e]) + (red[(2 * G + g) * HD + e] + red[(3 * G + g) * HD + e]);
+    const size_t row = ((size_t)li * kMaxCols + col) * a.Hq + kvh * G + g;
+    a.PO[(row * kMaxChunks + chunk) * HD + e] = v;
+    if (e == 0) {
+      a.PM[row * kMaxChunks + chunk] = mx[g];
+      a.PL[row * kMaxChunks + chunk] = sum[g];
+    }
+  }
+}
+
+// Merge the chunks of one (layer, column, query head) and round the result to T.
+// grid = (k * columns, Hq), block = hd.
+template <typename T>
+__global__ void attn_merge_kernel(AttnArgs a, Cols c) {
+  const int li = blockIdx.x / c.n, col = blockIdx.x % c.n, head = blockIdx.y, e = threadIdx.x;
+  const int hd = blockDim.x;
+  const int nch = (c.pos[col] + a.CH) / a.CH;  // ceil((pos+1)/CH)
+  const size_t row = ((size_t)li * kMaxCols + col) * a.Hq + head;
+  float m = -INFINITY;
+  for (int ch = 0; ch < nch; ++ch) m = fmaxf(m, a.PM[row * kMaxChunks + ch]);
+  float l = 0.f, o = 0.f;
+  for (int ch = 0; ch < nch; ++ch) {
+    const float wgt = expf(a.PM[row * kMaxChunks + ch] - m);
+    l += a.PL[row * kMaxChunks + ch] * wgt;
+    o += a.PO[(row * kMaxChunks + ch) * hd + e] * wgt;
+  }
+  store1<T>(reinterpret_cast<T*>(a.AO) + ((size_t)li * kMaxCols + col) * (a.Hq * hd) + head * hd + e, o / l);
+}
+
+// ------------------------------------------------------------------------------------------
+// Small utilities.
+// ------------------------------------------------------------------------------------------
+
+// Row-major [rows][K] -> 1 KB tiles; rows padded with zeros up to a multiple of 16.
+template <typename T>
+__global__ void repack_kernel(const T* __restrict__ src, u32x4* __restrict__ dst, int rows, int K, size_t n_frag) {
+  constexpr int EPL = Tr<T>::EPL, KT = Tr<T>::KT;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_frag) return;
+  const int nkt = K / KT;
+  const int lane = (int)(i & 63);
+  const size_t tile = i >> 6;
+  const int kt = (int)(tile % nkt);
+  const size_t rt = tile / nkt;
+  const size_t row = rt * 16 + (lane & 15);
+  u32x4 v = {0u, 0u, 0u, 0u};
+  if (row < (size_t)rows) v = *reinterpret_cast<const u32x4*>(src + row * K + (size_t)kt * KT + (lane >> 4) * EPL);
+  dst[i] = v;
+}
+
+__global__ void accept_kernel(const int32_t* draft, const int32_t* target, int batch, int gamma, int32_t* accept_len,
+                              int32_t* bonus) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= batch) return;
+  int m = 0;
+  while (m < gamma && draft[b * gamma + m] == target[b * (gamma + 1) + m]) ++m;
+  accept_len[b] = m;
+  bonus[b] = target[b * (gamma + 1) + m];
+}
+
+// user [L][Hkv][n][hd] <-> cache [L][B][Hkv][max_ctx][hd], 16-byte fragments
+__global__ void kv_copy_kernel(u32x4* cache, u32x4* user, int L, int B, int Hkv, int max_ctx, int n, int frag_per_row,
+                               int seq, int to_cache) {
+  const size_t total = (size_t)L * Hkv * n * frag_per_row;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int f = (int)(i % frag_per_row);
+  size_t r = i / frag_per_row;
+  const int s = (int)(r % n);
+  r /= n;
+  const int h = (int)(r % Hkv);
+  const int l = (int)(r / Hkv);
+  const size_t ci = ((((size_t)l * B + seq) * Hkv + h) * max_ctx + s) * frag_per_row + f;
+  if (to_cache) cache[ci] = user[i];
+  else user[i] = cache[ci];
+}
+
+// ------------------------------------------------------------------------------------------
+// Launch wrappers
+// ------------------------------------------------------------------------------------------
+
+static int env_int(const char* name, int dflt) {
+  const char* v = getenv(name);
+  return v ? atoi(v) : dflt;
+}
+
+// Waves per workgroup: enough workgroup-waves to cover the chip several times over, but every
+// wave keeps at least 8 k-tiles of work.
+static int pick_waves(int n_blocks, int nkt, const char* env) {
+  static const int target = env_int("EASYSPEC_TARGET_WAVES", 4096);
+  int forced = env_int(env, 0);
+  int nw = 1;
+  if (forced > 0) nw = forced;
+  else {
+    while (nw < 16 && n_blocks * nw < target) nw *= 2;
+  }
+  while (nw > 1 && nkt / nw < 8) nw /= 2;
+  return nw;
+}
+
+static size_t red_bytes(int nw, int rt) { return (size_t)(nw > 1 ? nw - 1 : 0) * rt * 64 * sizeof(f32x4); }
+
+#define DISPATCH_T(dtype, ...)                    \
+  do {                                            \
+    if ((dtype) == 1) { typedef bf16_t T; __VA_ARGS__; } \
+    else { typedef float T; __VA_ARGS__; }        \
+  } while (0)
+
+static size_t tile_stride(int rows, int K, int dtype) {  // u32x4 per matrix
+  const int kt = dtype == 1 ? 32 : 16;
+  return (size_t)((rows + 15) / 16) * (K / kt) * 64;
+}
+
+void launch_repack(int dtype, const void* src, void* dst, int rows, int K, hipStream_t st) {
+  const size_t n_frag = tile_stride(rows, K, dtype);
+  const unsigned grid = (unsigned)((n_frag + 255) / 256);
+  DISPATCH_T(dtype, hipLaunchKernelGGL(repack_kernel<T>, dim3(grid), dim3(256), 0, st, (const T*)src, (u32x4*)dst, rows, K, n_frag));
+}
+
+void launch_embed(const Shape& s, const Buffers& b, const Cols& c, const int32_t* tokens, int layer0, int n_set,
+                  hipStream_t st) {
+  DISPATCH_T(s.dtype, hipLaunchKernelGGL(embed_kernel<T>, dim3(c.n), dim3(256), 0, st, (const T*)b.embed, tokens,
+                                         b.g_attn + (size_t)layer0 * s.d, n_set, s.d, s.V, b.H, (T*)b.XA, b.ssp, c));
+}
+
+void launch_qkv(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st) {
+  QkvArgs a;
+  const size_t stride = tile_stride(s.RQKV, s.d, s.dtype);
+  a.w = (const u32x4*)b.wqkv + (size_t)layer0 * stride;
+  a.w_layer_stride = stride;
+  a.x = b.XA;
+  a.ssp = b.ssp;
+  a.bias = s.has_bias ? b.bqkv + (size_t)layer0 * s.RQKV : nullptr;
+  a.rope = b.rope;
+  a.q = b.Q;
+  a.kc = b.kc;
+  a.vc = b.vc;
+  a.layer0 = layer0; a.d = s.d; a.Hq = s.Hq; a.Hkv = s.Hkv; a.hd = s.hd; a.B = s.B; a.max_ctx = s.max_ctx;
+  a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
+  const int grid = n_set * (s.Hq + 2 * s.Hkv) * (s.hd / 32);
+  const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
+  const int nw = pick_waves(grid, nkt, "EASYSPEC_NW_QKV");
+  DISPATCH_T(s.dtype, hipLaunchKernelGGL(qkv_kernel<T>, dim3(grid), dim3(64 * nw), red_bytes(nw, 2), st, a, c));
+}
+
+template <typename T, int HD>
+static void launch_attn_g(int G, dim3 grid, size_t lds, hipStream_t st, const AttnArgs& a, const Cols& c) {
+  switch (G) {
+    case 1: hipLaunchKernelGGL((attn_partial_kernel<T, HD, 1>), grid, dim3(256), lds, st, a, c); break;
+    case 2: hipLaunchKernelGGL((attn_partial_kernel<T, HD, 2>), grid, dim3(256), lds, st, a, c); break;
+    case 4: hipLaunchKernelGGL((attn_partial_kernel<T, HD, 4>), grid, dim3(256), lds, st, a, c); break;
+    case 7: hipLaunchKernelGGL((attn_partial_kernel<T, HD, 7>), grid, dim3(256), lds, st, a, c); break;
+    case 8: hipLaunchKernelGGL((attn_partial_kernel<T, HD, 8>), grid, dim3(256), lds, st, a, c); break;
+    default: break;  // rejected at create
+  }
+}
+
+void launch_attn(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, int chunk, int n_chunks,
+                 hipStream_t st) {
+  AttnArgs a;
+  a.Q = b.Q; a.kc = b.kc; a.vc = b.vc; a.PO = b.PO; a.PM = b.PM; a.PL = b.PL; a.AO = b.AO;
+  a.layer0 = layer0; a.Hq = s.Hq; a.Hkv = s.Hkv; a.B = s.B; a.max_ctx = s.max_ctx; a.CH = chunk;
+  a.scale = 1.0f / sqrtf((float)s.hd);
+  const int G = s.Hq / s.Hkv;
+  const dim3 grid(n_chunks, s.Hkv, n_set * c.n);
+  const size_t lds = ((size_t)G * chunk + 4 * (size_t)G * s.hd) * sizeof(float);
+  DISPATCH_T(s.dtype, {
+    if (s.hd == 128) launch_attn_g<T, 128>(G, grid, lds, st, a, c);
+    else launch_attn_g<T, 64>(G, grid, lds, st, a, c);
+  });
+  DISPATCH_T(s.dtype, hipLaunchKernelGGL(attn_merge_kernel<T>, dim3(n_set * c.n, s.Hq), dim3(s.hd), 0, st, a, c));
+}
+
+void launch_oproj(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st) {
+  ProjArgs a;
+  const size_t stride = tile_stride(s.d, s.HQ, s.dtype);
+  a.w = (const u32x4*)b.wo + (size_t)layer0 * stride;
+  a.w_layer_stride = stride;
+  a.x = b.AO;
+  a.K = s.HQ; a.d = s.d;
+  a.H = b.H; a.A = b.A; a.a_add = -1;
+  a.gain = b.g_mlp + (size_t)layer0 * s.d;
+  a.n_gain = 1;
+  a.xout = b.XM;
+  a.ssp = b.ssp;
+  const int grid = n_set * (s.d / 16);
+  const int nkt = s.HQ / (s.dtype == 1 ? 32 : 16);
+  const int nw = pick_waves(grid, nkt, "EASYSPEC_NW_O");
+  DISPATCH_T(s.dtype, hipLaunchKernelGGL(proj_resid_kernel<T>, dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+}
+
+void launch_gateup(const Shape& s, const Buffers& b, const Cols& c, int layer, hipStream_t st) {
+  GateUpArgs a;
+  const size_t stride = tile_stride(s.F, s.d, s.dtype);
+  a.wg = (const u32x4*)b.wg + (size_t)layer * stride;
+  a.wu = (const u32x4*)b.wu + (size_t)layer * stride;
+  a.x = b.XM; a.ssp = b.ssp; a.act = b.ACT; a.d = s.d; a.F = s.F;
+  a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
+  const int grid = s.F / 16;
+  const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
+  const int nw = pick_waves(grid, nkt, "EASYSPEC_NW_GU");
+  DISPATCH_T(s.dtype, hipLaunchKernelGGL(gateup_kernel<T>, dim3(grid), dim3(64 * nw), red_bytes(nw, 2), st, a, c));
+}
+
+void launch_down(const Shape& s, const Buffers& b, const Cols& c, int layer, int a_next, const float* gain, int n_gain,
+                 void* xout, hipStream_t st) {
+  ProjArgs a;
+  const size_t stride = tile_stride(s.d, s.F, s.dtype);
+  a.w = (const u32x4*)b.wd + (size_t)layer * stride;
+  a.w_layer_stride = stride;
+  a.x = b.ACT;
+  a.K = s.F; a.d = s.d;
+  a.H = b.H; a.A = b.A; a.a_add = a_next;
+  a.gain = gain; a.n_gain = n_gain; a.xout = xout; a.ssp = b.ssp;
+  const int grid = s.d / 16;
+  const int nkt = s.F / (s.dtype == 1 ? 32 : 16);
+  const int nw = pick_waves(grid, nkt, "EASYSPEC_NW_DOWN");
+  DISPATCH_T(s.dtype, hipLaunchKernelGGL(proj_resid_kernel<T>, dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+}
+
+void launch_head(const Shape& s, const Buffers& b, const Cols& c, float* logits_out, int32_t* tokens_out, hipStream_t st) {
+  HeadArgs a;
+  a.w = (const u32x4*)b.wlm; a.x = b.XA; a.ssp = b.ssp; a.logits = logits_out;
+  a.cand_val = b.amax_val; a.cand_idx = b.amax_idx;
+  a.d = s.d; a.V = s.V; a.nblk = (s.V + 15) / 16;
+  a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
+  const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
+  const int nw = pick_waves(a.nblk, nkt, "EASYSPEC_NW_HEAD");
+  DISPATCH_T(s.dtype, hipLaunchKernelGGL(head_kernel<T>, dim3(a.nblk), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+  hipLaunchKernelGGL(argmax_final_kernel, dim3(c.n), dim3(256), 0, st, a.cand_val, a.cand_idx, a.nblk, tokens_out, c);
+}
+
+void launch_accept(const int32_t* draft, const int32_t* target, int batch, int gamma, int32_t* accept_len, int32_t* bonus,
+                   hipStream_t st) {
+  hipLaunchKernelGGL(accept_kernel, dim3((batch + 63) / 64), dim3(64), 0, st, draft, target, batch, gamma, accept_len, bonus);
+}
+
+void launch_kv_copy(const Shape& s, const Buffers& b, int seq, void* k_user, void* v_user, int n_slots, int to_cache,
+                    hipStream_t st) {
+  const int fpr = s.hd * (s.dtype == 1 ? 2 : 4) / 16;
+  const size_t total = (size_t)s.L * s.Hkv * n_slots * fpr;
+  if (total == 0) return;
+  const unsigned grid = (unsigned)((total + 255) / 256);
+  hipLaunchKernelGGL(kv_copy_kernel, dim3(grid), dim3(256), 0, st, (u32x4*)b.kc, (u32x4*)k_user, s.L, s.B, s.Hkv, s.max_ctx,
+                     n_slots, fpr, seq, to_cache);
+  hipLaunchKernelGGL(kv_copy_kernel, dim3(grid), dim3(256), 0, st, (u32x4*)b.vc, (u32x4*)v_user, s.L, s.B, s.Hkv, s.max_ctx,
+                     n_slots, fpr, seq, to_cache);
+}
+
+}  // namespace es

@@ -66,6 +66,7 @@ def test_matvec_vs_numpy(oracle):
     x = rng.standard_normal(53)
     b = rng.standard_normal(37).astype(np.float32)
     assert np.allclose(oracle.matvec(w, x, b), w.astype(np.float64) @ x + b, rtol=1e-13, atol=1e-13)
+    assert np.allclose(oracle.matvec(w, x, b, scale=0.37), 0.37 * (w.astype(np.float64) @ x) + b, rtol=1e-13, atol=1e-13)
     wb = synth.f32_to_bf16_bits(w)
     assert np.allclose(oracle.matvec(wb, x), synth.bf16_bits_to_f32(wb).astype(np.float64) @ x, rtol=1e-13, atol=1e-13)
 
