@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Benchmark of the EasySpec draft hot path on one MI355X.
+
+One "step" is one drafting iteration of the three-stage loop: bonus calibration over gamma+1
+tokens (which also yields the first draft token), gamma-1 layer-parallel fuzzy draft steps,
+and greedy acceptance against a synthetic verifier output.  `value` is drafted tokens per
+second over whole iterations (gamma tokens per iteration); the per-call figures the metric
+names (fuzzy draft-step tokens/s, calibration microseconds, each with its share of the HBM
+roofline) are reported in the same JSON line.
+
+Inputs are seeded and synthetic: random-init weights of the named shape, a synthetic KV prefix
+standing in for a prefilled context, uniform random token ids.  Everything is resident in HBM
+before the timed region starts.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="llama3_8b_ctx2048")
+    ap.add_argument("--seed", type=int, default=2025)
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging; makes the result invalid)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=20.0, help="budget of the oracle baseline leg")
+    ap.add_argument("--traffic-kib", type=float, default=None,
+                    help="HBM KiB per launch of the dominant kernel from rocprofv3 --pmc runs (else null)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import easyspec_synth as synth
+    import paper_2502_02493_amd as es
+
+    if not torch.cuda.is_available():
+        print("bench.py: no HIP device visible", file=sys.stderr)
+        sys.exit(3)
+    es.load_library()
+    wl = dict(synth.WORKLOADS[args.workload])
+    if isinstance(wl["context"], tuple):
+        print("bench.py: batched long-context workload is a parity case, not a bench line", file=sys.stderr)
+        sys.exit(2)
+    over = {"n_layers": args.layers} if args.layers else {}
+    cfg = synth.model_shape(wl["model"], **over)
+    gamma, ctx_len, B = wl["gamma"], wl["context"], 1
+    M = gamma + 1
+    policy = es.EASYSPEC_POLICY_ALIGNED if wl["group_policy"] == "aligned" else es.EASYSPEC_POLICY_PACKED
+    bounds = es.easyspec_default_groups(cfg["n_layers"], wl["group_size"], policy)
+    max_ctx = ctx_len + M + gamma + 8
+
+    t0 = time.time()
+    weights = synth.make_weights(cfg, args.seed)
+    kpre, vpre = synth.make_kv_prefix(cfg, args.seed + 1, ctx_len)
+    log(f"[bench] synthetic inputs drawn in {time.time() - t0:.1f}s")
+
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.current_stream().cuda_stream
+    ctx = es.easyspec_create(es.make_config(cfg, B, max_ctx, 16), stream)
+    t0 = time.time()
+    es.easyspec_load_weights(ctx, weights)
+    es.easyspec_set_groups(ctx, bounds)
+    es.easyspec_kv_import(ctx, 0, kpre, vpre, ctx_len)
+    log(f"[bench] weights packed and KV prefix imported in {time.time() - t0:.1f}s")
+
+    calib_tok = torch.from_numpy(synth.make_tokens(args.seed + 2, 16, cfg["vocab"]).reshape(1, 16)).to(dev)
+    n_tok = np.array([M], np.int32)
+    draft = torch.zeros(gamma + 1, dtype=torch.int32, device=dev)      # draft[j] = j-th drafted token
+    target = torch.from_numpy(synth.make_tokens(args.seed + 3, gamma + 1, cfg["vocab"]).reshape(1, gamma + 1)).to(dev)
+    acc = torch.zeros(1, dtype=torch.int32, device=dev)
+    bonus = torch.zeros(1, dtype=torch.int32, device=dev)
+    esz = 4
+    dptr = draft.data_ptr()
+
+    def iteration(ev=None):
+        es.easyspec_truncate(ctx, 0, ctx_len)
+        if ev: ev[0].record()
+        es.easyspec_calibrate(ctx, calib_tok, n_tok, dptr, None, 0)       # first draft token -> draft[0]
+        if ev: ev[1].record()
+        for j in range(1, gamma):
+            es.easyspec_draft_step(ctx, dptr + (j - 1) * esz, dptr + j * esz, None)
+        if ev: ev[2].record()
+        es.easyspec_greedy_accept(dptr, target, 1, gamma, acc, bonus, stream)
+
+    for _ in range(args.warmup):
+        iteration()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        iteration(evs[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    calib_us = 1e3 * float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
+    step_us = 1e3 * float(np.mean([e[1].elapsed_time(e[2]) for e in evs])) / (gamma - 1)
+
+    # algorithmic bytes (weights once + the KV slots read)
+    es.easyspec_truncate(ctx, 0, ctx_len)
+    step_bytes = es.easyspec_step_bytes(ctx)              # one draft step at this context
+    e = 2 if cfg["dtype"] == "bf16" else 4
+    calib_bytes = step_bytes + (M - 1) * cfg["n_layers"] * 2 * cfg["n_kv_heads"] * cfg["head_dim"] * e
+    gu_bytes = 2 * cfg["d_ffn"] * cfg["d_model"] * e
+
+    # dominant kernel (gate/up projection: 2*F*d weights per launch), HIP events around each launch,
+    # same iteration sequence again
+    n_launch = args.steps * gamma * cfg["n_layers"]
+    es.easyspec_profile_begin(ctx, es.EASYSPEC_OP_GATEUP, n_launch)
+    for k in range(args.steps):
+        iteration()
+    n_timed, total_ms = es.easyspec_profile_end(ctx)
+    gu_ms = total_ms / max(n_timed, 1)
+    gu_gbs = gu_bytes / (gu_ms * 1e-3) / 1e9
+    per_op = {}
+    for name, op in (("qkv", es.EASYSPEC_OP_QKV), ("attn", es.EASYSPEC_OP_ATTN), ("oproj", es.EASYSPEC_OP_OPROJ),
+                     ("down", es.EASYSPEC_OP_DOWN), ("head", es.EASYSPEC_OP_HEAD)):
+        es.easyspec_profile_begin(ctx, op, 4096)
+        iteration()
+        n_, ms_ = es.easyspec_profile_end(ctx)
+        per_op[name + "_us_per_iteration"] = round(1e3 * ms_, 1)
+    per_op["gateup_us_per_iteration"] = round(1e3 * gu_ms * gamma * cfg["n_layers"], 1)
+
+    out = {
+        "metric": "draft tokens/sec (whole drafting iteration: calibration + fuzzy steps + accept)",
+        "value": round(gamma * args.steps / wall, 2),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(1e3 * wall / args.steps, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg["dtype"], "data": "synthetic",
+        "config": {"workload": args.workload + ("" if not args.layers else f"_L{args.layers}_INVALID"),
+                   "shape": cfg["name"], "context": ctx_len, "batch": B,
+                   "group_size": wl["group_size"], "sets": [int(x) for x in bounds], "gamma": gamma, "calib_tokens": M},
+        "draft_step": {"us": round(step_us, 1), "tokens_per_s": round(1e6 / step_us, 2), "bytes": int(step_bytes),
+                       "hbm_frac": round(step_bytes / (step_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)},
+        "calibrate": {"us": round(calib_us, 1), "tokens": M, "bytes": int(calib_bytes),
+                      "hbm_frac": round(calib_bytes / (calib_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)},
+        "roofline": {"bound": "hbm", "kernel": "gateup_kernel", "achieved": round(gu_gbs, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(gu_gbs / HBM_PEAK_GBS, 4),
+                     "traffic": None if args.traffic_kib is None else args.traffic_kib * 1024,
+                     "bytes_per_launch": int(gu_bytes), "avg_launch_us": round(1e3 * gu_ms, 2), "launches_timed": n_timed},
+        "kernel_time": per_op,
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"], out["parity_sample"] = cpu_baseline(args, cfg, weights, kpre, vpre, bounds, ctx, ctx_len, dev)
+    print(json.dumps(out), flush=True)
+    es.easyspec_destroy(ctx)
+
+
+def cpu_baseline(args, cfg, weights, kpre, vpre, bounds, ctx, ctx_len, dev):
+    """The oracle, as it stands, on the host cores: fuzzy draft steps at the same context on the
+    same weights and KV prefix; the first step doubles as a full-size parity sample."""
+    import torch
+    import easyspec_synth as synth
+    import paper_2502_02493_amd as es
+    from oracle import easyspec_oracle as eso
+
+    cores = int(os.environ.get("OMP_NUM_THREADS", 0)) or (os.cpu_count() or 1)
+    model = eso.Model(cfg, weights, ctx_len + 64)
+    seq = eso.Sequence(model)
+    seq.import_kv(kpre, vpre)
+    tok = int(synth.make_tokens(args.seed + 4, 1, cfg["vocab"])[0])
+
+    es.easyspec_truncate(ctx, 0, ctx_len)
+    tin = torch.tensor([tok], dtype=torch.int32, device=dev)
+    tout = torch.zeros(1, dtype=torch.int32, device=dev)
+    lg = torch.zeros(1, cfg["vocab"], dtype=torch.float32, device=dev)
+    es.easyspec_draft_step(ctx, tin, tout, lg)
+    torch.cuda.synchronize()
+    got = lg[0].cpu().numpy().astype(np.float64)
+
+    t0 = time.perf_counter()
+    want = seq.fuzzy_step(bounds, tok)
+    n, tk = 1, tok
+    while time.perf_counter() - t0 < args.cpu_seconds and n < 64:
+        tk = eso.argmax(seq.fuzzy_step(bounds, tk))
+        n += 1
+    dt = time.perf_counter() - t0
+    wid, margin = eso.argmax(want, with_margin=True)
+    parity = {"what": "one fuzzy draft step at full size, logits vs oracle",
+              "rel_l2": float(np.linalg.norm(got - want) / np.linalg.norm(want)),
+              "argmax_equal": bool(int(tout.item()) == wid), "oracle_top2_margin_over_std": float(margin / np.std(want))}
+    base = {"value": round(n / dt, 4), "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"{n} fuzzy draft steps (batch 1, context {ctx_len}+) in {dt:.1f}s on the same weights and KV prefix"}
+    return base, parity
+
+
+if __name__ == "__main__":
+    main()

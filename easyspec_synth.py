@@ -62,8 +62,12 @@ def model_shape(name: str, **overrides) -> dict:
 def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
     """float32 -> bf16 bit patterns (uint16), round-to-nearest-even.  Finite inputs only."""
     u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
-    lsb = (u >> np.uint32(16)) & np.uint32(1)
-    return ((u + np.uint32(0x7FFF) + lsb) >> np.uint32(16)).astype(np.uint16)
+    r = u >> np.uint32(16)
+    r &= np.uint32(1)
+    r += np.uint32(0x7FFF)
+    r += u
+    r >>= np.uint32(16)
+    return r.astype(np.uint16)
 
 
 def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
@@ -132,8 +136,7 @@ def make_weights(cfg: dict, seed: int, std: float = 0.02) -> dict:
     d, hq, hkv, hd, f, v = (cfg["d_model"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"],
                             cfg["d_ffn"], cfg["vocab"])
     dt = cfg["dtype"]
-    big = cfg["n_layers"] * d * f > (1 << 26)
-    pool = ThreadPoolExecutor(_n_workers()) if big else None
+    pool = ThreadPoolExecutor(_n_workers()) if max(d * f, v * d) > _CHUNK_ELEMS else None
     try:
         layers = []
         for l in range(cfg["n_layers"]):

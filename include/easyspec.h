@@ -167,6 +167,21 @@ int easyspec_get_hidden(easyspec_ctx *ctx, float *out, int32_t max_rows, int32_t
  * KV slots each live sequence reads.  Pure host arithmetic, for roofline reports. */
 int64_t easyspec_step_bytes(const easyspec_ctx *ctx);
 
+/* Per-kernel timing for roofline reports.  Between profile_begin and profile_end every launch
+ * of the kernel class `op` made by draft steps and calibrations is bracketed by a pair of HIP
+ * events on the context's stream (at most max_launches pairs; later launches run untimed).
+ * profile_end synchronises the stream and returns the number of timed launches and the sum of
+ * their durations in milliseconds.  Not meant to stay on in production: the events add a few
+ * microseconds per launch. */
+#define EASYSPEC_OP_QKV 0    /* stacked QKV projection + rotary + cache write */
+#define EASYSPEC_OP_ATTN 1   /* split-KV decode attention (partial + merge kernels together) */
+#define EASYSPEC_OP_OPROJ 2  /* stacked O projection */
+#define EASYSPEC_OP_GATEUP 3 /* gate/up projection + SiLU*up */
+#define EASYSPEC_OP_DOWN 4   /* down projection + residual */
+#define EASYSPEC_OP_HEAD 5   /* LM head + argmax (both kernels together) */
+int easyspec_profile_begin(easyspec_ctx *ctx, int32_t op, int32_t max_launches);
+int easyspec_profile_end(easyspec_ctx *ctx, int32_t *n_launches, float *total_ms);
+
 /* Message of the last failed call on ctx (ctx == NULL: of the last failed easyspec_create or
  * context-free call on this thread).  Never NULL. */
 const char *easyspec_last_error(const easyspec_ctx *ctx);

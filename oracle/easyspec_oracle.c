@@ -9,8 +9,9 @@
  * caller's arrays (float32, or bf16 bit patterns widened on the fly).  When cfg.bf16 == 1
  * the storage rounding points of a bf16 model apply: the KV cache holds bf16 values, and
  * every vector that enters a weight contraction (gained hidden state, attention output,
- * SiLU(gate)*up) is rounded to bf16 first.  With cfg.bf16 == 0 nothing is rounded except the
- * KV cache, which holds float32.  The paper fixes no precision, so the placement of these
+ * SiLU(gate)*up) is first rounded to the sum of two bf16 numbers, hi = bf16(x) and
+ * lo = bf16(x - hi), i.e. to about 16 significant bits.  With cfg.bf16 == 0 nothing is rounded
+ * except the KV cache, which holds float32.  The paper fixes no precision, so the placement of these
  * roundings is a reading; one of them concerns RMSNorm: the normalised input of a contraction
  * is carried as the vector x*g (rounded) and the scalar rsqrt(mean(x^2)+eps), and the scalar
  * multiplies the contraction's result.  Without rounding this is the same function.
@@ -90,7 +91,15 @@ static double weight_at(const void *w, int bf16, size_t idx) {
   return bf16 ? (double)bf16_bits_to_float(((const uint16_t *)w)[idx]) : (double)((const float *)w)[idx];
 }
 
-static double act_round(const eso_config *c, double x) { return c->bf16 ? eso_bf16_round(x) : x; }
+/* value carried by an activation that enters a contraction: two bf16 terms in a bf16 model */
+double eso_bf16_pair_round(double x) {
+  float xf = (float)x;
+  double hi = eso_bf16_round((double)xf);
+  double lo = eso_bf16_round((double)xf - hi);
+  return hi + lo;
+}
+
+static double act_round(const eso_config *c, double x) { return c->bf16 ? eso_bf16_pair_round(x) : x; }
 static float kv_store(const eso_config *c, double x) { return c->bf16 ? (float)eso_bf16_round(x) : (float)x; }
 
 /* ---------------------------------------------------------------- primitives */

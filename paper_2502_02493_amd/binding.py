@@ -19,7 +19,9 @@ EASYSPEC_MAX_BATCH, EASYSPEC_MAX_CALIB_TOKENS, EASYSPEC_MAX_SET = 16, 16, 8
 EXPORTS = ["easyspec_create", "easyspec_destroy", "easyspec_load_weights", "easyspec_set_groups",
            "easyspec_default_groups", "easyspec_draft_step", "easyspec_calibrate", "easyspec_greedy_accept",
            "easyspec_get_lens", "easyspec_truncate", "easyspec_kv_import", "easyspec_kv_export",
-           "easyspec_get_hidden", "easyspec_step_bytes", "easyspec_last_error"]
+           "easyspec_get_hidden", "easyspec_step_bytes", "easyspec_profile_begin", "easyspec_profile_end",
+           "easyspec_last_error"]
+EASYSPEC_OP_QKV, EASYSPEC_OP_ATTN, EASYSPEC_OP_OPROJ, EASYSPEC_OP_GATEUP, EASYSPEC_OP_DOWN, EASYSPEC_OP_HEAD = range(6)
 
 
 class EasySpecError(RuntimeError):
@@ -71,6 +73,8 @@ def load_library():
         L.easyspec_get_hidden.argtypes = [vp, vp, i32, C.POINTER(i32)]
         L.easyspec_step_bytes.argtypes = [vp]
         L.easyspec_step_bytes.restype = C.c_int64
+        L.easyspec_profile_begin.argtypes = [vp, i32, i32]
+        L.easyspec_profile_end.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_float)]
         L.easyspec_last_error.argtypes = [vp]
         L.easyspec_last_error.restype = C.c_char_p
         _lib = L
@@ -188,6 +192,17 @@ def easyspec_get_hidden(ctx, out, max_rows: int) -> int:
 
 def easyspec_step_bytes(ctx) -> int:
     return int(load_library().easyspec_step_bytes(ctx))
+
+
+def easyspec_profile_begin(ctx, op: int, max_launches: int):
+    _check(load_library().easyspec_profile_begin(ctx, op, max_launches), ctx)
+
+
+def easyspec_profile_end(ctx):
+    """Returns (timed launches, total milliseconds)."""
+    n, ms = C.c_int32(0), C.c_float(0.0)
+    _check(load_library().easyspec_profile_end(ctx, C.byref(n), C.byref(ms)), ctx)
+    return n.value, ms.value
 
 
 def make_config(shape: dict, max_batch: int, max_ctx: int, max_calib_tokens: int) -> easyspec_config:

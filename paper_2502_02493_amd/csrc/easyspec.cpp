@@ -26,6 +26,10 @@ struct easyspec_ctx {
   std::vector<int32_t> single;  // every layer alone (Alg. 1 order)
   std::vector<void*> allocs;
   int32_t last_rows;
+  // per-kernel timing (easyspec_profile_*)
+  int32_t prof_op;
+  size_t prof_used;
+  std::vector<hipEvent_t> prof_ev;  // start/stop pairs
   std::string err;
 };
 
@@ -99,6 +103,8 @@ extern "C" int easyspec_create(const easyspec_config* cfg, void* hip_stream, eas
   ctx->stream = (hipStream_t)hip_stream;
   ctx->weights_loaded = false;
   ctx->last_rows = 0;
+  ctx->prof_op = -1;
+  ctx->prof_used = 0;
   Shape& s = ctx->s;
   s.dtype = cfg->dtype; s.L = cfg->n_layers; s.d = cfg->d_model; s.Hq = cfg->n_q_heads; s.Hkv = cfg->n_kv_heads;
   s.hd = cfg->head_dim; s.F = cfg->d_ffn; s.V = cfg->vocab; s.HQ = s.Hq * s.hd; s.RQKV = (s.Hq + 2 * s.Hkv) * s.hd;
@@ -112,6 +118,7 @@ extern "C" int easyspec_create(const easyspec_config* cfg, void* hip_stream, eas
     Buffers& b = ctx->b;
     memset(&b, 0, sizeof b);
     const size_t es_ = esize(s);
+    const size_t act_ = es_ * (s.dtype == EASYSPEC_DTYPE_BF16 ? 2 : 1);  // bf16 activations: hi and lo arrays
     ALLOC(ctx, b.wqkv, (size_t)s.L * packed_bytes(s, s.RQKV, s.d));
     ALLOC(ctx, b.wo, (size_t)s.L * packed_bytes(s, s.d, s.HQ));
     ALLOC(ctx, b.wg, (size_t)s.L * packed_bytes(s, s.F, s.d));
@@ -129,12 +136,12 @@ extern "C" int easyspec_create(const easyspec_config* cfg, void* hip_stream, eas
     ALLOC(ctx, b.vc, kv_bytes);
     ALLOC(ctx, b.H, (size_t)kMaxCols * s.d * sizeof(float));
     ALLOC(ctx, b.ssp, (size_t)kMaxCols * (s.d / 16) * sizeof(float));
-    ALLOC(ctx, b.XA, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.d * es_);
-    ALLOC(ctx, b.XM, (size_t)kMaxCols * s.d * es_);
+    ALLOC(ctx, b.XA, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.d * act_);
+    ALLOC(ctx, b.XM, (size_t)kMaxCols * s.d * act_);
     ALLOC(ctx, b.Q, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.HQ * sizeof(float));
-    ALLOC(ctx, b.AO, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.HQ * es_);
+    ALLOC(ctx, b.AO, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.HQ * act_);
     ALLOC(ctx, b.A, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.d * sizeof(float));
-    ALLOC(ctx, b.ACT, (size_t)kMaxCols * s.F * es_);
+    ALLOC(ctx, b.ACT, (size_t)kMaxCols * s.F * act_);
     const size_t prow = (size_t)EASYSPEC_MAX_SET * kMaxCols * s.Hq;
     ALLOC(ctx, b.PO, prow * kMaxChunks * s.hd * sizeof(float));
     ALLOC(ctx, b.PM, prow * kMaxChunks * sizeof(float));
@@ -173,6 +180,7 @@ extern "C" int easyspec_create(const easyspec_config* cfg, void* hip_stream, eas
 extern "C" void easyspec_destroy(easyspec_ctx* ctx) {
   if (!ctx) return;
   (void)hipStreamSynchronize(ctx->stream);
+  for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
   for (void* p : ctx->allocs) (void)hipFree(p);
   delete ctx;
 }
@@ -303,6 +311,21 @@ static void pick_chunk(const Shape& s, const Cols& c, int n_set_max, int* chunk,
   *n_chunks = nch(ch);
 }
 
+// Brackets the launches of one kernel class with an event pair while profiling is on.
+struct ProfScope {
+  easyspec_ctx* ctx;
+  bool on;
+  ProfScope(easyspec_ctx* c, int op) : ctx(c), on(c->prof_op == op && c->prof_used + 2 <= c->prof_ev.size()) {
+    if (on) (void)hipEventRecord(ctx->prof_ev[ctx->prof_used], ctx->stream);
+  }
+  ~ProfScope() {
+    if (on) {
+      (void)hipEventRecord(ctx->prof_ev[ctx->prof_used + 1], ctx->stream);
+      ctx->prof_used += 2;
+    }
+  }
+};
+
 static int forward(easyspec_ctx* ctx, const Cols& c, const int32_t* tokens, const std::vector<int32_t>& bounds,
                    float* logits_out, int32_t* tokens_out) {
   const Shape& s = ctx->s;
@@ -315,12 +338,13 @@ static int forward(easyspec_ctx* ctx, const Cols& c, const int32_t* tokens, cons
     int chunk, n_chunks;
     pick_chunk(s, c, k, &chunk, &n_chunks);
     // every attention layer of the set reads the hidden state that enters the set
-    launch_qkv(s, b, c, lo, k, st);
-    launch_attn(s, b, c, lo, k, chunk, n_chunks, st);
-    launch_oproj(s, b, c, lo, k, st);
+    { ProfScope p(ctx, EASYSPEC_OP_QKV); launch_qkv(s, b, c, lo, k, st); }
+    { ProfScope p(ctx, EASYSPEC_OP_ATTN); launch_attn(s, b, c, lo, k, chunk, n_chunks, st); }
+    { ProfScope p(ctx, EASYSPEC_OP_OPROJ); launch_oproj(s, b, c, lo, k, st); }
     // the MLPs run in layer order on the running residual
     for (int i = lo; i < hi; ++i) {
-      launch_gateup(s, b, c, i, st);
+      { ProfScope p(ctx, EASYSPEC_OP_GATEUP); launch_gateup(s, b, c, i, st); }
+      ProfScope p(ctx, EASYSPEC_OP_DOWN);
       if (i + 1 < hi) {
         launch_down(s, b, c, i, i + 1 - lo, b.g_mlp + (size_t)(i + 1) * s.d, 1, b.XM, st);
       } else if (hi < s.L) {
@@ -330,7 +354,7 @@ static int forward(easyspec_ctx* ctx, const Cols& c, const int32_t* tokens, cons
       }
     }
   }
-  launch_head(s, b, c, logits_out, tokens_out, st);
+  { ProfScope p(ctx, EASYSPEC_OP_HEAD); launch_head(s, b, c, logits_out, tokens_out, st); }
   HIPCHK(ctx, hipGetLastError());
   ctx->last_rows = c.n;
   return EASYSPEC_OK;
@@ -504,6 +528,38 @@ extern "C" int easyspec_get_hidden(easyspec_ctx* ctx, float* out, int32_t max_ro
   if (max_rows < ctx->last_rows) return fail(ctx, EASYSPEC_ECAPACITY, "get_hidden: %d rows needed", ctx->last_rows);
   HIPCHK(ctx, hipMemcpyAsync(out, ctx->b.H, (size_t)ctx->last_rows * ctx->s.d * sizeof(float), hipMemcpyDeviceToDevice, ctx->stream));
   *n_rows = ctx->last_rows;
+  return EASYSPEC_OK;
+}
+
+extern "C" int easyspec_profile_begin(easyspec_ctx* ctx, int32_t op, int32_t max_launches) {
+  if (!ctx) return fail(nullptr, EASYSPEC_EINVAL, "ctx is NULL");
+  if (op < EASYSPEC_OP_QKV || op > EASYSPEC_OP_HEAD) return fail(ctx, EASYSPEC_EINVAL, "profile_begin: unknown op %d", op);
+  if (max_launches < 1 || max_launches > (1 << 20)) return fail(ctx, EASYSPEC_EINVAL, "profile_begin: bad max_launches");
+  if (ctx->prof_op >= 0) return fail(ctx, EASYSPEC_ESTATE, "profile_begin: already profiling");
+  while (ctx->prof_ev.size() < (size_t)max_launches * 2) {
+    hipEvent_t e;
+    HIPCHK(ctx, hipEventCreate(&e));
+    ctx->prof_ev.push_back(e);
+  }
+  ctx->prof_used = 0;
+  ctx->prof_op = op;
+  return EASYSPEC_OK;
+}
+
+extern "C" int easyspec_profile_end(easyspec_ctx* ctx, int32_t* n_launches, float* total_ms) {
+  if (!ctx) return fail(nullptr, EASYSPEC_EINVAL, "ctx is NULL");
+  if (!n_launches || !total_ms) return fail(ctx, EASYSPEC_EINVAL, "profile_end: NULL argument");
+  if (ctx->prof_op < 0) return fail(ctx, EASYSPEC_ESTATE, "profile_end: not profiling");
+  ctx->prof_op = -1;
+  HIPCHK(ctx, hipStreamSynchronize(ctx->stream));
+  float sum = 0.f;
+  for (size_t i = 0; i + 1 < ctx->prof_used; i += 2) {
+    float ms = 0.f;
+    HIPCHK(ctx, hipEventElapsedTime(&ms, ctx->prof_ev[i], ctx->prof_ev[i + 1]));
+    sum += ms;
+  }
+  *n_launches = (int32_t)(ctx->prof_used / 2);
+  *total_ms = sum;
   return EASYSPEC_OK;
 }
 

@@ -29,7 +29,8 @@ struct Shape {
   int32_t has_bias;
 };
 
-// Device buffers of a context.  "T" = storage dtype.  Packed matrices are arrays of 1 KB tiles
+// Device buffers of a context.  "T" = storage dtype.  Activation arrays in T hold two parts
+// [hi | lo] per slot when T is bf16 (the value is hi + lo), one part when T is fp32.  Packed matrices are arrays of 1 KB tiles
 // (16 rows x 16 bytes per lane-group, see kernels.hip) ordered [layer][row tile][k tile].
 struct Buffers {
   // weights

@@ -38,11 +38,14 @@ template <typename T>
 struct Tr;
 template <>
 struct Tr<float> {
-  static constexpr int EPL = 4, KT = 16;
+  static constexpr int EPL = 4, KT = 16, PARTS = 1;
 };
+// bf16 activations are carried as two bf16 terms, hi = bf16(x) and lo = bf16(x - hi), stored as
+// two arrays [hi | lo]; the contraction runs one MFMA per term.  MFMA issue slots are idle in
+// this HBM-bound work, so the second term is free and keeps activations at ~16 mantissa bits.
 template <>
 struct Tr<bf16_t> {
-  static constexpr int EPL = 8, KT = 32;
+  static constexpr int EPL = 8, KT = 32, PARTS = 2;
 };
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
@@ -88,6 +91,34 @@ __device__ __forceinline__ void store4<bf16_t>(bf16_t* p, float a, float b, floa
   *reinterpret_cast<u32x2*>(p) = v;
 }
 
+// Activation stores: p points into the "hi" array, the "lo" array starts part elements later.
+template <typename T>
+__device__ __forceinline__ void store_act1(T* p, size_t part, float v);
+template <>
+__device__ __forceinline__ void store_act1<float>(float* p, size_t, float v) {
+  *p = v;
+}
+template <>
+__device__ __forceinline__ void store_act1<bf16_t>(bf16_t* p, size_t part, float v) {
+  const uint32_t hi = float_to_bf16_bits(v);
+  p->bits = (uint16_t)hi;
+  p[part].bits = (uint16_t)float_to_bf16_bits(v - bf16_bits_to_float(hi));
+}
+template <typename T>
+__device__ __forceinline__ void store_act4(T* p, size_t part, float a, float b, float c, float d);
+template <>
+__device__ __forceinline__ void store_act4<float>(float* p, size_t, float a, float b, float c, float d) {
+  store4<float>(p, a, b, c, d);
+}
+template <>
+__device__ __forceinline__ void store_act4<bf16_t>(bf16_t* p, size_t part, float a, float b, float c, float d) {
+  const uint32_t ha = float_to_bf16_bits(a), hb = float_to_bf16_bits(b), hc = float_to_bf16_bits(c), hd = float_to_bf16_bits(d);
+  u32x2 hi = {ha | (hb << 16), hc | (hd << 16)};
+  *reinterpret_cast<u32x2*>(p) = hi;
+  store4<bf16_t>(p + part, a - bf16_bits_to_float(ha), b - bf16_bits_to_float(hb), c - bf16_bits_to_float(hc),
+                 d - bf16_bits_to_float(hd));
+}
+
 // unpack the EPL elements of one 16-byte fragment
 template <typename T>
 __device__ __forceinline__ void unpack(const u32x4& r, float (&out)[Tr<T>::EPL]);
@@ -121,14 +152,15 @@ __device__ __forceinline__ void mma<float>(f32x4& acc, const u32x4& a, const u32
 
 // ------------------------------------------------------------------------------------------
 // The shared core.  w[r]: first tile of row tile r (tiles of one row tile are consecutive,
-// 64 u32x4 each).  x: activations [col][K] in T.  The calling wave accumulates k-tiles
+// 64 u32x4 each).  x: activations [part][col][K] in T.  The calling wave accumulates k-tiles
 // wave, wave+NW, ... into acc.
 // ------------------------------------------------------------------------------------------
 template <typename T, int RT>
 __device__ __forceinline__ void gemm_accumulate(const u32x4* const (&w)[RT], const T* __restrict__ x, int K, int ncols,
                                                 f32x4 (&acc)[RT]) {
-  constexpr int EPL = Tr<T>::EPL, KT = Tr<T>::KT;
+  constexpr int EPL = Tr<T>::EPL, KT = Tr<T>::KT, PARTS = Tr<T>::PARTS;
   constexpr int U = 8 / RT;  // k-tiles in flight per wave (8 KB of weights)
+  const size_t lo = (size_t)kMaxCols * K * sizeof(T) / 16;  // u32x4 between the hi and lo arrays
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, NW = blockDim.x >> 6;
   const int col = lane & 15, kg = lane >> 4;
   const int nkt = K / KT;
@@ -140,26 +172,35 @@ __device__ __forceinline__ void gemm_accumulate(const u32x4* const (&w)[RT], con
   const u32x4 zero = {0u, 0u, 0u, 0u};
   int kt = wave;
   for (; kt + (U - 1) * NW < nkt; kt += U * NW) {
-    u32x4 a[RT][U], b[U];
+    u32x4 a[RT][U], b[PARTS][U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
 #pragma unroll
       for (int r = 0; r < RT; ++r) a[r][u] = __builtin_nontemporal_load(wp[r] + (size_t)(kt + u * NW) * 64);
     }
 #pragma unroll
-    for (int u = 0; u < U; ++u) b[u] = colok ? xp[(size_t)(kt + u * NW) * 4] : zero;
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int q = 0; q < PARTS; ++q) b[q][u] = colok ? xp[(size_t)(kt + u * NW) * 4 + q * lo] : zero;
+    }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
 #pragma unroll
-      for (int r = 0; r < RT; ++r) mma<T>(acc[r], a[r][u], b[u]);
+      for (int r = 0; r < RT; ++r) {
+#pragma unroll
+        for (int q = 0; q < PARTS; ++q) mma<T>(acc[r], a[r][u], b[q][u]);
+      }
     }
   }
   for (; kt < nkt; kt += NW) {
-    u32x4 b = colok ? xp[(size_t)kt * 4] : zero;
+    u32x4 b[PARTS];
+#pragma unroll
+    for (int q = 0; q < PARTS; ++q) b[q] = colok ? xp[(size_t)kt * 4 + q * lo] : zero;
 #pragma unroll
     for (int r = 0; r < RT; ++r) {
       u32x4 a = __builtin_nontemporal_load(wp[r] + (size_t)kt * 64);
-      mma<T>(acc[r], a, b);
+#pragma unroll
+      for (int q = 0; q < PARTS; ++q) mma<T>(acc[r], a, b[q]);
     }
   }
 }
@@ -231,7 +272,7 @@ __global__ __launch_bounds__(1024) void qkv_kernel(QkvArgs a, Cols c) {
   const int rt0 = head * (a.hd / 16) + p, rt1 = rt0 + pairs;
   const u32x4* wl = a.w + (size_t)li * a.w_layer_stride;
   const u32x4* const w[2] = {wl + (size_t)rt0 * nkt * 64, wl + (size_t)rt1 * nkt * 64};
-  const T* x = reinterpret_cast<const T*>(a.x) + (size_t)li * kMaxCols * a.d;
+  const T* x = reinterpret_cast<const T*>(a.x) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.d;
   f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
   gemm_accumulate<T, 2>(w, x, a.d, c.n, acc);
   compute_rstd(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, s_rstd);
@@ -303,7 +344,7 @@ __global__ __launch_bounds__(1024) void proj_resid_kernel(ProjArgs a, Cols c) {
   const int ntile = a.d / 16;
   const int li = blockIdx.x / ntile, t = blockIdx.x % ntile;
   const u32x4* const w[1] = {a.w + (size_t)li * a.w_layer_stride + (size_t)t * nkt * 64};
-  const T* x = reinterpret_cast<const T*>(a.x) + (size_t)li * kMaxCols * a.K;
+  const T* x = reinterpret_cast<const T*>(a.x) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.K;
   f32x4 acc[1] = {{0.f, 0.f, 0.f, 0.f}};
   gemm_accumulate<T, 1>(w, x, a.K, c.n, acc);
   if (!reduce_waves<1>(acc, dyn_red)) return;
@@ -324,8 +365,8 @@ __global__ __launch_bounds__(1024) void proj_resid_kernel(ProjArgs a, Cols c) {
     *reinterpret_cast<f32x4*>(hp) = h;
     for (int j = 0; j < a.n_gain; ++j) {
       const f32x4 g = *reinterpret_cast<const f32x4*>(a.gain + (size_t)j * a.d + r0);
-      T* xo = reinterpret_cast<T*>(a.xout) + ((size_t)j * kMaxCols + col) * a.d + r0;
-      store4<T>(xo, h[0] * g[0], h[1] * g[1], h[2] * g[2], h[3] * g[3]);
+      T* xo = reinterpret_cast<T*>(a.xout) + ((size_t)j * Tr<T>::PARTS * kMaxCols + col) * a.d + r0;
+      store_act4<T>(xo, (size_t)kMaxCols * a.d, h[0] * g[0], h[1] * g[1], h[2] * g[2], h[3] * g[3]);
     }
     ss = h[0] * h[0] + h[1] * h[1] + h[2] * h[2] + h[3] * h[3];
   }
@@ -367,7 +408,7 @@ __global__ __launch_bounds__(1024) void gateup_kernel(GateUpArgs a, Cols c) {
     o[i] = (g / (1.0f + expf(-g))) * u;
   }
   T* dst = reinterpret_cast<T*>(a.act) + (size_t)col * a.F + t * 16 + (lane >> 4) * 4;
-  store4<T>(dst, o[0], o[1], o[2], o[3]);
+  store_act4<T>(dst, (size_t)kMaxCols * a.F, o[0], o[1], o[2], o[3]);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -460,7 +501,8 @@ __global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ E, con
   for (int j = tid; j < d; j += 256) {
     const float h = load1<T>(E + (size_t)tok * d + j);
     H[(size_t)col * d + j] = h;
-    for (int i = 0; i < n_gain; ++i) store1<T>(xa + ((size_t)i * kMaxCols + col) * d + j, h * gain[(size_t)i * d + j]);
+    for (int i = 0; i < n_gain; ++i)
+      store_act1<T>(xa + ((size_t)i * Tr<T>::PARTS * kMaxCols + col) * d + j, (size_t)kMaxCols * d, h * gain[(size_t)i * d + j]);
     ss += h * h;
   }
 #pragma unroll
@@ -634,7 +676,8 @@ __global__ void attn_merge_kernel(AttnArgs a, Cols c) {
     l += a.PL[row * kMaxChunks + ch] * wgt;
     o += a.PO[(row * kMaxChunks + ch) * hd + e] * wgt;
   }
-  store1<T>(reinterpret_cast<T*>(a.AO) + ((size_t)li * kMaxCols + col) * (a.Hq * hd) + head * hd + e, o / l);
+  store_act1<T>(reinterpret_cast<T*>(a.AO) + ((size_t)li * Tr<T>::PARTS * kMaxCols + col) * (a.Hq * hd) + head * hd + e,
+                (size_t)kMaxCols * a.Hq * hd, o / l);
 }
 
 // ------------------------------------------------------------------------------------------
