@@ -247,7 +247,7 @@ static void attn_block(eso_seq *s, int layer, const double *h, int pos, double *
   double *k = (double *)malloc(sizeof(double) * (size_t)nkv * hd);
   double *v = (double *)malloc(sizeof(double) * (size_t)nkv * hd);
   double *o = (double *)malloc(sizeof(double) * (size_t)nq * hd);
-  double *sc = (double *)malloc(sizeof(double) * (size_t)(pos + 1));
+  double *scores = (double *)malloc(sizeof(double) * (size_t)nq * (size_t)(pos + 1));
 
   double rs = eso_rmsnorm_split(h, l->g_attn, d, c->rms_eps, n);
   for (int j = 0; j < d; ++j) n[j] = act_round(c, n[j]);
@@ -264,9 +264,11 @@ static void attn_block(eso_seq *s, int layer, const double *h, int pos, double *
     }
   }
   double scale = 1.0 / sqrt((double)hd);
-  for (int a = 0; a < nq; ++a) {
+#pragma omp parallel for schedule(static)
+  for (int a = 0; a < nq; ++a) { /* heads are independent; each uses its own score row */
     int g = a / grp; /* query head a reads KV head a / (Hq/Hkv) */
     const double *qa = q + (size_t)a * hd;
+    double *sc = scores + (size_t)a * (size_t)(pos + 1);
     for (int t = 0; t <= pos; ++t) {
       const float *kr = kv_row(s, s->K, layer, g, t);
       double dot = 0.0;
@@ -281,7 +283,7 @@ static void attn_block(eso_seq *s, int layer, const double *h, int pos, double *
     }
   }
   eso_matvec(l->wo, c->bf16, NULL, 1.0, d, nq * hd, o, out);
-  free(n); free(q); free(k); free(v); free(o); free(sc);
+  free(n); free(q); free(k); free(v); free(o); free(scores);
 }
 
 /* MLPoutput = MLP_layer(h) */

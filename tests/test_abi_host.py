@@ -1,0 +1,125 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares,
+and its host-side logic (strategy helper, host greedy acceptance, argument checks) is right.
+No kernel is launched here."""
+import itertools
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2502_02493_amd as es
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "easyspec.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(easyspec_[a-z_]+)\s*\(", header))
+    assert declared, "no declarations found"
+    lib = es.load_library()
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"{name} declared in easyspec.h but not exported"
+    assert declared == set(es.EXPORTS), declared ^ set(es.EXPORTS)
+
+
+def test_header_constants_match_binding():
+    header = open(os.path.join(ROOT, "include", "easyspec.h")).read()
+    for name in ("EASYSPEC_OK", "EASYSPEC_EINVAL", "EASYSPEC_ECAPACITY", "EASYSPEC_ESTATE", "EASYSPEC_EHIP",
+                 "EASYSPEC_DTYPE_F32", "EASYSPEC_DTYPE_BF16", "EASYSPEC_POLICY_ALIGNED", "EASYSPEC_POLICY_PACKED",
+                 "EASYSPEC_MAX_BATCH", "EASYSPEC_MAX_CALIB_TOKENS", "EASYSPEC_MAX_SET", "EASYSPEC_OP_QKV",
+                 "EASYSPEC_OP_ATTN", "EASYSPEC_OP_OPROJ", "EASYSPEC_OP_GATEUP", "EASYSPEC_OP_DOWN", "EASYSPEC_OP_HEAD"):
+        m = re.search(rf"#define\s+{name}\s+\(?(-?\d+)\)?", header)
+        assert m, name
+        assert int(m.group(1)) == getattr(es.binding, name), name
+
+
+def test_default_groups_matches_paper_table_and_oracle(oracle):
+    """The product's own helper against the rows printed in Sec. 3.1.1 and against the oracle's
+    independently written helper over a sweep of shapes."""
+    def sets(bounds):
+        return [f"{a}" if b - a == 1 else f"{a}-{b - 1}" for a, b in zip(bounds[:-1], bounds[1:])]
+    rows = [l for l in open(os.path.join(ROOT, "tests", "golden", "layer_parallel_strategies.txt"))
+            if l.strip() and l[0] != "#"]
+    for row in rows:
+        left, head, tail = [p.split() for p in row.split("|")]
+        L, N = int(left[0]), int(left[1])
+        pol = es.EASYSPEC_POLICY_ALIGNED if left[2] == "aligned" else es.EASYSPEC_POLICY_PACKED
+        got = sets(es.easyspec_default_groups(L, N, pol))
+        assert got[: len(head)] == head and got[-len(tail):] == tail
+    for L, N in itertools.product(range(1, 40), range(1, 9)):
+        for pol, name in ((0, "aligned"), (1, "packed")):
+            b = es.easyspec_default_groups(L, N, pol)
+            assert list(b) == list(oracle.default_groups(L, N, name)), (L, N, name)
+            assert b[0] == 0 and b[-1] == L and np.all(np.diff(b) >= 1) and np.all(np.diff(b) <= max(N, 1))
+            if L >= 3:
+                assert b[1] == 1 and b[-2] == L - 1          # first and last layer are sets of their own
+
+
+def test_default_groups_rejects_bad_arguments():
+    for args in ((0, 4, 0), (8, 0, 0), (8, 4, 2), (-1, 4, 0)):
+        with pytest.raises(es.EasySpecError) as e:
+            es.easyspec_default_groups(*args)
+        assert e.value.code == es.EASYSPEC_EINVAL
+
+
+def test_greedy_accept_host_path(oracle):
+    """Host loop of the C ABI against the oracle on every draft/target pair for gamma <= 3 over
+    three symbols, batched, plus gamma = 0 (nothing drafted: the bonus is the only token)."""
+    for gamma in (1, 2, 3):
+        drafts = list(itertools.product(range(3), repeat=gamma))
+        targets = list(itertools.product(range(3), repeat=gamma + 1))
+        pairs = list(itertools.product(drafts, targets))
+        d = np.array([p[0] for p in pairs], np.int32)
+        t = np.array([p[1] for p in pairs], np.int32)
+        acc, bonus = np.zeros(len(pairs), np.int32), np.zeros(len(pairs), np.int32)
+        es.easyspec_greedy_accept(d, t, len(pairs), gamma, acc, bonus, None)
+        for i, (dd, tt) in enumerate(pairs):
+            assert (int(acc[i]), int(bonus[i])) == oracle.greedy_accept(dd, tt)
+    acc, bonus = np.zeros(2, np.int32), np.zeros(2, np.int32)
+    es.easyspec_greedy_accept(np.zeros(0, np.int32), np.array([[7], [9]], np.int32), 2, 0, acc, bonus, None)
+    assert list(acc) == [0, 0] and list(bonus) == [7, 9]
+    with pytest.raises(es.EasySpecError):
+        es.easyspec_greedy_accept(None, np.zeros(2, np.int32), 1, 1, acc, bonus, None)
+    with pytest.raises(es.EasySpecError):
+        es.easyspec_greedy_accept(np.zeros(1, np.int32), np.zeros(2, np.int32), 0, 1, acc, bonus, None)
+
+
+def test_create_rejects_bad_shapes_before_touching_the_device():
+    import easyspec_synth as synth
+    good = synth.model_shape("tiny")
+    bad = [dict(head_dim=48), dict(d_model=250), dict(d_ffn=1000), dict(n_q_heads=6, n_kv_heads=2, d_model=384),
+           dict(n_kv_heads=3), dict(n_layers=0), dict(vocab=0), dict(rope_theta=0.0)]
+    for over in bad:
+        with pytest.raises(es.EasySpecError) as e:
+            es.easyspec_create(es.make_config(dict(good, **over), 1, 64, 4))
+        assert e.value.code == es.EASYSPEC_EINVAL, over
+    for mb, mc, mt in ((0, 64, 4), (17, 64, 4), (1, 0, 4), (1, 64 * 1024 + 1, 4), (1, 64, 0), (1, 64, 17)):
+        with pytest.raises(es.EasySpecError) as e:
+            es.easyspec_create(es.make_config(good, mb, mc, mt))
+        assert e.value.code == es.EASYSPEC_EINVAL
+
+
+def test_no_cpu_fallback():
+    """Without a HIP device the library refuses to create a context (EASYSPEC_EHIP): there is no
+    CPU path that a parity test could silently run on."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is visible here")
+    import easyspec_synth as synth
+    with pytest.raises(es.EasySpecError) as e:
+        es.easyspec_create(es.make_config(synth.model_shape("tiny"), 1, 64, 4))
+    assert e.value.code == es.EASYSPEC_EHIP
+    assert "no HIP device" in str(e.value)
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2502_02493_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".cpp", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text, f"{f} mentions the oracle"
+    assert "paper_2502_02493_amd" not in open(os.path.join(ROOT, "oracle", "easyspec_oracle.py")).read()
+    assert "paper_2502_02493_amd" not in open(os.path.join(ROOT, "oracle", "easyspec_oracle.c")).read()

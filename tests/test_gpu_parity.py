@@ -1,5 +1,6 @@
 """GPU parity: the HIP path through the C ABI against the CPU oracle, element by element, on
-the same seeded inputs.  Tolerances: rel-L2 <= 1e-5 (fp32 models) / 2e-2 (bf16 models) on
+the same seeded inputs.  Tolerances: rel-L2 <= 1e-5 (fp32 models) / 2e-3 (bf16 models; the
+required bar is 2e-2, the two-term bf16 activations leave room for a ten times tighter one) on
 logits and hidden states; token ids and lengths exact (ids are compared wherever the oracle's
 top-1/top-2 logit gap exceeds the numerical noise floor, so that a genuine near-tie between
 two vocabulary entries cannot fail a correct kernel; the count of skipped comparisons is
@@ -11,8 +12,8 @@ import easyspec_synth as synth
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"fp32": 1e-5, "bf16": 2e-2}
-MARGIN = {"fp32": 1e-4, "bf16": 2e-2}    # in units of std(logits)
+TOL = {"fp32": 1e-5, "bf16": 2e-3}
+MARGIN = {"fp32": 1e-4, "bf16": 5e-3}    # in units of std(logits)
 
 
 @pytest.fixture(scope="module")
@@ -40,6 +41,7 @@ class IdCheck:
 
 def kv_check(gpu, g, seq_o, b, n, tol):
     k, v = g.export_kv(b, n)
+    # a bf16 cache may differ by one unit in the last place (2^-8 relative) on a few entries
     assert gpu.rel_l2(k, seq_o.K[:, :, :n]) < tol, "K cache"
     assert gpu.rel_l2(v, seq_o.V[:, :, :n]) < tol, "V cache"
     # per layer as well, so that one bad layer cannot hide in the norm of the others

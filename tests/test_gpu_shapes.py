@@ -1,0 +1,213 @@
+"""GPU parity at the benchmark shapes and in the batched / ragged / degenerate cases.
+
+Full-depth 8B-shape runs are sampled (one iteration); the layer shapes of both model
+families are also run at reduced depth so that the oracle can follow every step, with a
+seeded synthetic KV prefix (imported by both sides) standing in for a long prefilled context.
+"""
+import numpy as np
+import pytest
+
+import easyspec_synth as synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"fp32": 1e-5, "bf16": 2e-3}       # rel-L2 on logits / hidden states (the required bar for bf16 is 2e-2)
+MARGIN = {"fp32": 1e-4, "bf16": 5e-3}    # id comparisons need an oracle top-2 gap above this many std(logits)
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a HIP device; none is visible")
+    import gpu_harness
+    return gpu_harness
+
+
+def check_ids(oracle, dtype, got, want_logits, stats):
+    want, margin = oracle.argmax(want_logits, with_margin=True)
+    if margin > MARGIN[dtype] * float(np.std(want_logits)):
+        assert int(got) == want
+        stats[0] += 1
+    else:
+        stats[1] += 1
+    return want
+
+
+def groups(es, cfg, N, policy="aligned"):
+    pol = es.EASYSPEC_POLICY_ALIGNED if policy == "aligned" else es.EASYSPEC_POLICY_PACKED
+    return es.easyspec_default_groups(cfg["n_layers"], N, pol)
+
+
+def one_iteration(oracle, gpu, cfg, seed, bounds, ctx_len, gamma, accept, max_ctx=None):
+    """Synthetic KV prefix of ctx_len slots, calibration of 2 tokens, gamma-1 fuzzy steps,
+    calibration of `accept` drafted tokens + bonus.  Compares logits, hidden states, ids, KV."""
+    import paper_2502_02493_amd  # noqa: F401
+    tol, dt = TOL[cfg["dtype"]], cfg["dtype"]
+    w = synth.make_weights(cfg, seed)
+    max_ctx = max_ctx or ctx_len + gamma + 16
+    so = oracle.Sequence(oracle.Model(cfg, w, max_ctx))
+    g = gpu.GpuDrafter(cfg, w, max_batch=1, max_ctx=max_ctx, max_calib=16)
+    stats = [0, 0]
+    try:
+        g.set_groups(bounds)
+        k, v = synth.make_kv_prefix(cfg, seed + 1, ctx_len)
+        so.import_kv(k, v)
+        g.import_kv(0, k, v)
+        toks = synth.make_tokens(seed + 2, 3, cfg["vocab"])
+        wl = so.calibrate(toks[:2], all_rows=True)
+        gt, gl = g.calibrate({0: list(toks[:2])}, all_rows=True)
+        assert gpu.rel_l2(gl[0], wl) < tol, "calibration logits"
+        drafted = [check_ids(oracle, dt, gt[0], wl[-1], stats)]
+        for _ in range(gamma - 1):
+            wl, wh = so.fuzzy_step(bounds, drafted[-1], want_hidden=True)
+            gtok, glog = g.draft_step({0: drafted[-1]})
+            assert gpu.rel_l2(glog[0], wl) < tol, "fuzzy logits"
+            assert gpu.rel_l2(g.hidden()[0], wh) < tol, "fuzzy hidden state"
+            drafted.append(check_ids(oracle, dt, gtok[0], wl, stats))
+        n = so.precise + so.fuzzy
+        gk, gv = g.export_kv(0, n)
+        # only the slots written by this run; the imported prefix is trivially equal
+        assert gpu.rel_l2(gk[:, :, ctx_len:], so.K[:, :, ctx_len:n]) < max(tol, 4e-3 if dt == "bf16" else 0), "K"
+        assert gpu.rel_l2(gv[:, :, ctx_len:], so.V[:, :, ctx_len:n]) < max(tol, 4e-3 if dt == "bf16" else 0), "V"
+        calib = drafted[:accept] + [int(toks[2])]
+        wl, wh = so.calibrate(calib, all_rows=True, want_hidden=True)
+        gt, gl = g.calibrate({0: calib}, all_rows=True)
+        assert gpu.rel_l2(gl[0], wl) < tol, "bonus calibration logits"
+        assert gpu.rel_l2(g.hidden(), wh) < tol, "bonus calibration hidden"
+        check_ids(oracle, dt, gt[0], wl[-1], stats)
+        p, f = g.lens()
+        assert (int(p[0]), int(f[0])) == (so.precise, 0) == (ctx_len + 2 + accept + 1, 0)
+        assert stats[0] >= 1
+    finally:
+        g.close()
+    return stats
+
+
+def test_llama3_8b_layer_shape_reduced_depth(oracle, gpu):
+    """8B layer shape, 6 layers, sets {0},{1,2,3},{4},{5} (aligned, N=4), context 256, gamma 5."""
+    import paper_2502_02493_amd as es
+    cfg = synth.model_shape("llama3_8b", n_layers=6, vocab=8192)
+    b = groups(es, cfg, 4)
+    assert list(b) == [0, 1, 4, 5, 6]
+    one_iteration(oracle, gpu, cfg, 500, b, 256, 5, accept=3)
+
+
+@pytest.mark.parametrize("N", [2, 4, 7])
+def test_qwen2_7b_layer_shape_reduced_depth(oracle, gpu, N):
+    """Qwen2-7B layer shape (7 query heads per KV head, QKV bias), 9 layers, group sizes 2/4/7,
+    vocabulary not a multiple of 16, context 300 (ragged against every tile size)."""
+    import paper_2502_02493_amd as es
+    cfg = synth.model_shape("qwen2_7b", n_layers=9, vocab=5003)
+    one_iteration(oracle, gpu, cfg, 510 + N, groups(es, cfg, N), 300, 5, accept=5 if N == 7 else 1)
+
+
+@pytest.mark.parametrize("ctx_len", [4096, 8191])
+def test_calibration_lengths_long_context(oracle, gpu, ctx_len):
+    """Calibration-dominant case at reduced depth: every calibration length 1..9 (gamma 8) behind
+    a long synthetic context, partial KV rewrites included (what is accepted varies per round)."""
+    import paper_2502_02493_amd as es
+    cfg = synth.model_shape("llama3_8b", n_layers=2, vocab=4096)
+    w = synth.make_weights(cfg, 520)
+    max_ctx = ctx_len + 80
+    so = oracle.Sequence(oracle.Model(cfg, w, max_ctx))
+    g = gpu.GpuDrafter(cfg, w, max_batch=1, max_ctx=max_ctx, max_calib=9)
+    try:
+        bounds = groups(es, cfg, 4)
+        g.set_groups(bounds)
+        k, v = synth.make_kv_prefix(cfg, 521, ctx_len)
+        so.import_kv(k, v); g.import_kv(0, k, v)
+        toks = synth.make_tokens(522, 64, cfg["vocab"])
+        at = 0
+        for m in (9, 1, 5, 2, 8, 3, 7, 4, 6):
+            for j in range(2):                         # fuzzy slots that the calibration must drop
+                so.fuzzy_step(bounds, int(toks[at])); g.draft_step({0: int(toks[at])}); at += 1
+            calib = [int(t) for t in toks[at: at + m]]
+            wl = so.calibrate(calib, all_rows=True)
+            gt, gl = g.calibrate({0: calib}, all_rows=True)
+            assert gpu.rel_l2(gl[0], wl) < TOL["bf16"], f"calibration of {m} tokens"
+            p, f = g.lens()
+            assert (int(p[0]), int(f[0])) == (so.precise, 0)
+        n = so.precise
+        gk, gv = g.export_kv(0, n)
+        assert gpu.rel_l2(gk[:, :, ctx_len:], so.K[:, :, ctx_len:n]) < 4e-3
+        assert gpu.rel_l2(gv[:, :, ctx_len:], so.V[:, :, ctx_len:n]) < 4e-3
+    finally:
+        g.close()
+
+
+def test_batch4_ragged_long_contexts(oracle, gpu):
+    """Long-context batched draft at reduced depth: 4 sequences with contexts
+    4096/8192/16384/32768 (ragged: minus 0/1/17/63), group size 4, fuzzy steps for all four at
+    once, then a calibration that skips one sequence."""
+    import paper_2502_02493_amd as es
+    cfg = synth.model_shape("llama3_8b", n_layers=3, vocab=4096)
+    w = synth.make_weights(cfg, 530)
+    ctxs = [4096, 8191, 16367, 32705]
+    max_ctx = 32768
+    model = oracle.Model(cfg, w, max_ctx)
+    seqs = [oracle.Sequence(model) for _ in ctxs]
+    g = gpu.GpuDrafter(cfg, w, max_batch=4, max_ctx=max_ctx, max_calib=6)
+    try:
+        bounds = np.array([0, 3], np.int32)            # one 3-layer set: the grouped-attention case
+        g.set_groups(bounds)
+        for b, n in enumerate(ctxs):
+            k, v = synth.make_kv_prefix(cfg, 531, n, seq=b)
+            seqs[b].import_kv(k, v); g.import_kv(b, k, v)
+        toks = synth.make_tokens(532, 64, cfg["vocab"]).reshape(4, 16)
+        for step in range(3):
+            feed = {b: int(toks[b, step]) for b in range(4)}
+            gt, gl = g.draft_step(feed)
+            for b in range(4):
+                wl = seqs[b].fuzzy_step(bounds, feed[b])
+                assert gpu.rel_l2(gl[b], wl) < TOL["bf16"], f"fuzzy logits, sequence {b}, step {step}"
+        calib = {0: [int(t) for t in toks[0, 4:10]], 1: [int(toks[1, 4])], 3: [int(t) for t in toks[3, 4:7]]}
+        gt, gl = g.calibrate(calib, all_rows=True)
+        for b, t in calib.items():
+            wl = seqs[b].calibrate(t, all_rows=True)
+            assert gpu.rel_l2(gl[b], wl) < TOL["bf16"], f"calibration logits, sequence {b}"
+        p, f = g.lens()
+        assert [int(x) for x in p] == [s.precise for s in seqs] and [int(x) for x in f] == [s.fuzzy for s in seqs]
+        assert seqs[2].fuzzy == 3 and seqs[0].fuzzy == 0
+        feed = {b: int(toks[b, 12]) for b in range(4)}
+        gt, gl = g.draft_step(feed)
+        for b in range(4):
+            assert gpu.rel_l2(gl[b], seqs[b].fuzzy_step(bounds, feed[b])) < TOL["bf16"]
+    finally:
+        g.close()
+
+
+def test_full_size_llama3_8b_sampled(oracle, gpu):
+    """The benchmark configuration itself (32 layers, context 2048, aligned N=4 sets, gamma 5,
+    6-token calibration): one calibration and two fuzzy steps checked against the oracle."""
+    import paper_2502_02493_amd as es
+    cfg = synth.model_shape("llama3_8b")
+    print("drawing 8B-shape weights ...", flush=True)
+    w = synth.make_weights(cfg, 2025)
+    ctx_len, bounds = 2048, groups(es, cfg, 4)
+    assert list(bounds) == [0, 1, 4, 8, 12, 16, 20, 24, 28, 31, 32]
+    so = oracle.Sequence(oracle.Model(cfg, w, ctx_len + 32))
+    g = gpu.GpuDrafter(cfg, w, max_batch=1, max_ctx=ctx_len + 32, max_calib=16)
+    stats = [0, 0]
+    try:
+        g.set_groups(bounds)
+        k, v = synth.make_kv_prefix(cfg, 2026, ctx_len)
+        so.import_kv(k, v); g.import_kv(0, k, v)
+        calib = [int(t) for t in synth.make_tokens(2027, 6, cfg["vocab"])]
+        print("oracle calibration ...", flush=True)
+        wl = so.calibrate(calib, all_rows=False)
+        gt, gl = g.calibrate({0: calib}, all_rows=False)
+        err = gpu.rel_l2(gl[0], wl)
+        print("calibration rel-L2", err, flush=True)
+        assert err < TOL["bf16"]
+        tok = check_ids(oracle, "bf16", gt[0], wl, stats)
+        for _ in range(2):
+            wl = so.fuzzy_step(bounds, tok)
+            gtok, glog = g.draft_step({0: tok})
+            err = gpu.rel_l2(glog[0], wl)
+            print("fuzzy step rel-L2", err, flush=True)
+            assert err < TOL["bf16"]
+            tok = check_ids(oracle, "bf16", gtok[0], wl, stats)
+        assert stats[0] >= 2, stats
+    finally:
+        g.close()
