@@ -300,13 +300,15 @@ extern "C" int easyspec_set_groups(easyspec_ctx* ctx, const int32_t* bounds, int
 // one forward pass over the columns `c` (launch sequence of Alg. 1 / Alg. 2)
 // ---------------------------------------------------------------------------------------------
 
-static void pick_chunk(const Shape& s, const Cols& c, int n_set_max, int* chunk, int* n_chunks) {
+static void pick_chunk(const Shape& s, const Cols& c, int n_set, int* chunk, int* n_chunks) {
   int max_len = 1;
   for (int i = 0; i < c.n; ++i)
     if (c.pos[i] + 1 > max_len) max_len = c.pos[i] + 1;
-  int ch = 64;
+  // chunks are multiples of what one workgroup covers per batch; grow them until the chunk count
+  // fits the partial buffers and the launch is not cut finer than a few workgroups per CU
+  int ch = attn_block_slots(s);
   auto nch = [&](int ch_) { return (max_len + ch_ - 1) / ch_; };
-  while (ch < 1024 && (nch(ch) > kMaxChunks || (long)nch(ch) * s.Hkv * n_set_max * c.n > 1024)) ch *= 2;
+  while (ch < 1024 && (nch(ch) > kMaxChunks || (long)nch(ch) * s.Hkv * n_set * c.n > 1536)) ch *= 2;
   *chunk = ch;
   *n_chunks = nch(ch);
 }

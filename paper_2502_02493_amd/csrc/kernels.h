@@ -61,6 +61,8 @@ void launch_repack(int dtype, const void* src, void* dst, int rows, int K, hipSt
 void launch_embed(const Shape& s, const Buffers& b, const Cols& c, const int32_t* tokens, int layer0, int n_set,
                   hipStream_t st);
 void launch_qkv(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st);
+// Chunk sizes of launch_attn must be multiples of this many slots.
+int attn_block_slots(const Shape& s);
 void launch_attn(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, int chunk, int n_chunks,
                  hipStream_t st);
 // O projection of the set's layers; the first layer's result goes straight into the residual.

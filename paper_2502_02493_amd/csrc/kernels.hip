@@ -154,25 +154,29 @@ __device__ __forceinline__ void mma<float>(f32x4& acc, const u32x4& a, const u32
 // The shared core.  w[r]: first tile of row tile r (tiles of one row tile are consecutive,
 // 64 u32x4 each).  x: activations [part][col][K] in T.  The calling wave accumulates k-tiles
 // wave, wave+NW, ... into acc.
+//
+// NB = B fragments (and MFMAs) per weight tile.  With two-term activations and at most 8
+// columns, the lo terms ride in MFMA columns ncols..2*ncols-1 of the same instruction
+// ("folded", NB = 1) and fold_columns() adds the two halves afterwards; with more columns the
+// hi and lo terms take one MFMA each (NB = 2).
 // ------------------------------------------------------------------------------------------
-template <typename T, int RT>
-__device__ __forceinline__ void gemm_accumulate(const u32x4* const (&w)[RT], const T* __restrict__ x, int K, int ncols,
-                                                f32x4 (&acc)[RT]) {
-  constexpr int EPL = Tr<T>::EPL, KT = Tr<T>::KT, PARTS = Tr<T>::PARTS;
+template <typename T>
+__device__ __forceinline__ bool folded(int ncols) {
+  return Tr<T>::PARTS == 2 && 2 * ncols <= kMaxCols;
+}
+
+template <typename T, int RT, int NB>
+__device__ __forceinline__ void gemm_loop(const u32x4* const (&w)[RT], const u32x4* const (&xp)[NB], bool colok, int nkt,
+                                          f32x4 (&acc)[RT]) {
   constexpr int U = 8 / RT;  // k-tiles in flight per wave (8 KB of weights)
-  const size_t lo = (size_t)kMaxCols * K * sizeof(T) / 16;  // u32x4 between the hi and lo arrays
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, NW = blockDim.x >> 6;
-  const int col = lane & 15, kg = lane >> 4;
-  const int nkt = K / KT;
-  const bool colok = col < ncols;
-  const u32x4* xp = reinterpret_cast<const u32x4*>(x + (size_t)(colok ? col : 0) * K + kg * EPL);
   const u32x4* wp[RT];
 #pragma unroll
   for (int r = 0; r < RT; ++r) wp[r] = w[r] + lane;
   const u32x4 zero = {0u, 0u, 0u, 0u};
   int kt = wave;
   for (; kt + (U - 1) * NW < nkt; kt += U * NW) {
-    u32x4 a[RT][U], b[PARTS][U];
+    u32x4 a[RT][U], b[NB][U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
 #pragma unroll
@@ -181,28 +185,63 @@ __device__ __forceinline__ void gemm_accumulate(const u32x4* const (&w)[RT], con
 #pragma unroll
     for (int u = 0; u < U; ++u) {
 #pragma unroll
-      for (int q = 0; q < PARTS; ++q) b[q][u] = colok ? xp[(size_t)(kt + u * NW) * 4 + q * lo] : zero;
+      for (int q = 0; q < NB; ++q) b[q][u] = colok ? xp[q][(size_t)(kt + u * NW) * 4] : zero;
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
 #pragma unroll
       for (int r = 0; r < RT; ++r) {
 #pragma unroll
-        for (int q = 0; q < PARTS; ++q) mma<T>(acc[r], a[r][u], b[q][u]);
+        for (int q = 0; q < NB; ++q) mma<T>(acc[r], a[r][u], b[q][u]);
       }
     }
   }
   for (; kt < nkt; kt += NW) {
-    u32x4 b[PARTS];
+    u32x4 b[NB];
 #pragma unroll
-    for (int q = 0; q < PARTS; ++q) b[q] = colok ? xp[(size_t)kt * 4 + q * lo] : zero;
+    for (int q = 0; q < NB; ++q) b[q] = colok ? xp[q][(size_t)kt * 4] : zero;
 #pragma unroll
     for (int r = 0; r < RT; ++r) {
       u32x4 a = __builtin_nontemporal_load(wp[r] + (size_t)kt * 64);
 #pragma unroll
-      for (int q = 0; q < PARTS; ++q) mma<T>(acc[r], a, b[q]);
+      for (int q = 0; q < NB; ++q) mma<T>(acc[r], a, b[q]);
     }
   }
+}
+
+template <typename T, int RT>
+__device__ __forceinline__ void gemm_accumulate(const u32x4* const (&w)[RT], const T* __restrict__ x, int K, int ncols,
+                                                f32x4 (&acc)[RT]) {
+  constexpr int EPL = Tr<T>::EPL, KT = Tr<T>::KT, PARTS = Tr<T>::PARTS;
+  const int lane = threadIdx.x & 63;
+  const int col = lane & 15, kg = lane >> 4;
+  const int nkt = K / KT;
+  const size_t part = (size_t)kMaxCols * K;  // elements between the hi and lo arrays
+  if (PARTS == 1 || folded<T>(ncols)) {
+    // lane column c < ncols reads the hi term of column c, column ncols + c its lo term
+    const bool is_lo = PARTS == 2 && col >= ncols;
+    const int src = is_lo ? col - ncols : col;
+    const bool colok = src < ncols;
+    const u32x4* const xp[1] = {
+        reinterpret_cast<const u32x4*>(x + (is_lo ? part : 0) + (size_t)(colok ? src : 0) * K + kg * EPL)};
+    gemm_loop<T, RT, 1>(w, xp, colok, nkt, acc);
+  } else {
+    const bool colok = col < ncols;
+    const T* base = x + (size_t)(colok ? col : 0) * K + kg * EPL;
+    const u32x4* const xp[2] = {reinterpret_cast<const u32x4*>(base), reinterpret_cast<const u32x4*>(base + part)};
+    gemm_loop<T, RT, 2>(w, xp, colok, nkt, acc);
+  }
+}
+
+// After reduce_waves, in the wave that holds the totals: add the lo-term columns onto the
+// hi-term columns when the contraction ran folded.  All 64 lanes must call it.
+template <typename T, int RT>
+__device__ __forceinline__ void fold_columns(f32x4 (&acc)[RT], int ncols) {
+  if (!folded<T>(ncols)) return;
+#pragma unroll
+  for (int r = 0; r < RT; ++r)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[r][i] += __shfl_down(acc[r][i], ncols, 64);
 }
 
 // Sum the waves' partial accumulators through LDS in wave order; true for the wave that holds
@@ -277,6 +316,7 @@ __global__ __launch_bounds__(1024) void qkv_kernel(QkvArgs a, Cols c) {
   gemm_accumulate<T, 2>(w, x, a.d, c.n, acc);
   compute_rstd(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, s_rstd);
   if (!reduce_waves<2>(acc, dyn_red)) return;
+  fold_columns<T, 2>(acc, c.n);
 
   const int lane = threadIdx.x & 63, col = lane & 15;
   if (col >= c.n) return;
@@ -348,6 +388,7 @@ __global__ __launch_bounds__(1024) void proj_resid_kernel(ProjArgs a, Cols c) {
   f32x4 acc[1] = {{0.f, 0.f, 0.f, 0.f}};
   gemm_accumulate<T, 1>(w, x, a.K, c.n, acc);
   if (!reduce_waves<1>(acc, dyn_red)) return;
+  fold_columns<T, 1>(acc, c.n);
 
   const int lane = threadIdx.x & 63, col = lane & 15;
   const bool ok = col < c.n;
@@ -398,6 +439,7 @@ __global__ __launch_bounds__(1024) void gateup_kernel(GateUpArgs a, Cols c) {
   gemm_accumulate<T, 2>(w, reinterpret_cast<const T*>(a.x), a.d, c.n, acc);
   compute_rstd(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, s_rstd);
   if (!reduce_waves<2>(acc, dyn_red)) return;
+  fold_columns<T, 2>(acc, c.n);
   const int lane = threadIdx.x & 63, col = lane & 15;
   if (col >= c.n) return;
   const float r = s_rstd[col];
@@ -437,6 +479,7 @@ __global__ __launch_bounds__(1024) void head_kernel(HeadArgs a, Cols c) {
   gemm_accumulate<T, 1>(w, reinterpret_cast<const T*>(a.x), a.d, c.n, acc);
   compute_rstd(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, s_rstd);
   if (!reduce_waves<1>(acc, dyn_red)) return;
+  fold_columns<T, 1>(acc, c.n);
   const int lane = threadIdx.x & 63, col = lane & 15;
   const bool ok = col < c.n;
   const float r = ok ? s_rstd[col] : 0.f;
@@ -464,61 +507,99 @@ __global__ __launch_bounds__(1024) void head_kernel(HeadArgs a, Cols c) {
   }
 }
 
-__global__ __launch_bounds__(256) void argmax_final_kernel(const float* cand_val, const int32_t* cand_idx, int nblk,
-                                                           int32_t* tokens_out, Cols c) {
-  __shared__ float sv[256];
-  __shared__ int si[256];
+__global__ __launch_bounds__(1024) void argmax_final_kernel(const float* cand_val, const int32_t* cand_idx, int nblk,
+                                                            int32_t* tokens_out, Cols c) {
+  __shared__ float sv[16];
+  __shared__ int si[16];
   const int col = blockIdx.x, tid = threadIdx.x;
   float bv = -INFINITY;
   int bi = 0x7FFFFFFF;
-  for (int j = tid; j < nblk; j += 256) {
-    const float v = cand_val[(size_t)col * nblk + j];
-    const int i = cand_idx[(size_t)col * nblk + j];
-    if (better(v, i, bv, bi)) { bv = v; bi = i; }
+  for (int j0 = tid; j0 < nblk; j0 += 8 * 1024) {
+    float v[8];
+    int ix[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {  // independent loads, issued together
+      const int j = j0 + u * 1024;
+      const bool in = j < nblk;
+      v[u] = in ? cand_val[(size_t)col * nblk + j] : -INFINITY;
+      ix[u] = in ? cand_idx[(size_t)col * nblk + j] : 0x7FFFFFFF;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (better(v[u], ix[u], bv, bi)) { bv = v[u]; bi = ix[u]; }
   }
-  sv[tid] = bv;
-  si[tid] = bi;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const float ov = __shfl_xor(bv, off, 64);
+    const int oi = __shfl_xor(bi, off, 64);
+    if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+  }
+  if ((tid & 63) == 0) { sv[tid >> 6] = bv; si[tid >> 6] = bi; }
   __syncthreads();
-  for (int s = 128; s > 0; s >>= 1) {
-    if (tid < s && better(sv[tid + s], si[tid + s], sv[tid], si[tid])) { sv[tid] = sv[tid + s]; si[tid] = si[tid + s]; }
-    __syncthreads();
+  if (tid == 0) {
+    for (int w = 1; w < 16; ++w)
+      if (better(sv[w], si[w], bv, bi)) { bv = sv[w]; bi = si[w]; }
+    if (c.out_idx[col] >= 0) tokens_out[c.out_idx[col]] = bi;
   }
-  if (tid == 0 && c.out_idx[col] >= 0) tokens_out[c.out_idx[col]] = si[0];
+}
+
+// four consecutive elements as floats, p aligned to 4 elements
+template <typename T>
+__device__ __forceinline__ f32x4 load4(const T* p);
+template <>
+__device__ __forceinline__ f32x4 load4<float>(const float* p) {
+  return *reinterpret_cast<const f32x4*>(p);
+}
+template <>
+__device__ __forceinline__ f32x4 load4<bf16_t>(const bf16_t* p) {
+  const u32x2 r = *reinterpret_cast<const u32x2*>(p);
+  f32x4 v = {__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xFFFF0000u), __uint_as_float(r.y << 16),
+             __uint_as_float(r.y & 0xFFFF0000u)};
+  return v;
 }
 
 // ------------------------------------------------------------------------------------------
 // Embedding gather: H = E[token]; sum of squares; T(H * g_attn) for the layers of the first set.
-// grid = columns.
+// grid = columns, 1024 threads, four elements per thread and pass.
 // ------------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ E, const int32_t* __restrict__ tokens,
-                                                    const float* __restrict__ gain, int n_gain, int d, int V, float* H,
-                                                    T* xa, float* ssp, Cols c) {
-  __shared__ float red[4];
+__global__ __launch_bounds__(1024) void embed_kernel(const T* __restrict__ E, const int32_t* __restrict__ tokens,
+                                                     const float* __restrict__ gain, int n_gain, int d, int V, float* H,
+                                                     T* xa, float* ssp, Cols c) {
+  __shared__ float red[16];
   const int col = blockIdx.x, tid = threadIdx.x;
   const int tok = min(max(tokens[c.tok_idx[col]], 0), V - 1);  // ids outside the vocabulary are clamped
   float ss = 0.f;
-  for (int j = tid; j < d; j += 256) {
-    const float h = load1<T>(E + (size_t)tok * d + j);
-    H[(size_t)col * d + j] = h;
-    for (int i = 0; i < n_gain; ++i)
-      store_act1<T>(xa + ((size_t)i * Tr<T>::PARTS * kMaxCols + col) * d + j, (size_t)kMaxCols * d, h * gain[(size_t)i * d + j]);
-    ss += h * h;
+  for (int j = tid * 4; j < d; j += 4096) {
+    const f32x4 h = load4<T>(E + (size_t)tok * d + j);
+    *reinterpret_cast<f32x4*>(H + (size_t)col * d + j) = h;
+    for (int i = 0; i < n_gain; ++i) {
+      const f32x4 g = *reinterpret_cast<const f32x4*>(gain + (size_t)i * d + j);
+      store_act4<T>(xa + ((size_t)i * Tr<T>::PARTS * kMaxCols + col) * d + j, (size_t)kMaxCols * d, h[0] * g[0], h[1] * g[1],
+                    h[2] * g[2], h[3] * g[3]);
+    }
+    ss += (h[0] * h[0] + h[1] * h[1]) + (h[2] * h[2] + h[3] * h[3]);
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
   if ((tid & 63) == 0) red[tid >> 6] = ss;
   __syncthreads();
   const int ntile = d / 16;
-  for (int t = tid; t < ntile; t += 256) ssp[col * ntile + t] = (t == 0) ? ((red[0] + red[1]) + (red[2] + red[3])) : 0.f;
+  float total = 0.f;
+  for (int w = 0; w < 16; ++w) total += red[w];
+  for (int t = tid; t < ntile; t += 1024) ssp[col * ntile + t] = (t == 0) ? total : 0.f;
 }
 
 // ------------------------------------------------------------------------------------------
 // Decode attention over the KV caches of a set's layers, split along the context.
 // One workgroup = (context chunk, KV head, layer x column); it serves the G query heads that
 // share the KV head.  A K or V row (hd elements) is spread over LPS lanes, 16 bytes each, so a
-// wave load covers 64/LPS consecutive slots (1 KB, coalesced).  Scores of the chunk are kept
-// in LDS, so the softmax inside a chunk needs no rescaling; chunks are merged afterwards.
+// wave load covers SPW = 64/LPS consecutive slots (1 KB, coalesced).  Each wave walks its own
+// contiguous run of slots in batches of IT loads per operand, all issued before the first is
+// used, with a running (max, sum, accumulator) per query head: scores and probabilities never
+// leave registers, since K and V fragments of a slot sit in the same lanes.  The four waves'
+// states are combined through LDS; if the context has more than one chunk the workgroup
+// writes a partial (max, sum, accumulator) per head and attn_merge_kernel combines the chunks.
 // ------------------------------------------------------------------------------------------
 struct AttnArgs {
   const float* Q;
@@ -532,152 +613,210 @@ struct AttnArgs {
   float scale;
 };
 
+constexpr int kAttnIT = 8;  // loads in flight per operand per lane
+
+template <typename T, int HD>
+struct AttnGeom {
+  static constexpr int EPL = Tr<T>::EPL, LPS = HD / EPL, SPW = 64 / LPS;
+  static constexpr int WAVE_SLOTS = kAttnIT * SPW;    // slots one wave covers per batch
+  static constexpr int BLOCK_SLOTS = 4 * WAVE_SLOTS;  // chunk sizes are multiples of this
+};
+
 extern __shared__ float dyn_f[];
 
 template <typename T, int HD, int G>
-__global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a, Cols c) {
-  constexpr int EPL = Tr<T>::EPL, LPS = HD / EPL, SPW = 64 / LPS, SPB = 4 * SPW;
+__global__ __launch_bounds__(256) void attn_kernel(AttnArgs a, Cols c) {
+  typedef AttnGeom<T, HD> Geo;
+  constexpr int EPL = Geo::EPL, LPS = Geo::LPS, SPW = Geo::SPW, IT = kAttnIT;
   const int chunk = blockIdx.x, kvh = blockIdx.y;
   const int li = blockIdx.z / c.n, col = blockIdx.z % c.n;
   const int n_slots = c.pos[col] + 1;
   const int s0 = chunk * a.CH;
   if (s0 >= n_slots) return;
   const int s1 = min(s0 + a.CH, n_slots);
-  const int n = s1 - s0;
+  const int nch = (n_slots + a.CH - 1) / a.CH;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int sub = lane / LPS, e0 = (lane % LPS) * EPL;
 
-  float* sc = dyn_f;                   // [G][CH]
-  float* red = dyn_f + G * a.CH;       // [4][G*HD] (reused for [4][G] scalars before that)
   const size_t rowbase = (((size_t)(a.layer0 + li) * a.B + c.seq[col]) * a.Hkv + kvh) * (size_t)a.max_ctx;
   const T* kb = reinterpret_cast<const T*>(a.kc) + rowbase * HD + e0;
   const T* vb = reinterpret_cast<const T*>(a.vc) + rowbase * HD + e0;
   const int HQ = a.Hq * HD;
 
-  // ---- scores
-  {
-    float q[G][EPL];
+  float q[G][EPL], acc[G][EPL], m_run[G], l_run[G];
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      const float* qp = a.Q + ((size_t)li * kMaxCols + col) * HQ + (kvh * G + g) * HD + e0;
+  for (int g = 0; g < G; ++g) {
+    const float* qp = a.Q + ((size_t)li * kMaxCols + col) * HQ + (kvh * G + g) * HD + e0;
 #pragma unroll
-      for (int j = 0; j < EPL; ++j) q[g][j] = qp[j];
+    for (int j = 0; j < EPL; ++j) {
+      q[g][j] = qp[j];
+      acc[g][j] = 0.f;
     }
-    for (int sb = s0 + wave * SPW; sb < s1; sb += SPB) {
-      const int s = sb + sub;
-      const bool valid = s < s1;
-      float kv[EPL];
-      if (valid) {
-        const u32x4 raw = *reinterpret_cast<const u32x4*>(kb + (size_t)s * HD);
-        unpack<T>(raw, kv);
-      } else {
+    m_run[g] = -INFINITY;
+    l_run[g] = 0.f;
+  }
+
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  for (int base = s0 + wave * Geo::WAVE_SLOTS; base < s1; base += Geo::BLOCK_SLOTS) {  // wave-uniform
+    u32x4 kr[IT], vr[IT];
 #pragma unroll
-        for (int j = 0; j < EPL; ++j) kv[j] = 0.f;
-      }
+    for (int j = 0; j < IT; ++j) {
+      const int s = base + j * SPW + sub;
+      kr[j] = s < s1 ? *reinterpret_cast<const u32x4*>(kb + (size_t)s * HD) : zero;
+    }
+#pragma unroll
+    for (int j = 0; j < IT; ++j) {
+      const int s = base + j * SPW + sub;
+      vr[j] = s < s1 ? *reinterpret_cast<const u32x4*>(vb + (size_t)s * HD) : zero;
+    }
+    float sc[IT][G];
+#pragma unroll
+    for (int j = 0; j < IT; ++j) {
+      const bool valid = base + j * SPW + sub < s1;
+      float kv[EPL];
+      unpack<T>(kr[j], kv);
 #pragma unroll
       for (int g = 0; g < G; ++g) {
         float dot = 0.f;
 #pragma unroll
-        for (int j = 0; j < EPL; ++j) dot += q[g][j] * kv[j];
+        for (int e = 0; e < EPL; ++e) dot += q[g][e] * kv[e];
 #pragma unroll
         for (int off = 1; off < LPS; off <<= 1) dot += __shfl_xor(dot, off, 64);
-        if (valid && (lane % LPS) == 0) sc[g * a.CH + (s - s0)] = dot * a.scale;
+        sc[j][g] = valid ? dot * a.scale : -INFINITY;
       }
     }
-  }
-  __syncthreads();
-
-  // ---- chunk max, exponentials, chunk sum (per head)
-  float mx[G], sum[G];
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    float m = -INFINITY;
-    for (int j = tid; j < n; j += 256) m = fmaxf(m, sc[g * a.CH + j]);
+    for (int g = 0; g < G; ++g) {
+      float bm = sc[0][g];
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
-    if (lane == 0) red[wave * G + g] = m;
-  }
-  __syncthreads();
+      for (int j = 1; j < IT; ++j) bm = fmaxf(bm, sc[j][g]);
 #pragma unroll
-  for (int g = 0; g < G; ++g) mx[g] = fmaxf(fmaxf(red[g], red[G + g]), fmaxf(red[2 * G + g], red[3 * G + g]));
-  __syncthreads();
+      for (int off = LPS; off < 64; off <<= 1) bm = fmaxf(bm, __shfl_xor(bm, off, 64));
+      // the first slot of a batch is always valid, so bm is finite
+      const float m_new = fmaxf(m_run[g], bm);
+      const float alpha = __expf(m_run[g] - m_new);  // exp(-inf) = 0 on the first batch
+      m_run[g] = m_new;
+      l_run[g] *= alpha;
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    float s = 0.f;
-    for (int j = tid; j < n; j += 256) {
-      const float p = expf(sc[g * a.CH + j] - mx[g]);
-      sc[g * a.CH + j] = p;
-      s += p;
+      for (int e = 0; e < EPL; ++e) acc[g][e] *= alpha;
     }
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-    if (lane == 0) red[wave * G + g] = s;
-  }
-  __syncthreads();
-#pragma unroll
-  for (int g = 0; g < G; ++g) sum[g] = (red[g] + red[G + g]) + (red[2 * G + g] + red[3 * G + g]);
-  __syncthreads();
-
-  // ---- P * V
-  float acc[G][EPL];
-#pragma unroll
-  for (int g = 0; g < G; ++g)
-#pragma unroll
-    for (int j = 0; j < EPL; ++j) acc[g][j] = 0.f;
-  for (int sb = s0 + wave * SPW; sb < s1; sb += SPB) {
-    const int s = sb + sub;
-    if (s < s1) {
-      float v[EPL];
-      const u32x4 raw = *reinterpret_cast<const u32x4*>(vb + (size_t)s * HD);
-      unpack<T>(raw, v);
+    for (int j = 0; j < IT; ++j) {
+      float vv[EPL];
+      unpack<T>(vr[j], vv);
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        const float p = sc[g * a.CH + (s - s0)];
+        const float p = __expf(sc[j][g] - m_run[g]);  // 0 for slots past the end
+        l_run[g] += p;
 #pragma unroll
-        for (int j = 0; j < EPL; ++j) acc[g][j] += p * v[j];
+        for (int e = 0; e < EPL; ++e) acc[g][e] += p * vv[e];
       }
     }
   }
+
+  // combine the slot groups of the wave (l_run counts each slot once per group, every lane of a
+  // group holds the same value)
 #pragma unroll
-  for (int g = 0; g < G; ++g)
+  for (int g = 0; g < G; ++g) {
 #pragma unroll
-    for (int j = 0; j < EPL; ++j) {
-      float v = acc[g][j];
+    for (int off = LPS; off < 64; off <<= 1) {
+      l_run[g] += __shfl_xor(l_run[g], off, 64);
 #pragma unroll
-      for (int off = LPS; off < 64; off <<= 1) v += __shfl_xor(v, off, 64);
-      if (sub == 0) red[(wave * G + g) * HD + e0 + j] = v;
+      for (int e = 0; e < EPL; ++e) acc[g][e] += __shfl_xor(acc[g][e], off, 64);
     }
+  }
+  float* w_acc = dyn_f;                 // [4][G][HD]
+  float* w_m = dyn_f + 4 * G * HD;      // [4][G]
+  float* w_l = w_m + 4 * G;             // [4][G]
+  if (sub == 0) {
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) w_acc[(wave * G + g) * HD + e0 + e] = acc[g][e];
+  }
+  if (lane == 0) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      w_m[wave * G + g] = m_run[g];  // -inf for a wave that had no slots
+      w_l[wave * G + g] = l_run[g];
+    }
+  }
   __syncthreads();
+
+  const size_t arow = (size_t)li * kMaxCols + col;
   for (int idx = tid; idx < G * HD; idx += 256) {
     const int g = idx / HD, e = idx % HD;
-    const float v = (red[(0 * G + g) * HD + e] + red[(1 * G + g) * HD + e]) + (red[(2 * G + g) * HD + e] + red[(3 * G + g) * HD + e]);
-    const size_t row = ((size_t)li * kMaxCols + col) * a.Hq + kvh * G + g;
-    a.PO[(row * kMaxChunks + chunk) * HD + e] = v;
-    if (e == 0) {
-      a.PM[row * kMaxChunks + chunk] = mx[g];
-      a.PL[row * kMaxChunks + chunk] = sum[g];
+    float m = fmaxf(fmaxf(w_m[g], w_m[G + g]), fmaxf(w_m[2 * G + g], w_m[3 * G + g]));
+    float l = 0.f, o = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float wgt = __expf(w_m[w * G + g] - m);
+      l += w_l[w * G + g] * wgt;
+      o += w_acc[(w * G + g) * HD + e] * wgt;
+    }
+    const int head = kvh * G + g;
+    if (nch == 1) {
+      store_act1<T>(reinterpret_cast<T*>(a.AO) + ((size_t)li * Tr<T>::PARTS * kMaxCols + col) * HQ + head * HD + e,
+                    (size_t)kMaxCols * HQ, o / l);
+    } else {
+      const size_t row = arow * a.Hq + head;
+      a.PO[(row * kMaxChunks + chunk) * HD + e] = o;
+      if (e == 0) {
+        a.PM[row * kMaxChunks + chunk] = m;
+        a.PL[row * kMaxChunks + chunk] = l;
+      }
     }
   }
 }
 
-// Merge the chunks of one (layer, column, query head) and round the result to T.
-// grid = (k * columns, Hq), block = hd.
-template <typename T>
-__global__ void attn_merge_kernel(AttnArgs a, Cols c) {
-  const int li = blockIdx.x / c.n, col = blockIdx.x % c.n, head = blockIdx.y, e = threadIdx.x;
-  const int hd = blockDim.x;
-  const int nch = (c.pos[col] + a.CH) / a.CH;  // ceil((pos+1)/CH)
-  const size_t row = ((size_t)li * kMaxCols + col) * a.Hq + head;
-  float m = -INFINITY;
-  for (int ch = 0; ch < nch; ++ch) m = fmaxf(m, a.PM[row * kMaxChunks + ch]);
-  float l = 0.f, o = 0.f;
-  for (int ch = 0; ch < nch; ++ch) {
-    const float wgt = expf(a.PM[row * kMaxChunks + ch] - m);
-    l += a.PL[row * kMaxChunks + ch] * wgt;
-    o += a.PO[(row * kMaxChunks + ch) * hd + e] * wgt;
+// Merge the chunk partials of one (layer, column, KV head): all G query heads, chunks in
+// order.  Runs as its own launch: the kernel boundary is what makes the partials written by
+// workgroups on other XCDs visible (a device-scope fence inside the attention kernel costs an
+// L2 write-back per workgroup and was measured several times slower).  Columns whose context
+// fits one chunk were finished by attn_kernel.  grid = (k * columns, Hkv), block = 256.
+template <typename T, int HD>
+__global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, Cols c) {
+  __shared__ float s_w[8][kMaxChunks];  // per head: exp(m_chunk - m) ; chunk count <= 64 = one lane each
+  __shared__ float s_l[8];
+  const int li = blockIdx.x / c.n, col = blockIdx.x % c.n, kvh = blockIdx.y, tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int n_slots = c.pos[col] + 1;
+  const int nch = (n_slots + a.CH - 1) / a.CH;
+  if (nch == 1) return;
+  const int G = a.Hq / a.Hkv, HQ = a.Hq * HD;
+  const size_t arow = (size_t)li * kMaxCols + col;
+  for (int g = wave; g < G; g += 4) {  // one wave per head, one lane per chunk
+    const size_t row = arow * a.Hq + kvh * G + g;
+    const float pm = lane < nch ? a.PM[row * kMaxChunks + lane] : -INFINITY;
+    const float pl = lane < nch ? a.PL[row * kMaxChunks + lane] : 0.f;
+    float m = pm;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+    const float wgt = __expf(pm - m);
+    s_w[g][lane] = wgt;
+    // sum in chunk order so that the result does not depend on the reduction tree
+    float l = pl * wgt;
+    s_l[g] = 0.f;  // placeholder, written below by lane 0
+    float tot = 0.f;
+    for (int ch = 0; ch < nch; ++ch) tot += __shfl(l, ch, 64);
+    if (lane == 0) s_l[g] = tot;
   }
-  store_act1<T>(reinterpret_cast<T*>(a.AO) + ((size_t)li * Tr<T>::PARTS * kMaxCols + col) * (a.Hq * hd) + head * hd + e,
-                (size_t)kMaxCols * a.Hq * hd, o / l);
+  __syncthreads();
+  for (int idx = tid; idx < G * HD; idx += 256) {
+    const int g = idx / HD, e = idx % HD;
+    const int head = kvh * G + g;
+    const float* po = a.PO + (arow * a.Hq + head) * kMaxChunks * HD + e;
+    float o = 0.f;
+    for (int c0 = 0; c0 < nch; c0 += 8) {
+      float pv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) pv[u] = c0 + u < nch ? po[(size_t)(c0 + u) * HD] : 0.f;  // independent loads
+#pragma unroll
+      for (int u = 0; u < 8; ++u) o += pv[u] * (c0 + u < nch ? s_w[g][c0 + u] : 0.f);
+    }
+    store_act1<T>(reinterpret_cast<T*>(a.AO) + ((size_t)li * Tr<T>::PARTS * kMaxCols + col) * HQ + head * HD + e,
+                  (size_t)kMaxCols * HQ, o / s_l[g]);
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -737,16 +876,12 @@ static int env_int(const char* name, int dflt) {
   return v ? atoi(v) : dflt;
 }
 
-// Waves per workgroup: enough workgroup-waves to cover the chip several times over, but every
-// wave keeps at least 8 k-tiles of work.
-static int pick_waves(int n_blocks, int nkt, const char* env) {
-  static const int target = env_int("EASYSPEC_TARGET_WAVES", 4096);
-  int forced = env_int(env, 0);
-  int nw = 1;
-  if (forced > 0) nw = forced;
-  else {
-    while (nw < 16 && n_blocks * nw < target) nw *= 2;
-  }
+// Waves per workgroup (they split K).  `dflt` is the value measured best at the 8B shape for
+// that operation; a wave always keeps at least 8 k-tiles.  EASYSPEC_NW_* overrides for sweeps.
+static int pick_waves(int dflt, int nkt, const char* env) {
+  const int forced = env_int(env, 0);
+  int nw = forced > 0 ? forced : dflt;
+  if (nw > 16) nw = 16;
   while (nw > 1 && nkt / nw < 8) nw /= 2;
   return nw;
 }
@@ -772,7 +907,7 @@ void launch_repack(int dtype, const void* src, void* dst, int rows, int K, hipSt
 
 void launch_embed(const Shape& s, const Buffers& b, const Cols& c, const int32_t* tokens, int layer0, int n_set,
                   hipStream_t st) {
-  DISPATCH_T(s.dtype, hipLaunchKernelGGL(embed_kernel<T>, dim3(c.n), dim3(256), 0, st, (const T*)b.embed, tokens,
+  DISPATCH_T(s.dtype, hipLaunchKernelGGL(embed_kernel<T>, dim3(c.n), dim3(1024), 0, st, (const T*)b.embed, tokens,
                                          b.g_attn + (size_t)layer0 * s.d, n_set, s.d, s.V, b.H, (T*)b.XA, b.ssp, c));
 }
 
@@ -792,20 +927,26 @@ void launch_qkv(const Shape& s, const Buffers& b, const Cols& c, int layer0, int
   a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
   const int grid = n_set * (s.Hq + 2 * s.Hkv) * (s.hd / 32);
   const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
-  const int nw = pick_waves(grid, nkt, "EASYSPEC_NW_QKV");
+  const int nw = pick_waves(4, nkt, "EASYSPEC_NW_QKV");
   DISPATCH_T(s.dtype, hipLaunchKernelGGL(qkv_kernel<T>, dim3(grid), dim3(64 * nw), red_bytes(nw, 2), st, a, c));
 }
 
 template <typename T, int HD>
-static void launch_attn_g(int G, dim3 grid, size_t lds, hipStream_t st, const AttnArgs& a, const Cols& c) {
+static void launch_attn_g(int G, dim3 grid, hipStream_t st, const AttnArgs& a, const Cols& c) {
+  const size_t lds = (size_t)(4 * G * HD + 8 * G) * sizeof(float);
   switch (G) {
-    case 1: hipLaunchKernelGGL((attn_partial_kernel<T, HD, 1>), grid, dim3(256), lds, st, a, c); break;
-    case 2: hipLaunchKernelGGL((attn_partial_kernel<T, HD, 2>), grid, dim3(256), lds, st, a, c); break;
-    case 4: hipLaunchKernelGGL((attn_partial_kernel<T, HD, 4>), grid, dim3(256), lds, st, a, c); break;
-    case 7: hipLaunchKernelGGL((attn_partial_kernel<T, HD, 7>), grid, dim3(256), lds, st, a, c); break;
-    case 8: hipLaunchKernelGGL((attn_partial_kernel<T, HD, 8>), grid, dim3(256), lds, st, a, c); break;
+    case 1: hipLaunchKernelGGL((attn_kernel<T, HD, 1>), grid, dim3(256), lds, st, a, c); break;
+    case 2: hipLaunchKernelGGL((attn_kernel<T, HD, 2>), grid, dim3(256), lds, st, a, c); break;
+    case 4: hipLaunchKernelGGL((attn_kernel<T, HD, 4>), grid, dim3(256), lds, st, a, c); break;
+    case 7: hipLaunchKernelGGL((attn_kernel<T, HD, 7>), grid, dim3(256), lds, st, a, c); break;
+    case 8: hipLaunchKernelGGL((attn_kernel<T, HD, 8>), grid, dim3(256), lds, st, a, c); break;
     default: break;  // rejected at create
   }
+}
+
+int attn_block_slots(const Shape& s) {
+  const int lps = s.hd * (s.dtype == 1 ? 2 : 4) / 16;
+  return 4 * kAttnIT * (64 / lps);
 }
 
 void launch_attn(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, int chunk, int n_chunks,
@@ -816,12 +957,17 @@ void launch_attn(const Shape& s, const Buffers& b, const Cols& c, int layer0, in
   a.scale = 1.0f / sqrtf((float)s.hd);
   const int G = s.Hq / s.Hkv;
   const dim3 grid(n_chunks, s.Hkv, n_set * c.n);
-  const size_t lds = ((size_t)G * chunk + 4 * (size_t)G * s.hd) * sizeof(float);
   DISPATCH_T(s.dtype, {
-    if (s.hd == 128) launch_attn_g<T, 128>(G, grid, lds, st, a, c);
-    else launch_attn_g<T, 64>(G, grid, lds, st, a, c);
+    if (s.hd == 128) launch_attn_g<T, 128>(G, grid, st, a, c);
+    else launch_attn_g<T, 64>(G, grid, st, a, c);
   });
-  DISPATCH_T(s.dtype, hipLaunchKernelGGL(attn_merge_kernel<T>, dim3(n_set * c.n, s.Hq), dim3(s.hd), 0, st, a, c));
+  if (n_chunks > 1) {
+    const dim3 mgrid(n_set * c.n, s.Hkv);
+    DISPATCH_T(s.dtype, {
+      if (s.hd == 128) hipLaunchKernelGGL((attn_merge_kernel<T, 128>), mgrid, dim3(256), 0, st, a, c);
+      else hipLaunchKernelGGL((attn_merge_kernel<T, 64>), mgrid, dim3(256), 0, st, a, c);
+    });
+  }
 }
 
 void launch_oproj(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st) {
@@ -838,7 +984,7 @@ void launch_oproj(const Shape& s, const Buffers& b, const Cols& c, int layer0, i
   a.ssp = b.ssp;
   const int grid = n_set * (s.d / 16);
   const int nkt = s.HQ / (s.dtype == 1 ? 32 : 16);
-  const int nw = pick_waves(grid, nkt, "EASYSPEC_NW_O");
+  const int nw = pick_waves(4, nkt, "EASYSPEC_NW_O");
   DISPATCH_T(s.dtype, hipLaunchKernelGGL(proj_resid_kernel<T>, dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
 }
 
@@ -851,7 +997,7 @@ void launch_gateup(const Shape& s, const Buffers& b, const Cols& c, int layer, h
   a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
   const int grid = s.F / 16;
   const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
-  const int nw = pick_waves(grid, nkt, "EASYSPEC_NW_GU");
+  const int nw = pick_waves(8, nkt, "EASYSPEC_NW_GU");
   DISPATCH_T(s.dtype, hipLaunchKernelGGL(gateup_kernel<T>, dim3(grid), dim3(64 * nw), red_bytes(nw, 2), st, a, c));
 }
 
@@ -867,7 +1013,7 @@ void launch_down(const Shape& s, const Buffers& b, const Cols& c, int layer, int
   a.gain = gain; a.n_gain = n_gain; a.xout = xout; a.ssp = b.ssp;
   const int grid = s.d / 16;
   const int nkt = s.F / (s.dtype == 1 ? 32 : 16);
-  const int nw = pick_waves(grid, nkt, "EASYSPEC_NW_DOWN");
+  const int nw = pick_waves(8, nkt, "EASYSPEC_NW_DOWN");
   DISPATCH_T(s.dtype, hipLaunchKernelGGL(proj_resid_kernel<T>, dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
 }
 
@@ -878,9 +1024,9 @@ void launch_head(const Shape& s, const Buffers& b, const Cols& c, float* logits_
   a.d = s.d; a.V = s.V; a.nblk = (s.V + 15) / 16;
   a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
   const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
-  const int nw = pick_waves(a.nblk, nkt, "EASYSPEC_NW_HEAD");
+  const int nw = pick_waves(4, nkt, "EASYSPEC_NW_HEAD");
   DISPATCH_T(s.dtype, hipLaunchKernelGGL(head_kernel<T>, dim3(a.nblk), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
-  hipLaunchKernelGGL(argmax_final_kernel, dim3(c.n), dim3(256), 0, st, a.cand_val, a.cand_idx, a.nblk, tokens_out, c);
+  hipLaunchKernelGGL(argmax_final_kernel, dim3(c.n), dim3(1024), 0, st, a.cand_val, a.cand_idx, a.nblk, tokens_out, c);
 }
 
 void launch_accept(const int32_t* draft, const int32_t* target, int batch, int gamma, int32_t* accept_len, int32_t* bonus,
