@@ -26,6 +26,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM KiB per launch of the dominant kernel (gate/up projection) from the rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs summarised in profiles/hbm_traffic_llama3_8b_ctx2048.md (scaled by a 1 GiB copy).
+MEASURED_TRAFFIC_KIB = {"llama3_8b_ctx2048": 229846.0}
 
 
 def log(*a):
@@ -42,8 +45,11 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging; makes the result invalid)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="budget of the oracle baseline leg")
+    ap.add_argument("--copy-mib", type=int, default=0,
+                    help="also run a plain device copy of this many MiB (a kernel of known traffic, to scale "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--traffic-kib", type=float, default=None,
-                    help="HBM KiB per launch of the dominant kernel from rocprofv3 --pmc runs (else null)")
+                    help="HBM KiB per launch of the dominant kernel from rocprofv3 --pmc runs (default: the committed figure)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -102,6 +108,14 @@ def main():
         if ev: ev[2].record()
         es.easyspec_greedy_accept(dptr, target, 1, gamma, acc, bonus, stream)
 
+    if args.copy_mib:
+        src = torch.ones(args.copy_mib << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)          # reads and writes copy_mib MiB each
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         iteration()
     torch.cuda.synchronize()
@@ -128,7 +142,16 @@ def main():
     for k in range(args.steps):
         iteration()
     n_timed, total_ms = es.easyspec_profile_end(ctx)
-    gu_ms = total_ms / max(n_timed, 1)
+    # an event pair with nothing between still spans the gap between two stream markers: measure that
+    # gap the same way and take it off, so that the figure is the kernel's own duration
+    null = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(200)]
+    es.easyspec_draft_step(ctx, dptr, dptr + esz, None)
+    for a_, b_ in null:
+        a_.record(); b_.record()
+    torch.cuda.synchronize()
+    null_ms = float(np.median([a_.elapsed_time(b_) for a_, b_ in null]))
+    gu_raw_ms = total_ms / max(n_timed, 1)
+    gu_ms = gu_raw_ms - null_ms
     gu_gbs = gu_bytes / (gu_ms * 1e-3) / 1e9
     per_op = {}
     for name, op in (("qkv", es.EASYSPEC_OP_QKV), ("attn", es.EASYSPEC_OP_ATTN), ("oproj", es.EASYSPEC_OP_OPROJ),
@@ -139,6 +162,8 @@ def main():
         per_op[name + "_us_per_iteration"] = round(1e3 * ms_, 1)
     per_op["gateup_us_per_iteration"] = round(1e3 * gu_ms * gamma * cfg["n_layers"], 1)
 
+    traffic_kib = args.traffic_kib if args.traffic_kib is not None else (
+        None if args.layers else MEASURED_TRAFFIC_KIB.get(args.workload))
     out = {
         "metric": "draft tokens/sec (whole drafting iteration: calibration + fuzzy steps + accept)",
         "value": round(gamma * args.steps / wall, 2),
@@ -156,8 +181,10 @@ def main():
                       "hbm_frac": round(calib_bytes / (calib_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)},
         "roofline": {"bound": "hbm", "kernel": "gateup_kernel", "achieved": round(gu_gbs, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(gu_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": None if args.traffic_kib is None else args.traffic_kib * 1024,
-                     "bytes_per_launch": int(gu_bytes), "avg_launch_us": round(1e3 * gu_ms, 2), "launches_timed": n_timed},
+                     "traffic": traffic_kib * 1024 if traffic_kib else None,
+                     "bytes_per_launch": int(gu_bytes), "avg_launch_us": round(1e3 * gu_ms, 2),
+                     "event_pair_us": round(1e3 * gu_raw_ms, 2), "empty_event_pair_us": round(1e3 * null_ms, 2),
+                     "launches_timed": n_timed},
         "kernel_time": per_op,
     }
 
