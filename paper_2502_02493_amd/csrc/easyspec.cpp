@@ -6,6 +6,7 @@
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <string>
@@ -308,7 +309,8 @@ static void pick_chunk(const Shape& s, const Cols& c, int n_set, int* chunk, int
   // fits the partial buffers and the launch is not cut finer than a few workgroups per CU
   int ch = attn_block_slots(s);
   auto nch = [&](int ch_) { return (max_len + ch_ - 1) / ch_; };
-  while (ch < 1024 && (nch(ch) > kMaxChunks || (long)nch(ch) * s.Hkv * n_set * c.n > 1536)) ch *= 2;
+  static const long max_wg = getenv("EASYSPEC_ATTN_WG") ? atol(getenv("EASYSPEC_ATTN_WG")) : 512;
+  while (ch < 1024 && (nch(ch) > kMaxChunks || (long)nch(ch) * s.Hkv * n_set * c.n > max_wg)) ch *= 2;
   *chunk = ch;
   *n_chunks = nch(ch);
 }
