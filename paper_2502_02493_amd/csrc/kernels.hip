@@ -165,30 +165,59 @@ __device__ __forceinline__ bool folded(int ncols) {
   return Tr<T>::PARTS == 2 && 2 * ncols <= kMaxCols;
 }
 
-template <typename T, int RT, int NB>
+// DEPTH = batches of 8 KB a wave keeps in flight (1, or 2 for launches with few waves per CU).
+template <typename T, int RT, int NB, int DEPTH>
 __device__ __forceinline__ void gemm_loop(const u32x4* const (&w)[RT], const u32x4* const (&xp)[NB], bool colok, int nkt,
                                           f32x4 (&acc)[RT]) {
-  constexpr int U = 8 / RT;  // k-tiles in flight per wave (8 KB of weights)
+  constexpr int UB = 8 / RT;      // k-tiles per batch (8 KB of weights)
+  constexpr int U = UB * DEPTH;   // k-tiles in flight per wave
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, NW = blockDim.x >> 6;
   const u32x4* wp[RT];
 #pragma unroll
   for (int r = 0; r < RT; ++r) wp[r] = w[r] + lane;
   const u32x4 zero = {0u, 0u, 0u, 0u};
   int kt = wave;
-  for (; kt + (U - 1) * NW < nkt; kt += U * NW) {
-    u32x4 a[RT][U], b[NB][U];
+  if (DEPTH > 1) {
+    for (; kt + (U - 1) * NW < nkt; kt += U * NW) {
+      u32x4 a[RT][U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
+      for (int u = 0; u < U; ++u) {
+#pragma unroll
+        for (int r = 0; r < RT; ++r) a[r][u] = __builtin_nontemporal_load(wp[r] + (size_t)(kt + u * NW) * 64);
+      }
+#pragma unroll
+      for (int s = 0; s < DEPTH; ++s) {
+        u32x4 b[NB][UB];
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+#pragma unroll
+          for (int q = 0; q < NB; ++q) b[q][u] = colok ? xp[q][(size_t)(kt + (s * UB + u) * NW) * 4] : zero;
+        }
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+#pragma unroll
+          for (int r = 0; r < RT; ++r) {
+#pragma unroll
+            for (int q = 0; q < NB; ++q) mma<T>(acc[r], a[r][s * UB + u], b[q][u]);
+          }
+        }
+      }
+    }
+  }
+  for (; kt + (UB - 1) * NW < nkt; kt += UB * NW) {
+    u32x4 a[RT][UB], b[NB][UB];
+#pragma unroll
+    for (int u = 0; u < UB; ++u) {
 #pragma unroll
       for (int r = 0; r < RT; ++r) a[r][u] = __builtin_nontemporal_load(wp[r] + (size_t)(kt + u * NW) * 64);
     }
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
+    for (int u = 0; u < UB; ++u) {
 #pragma unroll
       for (int q = 0; q < NB; ++q) b[q][u] = colok ? xp[q][(size_t)(kt + u * NW) * 4] : zero;
     }
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
+    for (int u = 0; u < UB; ++u) {
 #pragma unroll
       for (int r = 0; r < RT; ++r) {
 #pragma unroll
@@ -209,7 +238,7 @@ __device__ __forceinline__ void gemm_loop(const u32x4* const (&w)[RT], const u32
   }
 }
 
-template <typename T, int RT>
+template <typename T, int RT, int DEPTH = 1>
 __device__ __forceinline__ void gemm_accumulate(const u32x4* const (&w)[RT], const T* __restrict__ x, int K, int ncols,
                                                 f32x4 (&acc)[RT]) {
   constexpr int EPL = Tr<T>::EPL, KT = Tr<T>::KT, PARTS = Tr<T>::PARTS;
@@ -224,12 +253,12 @@ __device__ __forceinline__ void gemm_accumulate(const u32x4* const (&w)[RT], con
     const bool colok = src < ncols;
     const u32x4* const xp[1] = {
         reinterpret_cast<const u32x4*>(x + (is_lo ? part : 0) + (size_t)(colok ? src : 0) * K + kg * EPL)};
-    gemm_loop<T, RT, 1>(w, xp, colok, nkt, acc);
+    gemm_loop<T, RT, 1, DEPTH>(w, xp, colok, nkt, acc);
   } else {
     const bool colok = col < ncols;
     const T* base = x + (size_t)(colok ? col : 0) * K + kg * EPL;
     const u32x4* const xp[2] = {reinterpret_cast<const u32x4*>(base), reinterpret_cast<const u32x4*>(base + part)};
-    gemm_loop<T, RT, 2>(w, xp, colok, nkt, acc);
+    gemm_loop<T, RT, 2, DEPTH>(w, xp, colok, nkt, acc);
   }
 }
 
@@ -278,6 +307,53 @@ __device__ __forceinline__ void compute_rstd(const float* __restrict__ ssp, int 
   __syncthreads();
 }
 
+// The same quantity with its loads issued BEFORE the weight stream of the workgroup starts and
+// its arithmetic done after: the L2 latency of the partial sums then hides behind the stream
+// instead of sitting in the tail of the kernel.  Covers d <= 4096 and up to two columns per
+// wave (the common cases); otherwise rstd_finish falls back to compute_rstd.  Same summation
+// order as compute_rstd, so both give identical bits.
+struct RstdPre {
+  float v[2][4];
+  bool fast;
+};
+
+__device__ __forceinline__ void rstd_issue(const float* __restrict__ ssp, int ntile, int ncols, RstdPre& p) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, NW = blockDim.x >> 6;
+  p.fast = ntile <= 256 && ncols <= 2 * NW;
+  if (!p.fast) return;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int col = wave + i * NW;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int t = lane + 64 * j;
+      p.v[i][j] = (col < ncols && t < ntile) ? ssp[col * ntile + t] : 0.f;
+    }
+  }
+}
+
+// Ends with a barrier unless the caller's reduce_waves provides one (NW > 1).
+__device__ __forceinline__ void rstd_finish(const float* __restrict__ ssp, int ntile, int ncols, float inv_d, float eps,
+                                            const RstdPre& p, float* s_rstd) {
+  if (!p.fast) {
+    compute_rstd(ssp, ntile, ncols, inv_d, eps, s_rstd);
+    return;
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, NW = blockDim.x >> 6;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int col = wave + i * NW;
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (lane + 64 * j < ntile) s += p.v[i][j];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    if (lane == 0 && col < ncols) s_rstd[col] = 1.0f / sqrtf(s * inv_d + eps);
+  }
+  if (NW == 1) __syncthreads();
+}
+
 extern __shared__ f32x4 dyn_red[];
 
 // ------------------------------------------------------------------------------------------
@@ -299,8 +375,9 @@ struct QkvArgs {
   float inv_d, eps;
 };
 
-template <typename T>
-__global__ __launch_bounds__(1024) void qkv_kernel(QkvArgs a, Cols c) {
+// DEPTH 2 is launched with at most 512 threads, which leaves it twice the registers.
+template <typename T, int DEPTH>
+__global__ __launch_bounds__(DEPTH > 1 ? 512 : 1024) void qkv_kernel(QkvArgs a, Cols c) {
   __shared__ float s_rstd[kMaxCols];
   const int KT = Tr<T>::KT;
   const int nkt = a.d / KT;
@@ -312,35 +389,45 @@ __global__ __launch_bounds__(1024) void qkv_kernel(QkvArgs a, Cols c) {
   const u32x4* wl = a.w + (size_t)li * a.w_layer_stride;
   const u32x4* const w[2] = {wl + (size_t)rt0 * nkt * 64, wl + (size_t)rt1 * nkt * 64};
   const T* x = reinterpret_cast<const T*>(a.x) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.d;
-  f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-  gemm_accumulate<T, 2>(w, x, a.d, c.n, acc);
-  compute_rstd(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, s_rstd);
-  if (!reduce_waves<2>(acc, dyn_red)) return;
-  fold_columns<T, 2>(acc, c.n);
-
+  // operands of the epilogue (wave 0 only) and of the norm scale are fetched before the weight
+  // stream starts, so that their latency does not sit in the tail of the kernel
   const int lane = threadIdx.x & 63, col = lane & 15;
-  if (col >= c.n) return;
-  const float r = s_rstd[col];
-  const int pos = c.pos[col], seq = c.seq[col];
   const int e0 = p * 16 + (lane >> 4) * 4;  // element inside the head, < hd/2
   const int half = a.hd / 2;
   const int RQKV = (a.Hq + 2 * a.Hkv) * a.hd;
+  const bool epi = threadIdx.x < 64 && col < c.n;
+  const int pos = epi ? c.pos[col] : 0, seq = epi ? c.seq[col] : 0;
+  f32x4 b_lo = {0.f, 0.f, 0.f, 0.f}, b_hi = {0.f, 0.f, 0.f, 0.f}, cs01 = {1.f, 0.f, 1.f, 0.f}, cs23 = {1.f, 0.f, 1.f, 0.f};
+  if (epi) {
+    if (a.bias) {
+      b_lo = *reinterpret_cast<const f32x4*>(a.bias + (size_t)li * RQKV + head * a.hd + e0);
+      b_hi = *reinterpret_cast<const f32x4*>(a.bias + (size_t)li * RQKV + head * a.hd + e0 + half);
+    }
+    if (head < a.Hq + a.Hkv) {
+      const f32x4* rp = reinterpret_cast<const f32x4*>(a.rope + (size_t)pos * half + e0);  // 4 x (cos, sin)
+      cs01 = rp[0];
+      cs23 = rp[1];
+    }
+  }
+  RstdPre pre;
+  rstd_issue(a.ssp, a.d / 16, c.n, pre);
+
+  f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+  gemm_accumulate<T, 2, DEPTH>(w, x, a.d, c.n, acc);
+  rstd_finish(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
+  if (!reduce_waves<2>(acc, dyn_red)) return;
+  fold_columns<T, 2>(acc, c.n);
+
+  if (col >= c.n) return;
+  const float r = s_rstd[col];
+  const float cosv[4] = {cs01[0], cs01[2], cs23[0], cs23[2]}, sinv[4] = {cs01[1], cs01[3], cs23[1], cs23[3]};
   float lo[4], hi[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    float v0 = acc[0][i] * r, v1 = acc[1][i] * r;
-    if (a.bias) {
-      v0 += a.bias[(size_t)li * RQKV + head * a.hd + e0 + i];
-      v1 += a.bias[(size_t)li * RQKV + head * a.hd + e0 + i + half];
-    }
-    if (head < a.Hq + a.Hkv) {
-      const float2 cs = a.rope[(size_t)pos * half + e0 + i];
-      lo[i] = v0 * cs.x - v1 * cs.y;
-      hi[i] = v1 * cs.x + v0 * cs.y;
-    } else {
-      lo[i] = v0;
-      hi[i] = v1;
-    }
+    // identity rotation (cos 1, sin 0) for the V rows; bias 0 without bias
+    const float v0 = acc[0][i] * r + b_lo[i], v1 = acc[1][i] * r + b_hi[i];
+    lo[i] = v0 * cosv[i] - v1 * sinv[i];
+    hi[i] = v1 * cosv[i] + v0 * sinv[i];
   }
   if (head < a.Hq) {
     float* q = a.q + ((size_t)li * kMaxCols + col) * (a.Hq * a.hd) + head * a.hd + e0;
@@ -377,22 +464,29 @@ struct ProjArgs {
   float* ssp;
 };
 
-template <typename T>
-__global__ __launch_bounds__(1024) void proj_resid_kernel(ProjArgs a, Cols c) {
+template <typename T, int DEPTH>
+__global__ __launch_bounds__(DEPTH > 1 ? 512 : 1024) void proj_resid_kernel(ProjArgs a, Cols c) {
   const int KT = Tr<T>::KT;
   const int nkt = a.K / KT;
   const int ntile = a.d / 16;
   const int li = blockIdx.x / ntile, t = blockIdx.x % ntile;
   const u32x4* const w[1] = {a.w + (size_t)li * a.w_layer_stride + (size_t)t * nkt * 64};
   const T* x = reinterpret_cast<const T*>(a.x) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.K;
-  f32x4 acc[1] = {{0.f, 0.f, 0.f, 0.f}};
-  gemm_accumulate<T, 1>(w, x, a.K, c.n, acc);
-  if (!reduce_waves<1>(acc, dyn_red)) return;
-  fold_columns<T, 1>(acc, c.n);
-
+  // residual-update operands (wave 0 of a layer-0 workgroup) are fetched before the weight stream
   const int lane = threadIdx.x & 63, col = lane & 15;
   const bool ok = col < c.n;
   const int r0 = t * 16 + (lane >> 4) * 4;
+  f32x4 h_in = {0.f, 0.f, 0.f, 0.f}, a_in = {0.f, 0.f, 0.f, 0.f}, g_in = {0.f, 0.f, 0.f, 0.f};
+  if (threadIdx.x < 64 && li == 0 && ok) {
+    h_in = *reinterpret_cast<const f32x4*>(a.H + (size_t)col * a.d + r0);
+    if (a.a_add >= 0) a_in = *reinterpret_cast<const f32x4*>(a.A + ((size_t)a.a_add * kMaxCols + col) * a.d + r0);
+    g_in = *reinterpret_cast<const f32x4*>(a.gain + r0);
+  }
+  f32x4 acc[1] = {{0.f, 0.f, 0.f, 0.f}};
+  gemm_accumulate<T, 1, DEPTH>(w, x, a.K, c.n, acc);
+  if (!reduce_waves<1>(acc, dyn_red)) return;
+  fold_columns<T, 1>(acc, c.n);
+
   if (li > 0) {
     if (ok) store4<float>(a.A + ((size_t)li * kMaxCols + col) * a.d + r0, acc[0][0], acc[0][1], acc[0][2], acc[0][3]);
     return;
@@ -400,12 +494,12 @@ __global__ __launch_bounds__(1024) void proj_resid_kernel(ProjArgs a, Cols c) {
   float ss = 0.f;
   if (ok) {
     float* hp = a.H + (size_t)col * a.d + r0;
-    f32x4 h = *reinterpret_cast<const f32x4*>(hp);
+    f32x4 h = h_in;
     h += acc[0];
-    if (a.a_add >= 0) h += *reinterpret_cast<const f32x4*>(a.A + ((size_t)a.a_add * kMaxCols + col) * a.d + r0);
+    if (a.a_add >= 0) h += a_in;
     *reinterpret_cast<f32x4*>(hp) = h;
     for (int j = 0; j < a.n_gain; ++j) {
-      const f32x4 g = *reinterpret_cast<const f32x4*>(a.gain + (size_t)j * a.d + r0);
+      const f32x4 g = j == 0 ? g_in : *reinterpret_cast<const f32x4*>(a.gain + (size_t)j * a.d + r0);
       T* xo = reinterpret_cast<T*>(a.xout) + ((size_t)j * Tr<T>::PARTS * kMaxCols + col) * a.d + r0;
       store_act4<T>(xo, (size_t)kMaxCols * a.d, h[0] * g[0], h[1] * g[1], h[2] * g[2], h[3] * g[3]);
     }
@@ -435,9 +529,11 @@ __global__ __launch_bounds__(1024) void gateup_kernel(GateUpArgs a, Cols c) {
   const int nkt = a.d / Tr<T>::KT;
   const int t = blockIdx.x;
   const u32x4* const w[2] = {a.wg + (size_t)t * nkt * 64, a.wu + (size_t)t * nkt * 64};
+  RstdPre pre;
+  rstd_issue(a.ssp, a.d / 16, c.n, pre);
   f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
   gemm_accumulate<T, 2>(w, reinterpret_cast<const T*>(a.x), a.d, c.n, acc);
-  compute_rstd(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, s_rstd);
+  rstd_finish(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
   if (!reduce_waves<2>(acc, dyn_red)) return;
   fold_columns<T, 2>(acc, c.n);
   const int lane = threadIdx.x & 63, col = lane & 15;
@@ -475,9 +571,11 @@ __global__ __launch_bounds__(1024) void head_kernel(HeadArgs a, Cols c) {
   const int nkt = a.d / Tr<T>::KT;
   const int t = blockIdx.x;
   const u32x4* const w[1] = {a.w + (size_t)t * nkt * 64};
+  RstdPre pre;
+  rstd_issue(a.ssp, a.d / 16, c.n, pre);
   f32x4 acc[1] = {{0.f, 0.f, 0.f, 0.f}};
   gemm_accumulate<T, 1>(w, reinterpret_cast<const T*>(a.x), a.d, c.n, acc);
-  compute_rstd(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, s_rstd);
+  rstd_finish(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
   if (!reduce_waves<1>(acc, dyn_red)) return;
   fold_columns<T, 1>(acc, c.n);
   const int lane = threadIdx.x & 63, col = lane & 15;
@@ -619,13 +717,13 @@ template <typename T, int HD>
 struct AttnGeom {
   static constexpr int EPL = Tr<T>::EPL, LPS = HD / EPL, SPW = 64 / LPS;
   static constexpr int WAVE_SLOTS = kAttnIT * SPW;    // slots one wave covers per batch
-  static constexpr int BLOCK_SLOTS = 4 * WAVE_SLOTS;  // chunk sizes are multiples of this
+  static constexpr int BLOCK_SLOTS = 4 * WAVE_SLOTS;  // chunk sizes are multiples of this (4-wave launches)
 };
 
 extern __shared__ float dyn_f[];
 
 template <typename T, int HD, int G>
-__global__ __launch_bounds__(256) void attn_kernel(AttnArgs a, Cols c) {
+__global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
   typedef AttnGeom<T, HD> Geo;
   constexpr int EPL = Geo::EPL, LPS = Geo::LPS, SPW = Geo::SPW, IT = kAttnIT;
   const int chunk = blockIdx.x, kvh = blockIdx.y;
@@ -635,7 +733,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a, Cols c) {
   if (s0 >= n_slots) return;
   const int s1 = min(s0 + a.CH, n_slots);
   const int nch = (n_slots + a.CH - 1) / a.CH;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, NWV = blockDim.x >> 6;  // 4 or 8 waves
   const int sub = lane / LPS, e0 = (lane % LPS) * EPL;
 
   const size_t rowbase = (((size_t)(a.layer0 + li) * a.B + c.seq[col]) * a.Hkv + kvh) * (size_t)a.max_ctx;
@@ -657,7 +755,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a, Cols c) {
   }
 
   const u32x4 zero = {0u, 0u, 0u, 0u};
-  for (int base = s0 + wave * Geo::WAVE_SLOTS; base < s1; base += Geo::BLOCK_SLOTS) {  // wave-uniform
+  for (int base = s0 + wave * Geo::WAVE_SLOTS; base < s1; base += NWV * Geo::WAVE_SLOTS) {  // wave-uniform
     u32x4 kr[IT], vr[IT];
 #pragma unroll
     for (int j = 0; j < IT; ++j) {
@@ -725,9 +823,9 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a, Cols c) {
       for (int e = 0; e < EPL; ++e) acc[g][e] += __shfl_xor(acc[g][e], off, 64);
     }
   }
-  float* w_acc = dyn_f;                 // [4][G][HD]
-  float* w_m = dyn_f + 4 * G * HD;      // [4][G]
-  float* w_l = w_m + 4 * G;             // [4][G]
+  float* w_acc = dyn_f;                 // [NWV][G][HD]
+  float* w_m = dyn_f + NWV * G * HD;    // [NWV][G]
+  float* w_l = w_m + NWV * G;           // [NWV][G]
   if (sub == 0) {
 #pragma unroll
     for (int g = 0; g < G; ++g)
@@ -744,12 +842,12 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a, Cols c) {
   __syncthreads();
 
   const size_t arow = (size_t)li * kMaxCols + col;
-  for (int idx = tid; idx < G * HD; idx += 256) {
+  for (int idx = tid; idx < G * HD; idx += blockDim.x) {
     const int g = idx / HD, e = idx % HD;
-    float m = fmaxf(fmaxf(w_m[g], w_m[G + g]), fmaxf(w_m[2 * G + g], w_m[3 * G + g]));
+    float m = w_m[g];
+    for (int w = 1; w < NWV; ++w) m = fmaxf(m, w_m[w * G + g]);
     float l = 0.f, o = 0.f;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
+    for (int w = 0; w < NWV; ++w) {
       const float wgt = __expf(w_m[w * G + g] - m);
       l += w_l[w * G + g] * wgt;
       o += w_acc[(w * G + g) * HD + e] * wgt;
@@ -785,6 +883,19 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, Cols c) {
   if (nch == 1) return;
   const int G = a.Hq / a.Hkv, HQ = a.Hq * HD;
   const size_t arow = (size_t)li * kMaxCols + col;
+  // every load of the kernel is issued up front: the first 16 chunk partials of this thread's
+  // output elements (all of them for contexts up to 16 chunks) together with the chunk maxima
+  // and sums, so that the kernel costs one memory latency, not three
+  constexpr int EPT = (8 * HD + 255) / 256;  // output elements per thread, at most (G <= 8)
+  float pv[EPT][16];
+#pragma unroll
+  for (int k = 0; k < EPT; ++k) {
+    const int idx = tid + 256 * k;
+    const int g = idx / HD, e = idx % HD;
+    const float* po = a.PO + (arow * a.Hq + kvh * G + g) * kMaxChunks * HD + e;
+#pragma unroll
+    for (int u = 0; u < 16; ++u) pv[k][u] = (idx < G * HD && u < nch) ? po[(size_t)u * HD] : 0.f;
+  }
   for (int g = wave; g < G; g += 4) {  // one wave per head, one lane per chunk
     const size_t row = arow * a.Hq + kvh * G + g;
     const float pm = lane < nch ? a.PM[row * kMaxChunks + lane] : -INFINITY;
@@ -795,24 +906,28 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, Cols c) {
     const float wgt = __expf(pm - m);
     s_w[g][lane] = wgt;
     // sum in chunk order so that the result does not depend on the reduction tree
-    float l = pl * wgt;
-    s_l[g] = 0.f;  // placeholder, written below by lane 0
+    const float l = pl * wgt;
     float tot = 0.f;
     for (int ch = 0; ch < nch; ++ch) tot += __shfl(l, ch, 64);
     if (lane == 0) s_l[g] = tot;
   }
   __syncthreads();
-  for (int idx = tid; idx < G * HD; idx += 256) {
+#pragma unroll
+  for (int k = 0; k < EPT; ++k) {
+    const int idx = tid + 256 * k;
+    if (idx >= G * HD) break;
     const int g = idx / HD, e = idx % HD;
     const int head = kvh * G + g;
     const float* po = a.PO + (arow * a.Hq + head) * kMaxChunks * HD + e;
     float o = 0.f;
-    for (int c0 = 0; c0 < nch; c0 += 8) {
-      float pv[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) pv[u] = c0 + u < nch ? po[(size_t)(c0 + u) * HD] : 0.f;  // independent loads
+    for (int u = 0; u < 16; ++u) o += pv[k][u] * (u < nch ? s_w[g][u] : 0.f);
+    for (int c0 = 16; c0 < nch; c0 += 8) {
+      float pw[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) o += pv[u] * (c0 + u < nch ? s_w[g][c0 + u] : 0.f);
+      for (int u = 0; u < 8; ++u) pw[u] = c0 + u < nch ? po[(size_t)(c0 + u) * HD] : 0.f;  // independent loads
+#pragma unroll
+      for (int u = 0; u < 8; ++u) o += pw[u] * (c0 + u < nch ? s_w[g][c0 + u] : 0.f);
     }
     store_act1<T>(reinterpret_cast<T*>(a.AO) + ((size_t)li * Tr<T>::PARTS * kMaxCols + col) * HQ + head * HD + e,
                   (size_t)kMaxCols * HQ, o / s_l[g]);
@@ -927,19 +1042,27 @@ void launch_qkv(const Shape& s, const Buffers& b, const Cols& c, int layer0, int
   a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
   const int grid = n_set * (s.Hq + 2 * s.Hkv) * (s.hd / 32);
   const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
-  const int nw = pick_waves(4, nkt, "EASYSPEC_NW_QKV");
-  DISPATCH_T(s.dtype, hipLaunchKernelGGL(qkv_kernel<T>, dim3(grid), dim3(64 * nw), red_bytes(nw, 2), st, a, c));
+  // few workgroups (a set of one layer): more waves; EASYSPEC_DEEP=1 also doubles the batches in
+  // flight per wave (measured slower at the 8B shape: the extra registers cost occupancy)
+  const bool sparse = grid < 512;
+  const int nw = pick_waves(sparse ? 8 : 4, nkt, "EASYSPEC_NW_QKV");
+  if (sparse && env_int("EASYSPEC_DEEP", 0)) {
+    DISPATCH_T(s.dtype, hipLaunchKernelGGL((qkv_kernel<T, 2>), dim3(grid), dim3(64 * nw), red_bytes(nw, 2), st, a, c));
+  } else {
+    DISPATCH_T(s.dtype, hipLaunchKernelGGL((qkv_kernel<T, 1>), dim3(grid), dim3(64 * nw), red_bytes(nw, 2), st, a, c));
+  }
 }
 
 template <typename T, int HD>
-static void launch_attn_g(int G, dim3 grid, hipStream_t st, const AttnArgs& a, const Cols& c) {
-  const size_t lds = (size_t)(4 * G * HD + 8 * G) * sizeof(float);
+static void launch_attn_g(int G, dim3 grid, int nwv, hipStream_t st, const AttnArgs& a, const Cols& c) {
+  const size_t lds = (size_t)(nwv * G * HD + 2 * nwv * G) * sizeof(float);
+  const dim3 blk(64 * nwv);
   switch (G) {
-    case 1: hipLaunchKernelGGL((attn_kernel<T, HD, 1>), grid, dim3(256), lds, st, a, c); break;
-    case 2: hipLaunchKernelGGL((attn_kernel<T, HD, 2>), grid, dim3(256), lds, st, a, c); break;
-    case 4: hipLaunchKernelGGL((attn_kernel<T, HD, 4>), grid, dim3(256), lds, st, a, c); break;
-    case 7: hipLaunchKernelGGL((attn_kernel<T, HD, 7>), grid, dim3(256), lds, st, a, c); break;
-    case 8: hipLaunchKernelGGL((attn_kernel<T, HD, 8>), grid, dim3(256), lds, st, a, c); break;
+    case 1: hipLaunchKernelGGL((attn_kernel<T, HD, 1>), grid, blk, lds, st, a, c); break;
+    case 2: hipLaunchKernelGGL((attn_kernel<T, HD, 2>), grid, blk, lds, st, a, c); break;
+    case 4: hipLaunchKernelGGL((attn_kernel<T, HD, 4>), grid, blk, lds, st, a, c); break;
+    case 7: hipLaunchKernelGGL((attn_kernel<T, HD, 7>), grid, blk, lds, st, a, c); break;
+    case 8: hipLaunchKernelGGL((attn_kernel<T, HD, 8>), grid, blk, lds, st, a, c); break;
     default: break;  // rejected at create
   }
 }
@@ -957,9 +1080,12 @@ void launch_attn(const Shape& s, const Buffers& b, const Cols& c, int layer0, in
   a.scale = 1.0f / sqrtf((float)s.hd);
   const int G = s.Hq / s.Hkv;
   const dim3 grid(n_chunks, s.Hkv, n_set * c.n);
+  // one chunk per context: eight waves share the whole context of a (layer, column, KV head) and
+  // no merge launch is needed; several chunks: four waves per chunk
+  const int nwv = n_chunks == 1 ? 8 : 4;
   DISPATCH_T(s.dtype, {
-    if (s.hd == 128) launch_attn_g<T, 128>(G, grid, st, a, c);
-    else launch_attn_g<T, 64>(G, grid, st, a, c);
+    if (s.hd == 128) launch_attn_g<T, 128>(G, grid, nwv, st, a, c);
+    else launch_attn_g<T, 64>(G, grid, nwv, st, a, c);
   });
   if (n_chunks > 1) {
     const dim3 mgrid(n_set * c.n, s.Hkv);
@@ -984,8 +1110,13 @@ void launch_oproj(const Shape& s, const Buffers& b, const Cols& c, int layer0, i
   a.ssp = b.ssp;
   const int grid = n_set * (s.d / 16);
   const int nkt = s.HQ / (s.dtype == 1 ? 32 : 16);
-  const int nw = pick_waves(4, nkt, "EASYSPEC_NW_O");
-  DISPATCH_T(s.dtype, hipLaunchKernelGGL(proj_resid_kernel<T>, dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+  const bool sparse = grid < 512;
+  const int nw = pick_waves(sparse ? 8 : 4, nkt, "EASYSPEC_NW_O");
+  if (sparse && env_int("EASYSPEC_DEEP", 0)) {
+    DISPATCH_T(s.dtype, hipLaunchKernelGGL((proj_resid_kernel<T, 2>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+  } else {
+    DISPATCH_T(s.dtype, hipLaunchKernelGGL((proj_resid_kernel<T, 1>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+  }
 }
 
 void launch_gateup(const Shape& s, const Buffers& b, const Cols& c, int layer, hipStream_t st) {
@@ -1014,7 +1145,11 @@ void launch_down(const Shape& s, const Buffers& b, const Cols& c, int layer, int
   const int grid = s.d / 16;
   const int nkt = s.F / (s.dtype == 1 ? 32 : 16);
   const int nw = pick_waves(8, nkt, "EASYSPEC_NW_DOWN");
-  DISPATCH_T(s.dtype, hipLaunchKernelGGL(proj_resid_kernel<T>, dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+  if (env_int("EASYSPEC_DEEP", 0)) {  // d/16 workgroups only; off by default, see launch_qkv
+    DISPATCH_T(s.dtype, hipLaunchKernelGGL((proj_resid_kernel<T, 2>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+  } else {
+    DISPATCH_T(s.dtype, hipLaunchKernelGGL((proj_resid_kernel<T, 1>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+  }
 }
 
 void launch_head(const Shape& s, const Buffers& b, const Cols& c, float* logits_out, int32_t* tokens_out, hipStream_t st) {
