@@ -158,66 +158,38 @@ __device__ __forceinline__ void mma<float>(f32x4& acc, const u32x4& a, const u32
 // NB = B fragments (and MFMAs) per weight tile.  With two-term activations and at most 8
 // columns, the lo terms ride in MFMA columns ncols..2*ncols-1 of the same instruction
 // ("folded", NB = 1) and fold_columns() adds the two halves afterwards; with more columns the
-// hi and lo terms take one MFMA each (NB = 2).
+// hi and lo terms take one MFMA each (NB = 2).  A wave keeps one batch of 8 KB in flight; two
+// batches per wave were measured slower (the registers cost more occupancy than they hide).
 // ------------------------------------------------------------------------------------------
 template <typename T>
 __device__ __forceinline__ bool folded(int ncols) {
   return Tr<T>::PARTS == 2 && 2 * ncols <= kMaxCols;
 }
 
-// DEPTH = batches of 8 KB a wave keeps in flight (1, or 2 for launches with few waves per CU).
-template <typename T, int RT, int NB, int DEPTH>
+template <typename T, int RT, int NB>
 __device__ __forceinline__ void gemm_loop(const u32x4* const (&w)[RT], const u32x4* const (&xp)[NB], bool colok, int nkt,
                                           f32x4 (&acc)[RT]) {
-  constexpr int UB = 8 / RT;      // k-tiles per batch (8 KB of weights)
-  constexpr int U = UB * DEPTH;   // k-tiles in flight per wave
+  constexpr int U = 8 / RT;  // k-tiles per batch: 8 KB of weights in flight per wave
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, NW = blockDim.x >> 6;
   const u32x4* wp[RT];
 #pragma unroll
   for (int r = 0; r < RT; ++r) wp[r] = w[r] + lane;
   const u32x4 zero = {0u, 0u, 0u, 0u};
   int kt = wave;
-  if (DEPTH > 1) {
-    for (; kt + (U - 1) * NW < nkt; kt += U * NW) {
-      u32x4 a[RT][U];
+  for (; kt + (U - 1) * NW < nkt; kt += U * NW) {
+    u32x4 a[RT][U], b[NB][U];
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-#pragma unroll
-        for (int r = 0; r < RT; ++r) a[r][u] = __builtin_nontemporal_load(wp[r] + (size_t)(kt + u * NW) * 64);
-      }
-#pragma unroll
-      for (int s = 0; s < DEPTH; ++s) {
-        u32x4 b[NB][UB];
-#pragma unroll
-        for (int u = 0; u < UB; ++u) {
-#pragma unroll
-          for (int q = 0; q < NB; ++q) b[q][u] = colok ? xp[q][(size_t)(kt + (s * UB + u) * NW) * 4] : zero;
-        }
-#pragma unroll
-        for (int u = 0; u < UB; ++u) {
-#pragma unroll
-          for (int r = 0; r < RT; ++r) {
-#pragma unroll
-            for (int q = 0; q < NB; ++q) mma<T>(acc[r], a[r][s * UB + u], b[q][u]);
-          }
-        }
-      }
-    }
-  }
-  for (; kt + (UB - 1) * NW < nkt; kt += UB * NW) {
-    u32x4 a[RT][UB], b[NB][UB];
-#pragma unroll
-    for (int u = 0; u < UB; ++u) {
+    for (int u = 0; u < U; ++u) {
 #pragma unroll
       for (int r = 0; r < RT; ++r) a[r][u] = __builtin_nontemporal_load(wp[r] + (size_t)(kt + u * NW) * 64);
     }
 #pragma unroll
-    for (int u = 0; u < UB; ++u) {
+    for (int u = 0; u < U; ++u) {
 #pragma unroll
       for (int q = 0; q < NB; ++q) b[q][u] = colok ? xp[q][(size_t)(kt + u * NW) * 4] : zero;
     }
 #pragma unroll
-    for (int u = 0; u < UB; ++u) {
+    for (int u = 0; u < U; ++u) {
 #pragma unroll
       for (int r = 0; r < RT; ++r) {
 #pragma unroll
@@ -225,20 +197,37 @@ __device__ __forceinline__ void gemm_loop(const u32x4* const (&w)[RT], const u32
       }
     }
   }
-  for (; kt < nkt; kt += NW) {
-    u32x4 b[NB];
+  if (kt < nkt) {
+    // last, partial batch: same shape with the loads past the end switched off (wave-uniform), so
+    // that the remaining tiles are still fetched together instead of one latency at a time
+    u32x4 a[RT][U], b[NB][U];
 #pragma unroll
-    for (int q = 0; q < NB; ++q) b[q] = colok ? xp[q][(size_t)kt * 4] : zero;
+    for (int u = 0; u < U; ++u) {
+      const bool in = kt + u * NW < nkt;
 #pragma unroll
-    for (int r = 0; r < RT; ++r) {
-      u32x4 a = __builtin_nontemporal_load(wp[r] + (size_t)kt * 64);
+      for (int r = 0; r < RT; ++r) a[r][u] = in ? __builtin_nontemporal_load(wp[r] + (size_t)(kt + u * NW) * 64) : zero;
+    }
 #pragma unroll
-      for (int q = 0; q < NB; ++q) mma<T>(acc[r], a, b[q]);
+    for (int u = 0; u < U; ++u) {
+      const bool in = colok && kt + u * NW < nkt;
+#pragma unroll
+      for (int q = 0; q < NB; ++q) b[q][u] = in ? xp[q][(size_t)(kt + u * NW) * 4] : zero;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int r = 0; r < RT; ++r) {
+#pragma unroll
+        for (int q = 0; q < NB; ++q) mma<T>(acc[r], a[r][u], b[q][u]);
+      }
     }
   }
 }
 
-template <typename T, int RT, int DEPTH = 1>
+// NB is chosen by the host per launch: 1 when the activations have one term (fp32) or the
+// columns fold (at most 8), else 2.  Separate instantiations keep the common one-fragment path
+// free of the second path's registers.
+template <typename T, int RT, int NB>
 __device__ __forceinline__ void gemm_accumulate(const u32x4* const (&w)[RT], const T* __restrict__ x, int K, int ncols,
                                                 f32x4 (&acc)[RT]) {
   constexpr int EPL = Tr<T>::EPL, KT = Tr<T>::KT, PARTS = Tr<T>::PARTS;
@@ -246,19 +235,19 @@ __device__ __forceinline__ void gemm_accumulate(const u32x4* const (&w)[RT], con
   const int col = lane & 15, kg = lane >> 4;
   const int nkt = K / KT;
   const size_t part = (size_t)kMaxCols * K;  // elements between the hi and lo arrays
-  if (PARTS == 1 || folded<T>(ncols)) {
+  if (NB == 1) {
     // lane column c < ncols reads the hi term of column c, column ncols + c its lo term
     const bool is_lo = PARTS == 2 && col >= ncols;
     const int src = is_lo ? col - ncols : col;
     const bool colok = src < ncols;
     const u32x4* const xp[1] = {
         reinterpret_cast<const u32x4*>(x + (is_lo ? part : 0) + (size_t)(colok ? src : 0) * K + kg * EPL)};
-    gemm_loop<T, RT, 1, DEPTH>(w, xp, colok, nkt, acc);
+    gemm_loop<T, RT, 1>(w, xp, colok, nkt, acc);
   } else {
     const bool colok = col < ncols;
     const T* base = x + (size_t)(colok ? col : 0) * K + kg * EPL;
     const u32x4* const xp[2] = {reinterpret_cast<const u32x4*>(base), reinterpret_cast<const u32x4*>(base + part)};
-    gemm_loop<T, RT, 2, DEPTH>(w, xp, colok, nkt, acc);
+    gemm_loop<T, RT, 2>(w, xp, colok, nkt, acc);
   }
 }
 
@@ -375,9 +364,8 @@ struct QkvArgs {
   float inv_d, eps;
 };
 
-// DEPTH 2 is launched with at most 512 threads, which leaves it twice the registers.
-template <typename T, int DEPTH>
-__global__ __launch_bounds__(DEPTH > 1 ? 512 : 1024) void qkv_kernel(QkvArgs a, Cols c) {
+template <typename T, int NB>
+__global__ __launch_bounds__(1024) void qkv_kernel(QkvArgs a, Cols c) {
   __shared__ float s_rstd[kMaxCols];
   const int KT = Tr<T>::KT;
   const int nkt = a.d / KT;
@@ -413,7 +401,7 @@ __global__ __launch_bounds__(DEPTH > 1 ? 512 : 1024) void qkv_kernel(QkvArgs a, 
   rstd_issue(a.ssp, a.d / 16, c.n, pre);
 
   f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-  gemm_accumulate<T, 2, DEPTH>(w, x, a.d, c.n, acc);
+  gemm_accumulate<T, 2, NB>(w, x, a.d, c.n, acc);
   rstd_finish(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
   if (!reduce_waves<2>(acc, dyn_red)) return;
   fold_columns<T, 2>(acc, c.n);
@@ -464,8 +452,8 @@ struct ProjArgs {
   float* ssp;
 };
 
-template <typename T, int DEPTH>
-__global__ __launch_bounds__(DEPTH > 1 ? 512 : 1024) void proj_resid_kernel(ProjArgs a, Cols c) {
+template <typename T, int NB>
+__global__ __launch_bounds__(1024) void proj_resid_kernel(ProjArgs a, Cols c) {
   const int KT = Tr<T>::KT;
   const int nkt = a.K / KT;
   const int ntile = a.d / 16;
@@ -483,7 +471,7 @@ __global__ __launch_bounds__(DEPTH > 1 ? 512 : 1024) void proj_resid_kernel(Proj
     g_in = *reinterpret_cast<const f32x4*>(a.gain + r0);
   }
   f32x4 acc[1] = {{0.f, 0.f, 0.f, 0.f}};
-  gemm_accumulate<T, 1, DEPTH>(w, x, a.K, c.n, acc);
+  gemm_accumulate<T, 1, NB>(w, x, a.K, c.n, acc);
   if (!reduce_waves<1>(acc, dyn_red)) return;
   fold_columns<T, 1>(acc, c.n);
 
@@ -523,7 +511,7 @@ struct GateUpArgs {
   float inv_d, eps;
 };
 
-template <typename T>
+template <typename T, int NB>
 __global__ __launch_bounds__(1024) void gateup_kernel(GateUpArgs a, Cols c) {
   __shared__ float s_rstd[kMaxCols];
   const int nkt = a.d / Tr<T>::KT;
@@ -532,7 +520,7 @@ __global__ __launch_bounds__(1024) void gateup_kernel(GateUpArgs a, Cols c) {
   RstdPre pre;
   rstd_issue(a.ssp, a.d / 16, c.n, pre);
   f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-  gemm_accumulate<T, 2>(w, reinterpret_cast<const T*>(a.x), a.d, c.n, acc);
+  gemm_accumulate<T, 2, NB>(w, reinterpret_cast<const T*>(a.x), a.d, c.n, acc);
   rstd_finish(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
   if (!reduce_waves<2>(acc, dyn_red)) return;
   fold_columns<T, 2>(acc, c.n);
@@ -565,7 +553,7 @@ struct HeadArgs {
 
 __device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
 
-template <typename T>
+template <typename T, int NB>
 __global__ __launch_bounds__(1024) void head_kernel(HeadArgs a, Cols c) {
   __shared__ float s_rstd[kMaxCols];
   const int nkt = a.d / Tr<T>::KT;
@@ -574,7 +562,7 @@ __global__ __launch_bounds__(1024) void head_kernel(HeadArgs a, Cols c) {
   RstdPre pre;
   rstd_issue(a.ssp, a.d / 16, c.n, pre);
   f32x4 acc[1] = {{0.f, 0.f, 0.f, 0.f}};
-  gemm_accumulate<T, 1>(w, reinterpret_cast<const T*>(a.x), a.d, c.n, acc);
+  gemm_accumulate<T, 1, NB>(w, reinterpret_cast<const T*>(a.x), a.d, c.n, acc);
   rstd_finish(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
   if (!reduce_waves<1>(acc, dyn_red)) return;
   fold_columns<T, 1>(acc, c.n);
@@ -1003,6 +991,16 @@ static int pick_waves(int dflt, int nkt, const char* env) {
 
 static size_t red_bytes(int nw, int rt) { return (size_t)(nw > 1 ? nw - 1 : 0) * rt * 64 * sizeof(f32x4); }
 
+// bf16 with more than 8 columns: hi and lo activation terms take a fragment each
+static bool two_fragments(int dtype, const Cols& c) { return dtype == 1 && 2 * c.n > kMaxCols; }
+
+#define DISPATCH_TNB(dtype, two, ...)                                         \
+  do {                                                                        \
+    if ((dtype) == 1 && (two)) { typedef bf16_t T; constexpr int NB = 2; __VA_ARGS__; } \
+    else if ((dtype) == 1) { typedef bf16_t T; constexpr int NB = 1; __VA_ARGS__; }     \
+    else { typedef float T; constexpr int NB = 1; __VA_ARGS__; }              \
+  } while (0)
+
 #define DISPATCH_T(dtype, ...)                    \
   do {                                            \
     if ((dtype) == 1) { typedef bf16_t T; __VA_ARGS__; } \
@@ -1042,15 +1040,10 @@ void launch_qkv(const Shape& s, const Buffers& b, const Cols& c, int layer0, int
   a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
   const int grid = n_set * (s.Hq + 2 * s.Hkv) * (s.hd / 32);
   const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
-  // few workgroups (a set of one layer): more waves; EASYSPEC_DEEP=1 also doubles the batches in
-  // flight per wave (measured slower at the 8B shape: the extra registers cost occupancy)
-  const bool sparse = grid < 512;
-  const int nw = pick_waves(sparse ? 8 : 4, nkt, "EASYSPEC_NW_QKV");
-  if (sparse && env_int("EASYSPEC_DEEP", 0)) {
-    DISPATCH_T(s.dtype, hipLaunchKernelGGL((qkv_kernel<T, 2>), dim3(grid), dim3(64 * nw), red_bytes(nw, 2), st, a, c));
-  } else {
-    DISPATCH_T(s.dtype, hipLaunchKernelGGL((qkv_kernel<T, 1>), dim3(grid), dim3(64 * nw), red_bytes(nw, 2), st, a, c));
-  }
+  // few workgroups (a set of one layer): more waves per workgroup
+  const int nw = pick_waves(grid < 512 ? 8 : 4, nkt, "EASYSPEC_NW_QKV");
+  DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
+               hipLaunchKernelGGL((qkv_kernel<T, NB>), dim3(grid), dim3(64 * nw), red_bytes(nw, 2), st, a, c));
 }
 
 template <typename T, int HD>
@@ -1110,13 +1103,9 @@ void launch_oproj(const Shape& s, const Buffers& b, const Cols& c, int layer0, i
   a.ssp = b.ssp;
   const int grid = n_set * (s.d / 16);
   const int nkt = s.HQ / (s.dtype == 1 ? 32 : 16);
-  const bool sparse = grid < 512;
-  const int nw = pick_waves(sparse ? 8 : 4, nkt, "EASYSPEC_NW_O");
-  if (sparse && env_int("EASYSPEC_DEEP", 0)) {
-    DISPATCH_T(s.dtype, hipLaunchKernelGGL((proj_resid_kernel<T, 2>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
-  } else {
-    DISPATCH_T(s.dtype, hipLaunchKernelGGL((proj_resid_kernel<T, 1>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
-  }
+  const int nw = pick_waves(grid < 512 ? 8 : 4, nkt, "EASYSPEC_NW_O");
+  DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
+               hipLaunchKernelGGL((proj_resid_kernel<T, NB>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
 }
 
 void launch_gateup(const Shape& s, const Buffers& b, const Cols& c, int layer, hipStream_t st) {
@@ -1129,7 +1118,8 @@ void launch_gateup(const Shape& s, const Buffers& b, const Cols& c, int layer, h
   const int grid = s.F / 16;
   const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
   const int nw = pick_waves(8, nkt, "EASYSPEC_NW_GU");
-  DISPATCH_T(s.dtype, hipLaunchKernelGGL(gateup_kernel<T>, dim3(grid), dim3(64 * nw), red_bytes(nw, 2), st, a, c));
+  DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
+               hipLaunchKernelGGL((gateup_kernel<T, NB>), dim3(grid), dim3(64 * nw), red_bytes(nw, 2), st, a, c));
 }
 
 void launch_down(const Shape& s, const Buffers& b, const Cols& c, int layer, int a_next, const float* gain, int n_gain,
@@ -1145,11 +1135,8 @@ void launch_down(const Shape& s, const Buffers& b, const Cols& c, int layer, int
   const int grid = s.d / 16;
   const int nkt = s.F / (s.dtype == 1 ? 32 : 16);
   const int nw = pick_waves(8, nkt, "EASYSPEC_NW_DOWN");
-  if (env_int("EASYSPEC_DEEP", 0)) {  // d/16 workgroups only; off by default, see launch_qkv
-    DISPATCH_T(s.dtype, hipLaunchKernelGGL((proj_resid_kernel<T, 2>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
-  } else {
-    DISPATCH_T(s.dtype, hipLaunchKernelGGL((proj_resid_kernel<T, 1>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
-  }
+  DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
+               hipLaunchKernelGGL((proj_resid_kernel<T, NB>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
 }
 
 void launch_head(const Shape& s, const Buffers& b, const Cols& c, float* logits_out, int32_t* tokens_out, hipStream_t st) {
@@ -1160,7 +1147,8 @@ void launch_head(const Shape& s, const Buffers& b, const Cols& c, float* logits_
   a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
   const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
   const int nw = pick_waves(4, nkt, "EASYSPEC_NW_HEAD");
-  DISPATCH_T(s.dtype, hipLaunchKernelGGL(head_kernel<T>, dim3(a.nblk), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+  DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
+               hipLaunchKernelGGL((head_kernel<T, NB>), dim3(a.nblk), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
   hipLaunchKernelGGL(argmax_final_kernel, dim3(c.n), dim3(1024), 0, st, a.cand_val, a.cand_idx, a.nblk, tokens_out, c);
 }
 
