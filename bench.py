@@ -43,6 +43,7 @@ def main():
     ap.add_argument("--workload", default="llama3_8b_ctx2048")
     ap.add_argument("--seed", type=int, default=2025)
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging; makes the result invalid)")
+    ap.add_argument("--group-size", type=int, default=0, help="override the workload's layer-parallel size N (1 = sequential)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="budget of the oracle baseline leg")
     ap.add_argument("--copy-mib", type=int, default=0,
@@ -68,6 +69,8 @@ def main():
         print("bench.py: batched long-context workload is a parity case, not a bench line", file=sys.stderr)
         sys.exit(2)
     over = {"n_layers": args.layers} if args.layers else {}
+    if args.group_size:
+        wl["group_size"] = args.group_size
     cfg = synth.model_shape(wl["model"], **over)
     gamma, ctx_len, B = wl["gamma"], wl["context"], 1
     M = gamma + 1
