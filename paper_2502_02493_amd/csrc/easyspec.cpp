@@ -9,7 +9,6 @@
 #include <stdlib.h>
 #include <string.h>
 
-#include <algorithm>
 #include <string>
 #include <vector>
 
@@ -28,16 +27,6 @@ struct easyspec_ctx {
   std::vector<int32_t> single;  // every layer alone (Alg. 1 order)
   std::vector<void*> allocs;
   int32_t last_rows;
-  // chained launches (one per set: O projection .. next QKV projection / LM head)
-  struct Program {
-    PhaseDesc* dev = nullptr;          // capacity 4 L + 2 phases
-    std::vector<int32_t> first, count; // per set
-  };
-  Program prog_groups, prog_single;
-  bool chain_on;
-  int32_t chain_grid, chain_threads;
-  ChainSync sync;
-  unsigned long long sync_next;  // barrier arrivals after everything launched so far
   // per-kernel timing (easyspec_profile_*)
   int32_t prof_op;
   size_t prof_used;
@@ -101,43 +90,6 @@ static int check_config(const easyspec_config* c) {
   return EASYSPEC_OK;
 }
 
-// The chained launches of a layer-parallel strategy: for every set, the phases that follow its
-// attention (O projection of the set; gate/up and down of each layer in order; then the QKV
-// projection of the next set, or the LM head).  Same operations, same order and same arguments
-// as the separate launches of forward().
-static int build_program(easyspec_ctx* ctx, const std::vector<int32_t>& bounds, easyspec_ctx::Program& prog) {
-  const Shape& s = ctx->s;
-  const Buffers& b = ctx->b;
-  std::vector<PhaseDesc> ph;
-  prog.first.clear();
-  prog.count.clear();
-  const int n_sets = (int)bounds.size() - 1;
-  for (int j = 0; j < n_sets; ++j) {
-    const int lo = bounds[j], hi = bounds[j + 1];
-    prog.first.push_back((int32_t)ph.size());
-    PhaseDesc d;
-    make_phase_oproj(s, b, lo, hi - lo, &d);
-    ph.push_back(d);
-    for (int i = lo; i < hi; ++i) {
-      make_phase_gateup(s, b, i, &d);
-      ph.push_back(d);
-      if (i + 1 < hi) make_phase_down(s, b, i, i + 1 - lo, b.g_mlp + (size_t)(i + 1) * s.d, 1, b.XM, &d);
-      else if (hi < s.L) make_phase_down(s, b, i, -1, b.g_attn + (size_t)hi * s.d, bounds[j + 2] - hi, b.XA, &d);
-      else make_phase_down(s, b, i, -1, b.g_final, 1, b.XA, &d);
-      ph.push_back(d);
-    }
-    if (hi < s.L) make_phase_qkv(s, b, hi, bounds[j + 2] - hi, &d);
-    else make_phase_head(s, b, &d);
-    ph.push_back(d);
-    prog.count.push_back((int32_t)ph.size() - prog.first.back());
-  }
-  if (ph.size() > 4 * (size_t)s.L + 2) return fail(ctx, EASYSPEC_EINVAL, "internal: phase program too long");
-  // launches that read the previous program must have finished
-  HIPCHK(ctx, hipStreamSynchronize(ctx->stream));
-  HIPCHK(ctx, hipMemcpy(prog.dev, ph.data(), ph.size() * sizeof(PhaseDesc), hipMemcpyHostToDevice));
-  return EASYSPEC_OK;
-}
-
 extern "C" int easyspec_create(const easyspec_config* cfg, void* hip_stream, easyspec_ctx** out) {
   if (!out) return fail(nullptr, EASYSPEC_EINVAL, "out is NULL");
   *out = nullptr;
@@ -154,8 +106,6 @@ extern "C" int easyspec_create(const easyspec_config* cfg, void* hip_stream, eas
   ctx->last_rows = 0;
   ctx->prof_op = -1;
   ctx->prof_used = 0;
-  ctx->sync.abort = nullptr;
-  ctx->chain_on = false;
   Shape& s = ctx->s;
   s.dtype = cfg->dtype; s.L = cfg->n_layers; s.d = cfg->d_model; s.Hq = cfg->n_q_heads; s.Hkv = cfg->n_kv_heads;
   s.hd = cfg->head_dim; s.F = cfg->d_ffn; s.V = cfg->vocab; s.HQ = s.Hq * s.hd; s.RQKV = (s.Hq + 2 * s.Hkv) * s.hd;
@@ -200,20 +150,6 @@ extern "C" int easyspec_create(const easyspec_config* cfg, void* hip_stream, eas
     const size_t nblk = (size_t)(s.V + 15) / 16;
     ALLOC(ctx, b.amax_val, kMaxCols * nblk * sizeof(float));
     ALLOC(ctx, b.amax_idx, kMaxCols * nblk * sizeof(int32_t));
-    const size_t prog_cap = 4 * (size_t)s.L + 2;
-    ALLOC(ctx, ctx->prog_groups.dev, prog_cap * sizeof(PhaseDesc));
-    ALLOC(ctx, ctx->prog_single.dev, prog_cap * sizeof(PhaseDesc));
-    ALLOC(ctx, ctx->sync.counters, (size_t)kSyncLanes * kSyncStride * sizeof(unsigned long long));
-    HIPCHK(ctx, hipMemsetAsync(ctx->sync.counters, 0, (size_t)kSyncLanes * kSyncStride * sizeof(unsigned long long), ctx->stream));
-    HIPCHK(ctx, hipHostMalloc((void**)&ctx->sync.abort, 64, hipHostMallocDefault));
-    *ctx->sync.abort = 0;
-    ctx->sync.base = 0;
-    ctx->sync_next = 0;
-    ctx->chain_threads = getenv("EASYSPEC_CHAIN_THREADS") ? atoi(getenv("EASYSPEC_CHAIN_THREADS")) : 512;
-    if (ctx->chain_threads != 256 && ctx->chain_threads != 512 && ctx->chain_threads != 1024) ctx->chain_threads = 512;
-    const int want = getenv("EASYSPEC_CHAIN_GRID") ? atoi(getenv("EASYSPEC_CHAIN_GRID")) : 1024;
-    ctx->chain_grid = std::min(want, chain_capacity(s.dtype, ctx->chain_threads));
-    ctx->chain_on = (getenv("EASYSPEC_CHAIN") ? atoi(getenv("EASYSPEC_CHAIN")) : 0) != 0 && ctx->chain_grid >= 1;
     HIPCHK(ctx, hipMemsetAsync(b.kc, 0, kv_bytes, ctx->stream));
     HIPCHK(ctx, hipMemsetAsync(b.vc, 0, kv_bytes, ctx->stream));
 
@@ -229,15 +165,12 @@ extern "C" int easyspec_create(const easyspec_config* cfg, void* hip_stream, eas
       }
     HIPCHK(ctx, hipMemcpy(b.rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice));
     HIPCHK(ctx, hipStreamSynchronize(ctx->stream));
-    rc = build_program(ctx, ctx->single, ctx->prog_single);
-    if (rc != EASYSPEC_OK) return rc;
-    return build_program(ctx, ctx->bounds, ctx->prog_groups);
+    return EASYSPEC_OK;
   };
   rc = body();
   if (rc != EASYSPEC_OK) {
     g_err = ctx->err;
     for (void* p : ctx->allocs) (void)hipFree(p);
-    if (ctx->sync.abort) (void)hipHostFree(ctx->sync.abort);
     delete ctx;
     return rc;
   }
@@ -250,7 +183,6 @@ extern "C" void easyspec_destroy(easyspec_ctx* ctx) {
   (void)hipStreamSynchronize(ctx->stream);
   for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
   for (void* p : ctx->allocs) (void)hipFree(p);
-  if (ctx->sync.abort) (void)hipHostFree(ctx->sync.abort);
   delete ctx;
 }
 
@@ -362,7 +294,7 @@ extern "C" int easyspec_set_groups(easyspec_ctx* ctx, const int32_t* bounds, int
     if (k > EASYSPEC_MAX_SET) return fail(ctx, EASYSPEC_EINVAL, "set_groups: set of %d layers exceeds %d", k, EASYSPEC_MAX_SET);
   }
   ctx->bounds.assign(bounds, bounds + n_sets + 1);
-  return build_program(ctx, ctx->bounds, ctx->prog_groups);
+  return EASYSPEC_OK;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -408,28 +340,16 @@ struct ProfScope {
 };
 
 static int forward(easyspec_ctx* ctx, const Cols& c, const int32_t* tokens, const std::vector<int32_t>& bounds,
-                   const easyspec_ctx::Program& prog, float* logits_out, int32_t* tokens_out) {
+                   float* logits_out, int32_t* tokens_out) {
   const Shape& s = ctx->s;
   const Buffers& b = ctx->b;
   hipStream_t st = ctx->stream;
   const int n_sets = (int)bounds.size() - 1;
-  if (*ctx->sync.abort) return fail(ctx, EASYSPEC_EHIP, "a grid barrier of an earlier launch timed out; results since then are invalid");
-  // The chained form needs the folded single-fragment kernels (at most 8 bf16 columns) and
-  // cannot be timed per operation.
-  const bool chain = ctx->chain_on && !(s.dtype == EASYSPEC_DTYPE_BF16 && 2 * c.n > kMaxCols) && ctx->prof_op < 0;
   launch_embed(s, b, c, tokens, 0, bounds[1] - bounds[0], st);
-  if (chain) launch_qkv(s, b, c, 0, bounds[1] - bounds[0], st);
   for (int j = 0; j < n_sets; ++j) {
     const int lo = bounds[j], hi = bounds[j + 1], k = hi - lo;
     int chunk, n_chunks;
     pick_chunk(s, c, k, &chunk, &n_chunks);
-    if (chain) {
-      launch_attn(s, b, c, lo, k, chunk, n_chunks, st);
-      ctx->sync.base = ctx->sync_next;
-      launch_chain(s, c, prog.dev + prog.first[j], prog.count[j], ctx->sync, logits_out, ctx->chain_grid, ctx->chain_threads, st);
-      ctx->sync_next += (unsigned long long)(prog.count[j] - 1) * ctx->chain_grid;
-      continue;
-    }
     // every attention layer of the set reads the hidden state that enters the set
     { ProfScope p(ctx, EASYSPEC_OP_QKV); launch_qkv(s, b, c, lo, k, st); }
     { ProfScope p(ctx, EASYSPEC_OP_ATTN); launch_attn(s, b, c, lo, k, chunk, n_chunks, st); }
@@ -447,8 +367,7 @@ static int forward(easyspec_ctx* ctx, const Cols& c, const int32_t* tokens, cons
       }
     }
   }
-  if (chain) launch_argmax(s, b, c, tokens_out, st);
-  else { ProfScope p(ctx, EASYSPEC_OP_HEAD); launch_head(s, b, c, logits_out, tokens_out, st); }
+  { ProfScope p(ctx, EASYSPEC_OP_HEAD); launch_head(s, b, c, logits_out, tokens_out, st); }
   HIPCHK(ctx, hipGetLastError());
   ctx->last_rows = c.n;
   return EASYSPEC_OK;
@@ -469,7 +388,7 @@ extern "C" int easyspec_draft_step(easyspec_ctx* ctx, const int32_t* tokens_in, 
     ++c.n;
   }
   if (c.n == 0) return fail(ctx, EASYSPEC_ESTATE, "draft_step: no live sequence (calibrate a prompt first)");
-  const int rc = forward(ctx, c, tokens_in, ctx->bounds, ctx->prog_groups, logits_out, tokens_out);
+  const int rc = forward(ctx, c, tokens_in, ctx->bounds, logits_out, tokens_out);
   if (rc != EASYSPEC_OK) return rc;
   for (int i = 0; i < c.n; ++i) ctx->fuzzy[c.seq[i]] += 1;
   return EASYSPEC_OK;
@@ -511,7 +430,7 @@ extern "C" int easyspec_calibrate(easyspec_ctx* ctx, const int32_t* tokens, cons
       ++b;
     }
     if (c.n == 0) continue;
-    const int rc = forward(ctx, c, tokens, ctx->single, ctx->prog_single, logits_out, next_token_out);
+    const int rc = forward(ctx, c, tokens, ctx->single, logits_out, next_token_out);
     if (rc != EASYSPEC_OK) return rc;
   }
   for (int q = 0; q < s.B; ++q)

@@ -75,37 +75,6 @@ void launch_down(const Shape& s, const Buffers& b, const Cols& c, int layer, int
                  int n_gain, void* xout, hipStream_t st);
 void launch_head(const Shape& s, const Buffers& b, const Cols& c, float* logits_out, int32_t* tokens_out,
                  hipStream_t st);
-void launch_argmax(const Shape& s, const Buffers& b, const Cols& c, int32_t* tokens_out, hipStream_t st);
-
-// Chained launch: the weight contractions between two attention launches as phases of one
-// launch of resident workgroups with grid barriers between the phases.  A phase descriptor
-// holds what the corresponding launch_* above would pass to its kernel; it depends on the
-// layer(s) only, not on the columns, so a program is built once per layer-parallel strategy
-// and kept in device memory.
-struct PhaseDesc {
-  alignas(8) unsigned char raw[128];
-};
-void make_phase_qkv(const Shape& s, const Buffers& b, int layer0, int n_set, PhaseDesc* out);
-void make_phase_oproj(const Shape& s, const Buffers& b, int layer0, int n_set, PhaseDesc* out);
-void make_phase_gateup(const Shape& s, const Buffers& b, int layer, PhaseDesc* out);
-void make_phase_down(const Shape& s, const Buffers& b, int layer, int a_next, const float* gain, int n_gain, void* xout,
-                     PhaseDesc* out);
-void make_phase_head(const Shape& s, const Buffers& b, PhaseDesc* out);  // logits pointer comes with the launch
-
-constexpr int kSyncLanes = 16;   // arrival counters of the grid barrier
-constexpr int kSyncStride = 16;  // distance between them in 8-byte words (a 128-byte line each)
-struct ChainSync {
-  unsigned long long* counters;  // [kSyncLanes * kSyncStride], device memory, zero at creation, only ever grows
-  int* abort;                    // host-visible flag: a barrier wait gave up (results are invalid)
-  unsigned long long base;       // sum of the counters before this launch
-};
-// Largest grid of `threads`-wide workgroups that is resident at once (0: query failed).
-int chain_capacity(int dtype, int threads);
-// Runs phases prog[0..n_phases) (device memory).  grid <= chain_capacity().  The barrier counters
-// advance by (n_phases - 1) * grid.
-void launch_chain(const Shape& s, const Cols& c, const PhaseDesc* prog, int n_phases, const ChainSync& sy, float* logits_out,
-                  int grid, int threads, hipStream_t st);
-
 void launch_accept(const int32_t* draft, const int32_t* target, int batch, int gamma, int32_t* accept_len,
                    int32_t* bonus, hipStream_t st);
 void launch_kv_copy(const Shape& s, const Buffers& b, int seq, void* k_user, void* v_user, int n_slots,

@@ -23,9 +23,6 @@
 // rsqrt(mean(h^2) + eps).  Both sides of the parity tests use this order of roundings.
 #include "kernels.h"
 
-#include <algorithm>
-#include <cstring>
-
 namespace es {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -154,84 +151,6 @@ __device__ __forceinline__ void mma<float>(f32x4& acc, const u32x4& a, const u32
 }
 
 // ------------------------------------------------------------------------------------------
-// Accesses to data that another workgroup of the SAME launch produces or consumes (COH = true;
-// only the chained launch, where grid-wide barriers replace launch boundaries).  The eight XCDs
-// have private, mutually incoherent L2 caches, and device-scope fences (L2 write-back /
-// invalidate) cost tens of microseconds here.  Instead such data moves through device-scope
-// relaxed atomic accesses of 4 or 8 bytes: the stores write through to memory, the loads bypass
-// stale cache lines, and no fence wider than the workgroup is needed around the barrier.
-// COH = false is the plain access for data that crosses a launch boundary.
-// ------------------------------------------------------------------------------------------
-typedef unsigned long long u64;
-
-template <bool COH>
-__device__ __forceinline__ float ld_f32(const float* p) {
-  return COH ? __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *p;
-}
-template <bool COH>
-__device__ __forceinline__ u32x4 ld_u32x4(const u32x4* p) {
-  if (!COH) return *p;
-  const u64* q = reinterpret_cast<const u64*>(p);
-  const u64 lo = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  const u64 hi = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  u32x4 v = {(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32)};
-  return v;
-}
-template <bool COH>
-__device__ __forceinline__ f32x4 ld_f32x4(const float* p) {
-  return __builtin_bit_cast(f32x4, ld_u32x4<COH>(reinterpret_cast<const u32x4*>(p)));
-}
-template <bool COH>
-__device__ __forceinline__ void st_f32(float* p, float v) {
-  if (COH) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  else *p = v;
-}
-template <bool COH>
-__device__ __forceinline__ void st_u32x2(void* p, u32x2 v) {
-  if (COH) __hip_atomic_store(reinterpret_cast<u64*>(p), (u64)v.x | ((u64)v.y << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  else *reinterpret_cast<u32x2*>(p) = v;
-}
-template <bool COH>
-__device__ __forceinline__ void st_f32x4(float* p, f32x4 v) {
-  if (COH) {
-    const u32x4 u = __builtin_bit_cast(u32x4, v);
-    st_u32x2<true>(p, u32x2{u.x, u.y});
-    st_u32x2<true>(p + 2, u32x2{u.z, u.w});
-  } else {
-    *reinterpret_cast<f32x4*>(p) = v;
-  }
-}
-// four consecutive elements of T (a KV-cache row fragment)
-template <typename T, bool COH>
-__device__ __forceinline__ void st_row4(T* p, float a, float b, float c, float d);
-template <>
-__device__ __forceinline__ void st_row4<float, false>(float* p, float a, float b, float c, float d) { store4<float>(p, a, b, c, d); }
-template <>
-__device__ __forceinline__ void st_row4<float, true>(float* p, float a, float b, float c, float d) { st_f32x4<true>(p, f32x4{a, b, c, d}); }
-template <>
-__device__ __forceinline__ void st_row4<bf16_t, false>(bf16_t* p, float a, float b, float c, float d) { store4<bf16_t>(p, a, b, c, d); }
-template <>
-__device__ __forceinline__ void st_row4<bf16_t, true>(bf16_t* p, float a, float b, float c, float d) {
-  st_u32x2<true>(p, u32x2{float_to_bf16_bits(a) | (float_to_bf16_bits(b) << 16), float_to_bf16_bits(c) | (float_to_bf16_bits(d) << 16)});
-}
-// four consecutive activation elements: hi array at p, lo array part elements later (bf16)
-template <typename T, bool COH>
-__device__ __forceinline__ void st_act4(T* p, size_t part, float a, float b, float c, float d);
-template <>
-__device__ __forceinline__ void st_act4<float, false>(float* p, size_t part, float a, float b, float c, float d) { store_act4<float>(p, part, a, b, c, d); }
-template <>
-__device__ __forceinline__ void st_act4<float, true>(float* p, size_t, float a, float b, float c, float d) { st_f32x4<true>(p, f32x4{a, b, c, d}); }
-template <>
-__device__ __forceinline__ void st_act4<bf16_t, false>(bf16_t* p, size_t part, float a, float b, float c, float d) { store_act4<bf16_t>(p, part, a, b, c, d); }
-template <>
-__device__ __forceinline__ void st_act4<bf16_t, true>(bf16_t* p, size_t part, float a, float b, float c, float d) {
-  const uint32_t ha = float_to_bf16_bits(a), hb = float_to_bf16_bits(b), hc = float_to_bf16_bits(c), hd = float_to_bf16_bits(d);
-  st_u32x2<true>(p, u32x2{ha | (hb << 16), hc | (hd << 16)});
-  st_row4<bf16_t, true>(p + part, a - bf16_bits_to_float(ha), b - bf16_bits_to_float(hb), c - bf16_bits_to_float(hc),
-                        d - bf16_bits_to_float(hd));
-}
-
-// ------------------------------------------------------------------------------------------
 // The shared core.  w[r]: first tile of row tile r (tiles of one row tile are consecutive,
 // 64 u32x4 each).  x: activations [part][col][K] in T.  The calling wave accumulates k-tiles
 // wave, wave+NW, ... into acc.
@@ -247,7 +166,7 @@ __device__ __forceinline__ bool folded(int ncols) {
   return Tr<T>::PARTS == 2 && 2 * ncols <= kMaxCols;
 }
 
-template <typename T, int RT, int NB, bool COH>
+template <typename T, int RT, int NB>
 __device__ __forceinline__ void gemm_loop(const u32x4* const (&w)[RT], const u32x4* const (&xp)[NB], bool colok, int nkt,
                                           f32x4 (&acc)[RT]) {
   constexpr int U = 8 / RT;  // k-tiles per batch: 8 KB of weights in flight per wave
@@ -267,7 +186,7 @@ __device__ __forceinline__ void gemm_loop(const u32x4* const (&w)[RT], const u32
 #pragma unroll
     for (int u = 0; u < U; ++u) {
 #pragma unroll
-      for (int q = 0; q < NB; ++q) b[q][u] = colok ? ld_u32x4<COH>(xp[q] + (size_t)(kt + u * NW) * 4) : zero;
+      for (int q = 0; q < NB; ++q) b[q][u] = colok ? xp[q][(size_t)(kt + u * NW) * 4] : zero;
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -292,7 +211,7 @@ __device__ __forceinline__ void gemm_loop(const u32x4* const (&w)[RT], const u32
     for (int u = 0; u < U; ++u) {
       const bool in = colok && kt + u * NW < nkt;
 #pragma unroll
-      for (int q = 0; q < NB; ++q) b[q][u] = in ? ld_u32x4<COH>(xp[q] + (size_t)(kt + u * NW) * 4) : zero;
+      for (int q = 0; q < NB; ++q) b[q][u] = in ? xp[q][(size_t)(kt + u * NW) * 4] : zero;
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -308,7 +227,7 @@ __device__ __forceinline__ void gemm_loop(const u32x4* const (&w)[RT], const u32
 // NB is chosen by the host per launch: 1 when the activations have one term (fp32) or the
 // columns fold (at most 8), else 2.  Separate instantiations keep the common one-fragment path
 // free of the second path's registers.
-template <typename T, int RT, int NB, bool COH>
+template <typename T, int RT, int NB>
 __device__ __forceinline__ void gemm_accumulate(const u32x4* const (&w)[RT], const T* __restrict__ x, int K, int ncols,
                                                 f32x4 (&acc)[RT]) {
   constexpr int EPL = Tr<T>::EPL, KT = Tr<T>::KT, PARTS = Tr<T>::PARTS;
@@ -323,12 +242,12 @@ __device__ __forceinline__ void gemm_accumulate(const u32x4* const (&w)[RT], con
     const bool colok = src < ncols;
     const u32x4* const xp[1] = {
         reinterpret_cast<const u32x4*>(x + (is_lo ? part : 0) + (size_t)(colok ? src : 0) * K + kg * EPL)};
-    gemm_loop<T, RT, 1, COH>(w, xp, colok, nkt, acc);
+    gemm_loop<T, RT, 1>(w, xp, colok, nkt, acc);
   } else {
     const bool colok = col < ncols;
     const T* base = x + (size_t)(colok ? col : 0) * K + kg * EPL;
     const u32x4* const xp[2] = {reinterpret_cast<const u32x4*>(base), reinterpret_cast<const u32x4*>(base + part)};
-    gemm_loop<T, RT, 2, COH>(w, xp, colok, nkt, acc);
+    gemm_loop<T, RT, 2>(w, xp, colok, nkt, acc);
   }
 }
 
@@ -364,13 +283,12 @@ __device__ __forceinline__ bool reduce_waves(f32x4 (&acc)[RT], f32x4* red) {
 }
 
 // rstd[col] = rsqrt(sum_t ssp[col][t] / d + eps), summed in a fixed order.  Ends with a barrier.
-template <bool COH>
-__device__ __forceinline__ void compute_rstd(const float* ssp, int ntile, int ncols, float inv_d, float eps,
+__device__ __forceinline__ void compute_rstd(const float* __restrict__ ssp, int ntile, int ncols, float inv_d, float eps,
                                              float* s_rstd) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, NW = blockDim.x >> 6;
   for (int col = wave; col < ncols; col += NW) {
     float s = 0.f;
-    for (int t = lane; t < ntile; t += 64) s += ld_f32<COH>(ssp + col * ntile + t);
+    for (int t = lane; t < ntile; t += 64) s += ssp[col * ntile + t];
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
     if (lane == 0) s_rstd[col] = 1.0f / sqrtf(s * inv_d + eps);
@@ -388,8 +306,7 @@ struct RstdPre {
   bool fast;
 };
 
-template <bool COH>
-__device__ __forceinline__ void rstd_issue(const float* ssp, int ntile, int ncols, RstdPre& p) {
+__device__ __forceinline__ void rstd_issue(const float* __restrict__ ssp, int ntile, int ncols, RstdPre& p) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, NW = blockDim.x >> 6;
   p.fast = ntile <= 256 && ncols <= 2 * NW;
   if (!p.fast) return;
@@ -399,17 +316,16 @@ __device__ __forceinline__ void rstd_issue(const float* ssp, int ntile, int ncol
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int t = lane + 64 * j;
-      p.v[i][j] = (col < ncols && t < ntile) ? ld_f32<COH>(ssp + col * ntile + t) : 0.f;
+      p.v[i][j] = (col < ncols && t < ntile) ? ssp[col * ntile + t] : 0.f;
     }
   }
 }
 
 // Ends with a barrier unless the caller's reduce_waves provides one (NW > 1).
-template <bool COH>
-__device__ __forceinline__ void rstd_finish(const float* ssp, int ntile, int ncols, float inv_d, float eps,
+__device__ __forceinline__ void rstd_finish(const float* __restrict__ ssp, int ntile, int ncols, float inv_d, float eps,
                                             const RstdPre& p, float* s_rstd) {
   if (!p.fast) {
-    compute_rstd<COH>(ssp, ntile, ncols, inv_d, eps, s_rstd);
+    compute_rstd(ssp, ntile, ncols, inv_d, eps, s_rstd);
     return;
   }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, NW = blockDim.x >> 6;
@@ -429,16 +345,10 @@ __device__ __forceinline__ void rstd_finish(const float* ssp, int ntile, int nco
 
 extern __shared__ f32x4 dyn_red[];
 
-// Each weight contraction below is written as the work of ONE unit (one workgroup's worth: one
-// or two row tiles over all of K) in a __device__ function, used in two ways: by a plain kernel
-// whose workgroup index is the unit (COH = false), and by the chained kernel, whose resident
-// workgroups walk the units of one phase after the other with grid barriers between
-// (COH = true: see the access helpers above).  red: LDS for reduce_waves.
-
 // ------------------------------------------------------------------------------------------
 // QKV projection of the k layers of a set + bias + rotary + KV-cache write.
-// Unit: two row tiles of one head, rows e and e + hd/2, so that the rotation pairs sit in the
-// same lane.  units = k * (Hq + 2 Hkv) * (hd/32).
+// Unit of work: two row tiles of one head, rows e and e + hd/2, so that the rotation pairs
+// sit in the same lane.  grid = k * (Hq + 2 Hkv) * (hd/32).
 // ------------------------------------------------------------------------------------------
 struct QkvArgs {
   const u32x4* w;  // layer layer0
@@ -454,20 +364,21 @@ struct QkvArgs {
   float inv_d, eps;
 };
 
-template <typename T, int NB, bool COH>
-__device__ __forceinline__ void qkv_unit(const QkvArgs& a, const Cols& c, int unit, float* s_rstd, f32x4* red) {
+template <typename T, int NB>
+__global__ __launch_bounds__(1024) void qkv_kernel(QkvArgs a, Cols c) {
+  __shared__ float s_rstd[kMaxCols];
   const int KT = Tr<T>::KT;
   const int nkt = a.d / KT;
   const int pairs = a.hd / 32;
   const int units = (a.Hq + 2 * a.Hkv) * pairs;
-  const int li = unit / units, u = unit % units;
+  const int li = blockIdx.x / units, u = blockIdx.x % units;
   const int head = u / pairs, p = u % pairs;
   const int rt0 = head * (a.hd / 16) + p, rt1 = rt0 + pairs;
   const u32x4* wl = a.w + (size_t)li * a.w_layer_stride;
   const u32x4* const w[2] = {wl + (size_t)rt0 * nkt * 64, wl + (size_t)rt1 * nkt * 64};
   const T* x = reinterpret_cast<const T*>(a.x) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.d;
   // operands of the epilogue (wave 0 only) and of the norm scale are fetched before the weight
-  // stream starts, so that their latency does not sit in the tail of the unit
+  // stream starts, so that their latency does not sit in the tail of the kernel
   const int lane = threadIdx.x & 63, col = lane & 15;
   const int e0 = p * 16 + (lane >> 4) * 4;  // element inside the head, < hd/2
   const int half = a.hd / 2;
@@ -487,12 +398,12 @@ __device__ __forceinline__ void qkv_unit(const QkvArgs& a, const Cols& c, int un
     }
   }
   RstdPre pre;
-  rstd_issue<COH>(a.ssp, a.d / 16, c.n, pre);
+  rstd_issue(a.ssp, a.d / 16, c.n, pre);
 
   f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-  gemm_accumulate<T, 2, NB, COH>(w, x, a.d, c.n, acc);
-  rstd_finish<COH>(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
-  if (!reduce_waves<2>(acc, red)) return;
+  gemm_accumulate<T, 2, NB>(w, x, a.d, c.n, acc);
+  rstd_finish(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
+  if (!reduce_waves<2>(acc, dyn_red)) return;
   fold_columns<T, 2>(acc, c.n);
 
   if (col >= c.n) return;
@@ -508,23 +419,16 @@ __device__ __forceinline__ void qkv_unit(const QkvArgs& a, const Cols& c, int un
   }
   if (head < a.Hq) {
     float* q = a.q + ((size_t)li * kMaxCols + col) * (a.Hq * a.hd) + head * a.hd + e0;
-    // Q, K and V are read by the attention launch that follows, never inside this launch
-    st_f32x4<false>(q, f32x4{lo[0], lo[1], lo[2], lo[3]});
-    st_f32x4<false>(q + half, f32x4{hi[0], hi[1], hi[2], hi[3]});
+    store4<float>(q, lo[0], lo[1], lo[2], lo[3]);
+    store4<float>(q + half, hi[0], hi[1], hi[2], hi[3]);
   } else {
     const bool is_k = head < a.Hq + a.Hkv;
     const int kvh = is_k ? head - a.Hq : head - a.Hq - a.Hkv;
     T* base = reinterpret_cast<T*>(is_k ? a.kc : a.vc);
     T* row = base + ((((size_t)(a.layer0 + li) * a.B + seq) * a.Hkv + kvh) * a.max_ctx + pos) * a.hd + e0;
-    st_row4<T, false>(row, lo[0], lo[1], lo[2], lo[3]);
-    st_row4<T, false>(row + half, hi[0], hi[1], hi[2], hi[3]);
+    store4<T>(row, lo[0], lo[1], lo[2], lo[3]);
+    store4<T>(row + half, hi[0], hi[1], hi[2], hi[3]);
   }
-}
-
-template <typename T, int NB>
-__global__ __launch_bounds__(1024) void qkv_kernel(QkvArgs a, Cols c) {
-  __shared__ float s_rstd[kMaxCols];
-  qkv_unit<T, NB, false>(a, c, blockIdx.x, s_rstd, dyn_red);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -532,7 +436,7 @@ __global__ __launch_bounds__(1024) void qkv_kernel(QkvArgs a, Cols c) {
 // launch (k > 1), or one down projection (k = 1).  Layer 0 of the launch updates the
 // residual: h = H + acc (+ Attnoutput of the next layer), writes H, the sum of squares of h
 // and T(h * gain_j) for the consumer(s) that come next; the other layers only store their
-// Attnoutput for later.  units = k * d/16.
+// Attnoutput for later.  grid = k * d/16.
 // ------------------------------------------------------------------------------------------
 struct ProjArgs {
   const u32x4* w;
@@ -548,31 +452,31 @@ struct ProjArgs {
   float* ssp;
 };
 
-template <typename T, int NB, bool COH>
-__device__ __forceinline__ void proj_unit(const ProjArgs& a, const Cols& c, int unit, f32x4* red) {
+template <typename T, int NB>
+__global__ __launch_bounds__(1024) void proj_resid_kernel(ProjArgs a, Cols c) {
   const int KT = Tr<T>::KT;
   const int nkt = a.K / KT;
   const int ntile = a.d / 16;
-  const int li = unit / ntile, t = unit % ntile;
+  const int li = blockIdx.x / ntile, t = blockIdx.x % ntile;
   const u32x4* const w[1] = {a.w + (size_t)li * a.w_layer_stride + (size_t)t * nkt * 64};
   const T* x = reinterpret_cast<const T*>(a.x) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.K;
-  // residual-update operands (wave 0 of a layer-0 unit) are fetched before the weight stream
+  // residual-update operands (wave 0 of a layer-0 workgroup) are fetched before the weight stream
   const int lane = threadIdx.x & 63, col = lane & 15;
   const bool ok = col < c.n;
   const int r0 = t * 16 + (lane >> 4) * 4;
   f32x4 h_in = {0.f, 0.f, 0.f, 0.f}, a_in = {0.f, 0.f, 0.f, 0.f}, g_in = {0.f, 0.f, 0.f, 0.f};
   if (threadIdx.x < 64 && li == 0 && ok) {
-    h_in = ld_f32x4<COH>(a.H + (size_t)col * a.d + r0);
-    if (a.a_add >= 0) a_in = ld_f32x4<COH>(a.A + ((size_t)a.a_add * kMaxCols + col) * a.d + r0);
+    h_in = *reinterpret_cast<const f32x4*>(a.H + (size_t)col * a.d + r0);
+    if (a.a_add >= 0) a_in = *reinterpret_cast<const f32x4*>(a.A + ((size_t)a.a_add * kMaxCols + col) * a.d + r0);
     g_in = *reinterpret_cast<const f32x4*>(a.gain + r0);
   }
   f32x4 acc[1] = {{0.f, 0.f, 0.f, 0.f}};
-  gemm_accumulate<T, 1, NB, COH>(w, x, a.K, c.n, acc);
-  if (!reduce_waves<1>(acc, red)) return;
+  gemm_accumulate<T, 1, NB>(w, x, a.K, c.n, acc);
+  if (!reduce_waves<1>(acc, dyn_red)) return;
   fold_columns<T, 1>(acc, c.n);
 
   if (li > 0) {
-    if (ok) st_f32x4<COH>(a.A + ((size_t)li * kMaxCols + col) * a.d + r0, acc[0]);
+    if (ok) store4<float>(a.A + ((size_t)li * kMaxCols + col) * a.d + r0, acc[0][0], acc[0][1], acc[0][2], acc[0][3]);
     return;
   }
   float ss = 0.f;
@@ -581,26 +485,21 @@ __device__ __forceinline__ void proj_unit(const ProjArgs& a, const Cols& c, int 
     f32x4 h = h_in;
     h += acc[0];
     if (a.a_add >= 0) h += a_in;
-    st_f32x4<COH>(hp, h);
+    *reinterpret_cast<f32x4*>(hp) = h;
     for (int j = 0; j < a.n_gain; ++j) {
       const f32x4 g = j == 0 ? g_in : *reinterpret_cast<const f32x4*>(a.gain + (size_t)j * a.d + r0);
       T* xo = reinterpret_cast<T*>(a.xout) + ((size_t)j * Tr<T>::PARTS * kMaxCols + col) * a.d + r0;
-      st_act4<T, COH>(xo, (size_t)kMaxCols * a.d, h[0] * g[0], h[1] * g[1], h[2] * g[2], h[3] * g[3]);
+      store_act4<T>(xo, (size_t)kMaxCols * a.d, h[0] * g[0], h[1] * g[1], h[2] * g[2], h[3] * g[3]);
     }
     ss = h[0] * h[0] + h[1] * h[1] + h[2] * h[2] + h[3] * h[3];
   }
   ss += __shfl_xor(ss, 16, 64);
   ss += __shfl_xor(ss, 32, 64);
-  if (ok && lane < 16) st_f32<COH>(a.ssp + col * ntile + t, ss);
-}
-
-template <typename T, int NB>
-__global__ __launch_bounds__(1024) void proj_resid_kernel(ProjArgs a, Cols c) {
-  proj_unit<T, NB, false>(a, c, blockIdx.x, dyn_red);
+  if (ok && lane < 16) a.ssp[col * ntile + t] = ss;
 }
 
 // ------------------------------------------------------------------------------------------
-// Gate and up projections + SiLU(gate) * up.  Unit: gate tile t and up tile t.  units = F/16.
+// Gate and up projections + SiLU(gate) * up.  grid = F/16.
 // ------------------------------------------------------------------------------------------
 struct GateUpArgs {
   const u32x4* wg;
@@ -612,16 +511,18 @@ struct GateUpArgs {
   float inv_d, eps;
 };
 
-template <typename T, int NB, bool COH>
-__device__ __forceinline__ void gateup_unit(const GateUpArgs& a, const Cols& c, int t, float* s_rstd, f32x4* red) {
+template <typename T, int NB>
+__global__ __launch_bounds__(1024) void gateup_kernel(GateUpArgs a, Cols c) {
+  __shared__ float s_rstd[kMaxCols];
   const int nkt = a.d / Tr<T>::KT;
+  const int t = blockIdx.x;
   const u32x4* const w[2] = {a.wg + (size_t)t * nkt * 64, a.wu + (size_t)t * nkt * 64};
   RstdPre pre;
-  rstd_issue<COH>(a.ssp, a.d / 16, c.n, pre);
+  rstd_issue(a.ssp, a.d / 16, c.n, pre);
   f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-  gemm_accumulate<T, 2, NB, COH>(w, reinterpret_cast<const T*>(a.x), a.d, c.n, acc);
-  rstd_finish<COH>(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
-  if (!reduce_waves<2>(acc, red)) return;
+  gemm_accumulate<T, 2, NB>(w, reinterpret_cast<const T*>(a.x), a.d, c.n, acc);
+  rstd_finish(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
+  if (!reduce_waves<2>(acc, dyn_red)) return;
   fold_columns<T, 2>(acc, c.n);
   const int lane = threadIdx.x & 63, col = lane & 15;
   if (col >= c.n) return;
@@ -633,18 +534,11 @@ __device__ __forceinline__ void gateup_unit(const GateUpArgs& a, const Cols& c, 
     o[i] = (g / (1.0f + expf(-g))) * u;
   }
   T* dst = reinterpret_cast<T*>(a.act) + (size_t)col * a.F + t * 16 + (lane >> 4) * 4;
-  st_act4<T, COH>(dst, (size_t)kMaxCols * a.F, o[0], o[1], o[2], o[3]);
-}
-
-template <typename T, int NB>
-__global__ __launch_bounds__(1024) void gateup_kernel(GateUpArgs a, Cols c) {
-  __shared__ float s_rstd[kMaxCols];
-  gateup_unit<T, NB, false>(a, c, blockIdx.x, s_rstd, dyn_red);
+  store_act4<T>(dst, (size_t)kMaxCols * a.F, o[0], o[1], o[2], o[3]);
 }
 
 // ------------------------------------------------------------------------------------------
-// LM head: logits + per-row-tile argmax candidates (lowest index wins ties).  units = ceil(V/16).
-// Its outputs are consumed by a later launch, so they are always plain stores.
+// LM head: logits + per-workgroup argmax candidates (lowest index wins ties).  grid = ceil(V/16).
 // ------------------------------------------------------------------------------------------
 struct HeadArgs {
   const u32x4* w;
@@ -659,16 +553,18 @@ struct HeadArgs {
 
 __device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
 
-template <typename T, int NB, bool COH>
-__device__ __forceinline__ void head_unit(const HeadArgs& a, const Cols& c, int t, float* s_rstd, f32x4* red) {
+template <typename T, int NB>
+__global__ __launch_bounds__(1024) void head_kernel(HeadArgs a, Cols c) {
+  __shared__ float s_rstd[kMaxCols];
   const int nkt = a.d / Tr<T>::KT;
+  const int t = blockIdx.x;
   const u32x4* const w[1] = {a.w + (size_t)t * nkt * 64};
   RstdPre pre;
-  rstd_issue<COH>(a.ssp, a.d / 16, c.n, pre);
+  rstd_issue(a.ssp, a.d / 16, c.n, pre);
   f32x4 acc[1] = {{0.f, 0.f, 0.f, 0.f}};
-  gemm_accumulate<T, 1, NB, COH>(w, reinterpret_cast<const T*>(a.x), a.d, c.n, acc);
-  rstd_finish<COH>(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
-  if (!reduce_waves<1>(acc, red)) return;
+  gemm_accumulate<T, 1, NB>(w, reinterpret_cast<const T*>(a.x), a.d, c.n, acc);
+  rstd_finish(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
+  if (!reduce_waves<1>(acc, dyn_red)) return;
   fold_columns<T, 1>(acc, c.n);
   const int lane = threadIdx.x & 63, col = lane & 15;
   const bool ok = col < c.n;
@@ -694,97 +590,6 @@ __device__ __forceinline__ void head_unit(const HeadArgs& a, const Cols& c, int 
   if (ok && lane < 16) {
     a.cand_val[(size_t)col * a.nblk + t] = bv;
     a.cand_idx[(size_t)col * a.nblk + t] = bi;
-  }
-}
-
-template <typename T, int NB>
-__global__ __launch_bounds__(1024) void head_kernel(HeadArgs a, Cols c) {
-  __shared__ float s_rstd[kMaxCols];
-  head_unit<T, NB, false>(a, c, blockIdx.x, s_rstd, dyn_red);
-}
-
-// ------------------------------------------------------------------------------------------
-// The chained launch: the dependent weight contractions between two attention launches
-// (O projection of a set, gate/up and down of each of its layers in order, then the QKV
-// projection of the next set or the LM head) run as phases of ONE cooperative launch whose
-// workgroups stay resident; a grid barrier stands where a launch boundary stood.  A launch
-// boundary costs about 6.5 us on this chip, the barrier about 2: the units and their
-// arithmetic are those of the plain kernels, bit for bit.
-//
-// The barrier uses no device-scope fence (see the access helpers): every workgroup drains its
-// own memory operations (s_waitcnt), one thread bumps one of 16 arrival counters (device-scope
-// atomic, each on a cache line of its own), one wave polls their sum.  Every wait is bounded:
-// if it gives up it raises the abort flag, which ends all later waits at once, so the grid
-// always drains.  Counters only grow; the host passes the value they had before the launch.
-// ------------------------------------------------------------------------------------------
-enum PhaseType { kPhaseQkv = 0, kPhaseProj = 1, kPhaseGateUp = 2, kPhaseHead = 3 };
-
-struct alignas(sizeof(PhaseDesc)) Phase {
-  int32_t type;
-  int32_t n_units;
-  union {
-    QkvArgs qkv;
-    ProjArgs proj;
-    GateUpArgs gu;
-    HeadArgs head;
-  };
-};
-static_assert(sizeof(Phase) == sizeof(PhaseDesc), "the host indexes a program in units of PhaseDesc");
-
-constexpr unsigned kBarrierSpinLimit = 1u << 22;
-
-__device__ __forceinline__ void grid_barrier(ChainSync sy, u64 target) {
-  __builtin_amdgcn_s_waitcnt(0);  // this wave's loads and write-through stores have completed
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-  __syncthreads();
-  if (threadIdx.x < 64) {
-    const int lane = threadIdx.x;
-    if (lane == 0) atomicAdd(sy.counters + (blockIdx.x % kSyncLanes) * kSyncStride, 1ull);
-    unsigned spins = 0;
-    for (;;) {
-      u64 v = lane < kSyncLanes ? __hip_atomic_load(sy.counters + lane * kSyncStride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0ull;
-#pragma unroll
-      for (int off = 8; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-      v = __shfl(v, 0, 64);
-      if (v >= target) break;
-      ++spins;
-      if (spins > kBarrierSpinLimit || ((spins & 255u) == 0 && __hip_atomic_load(sy.abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM))) {
-        if (lane == 0) __hip_atomic_store(sy.abort, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-        break;
-      }
-      __builtin_amdgcn_s_sleep(2);
-    }
-  }
-  __syncthreads();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-}
-
-template <typename T, int NB>
-__global__ __launch_bounds__(1024) void chain_kernel(const Phase* __restrict__ prog, int n_phases, Cols c, ChainSync sy,
-                                                      float* logits_out) {
-  __shared__ float s_rstd[kMaxCols];
-  const int NW = blockDim.x >> 6;
-  const int red_stride = (NW - 1) * 2 * 64;  // f32x4 per LDS reduction buffer (two row tiles at most)
-  int parity = 0;
-  for (int ph = 0; ph < n_phases; ++ph) {
-    const Phase& P = prog[ph];
-    const int n_units = P.n_units;
-    for (int u = blockIdx.x; u < n_units; u += gridDim.x) {
-      // two LDS buffers in turn: wave 0 may still be summing unit j while the others write unit j+1
-      f32x4* red = dyn_red + parity * red_stride;
-      parity ^= 1;
-      switch (P.type) {
-        case kPhaseQkv: qkv_unit<T, NB, true>(P.qkv, c, u, s_rstd, red); break;
-        case kPhaseProj: proj_unit<T, NB, true>(P.proj, c, u, red); break;
-        case kPhaseGateUp: gateup_unit<T, NB, true>(P.gu, c, u, s_rstd, red); break;
-        default: {
-          HeadArgs h = P.head;
-          h.logits = logits_out;
-          head_unit<T, NB, true>(h, c, u, s_rstd, red);
-        } break;
-      }
-    }
-    if (ph + 1 < n_phases) grid_barrier(sy, sy.base + (u64)(ph + 1) * gridDim.x);
   }
 }
 
@@ -1219,7 +1024,8 @@ void launch_embed(const Shape& s, const Buffers& b, const Cols& c, const int32_t
                                          b.g_attn + (size_t)layer0 * s.d, n_set, s.d, s.V, b.H, (T*)b.XA, b.ssp, c));
 }
 
-static int fill_qkv(const Shape& s, const Buffers& b, int layer0, int n_set, QkvArgs& a) {
+void launch_qkv(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st) {
+  QkvArgs a;
   const size_t stride = tile_stride(s.RQKV, s.d, s.dtype);
   a.w = (const u32x4*)b.wqkv + (size_t)layer0 * stride;
   a.w_layer_stride = stride;
@@ -1232,12 +1038,7 @@ static int fill_qkv(const Shape& s, const Buffers& b, int layer0, int n_set, Qkv
   a.vc = b.vc;
   a.layer0 = layer0; a.d = s.d; a.Hq = s.Hq; a.Hkv = s.Hkv; a.hd = s.hd; a.B = s.B; a.max_ctx = s.max_ctx;
   a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
-  return n_set * (s.Hq + 2 * s.Hkv) * (s.hd / 32);
-}
-
-void launch_qkv(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st) {
-  QkvArgs a;
-  const int grid = fill_qkv(s, b, layer0, n_set, a);
+  const int grid = n_set * (s.Hq + 2 * s.Hkv) * (s.hd / 32);
   const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
   // few workgroups (a set of one layer): more waves per workgroup
   const int nw = pick_waves(grid < 512 ? 8 : 4, nkt, "EASYSPEC_NW_QKV");
@@ -1288,7 +1089,8 @@ void launch_attn(const Shape& s, const Buffers& b, const Cols& c, int layer0, in
   }
 }
 
-static int fill_oproj(const Shape& s, const Buffers& b, int layer0, int n_set, ProjArgs& a) {
+void launch_oproj(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st) {
+  ProjArgs a;
   const size_t stride = tile_stride(s.d, s.HQ, s.dtype);
   a.w = (const u32x4*)b.wo + (size_t)layer0 * stride;
   a.w_layer_stride = stride;
@@ -1299,38 +1101,30 @@ static int fill_oproj(const Shape& s, const Buffers& b, int layer0, int n_set, P
   a.n_gain = 1;
   a.xout = b.XM;
   a.ssp = b.ssp;
-  return n_set * (s.d / 16);
-}
-
-void launch_oproj(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st) {
-  ProjArgs a;
-  const int grid = fill_oproj(s, b, layer0, n_set, a);
+  const int grid = n_set * (s.d / 16);
   const int nkt = s.HQ / (s.dtype == 1 ? 32 : 16);
   const int nw = pick_waves(grid < 512 ? 8 : 4, nkt, "EASYSPEC_NW_O");
   DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
                hipLaunchKernelGGL((proj_resid_kernel<T, NB>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
 }
 
-static int fill_gateup(const Shape& s, const Buffers& b, int layer, GateUpArgs& a) {
+void launch_gateup(const Shape& s, const Buffers& b, const Cols& c, int layer, hipStream_t st) {
+  GateUpArgs a;
   const size_t stride = tile_stride(s.F, s.d, s.dtype);
   a.wg = (const u32x4*)b.wg + (size_t)layer * stride;
   a.wu = (const u32x4*)b.wu + (size_t)layer * stride;
   a.x = b.XM; a.ssp = b.ssp; a.act = b.ACT; a.d = s.d; a.F = s.F;
   a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
-  return s.F / 16;
-}
-
-void launch_gateup(const Shape& s, const Buffers& b, const Cols& c, int layer, hipStream_t st) {
-  GateUpArgs a;
-  const int grid = fill_gateup(s, b, layer, a);
+  const int grid = s.F / 16;
   const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
   const int nw = pick_waves(8, nkt, "EASYSPEC_NW_GU");
   DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
                hipLaunchKernelGGL((gateup_kernel<T, NB>), dim3(grid), dim3(64 * nw), red_bytes(nw, 2), st, a, c));
 }
 
-static int fill_down(const Shape& s, const Buffers& b, int layer, int a_next, const float* gain, int n_gain, void* xout,
-                     ProjArgs& a) {
+void launch_down(const Shape& s, const Buffers& b, const Cols& c, int layer, int a_next, const float* gain, int n_gain,
+                 void* xout, hipStream_t st) {
+  ProjArgs a;
   const size_t stride = tile_stride(s.d, s.F, s.dtype);
   a.w = (const u32x4*)b.wd + (size_t)layer * stride;
   a.w_layer_stride = stride;
@@ -1338,108 +1132,24 @@ static int fill_down(const Shape& s, const Buffers& b, int layer, int a_next, co
   a.K = s.F; a.d = s.d;
   a.H = b.H; a.A = b.A; a.a_add = a_next;
   a.gain = gain; a.n_gain = n_gain; a.xout = xout; a.ssp = b.ssp;
-  return s.d / 16;
-}
-
-void launch_down(const Shape& s, const Buffers& b, const Cols& c, int layer, int a_next, const float* gain, int n_gain,
-                 void* xout, hipStream_t st) {
-  ProjArgs a;
-  const int grid = fill_down(s, b, layer, a_next, gain, n_gain, xout, a);
+  const int grid = s.d / 16;
   const int nkt = s.F / (s.dtype == 1 ? 32 : 16);
   const int nw = pick_waves(8, nkt, "EASYSPEC_NW_DOWN");
   DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
                hipLaunchKernelGGL((proj_resid_kernel<T, NB>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
 }
 
-static int fill_head(const Shape& s, const Buffers& b, float* logits_out, HeadArgs& a) {
+void launch_head(const Shape& s, const Buffers& b, const Cols& c, float* logits_out, int32_t* tokens_out, hipStream_t st) {
+  HeadArgs a;
   a.w = (const u32x4*)b.wlm; a.x = b.XA; a.ssp = b.ssp; a.logits = logits_out;
   a.cand_val = b.amax_val; a.cand_idx = b.amax_idx;
   a.d = s.d; a.V = s.V; a.nblk = (s.V + 15) / 16;
   a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
-  return a.nblk;
-}
-
-void launch_head(const Shape& s, const Buffers& b, const Cols& c, float* logits_out, int32_t* tokens_out, hipStream_t st) {
-  HeadArgs a;
-  const int grid = fill_head(s, b, logits_out, a);
   const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
   const int nw = pick_waves(4, nkt, "EASYSPEC_NW_HEAD");
   DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
-               hipLaunchKernelGGL((head_kernel<T, NB>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
-  launch_argmax(s, b, c, tokens_out, st);
-}
-
-void launch_argmax(const Shape& s, const Buffers& b, const Cols& c, int32_t* tokens_out, hipStream_t st) {
-  hipLaunchKernelGGL(argmax_final_kernel, dim3(c.n), dim3(1024), 0, st, b.amax_val, b.amax_idx, (s.V + 15) / 16, tokens_out, c);
-}
-
-// ---- chained launch ----
-
-void make_phase_qkv(const Shape& s, const Buffers& b, int layer0, int n_set, PhaseDesc* out) {
-  Phase p;
-  memset(&p, 0, sizeof p);
-  p.type = kPhaseQkv;
-  p.n_units = fill_qkv(s, b, layer0, n_set, p.qkv);
-  memcpy(out, &p, sizeof p);
-}
-
-void make_phase_oproj(const Shape& s, const Buffers& b, int layer0, int n_set, PhaseDesc* out) {
-  Phase p;
-  memset(&p, 0, sizeof p);
-  p.type = kPhaseProj;
-  p.n_units = fill_oproj(s, b, layer0, n_set, p.proj);
-  memcpy(out, &p, sizeof p);
-}
-
-void make_phase_gateup(const Shape& s, const Buffers& b, int layer, PhaseDesc* out) {
-  Phase p;
-  memset(&p, 0, sizeof p);
-  p.type = kPhaseGateUp;
-  p.n_units = fill_gateup(s, b, layer, p.gu);
-  memcpy(out, &p, sizeof p);
-}
-
-void make_phase_down(const Shape& s, const Buffers& b, int layer, int a_next, const float* gain, int n_gain, void* xout,
-                     PhaseDesc* out) {
-  Phase p;
-  memset(&p, 0, sizeof p);
-  p.type = kPhaseProj;
-  p.n_units = fill_down(s, b, layer, a_next, gain, n_gain, xout, p.proj);
-  memcpy(out, &p, sizeof p);
-}
-
-void make_phase_head(const Shape& s, const Buffers& b, PhaseDesc* out) {
-  Phase p;
-  memset(&p, 0, sizeof p);
-  p.type = kPhaseHead;
-  p.n_units = fill_head(s, b, nullptr, p.head);
-  memcpy(out, &p, sizeof p);
-}
-
-static size_t chain_lds(int nw) { return 2 * red_bytes(nw, 2); }
-
-template <typename T, int NB>
-static int chain_capacity_t(int threads) {
-  int per_cu = 0, dev = 0;
-  hipDeviceProp_t prop;
-  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, chain_kernel<T, NB>, threads, chain_lds(threads / 64)) != hipSuccess)
-    return 0;
-  return per_cu * prop.multiProcessorCount;
-}
-
-int chain_capacity(int dtype, int threads) {
-  return dtype == 1 ? chain_capacity_t<bf16_t, 1>(threads) : chain_capacity_t<float, 1>(threads);
-}
-
-// Single-fragment form only (fp32, or bf16 with at most 8 columns): the caller checks.
-void launch_chain(const Shape& s, const Cols& c, const PhaseDesc* prog, int n_phases, const ChainSync& sy, float* logits_out,
-                  int grid, int threads, hipStream_t st) {
-  const Phase* p = reinterpret_cast<const Phase*>(prog);
-  if (s.dtype == 1)
-    hipLaunchKernelGGL((chain_kernel<bf16_t, 1>), dim3(grid), dim3(threads), chain_lds(threads / 64), st, p, n_phases, c, sy, logits_out);
-  else
-    hipLaunchKernelGGL((chain_kernel<float, 1>), dim3(grid), dim3(threads), chain_lds(threads / 64), st, p, n_phases, c, sy, logits_out);
+               hipLaunchKernelGGL((head_kernel<T, NB>), dim3(a.nblk), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+  hipLaunchKernelGGL(argmax_final_kernel, dim3(c.n), dim3(1024), 0, st, a.cand_val, a.cand_idx, a.nblk, tokens_out, c);
 }
 
 void launch_accept(const int32_t* draft, const int32_t* target, int batch, int gamma, int32_t* accept_len, int32_t* bonus,
