@@ -180,6 +180,20 @@ def make_accept_lengths(seed: int, n_iters: int, gamma: int) -> np.ndarray:
     return g.integers(0, gamma + 1, size=n_iters, dtype=np.int64).astype(np.int32)
 
 
+def make_uniforms(seed: int, n: int) -> np.ndarray:
+    """n float32 uniforms in [0, 1): the random numbers speculative sampling draws, handed to
+    both implementations as inputs."""
+    g = np.random.Generator(np.random.Philox(key=[int(seed) & (2**64 - 1), (1 << 40) + 13]))
+    return g.random(n, dtype=np.float32)
+
+
+def make_logits(seed: int, rows: int, vocab: int, std: float = 2.0) -> np.ndarray:
+    """[rows, vocab] float32 N(0, std) logits for acceptance tests (std 2 gives softmax
+    distributions with a few dominant tokens, as a trained model's are)."""
+    g = np.random.Generator(np.random.Philox(key=[int(seed) & (2**64 - 1), (1 << 40) + 17]))
+    return (g.standard_normal((rows, vocab), dtype=np.float32) * np.float32(std)).astype(np.float32)
+
+
 def make_kv_prefix(cfg: dict, seed: int, n_slots: int, seq: int = 0):
     """Synthetic KV prefix standing in for a prefilled context: two arrays
     ``[n_layers, n_kv_heads, n_slots, head_dim]`` of N(0,1) values in the model's storage

@@ -1,8 +1,9 @@
 /*
  * EasySpec CPU oracle.  TEST INFRASTRUCTURE ONLY: a plain, slow, double-precision
  * implementation of the draft model's layer-sequential step (paper Alg. 1), the
- * layer-parallel fuzzy step (paper Alg. 2), bonus calibration (paper Sec. 3.2) and greedy
- * acceptance (paper Alg. 3 at temperature 0).  Only the tests, the smoke check and the
+ * layer-parallel fuzzy step (paper Alg. 2), bonus calibration (paper Sec. 3.2), greedy
+ * acceptance (paper Alg. 3 at temperature 0) and acceptance by speculative sampling (Alg. 3,
+ * Sec. 2.1) with the random numbers passed in.  Only the tests, the smoke check and the
  * benchmark's cpu_baseline leg may call it; it shares no code with the HIP library.
  *
  * Arithmetic: every vector and accumulator is a double.  Parameters are read from the
@@ -27,7 +28,9 @@
  * Parity pins (tests/test_oracle_*.py): sequential step against an independent library
  * decoder; Alg. 2 with all sets of size one == Alg. 1 bit for bit; calibration == token by
  * token sequential decoding bit for bit; greedy speculative decoding == vanilla greedy
- * decoding.  The numeric value of a fuzzy step with sets larger than one is fixed by no
+ * decoding; speculative sampling reproduces the target distribution (exact integration over
+ * the random inputs on tiny vocabularies) and reduces to greedy acceptance for one-hot
+ * distributions.  The numeric value of a fuzzy step with sets larger than one is fixed by no
  * number in the paper (its similarity table needs trained weights): that part is pinned
  * by a second composition of the same library blocks and by structural invariants only.
  *
@@ -439,6 +442,78 @@ void eso_greedy_accept(const int32_t *draft, const int32_t *target, int32_t gamm
   while (m < gamma && draft[m] == target[m]) ++m;
   *accept_len = m;
   *bonus = target[m];
+}
+
+/* Acceptance by speculative sampling (Alg. 3; bonus distribution of Sec. 2.1) for one
+ * sequence, with the random numbers given: r[i] in [0,1) decides position i, u in [0,1)
+ * draws the bonus token.
+ *   p'_i = softmax(draft_logits[i] / T), i < gamma;  p_i = softmax(target_logits[i] / T), i <= gamma.
+ *   Position i is rejected when r_i > p_i(x'_i) / p'_i(x'_i), evaluated as r_i * p'_i(x'_i) > p_i(x'_i)
+ *   (same decision, no division by a vanishing probability); m = index of the first rejection,
+ *   or gamma.
+ *   Bonus distribution: q = max(0, p_m - p'_m) if m < gamma (the printed algorithm's index is
+ *   garbled; this is the equation of Sec. 2.1: the distributions at the first rejected
+ *   position), else q = p_gamma.  Normalisation and draw together: bonus = the lowest v whose
+ *   running sum q(0) + ... + q(v) exceeds u * sum(q).  If the residual is identically zero
+ *   (p_m == p'_m, where a rejection cannot happen for r < 1) q falls back to p_m.
+ * margin (optional): the smallest relative distance of any decision taken from its threshold,
+ * so that a comparison with another implementation can set aside decisions that rounding
+ * could flip. */
+static void softmax_t(const float *logits, int32_t V, double T, double *p) {
+  double mx = -INFINITY;
+  for (int v = 0; v < V; ++v) if ((double)logits[v] > mx) mx = (double)logits[v];
+  double z = 0.0;
+  for (int v = 0; v < V; ++v) { p[v] = exp(((double)logits[v] - mx) / T); z += p[v]; }
+  for (int v = 0; v < V; ++v) p[v] /= z;
+}
+
+int eso_accept(const int32_t *draft, const float *draft_logits, const float *target_logits, const float *r, float u,
+               int32_t gamma, int32_t V, double T, int32_t *accept_len, int32_t *bonus, double *margin) {
+  if (gamma < 0 || V < 1 || !(T > 0.0)) return -1;
+  double *p = (double *)malloc(sizeof(double) * (size_t)V), *pd = (double *)malloc(sizeof(double) * (size_t)V);
+  if (!p || !pd) { free(p); free(pd); return -1; }
+  double mg = INFINITY;
+  int m = 0;
+  for (; m < gamma; ++m) {
+    const int x = draft[m];
+    if (x < 0 || x >= V) { free(p); free(pd); return -1; }
+    softmax_t(target_logits + (size_t)m * V, V, T, p);
+    softmax_t(draft_logits + (size_t)m * V, V, T, pd);
+    const double lhs = (double)r[m] * pd[x], rhs = p[x];
+    const double big = fmax(fabs(lhs), fabs(rhs));
+    if (big > 0.0) mg = fmin(mg, fabs(lhs - rhs) / big);
+    if (lhs > rhs) break; /* rejected; p and pd hold the distributions of this position */
+  }
+  if (m == gamma) {
+    softmax_t(target_logits + (size_t)gamma * V, V, T, p);
+  } else {
+    double s = 0.0;
+    for (int v = 0; v < V; ++v) { pd[v] = fmax(0.0, p[v] - pd[v]); s += pd[v]; }
+    if (s > 0.0) memcpy(p, pd, sizeof(double) * (size_t)V);
+  }
+  double total = 0.0;
+  for (int v = 0; v < V; ++v) total += p[v];
+  const double thr = (double)u * total;
+  double run = 0.0;
+  int pick = -1, last_pos = 0;
+  for (int v = 0; v < V; ++v) {
+    if (p[v] > 0.0) last_pos = v;
+    const double before = run;
+    run += p[v];
+    if (run > thr) {
+      pick = v;
+      const double up = run - thr, down = v == 0 ? INFINITY : thr - before; /* distances to the two neighbouring outcomes */
+      mg = fmin(mg, fmin(up, down) / total);
+      break;
+    }
+  }
+  if (pick < 0) { pick = last_pos; mg = 0.0; }
+  *accept_len = m;
+  *bonus = pick;
+  if (margin) *margin = mg;
+  free(p);
+  free(pd);
+  return 0;
 }
 
 /* ---------------------------------------------------------------- layer-parallel strategy (Sec. 3.1.1) */

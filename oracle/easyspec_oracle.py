@@ -77,6 +77,8 @@ def lib():
         L.eso_calibrate_last.argtypes = [vp, ip, i32, dp]
         L.eso_greedy_accept.argtypes = [ip, ip, i32, ip, ip]
         L.eso_default_groups.argtypes = [i32, i32, i32, ip, ip]
+        fp = C.POINTER(C.c_float)
+        L.eso_accept.argtypes = [ip, fp, fp, fp, C.c_float, i32, i32, C.c_double, ip, ip, dp]
         _lib = L
     return _lib
 
@@ -147,6 +149,25 @@ def greedy_accept(draft, target):
     m, b = C.c_int32(-1), C.c_int32(-1)
     lib().eso_greedy_accept(_ip(draft), _ip(target), draft.size, C.byref(m), C.byref(b))
     return int(m.value), int(b.value)
+
+
+def accept(draft, draft_logits, target_logits, r, u, temperature, with_margin: bool = False):
+    """Acceptance by speculative sampling (paper Alg. 3 / Sec. 2.1) for one sequence; r [gamma] and
+    u are the uniform random numbers.  Returns (accept_len, bonus[, margin])."""
+    draft = np.ascontiguousarray(draft, dtype=np.int32)
+    dl = np.ascontiguousarray(draft_logits, dtype=np.float32)
+    tl = np.ascontiguousarray(target_logits, dtype=np.float32)
+    r = np.ascontiguousarray(r, dtype=np.float32)
+    gamma = draft.size
+    V = tl.shape[-1]
+    assert tl.shape == (gamma + 1, V) and dl.shape == (gamma, V) and r.size == gamma
+    fp = C.POINTER(C.c_float)
+    m, b, mg = C.c_int32(-1), C.c_int32(-1), C.c_double(0.0)
+    rc = lib().eso_accept(_ip(draft), dl.ctypes.data_as(fp), tl.ctypes.data_as(fp), r.ctypes.data_as(fp), float(np.float32(u)),
+                          gamma, V, float(temperature), C.byref(m), C.byref(b), C.byref(mg))
+    if rc != 0:
+        raise ValueError("bad accept arguments")
+    return (int(m.value), int(b.value), float(mg.value)) if with_margin else (int(m.value), int(b.value))
 
 
 def default_groups(n_layers: int, group_size: int, policy: str = "aligned"):
