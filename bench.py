@@ -165,6 +165,22 @@ def main():
         per_op[name + "_us_per_iteration"] = round(1e3 * ms_, 1)
     per_op["gateup_us_per_iteration"] = round(1e3 * gu_ms * gamma * cfg["n_layers"], 1)
 
+    # acceptance by speculative sampling (temperature 0.8, the paper's second setting) on logits of
+    # this vocabulary: reported beside the greedy iteration, not part of `value`
+    V = cfg["vocab"]
+    tl = torch.from_numpy(synth.make_logits(args.seed + 5, gamma + 1, V)).to(dev)
+    dl = (tl[:gamma] + 0.7 * torch.from_numpy(synth.make_logits(args.seed + 6, gamma, V, std=1.0)).to(dev)).contiguous()
+    ru = torch.from_numpy(synth.make_uniforms(args.seed + 7, gamma + 1)).to(dev)
+    ws = torch.empty(es.easyspec_accept_workspace_bytes(1, gamma) // 8, dtype=torch.float64, device=dev)
+    sa = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    n_acc = 50
+    for k in range(n_acc + 5):
+        if k == 5: sa[0].record()
+        es.easyspec_accept(draft, dl, tl, ru, ru[gamma:], 1, gamma, V, 0.8, acc, bonus, ws, stream)
+    sa[1].record()
+    torch.cuda.synchronize()
+    accept_us = 1e3 * sa[0].elapsed_time(sa[1]) / n_acc
+
     traffic_kib = args.traffic_kib if args.traffic_kib is not None else (
         None if args.layers else MEASURED_TRAFFIC_KIB.get(args.workload))
     out = {
@@ -189,6 +205,8 @@ def main():
                      "event_pair_us": round(1e3 * gu_raw_ms, 2), "empty_event_pair_us": round(1e3 * null_ms, 2),
                      "launches_timed": n_timed},
         "kernel_time": per_op,
+        "sample_accept": {"us": round(accept_us, 1), "temperature": 0.8, "gamma": gamma, "vocab": V, "dtype": "f64",
+                          "logit_bytes": (2 * gamma + 1) * V * 4},
     }
 
     if not args.no_cpu_baseline:

@@ -8,6 +8,8 @@
  *                             with precise values by one token-parallel, layer-sequential
  *                             forward (paper Sec. 3.2, Alg. 1)
  *   - easyspec_greedy_accept  acceptance of drafted tokens at temperature 0 (paper Alg. 3)
+ *   - easyspec_accept         acceptance by speculative sampling at a temperature > 0
+ *                             (paper Alg. 3, bonus distribution of Sec. 2.1)
  *
  * Model function: pre-norm decoder with RMSNorm, rotary embedding (pairs i, i + head_dim/2),
  * grouped-query attention (query head j reads KV head j / (n_q_heads/n_kv_heads)), SwiGLU MLP,
@@ -141,6 +143,31 @@ int easyspec_calibrate(easyspec_ctx *ctx, const int32_t *tokens, const int32_t *
  * are dev arrays and one small kernel is launched on that hipStream_t. */
 int easyspec_greedy_accept(const int32_t *draft, const int32_t *target_argmax, int32_t batch, int32_t gamma,
                            int32_t *accept_len, int32_t *bonus, void *hip_stream);
+
+/* Acceptance by speculative sampling (Alg. 3; Sec. 2.1) of `batch` sequences, in double
+ * precision on the device, with the random numbers supplied by the caller.
+ *   draft          dev [batch][gamma]            drafted tokens x'_i
+ *   draft_logits   dev [batch][gamma][vocab]     fp32; p'_i = softmax(draft_logits[i] / temperature)
+ *   target_logits  dev [batch][gamma+1][vocab]   fp32; p_i  = softmax(target_logits[i] / temperature)
+ *   r              dev [batch][gamma]            uniforms in [0,1): position i is rejected when
+ *                                                r_i > p_i(x'_i) / p'_i(x'_i)
+ *   u              dev [batch]                   uniform in [0,1) for the bonus draw
+ *   accept_len     dev [batch]  m = index of the first rejected position, or gamma
+ *   bonus          dev [batch]  drawn from max(0, p_m - p'_m) normalised if m < gamma (the distributions
+ *                               at the first rejected position), from p_gamma otherwise: the lowest token v
+ *                               whose running sum over tokens 0..v exceeds u times the total
+ *   workspace      dev, easyspec_accept_workspace_bytes(batch, gamma) bytes, 8-byte aligned;
+ *                  contents need not be kept between calls
+ *   hip_stream     the hipStream_t to launch on (NULL = the null stream); nothing is synchronised
+ * gamma may be 0 (plain sampling from p_0).  A drafted token outside 0..vocab-1 at or before
+ * the first rejected position gives accept_len = bonus = -1 for that sequence.  EASYSPEC_EINVAL for NULL pointers, batch < 1 or
+ * > 65535, gamma outside 0..64, vocab < 1, or a temperature that is not positive and finite
+ * (temperature 0 is easyspec_greedy_accept).  All arrays are the caller's and only read,
+ * except accept_len, bonus and workspace. */
+int easyspec_accept(const int32_t *draft, const float *draft_logits, const float *target_logits, const float *r,
+                    const float *u, int32_t batch, int32_t gamma, int32_t vocab, float temperature,
+                    int32_t *accept_len, int32_t *bonus, void *workspace, void *hip_stream);
+int64_t easyspec_accept_workspace_bytes(int32_t batch, int32_t gamma); /* -1 for bad arguments */
 
 /* Host copies of the per-sequence lengths; each of precise, fuzzy: host [max_batch] or NULL. */
 int easyspec_get_lens(const easyspec_ctx *ctx, int32_t *precise, int32_t *fuzzy);

@@ -18,6 +18,7 @@ EASYSPEC_MAX_BATCH, EASYSPEC_MAX_CALIB_TOKENS, EASYSPEC_MAX_SET = 16, 16, 8
 
 EXPORTS = ["easyspec_create", "easyspec_destroy", "easyspec_load_weights", "easyspec_set_groups",
            "easyspec_default_groups", "easyspec_draft_step", "easyspec_calibrate", "easyspec_greedy_accept",
+           "easyspec_accept", "easyspec_accept_workspace_bytes",
            "easyspec_get_lens", "easyspec_truncate", "easyspec_kv_import", "easyspec_kv_export",
            "easyspec_get_hidden", "easyspec_step_bytes", "easyspec_profile_begin", "easyspec_profile_end",
            "easyspec_last_error"]
@@ -66,6 +67,9 @@ def load_library():
         L.easyspec_draft_step.argtypes = [vp, vp, vp, vp]
         L.easyspec_calibrate.argtypes = [vp, vp, vp, vp, vp, i32]
         L.easyspec_greedy_accept.argtypes = [vp, vp, i32, i32, vp, vp, vp]
+        L.easyspec_accept.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, C.c_float, vp, vp, vp, vp]
+        L.easyspec_accept_workspace_bytes.argtypes = [i32, i32]
+        L.easyspec_accept_workspace_bytes.restype = C.c_int64
         L.easyspec_get_lens.argtypes = [vp, vp, vp]
         L.easyspec_truncate.argtypes = [vp, i32, i32]
         L.easyspec_kv_import.argtypes = [vp, i32, vp, vp, i32]
@@ -164,6 +168,17 @@ def easyspec_calibrate(ctx, tokens, n_tokens, next_token_out, logits_out=None, l
 def easyspec_greedy_accept(draft, target_argmax, batch, gamma, accept_len, bonus, hip_stream=None):
     _check(load_library().easyspec_greedy_accept(_ptr(draft), _ptr(target_argmax), batch, gamma, _ptr(accept_len),
                                                  _ptr(bonus), _ptr(hip_stream)), None)
+
+
+def easyspec_accept(draft, draft_logits, target_logits, r, u, batch, gamma, vocab, temperature, accept_len, bonus,
+                    workspace, hip_stream=None):
+    _check(load_library().easyspec_accept(_ptr(draft), _ptr(draft_logits), _ptr(target_logits), _ptr(r), _ptr(u), batch,
+                                          gamma, vocab, float(temperature), _ptr(accept_len), _ptr(bonus), _ptr(workspace),
+                                          _ptr(hip_stream)), None)
+
+
+def easyspec_accept_workspace_bytes(batch: int, gamma: int) -> int:
+    return int(load_library().easyspec_accept_workspace_bytes(batch, gamma))
 
 
 def easyspec_get_lens(ctx, max_batch: int):

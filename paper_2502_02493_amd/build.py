@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libeasyspec.so")
-SOURCES = ["easyspec.cpp", "kernels.hip"]
+SOURCES = ["easyspec.cpp", "kernels.hip", "accept.hip"]
 HEADERS = [os.path.join(CSRC, "kernels.h"), os.path.join(HERE, "..", "include", "easyspec.h")]
 
 # -packed-fp32-ops off: the compiler must not form packed fp32 VALU instructions.

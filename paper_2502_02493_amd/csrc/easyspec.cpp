@@ -465,6 +465,27 @@ extern "C" int easyspec_greedy_accept(const int32_t* draft, const int32_t* targe
   return EASYSPEC_OK;
 }
 
+extern "C" int64_t easyspec_accept_workspace_bytes(int32_t batch, int32_t gamma) {
+  if (batch < 1 || gamma < 0) return -1;
+  return (int64_t)batch * (2 * (int64_t)gamma + 1) * 2 * (int64_t)sizeof(double);
+}
+
+extern "C" int easyspec_accept(const int32_t* draft, const float* draft_logits, const float* target_logits, const float* r,
+                               const float* u, int32_t batch, int32_t gamma, int32_t vocab, float temperature,
+                               int32_t* accept_len, int32_t* bonus, void* workspace, void* hip_stream) {
+  if (!target_logits || !u || !accept_len || !bonus || !workspace) return fail(nullptr, EASYSPEC_EINVAL, "accept: NULL argument");
+  if (gamma > 0 && (!draft || !draft_logits || !r)) return fail(nullptr, EASYSPEC_EINVAL, "accept: NULL draft argument with gamma > 0");
+  if (batch < 1 || batch > 65535 || gamma < 0 || gamma > 64 || vocab < 1)
+    return fail(nullptr, EASYSPEC_EINVAL, "accept: need 1 <= batch <= 65535, 0 <= gamma <= 64, vocab >= 1");
+  if (!(temperature > 0.f) || !(temperature < INFINITY)) return fail(nullptr, EASYSPEC_EINVAL, "accept: temperature must be positive and finite (use easyspec_greedy_accept at 0)");
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) return fail(nullptr, EASYSPEC_EHIP, "no HIP device available (this library has no CPU path)");
+  launch_sample_accept(draft, draft_logits, target_logits, r, u, batch, gamma, vocab, (double)temperature, (double*)workspace,
+                       accept_len, bonus, (hipStream_t)hip_stream);
+  HIPCHK(nullptr, hipGetLastError());
+  return EASYSPEC_OK;
+}
+
 extern "C" int easyspec_get_lens(const easyspec_ctx* ctx, int32_t* precise, int32_t* fuzzy) {
   if (!ctx) return fail(nullptr, EASYSPEC_EINVAL, "ctx is NULL");
   for (int b = 0; b < ctx->s.B; ++b) {

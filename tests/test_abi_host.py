@@ -123,3 +123,24 @@ def test_product_does_not_import_the_oracle():
                 assert "oracle" not in text, f"{f} mentions the oracle"
     assert "paper_2502_02493_amd" not in open(os.path.join(ROOT, "oracle", "easyspec_oracle.py")).read()
     assert "paper_2502_02493_amd" not in open(os.path.join(ROOT, "oracle", "easyspec_oracle.c")).read()
+
+
+def test_accept_rejects_bad_arguments_on_the_host():
+    """Argument checks of the sampling acceptance come before any device work."""
+    a = np.zeros(8, np.float32)
+    i = np.zeros(8, np.int32)
+    w = np.zeros(64, np.float64)
+    ok = dict(draft=i, draft_logits=a, target_logits=a, r=a, u=a, batch=1, gamma=1, vocab=2, temperature=1.0,
+              accept_len=i, bonus=i, workspace=w)
+    for over in (dict(temperature=0.0), dict(temperature=-1.0), dict(temperature=float("inf")), dict(batch=0), dict(gamma=-1),
+                 dict(gamma=65), dict(vocab=0), dict(target_logits=None), dict(workspace=None), dict(draft=None), dict(u=None)):
+        with pytest.raises(es.EasySpecError) as e:
+            es.easyspec_accept(**dict(ok, **over))
+        assert e.value.code == es.EASYSPEC_EINVAL, over
+    assert es.easyspec_accept_workspace_bytes(4, 5) == 4 * 11 * 16
+    assert es.easyspec_accept_workspace_bytes(0, 5) == -1
+    import torch
+    if not torch.cuda.is_available():
+        with pytest.raises(es.EasySpecError) as e:      # valid arguments, no device: refused, never computed on the CPU
+            es.easyspec_accept(**ok)
+        assert e.value.code == es.EASYSPEC_EHIP
