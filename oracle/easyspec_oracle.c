@@ -3,7 +3,8 @@
  * implementation of the draft model's layer-sequential step (paper Alg. 1), the
  * layer-parallel fuzzy step (paper Alg. 2), bonus calibration (paper Sec. 3.2), greedy
  * acceptance (paper Alg. 3 at temperature 0) and acceptance by speculative sampling (Alg. 3,
- * Sec. 2.1) with the random numbers passed in.  Only the tests, the smoke check and the
+ * Sec. 2.1) with the random numbers passed in, and the fuzzy step over one level of a token
+ * tree (App. C).  Only the tests, the smoke check and the
  * benchmark's cpu_baseline leg may call it; it shares no code with the HIP library.
  *
  * Arithmetic: every vector and accumulator is a double.  Parameters are read from the
@@ -30,7 +31,8 @@
  * token sequential decoding bit for bit; greedy speculative decoding == vanilla greedy
  * decoding; speculative sampling reproduces the target distribution (exact integration over
  * the random inputs on tiny vocabularies) and reduces to greedy acceptance for one-hot
- * distributions.  The numeric value of a fuzzy step with sets larger than one is fixed by no
+ * distributions; every root-to-node path of a token tree == chain drafting of that path, bit
+ * for bit.  The numeric value of a fuzzy step with sets larger than one is fixed by no
  * number in the paper (its similarity table needs trained weights): that part is pinned
  * by a second composition of the same library blocks and by structural invariants only.
  *
@@ -62,12 +64,18 @@ typedef struct {
   const float *g_final;
 } eso_model;
 
+#define ESO_MAX_TREE 64 /* nodes of one token tree */
+
 typedef struct {
   const eso_model *m;
   float *K, *V; /* [layer][kv_head][slot][head_dim] */
   int32_t precise; /* slots [0, precise) hold values written by calibration */
   int32_t fuzzy;   /* slots [precise, precise+fuzzy) hold values written by fuzzy steps */
   double *attn_tap; /* optional [n_layers][d_model]: Attnoutput_i of the last single-token step */
+  /* token tree (App. C): when n_tree > 0 the fuzzy slots are the nodes of a tree, node t in
+   * slot precise + t, with its parent node (-1: child of the last precise token) and depth */
+  int32_t n_tree;
+  int32_t tree_parent[ESO_MAX_TREE], tree_depth[ESO_MAX_TREE];
 } eso_seq;
 
 /* ---------------------------------------------------------------- storage formats */
@@ -226,7 +234,7 @@ float *eso_seq_k(eso_seq *s) { return s->K; }
 float *eso_seq_v(eso_seq *s) { return s->V; }
 int32_t eso_seq_precise(const eso_seq *s) { return s->precise; }
 int32_t eso_seq_fuzzy(const eso_seq *s) { return s->fuzzy; }
-void eso_seq_set_lens(eso_seq *s, int32_t precise, int32_t fuzzy) { s->precise = precise; s->fuzzy = fuzzy; }
+void eso_seq_set_lens(eso_seq *s, int32_t precise, int32_t fuzzy) { s->precise = precise; s->fuzzy = fuzzy; s->n_tree = 0; }
 double *eso_seq_enable_attn_tap(eso_seq *s) {
   if (!s->attn_tap) s->attn_tap = (double *)calloc((size_t)s->m->cfg.n_layers * (size_t)s->m->cfg.d_model, sizeof(double));
   return s->attn_tap;
@@ -239,9 +247,11 @@ static float *kv_row(const eso_seq *s, float *base, int layer, int kvh, int slot
 
 /* ---------------------------------------------------------------- the three blocks */
 
-/* Attnoutput = Attn_layer(h) for the token at position pos; stores that token's k, v in
- * cache slot pos (values computed from THIS h, whatever h is) and attends to slots 0..pos. */
-static void attn_block(eso_seq *s, int layer, const double *h, int pos, double *out) {
+/* Attnoutput = Attn_layer(h) for a token whose rotary position is rpos; stores that token's
+ * k, v in cache slot `slot` (values computed from THIS h, whatever h is) and attends to the
+ * n_vis slots vis[0] < vis[1] < ... (which include `slot`); vis == NULL means slots 0..slot. */
+static void attn_block_vis(eso_seq *s, int layer, const double *h, int slot, int rpos, const int32_t *vis, int n_vis,
+                           double *out) {
   const eso_config *c = &s->m->cfg;
   const eso_layer *l = &s->m->layers[layer];
   int d = c->d_model, hd = c->head_dim, nq = c->n_q_heads, nkv = c->n_kv_heads, grp = nq / nkv;
@@ -250,17 +260,18 @@ static void attn_block(eso_seq *s, int layer, const double *h, int pos, double *
   double *k = (double *)malloc(sizeof(double) * (size_t)nkv * hd);
   double *v = (double *)malloc(sizeof(double) * (size_t)nkv * hd);
   double *o = (double *)malloc(sizeof(double) * (size_t)nq * hd);
-  double *scores = (double *)malloc(sizeof(double) * (size_t)nq * (size_t)(pos + 1));
+  const int nv = vis ? n_vis : slot + 1;
+  double *scores = (double *)malloc(sizeof(double) * (size_t)nq * (size_t)nv);
 
   double rs = eso_rmsnorm_split(h, l->g_attn, d, c->rms_eps, n);
   for (int j = 0; j < d; ++j) n[j] = act_round(c, n[j]);
   eso_matvec(l->wq, c->bf16, l->bq, rs, nq * hd, d, n, q);
   eso_matvec(l->wk, c->bf16, l->bk, rs, nkv * hd, d, n, k);
   eso_matvec(l->wv, c->bf16, l->bv, rs, nkv * hd, d, n, v);
-  for (int a = 0; a < nq; ++a) eso_rope(q + (size_t)a * hd, hd, pos, c->rope_theta);
+  for (int a = 0; a < nq; ++a) eso_rope(q + (size_t)a * hd, hd, rpos, c->rope_theta);
   for (int g = 0; g < nkv; ++g) {
-    eso_rope(k + (size_t)g * hd, hd, pos, c->rope_theta);
-    float *kr = kv_row(s, s->K, layer, g, pos), *vr = kv_row(s, s->V, layer, g, pos);
+    eso_rope(k + (size_t)g * hd, hd, rpos, c->rope_theta);
+    float *kr = kv_row(s, s->K, layer, g, slot), *vr = kv_row(s, s->V, layer, g, slot);
     for (int e = 0; e < hd; ++e) {
       kr[e] = kv_store(c, k[(size_t)g * hd + e]);
       vr[e] = kv_store(c, v[(size_t)g * hd + e]);
@@ -271,22 +282,27 @@ static void attn_block(eso_seq *s, int layer, const double *h, int pos, double *
   for (int a = 0; a < nq; ++a) { /* heads are independent; each uses its own score row */
     int g = a / grp; /* query head a reads KV head a / (Hq/Hkv) */
     const double *qa = q + (size_t)a * hd;
-    double *sc = scores + (size_t)a * (size_t)(pos + 1);
-    for (int t = 0; t <= pos; ++t) {
-      const float *kr = kv_row(s, s->K, layer, g, t);
+    double *sc = scores + (size_t)a * (size_t)nv;
+    for (int t = 0; t < nv; ++t) {
+      const float *kr = kv_row(s, s->K, layer, g, vis ? vis[t] : t);
       double dot = 0.0;
       for (int e = 0; e < hd; ++e) dot += qa[e] * (double)kr[e];
       sc[t] = dot * scale;
     }
-    eso_softmax(sc, pos + 1);
+    eso_softmax(sc, nv);
     for (int e = 0; e < hd; ++e) {
       double acc = 0.0;
-      for (int t = 0; t <= pos; ++t) acc += sc[t] * (double)kv_row(s, s->V, layer, g, t)[e];
+      for (int t = 0; t < nv; ++t) acc += sc[t] * (double)kv_row(s, s->V, layer, g, vis ? vis[t] : t)[e];
       o[(size_t)a * hd + e] = act_round(c, acc);
     }
   }
   eso_matvec(l->wo, c->bf16, NULL, 1.0, d, nq * hd, o, out);
   free(n); free(q); free(k); free(v); free(o); free(scores);
+}
+
+/* the causal case: the token at position pos sits in slot pos and attends to slots 0..pos */
+static void attn_block(eso_seq *s, int layer, const double *h, int pos, double *out) {
+  attn_block_vis(s, layer, h, pos, pos, NULL, 0, out);
 }
 
 /* MLPoutput = MLP_layer(h) */
@@ -357,7 +373,7 @@ int eso_fuzzy_step(eso_seq *s, const int32_t *bounds, int32_t n_sets, int32_t to
   if (n_sets < 1 || bounds[0] != 0 || bounds[n_sets] != c->n_layers) return -1;
   for (int j = 0; j < n_sets; ++j)
     if (bounds[j + 1] <= bounds[j]) return -1;
-  if (s->precise + s->fuzzy + 1 > c->max_ctx || token < 0 || token >= c->vocab) return -1;
+  if (s->precise + s->fuzzy + 1 > c->max_ctx || token < 0 || token >= c->vocab || s->n_tree != 0) return -1;
   int d = c->d_model, pos = s->precise + s->fuzzy;
   double *h = (double *)malloc(sizeof(double) * (size_t)d), *h1 = (double *)malloc(sizeof(double) * (size_t)d);
   double *a = (double *)malloc(sizeof(double) * (size_t)d * (size_t)c->n_layers);
@@ -382,6 +398,63 @@ int eso_fuzzy_step(eso_seq *s, const int32_t *bounds, int32_t n_sets, int32_t to
   return 0;
 }
 
+/* ---------------------------------------------------------------- token tree (App. C) */
+
+/* One layer-parallel fuzzy forward (Alg. 2) of the n tokens of one tree level.  Node j is the
+ * child of node parents[j] of the tree drafted so far (an index below the node count before
+ * this call), or of the last precise token (-1).  It takes the next free slot, its rotary
+ * position is precise + depth (the position it would have in its own root-to-node sequence),
+ * and it attends to the precise slots, its ancestors and itself: the row of the 2-D tree mask.
+ * The nodes of a level do not see each other, so each is one Alg. 2 forward of its own.
+ * Needs fuzzy == node count (no chain-drafted slots in between).  logits: [n][vocab] or NULL;
+ * hidden_out: [n][d_model] or NULL. */
+int eso_fuzzy_tree_step(eso_seq *s, const int32_t *bounds, int32_t n_sets, int32_t n, const int32_t *tokens,
+                        const int32_t *parents, double *logits, double *hidden_out) {
+  const eso_config *c = &s->m->cfg;
+  if (n_sets < 1 || bounds[0] != 0 || bounds[n_sets] != c->n_layers) return -1;
+  for (int j = 0; j < n_sets; ++j)
+    if (bounds[j + 1] <= bounds[j]) return -1;
+  if (n < 1 || s->fuzzy != s->n_tree || s->n_tree + n > ESO_MAX_TREE || s->precise + s->fuzzy + n > c->max_ctx) return -1;
+  for (int j = 0; j < n; ++j)
+    if (tokens[j] < 0 || tokens[j] >= c->vocab || parents[j] < -1 || parents[j] >= s->n_tree) return -1;
+  int d = c->d_model, P = s->precise, f = s->n_tree;
+  double *h = (double *)malloc(sizeof(double) * (size_t)d), *h1 = (double *)malloc(sizeof(double) * (size_t)d);
+  double *a = (double *)malloc(sizeof(double) * (size_t)d * (size_t)c->n_layers);
+  double *mo = (double *)malloc(sizeof(double) * (size_t)d);
+  int32_t *vis = (int32_t *)malloc(sizeof(int32_t) * (size_t)(P + ESO_MAX_TREE + 1));
+  for (int j = 0; j < n; ++j) {
+    const int node = f + j, slot = P + node;
+    const int depth = parents[j] < 0 ? 0 : s->tree_depth[parents[j]] + 1;
+    /* visible slots in ascending order: precise prefix, ancestors (root first), the node itself */
+    int nv = 0;
+    for (int t = 0; t < P; ++t) vis[nv++] = t;
+    int chain[ESO_MAX_TREE], nc = 0;
+    for (int t = parents[j]; t >= 0; t = s->tree_parent[t]) chain[nc++] = t;
+    for (int t = nc - 1; t >= 0; --t) vis[nv++] = P + chain[t]; /* a parent always has a lower index than its child */
+    vis[nv++] = slot;
+    embed_row(s->m, tokens[j], h);
+    for (int g = 0; g < n_sets; ++g) {
+      int lo = bounds[g], hi = bounds[g + 1];
+      memcpy(h1, h, sizeof(double) * (size_t)d);                                                      /* h_1 = h */
+      for (int i = lo; i < hi; ++i) attn_block_vis(s, i, h1, slot, P + depth, vis, nv, a + (size_t)i * d); /* Attn_i(h_1) */
+      for (int i = lo; i < hi; ++i) {
+        const double *ai = a + (size_t)i * d;
+        for (int e = 0; e < d; ++e) h[e] = h[e] + ai[e];  /* h'_i = h_i + Attnoutput_i */
+        mlp_block(s->m, i, h, mo);                        /* MLPoutput_i = MLP_i(h'_i) */
+        for (int e = 0; e < d; ++e) h[e] = h[e] + mo[e];  /* h_{i+1} = h'_i + MLPoutput_i */
+      }
+    }
+    if (hidden_out) memcpy(hidden_out + (size_t)j * d, h, sizeof(double) * (size_t)d);
+    if (logits) head(s->m, h, logits + (size_t)j * c->vocab);
+    s->tree_parent[node] = parents[j];
+    s->tree_depth[node] = depth;
+  }
+  s->n_tree += n;
+  s->fuzzy += n;
+  free(h); free(h1); free(a); free(mo); free(vis);
+  return 0;
+}
+
 /* ---------------------------------------------------------------- bonus calibration (Sec. 3.2) */
 
 /* Drop every fuzzy slot, then run ONE token-parallel, layer-sequential forward over the
@@ -394,6 +467,7 @@ int eso_calibrate(eso_seq *s, const int32_t *tokens, int32_t n, double *logits_a
   for (int r = 0; r < n; ++r)
     if (tokens[r] < 0 || tokens[r] >= c->vocab) return -1;
   s->fuzzy = 0;
+  s->n_tree = 0;
   int d = c->d_model, p0 = s->precise;
   double *H = (double *)malloc(sizeof(double) * (size_t)n * d);
   double *a = (double *)malloc(sizeof(double) * (size_t)d), *mo = (double *)malloc(sizeof(double) * (size_t)d);

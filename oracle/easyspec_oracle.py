@@ -73,6 +73,7 @@ def lib():
         L.eso_seq_enable_attn_tap.argtypes = [vp]
         L.eso_sequential_step.argtypes = [vp, i32, dp, dp]
         L.eso_fuzzy_step.argtypes = [vp, ip, i32, i32, dp, dp]
+        L.eso_fuzzy_tree_step.argtypes = [vp, ip, i32, i32, ip, ip, dp, dp]
         L.eso_calibrate.argtypes = [vp, ip, i32, dp, dp]
         L.eso_calibrate_last.argtypes = [vp, ip, i32, dp]
         L.eso_greedy_accept.argtypes = [ip, ip, i32, ip, ip]
@@ -300,6 +301,20 @@ class Sequence:
         hid = np.empty(c["d_model"], dtype=np.float64) if want_hidden else None
         if lib().eso_fuzzy_step(self._h, _ip(b), b.size - 1, int(token), _dp(logits), _dp(hid)) != 0:
             raise RuntimeError("oracle fuzzy_step: bad state or arguments")
+        return (logits, hid) if want_hidden else logits
+
+    def fuzzy_tree_step(self, bounds, tokens, parents, want_hidden=False):
+        """One level of a token tree (paper App. C): node j is the child of tree node parents[j]
+        (-1: of the last precise token).  Returns logits [n, V]."""
+        c = self.model.cfg
+        b = np.ascontiguousarray(bounds, dtype=np.int32)
+        t = np.ascontiguousarray(tokens, dtype=np.int32)
+        p = np.ascontiguousarray(parents, dtype=np.int32)
+        assert t.size == p.size
+        logits = np.empty((t.size, c["vocab"]), dtype=np.float64)
+        hid = np.empty((t.size, c["d_model"]), dtype=np.float64) if want_hidden else None
+        if lib().eso_fuzzy_tree_step(self._h, _ip(b), b.size - 1, t.size, _ip(t), _ip(p), _dp(logits), _dp(hid)) != 0:
+            raise RuntimeError("oracle fuzzy_tree_step: bad state or arguments")
         return (logits, hid) if want_hidden else logits
 
     def calibrate(self, tokens, all_rows=True, want_hidden=False):
