@@ -4,6 +4,7 @@
  * What the library computes (EasySpec, arXiv 2502.02493):
  *   - easyspec_draft_step     one layer-parallel "fuzzy" forward of the draft model
  *                             (paper Alg. 2; the layer-parallel strategy of Sec. 3.1.1)
+ *   - easyspec_draft_tree_step  the same fuzzy forward over one level of a token tree (App. C)
  *   - easyspec_calibrate      bonus calibration: drop the fuzzy KV entries, refill the cache
  *                             with precise values by one token-parallel, layer-sequential
  *                             forward (paper Sec. 3.2, Alg. 1)
@@ -51,6 +52,8 @@ extern "C" {
 #define EASYSPEC_MAX_BATCH 16        /* sequences per context */
 #define EASYSPEC_MAX_CALIB_TOKENS 16 /* tokens of one sequence per calibration call */
 #define EASYSPEC_MAX_SET 8           /* layers per layer-parallel set */
+#define EASYSPEC_MAX_TREE_WIDTH 16   /* nodes one easyspec_draft_tree_step call may add (all sequences together) */
+#define EASYSPEC_MAX_TREE_NODES 64   /* nodes of one sequence's token tree */
 
 typedef struct easyspec_config {
   int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
@@ -122,6 +125,30 @@ int easyspec_default_groups(int32_t n_layers, int32_t N, int32_t policy, int32_t
  * Afterwards fuzzy[b] += 1.  EASYSPEC_ESTATE if no sequence is live, EASYSPEC_ECAPACITY if a
  * live sequence is full. */
 int easyspec_draft_step(easyspec_ctx *ctx, const int32_t *tokens_in, int32_t *tokens_out, float *logits_out);
+
+/* One fuzzy forward (Alg. 2) over one level of a token tree (Sec. 3.1 last paragraph, App. C):
+ * the drafted tokens of a sequence form a tree, every root-to-node path being one candidate
+ * sequence; common prefixes share their KV entries and a node attends to the precise context,
+ * its ancestors and itself (its row of the 2-D tree mask).  How the tree is grown (which tokens
+ * become children of which node) is the caller's policy; the paper fixes none.
+ *   tokens_in   dev  [max_batch][EASYSPEC_MAX_TREE_WIDTH]  tokens of the new nodes of sequence b
+ *   n_nodes     host [max_batch]  number of new nodes of b, 0 = none; at most
+ *                    EASYSPEC_MAX_TREE_WIDTH over all sequences
+ *   parents     host [max_batch][EASYSPEC_MAX_TREE_WIDTH]  parent of new node j: a node index of b's
+ *                    tree as it stood before the call (nodes are numbered in the order they were
+ *                    added, 0 .. fuzzy[b]-1), or -1 = child of the last precise token
+ *   tokens_out  dev  [max_batch][EASYSPEC_MAX_TREE_WIDTH]  argmax after each new node
+ *   logits_out  dev  fp32 [max_batch][EASYSPEC_MAX_TREE_WIDTH][vocab] or NULL (for top-k children)
+ * New node j of b takes slot precise[b] + fuzzy[b] + j in every layer (its k, v are those of the
+ * fuzzy forward) and rotary position precise[b] + depth, depth = 0 for children of the last precise
+ * token.  Afterwards fuzzy[b] += n_nodes[b].  A tree whose every node is the child of the previous
+ * one is chain drafting.  Trees and easyspec_draft_step do not mix between two calibrations:
+ * EASYSPEC_ESTATE if b holds chain-drafted slots (and easyspec_draft_step refuses a sequence that
+ * holds a tree).  EASYSPEC_ECAPACITY beyond EASYSPEC_MAX_TREE_NODES nodes, max_ctx slots or the
+ * per-call width; EASYSPEC_EINVAL for a parent that is not an earlier node.  Calibration drops
+ * the whole tree like any fuzzy slots. */
+int easyspec_draft_tree_step(easyspec_ctx *ctx, const int32_t *tokens_in, const int32_t *n_nodes, const int32_t *parents,
+                             int32_t *tokens_out, float *logits_out);
 
 /* Bonus calibration (Sec. 3.2) of the sequences with n_tokens[b] > 0; also the prompt prefill
  * (repeat in chunks of max_calib_tokens).

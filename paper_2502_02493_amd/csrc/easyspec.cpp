@@ -23,6 +23,13 @@ struct easyspec_ctx {
   hipStream_t stream;
   bool weights_loaded;
   std::vector<int32_t> precise, fuzzy;
+  // token tree of each sequence (nodes = its fuzzy slots, node t in slot precise + t)
+  struct Tree {
+    int32_t n = 0;
+    int32_t depth[EASYSPEC_MAX_TREE_NODES];
+    uint64_t line[EASYSPEC_MAX_TREE_NODES];  // bit a set: node a is the node itself or an ancestor
+  };
+  std::vector<Tree> tree;
   std::vector<int32_t> bounds;  // current layer-parallel strategy
   std::vector<int32_t> single;  // every layer alone (Alg. 1 order)
   std::vector<void*> allocs;
@@ -112,6 +119,7 @@ extern "C" int easyspec_create(const easyspec_config* cfg, void* hip_stream, eas
   s.B = cfg->max_batch; s.max_ctx = cfg->max_ctx; s.eps = cfg->rms_eps; s.has_bias = cfg->qkv_bias ? 1 : 0;
   ctx->precise.assign(s.B, 0);
   ctx->fuzzy.assign(s.B, 0);
+  ctx->tree.assign(s.B, easyspec_ctx::Tree());
   for (int i = 0; i <= s.L; ++i) ctx->single.push_back(i);
   ctx->bounds = ctx->single;
 
@@ -384,13 +392,64 @@ extern "C" int easyspec_draft_step(easyspec_ctx* ctx, const int32_t* tokens_in, 
     if (ctx->precise[b] == 0) continue;
     const int pos = ctx->precise[b] + ctx->fuzzy[b];
     if (pos + 1 > s.max_ctx) return fail(ctx, EASYSPEC_ECAPACITY, "draft_step: sequence %d is full (%d slots)", b, s.max_ctx);
+    if (ctx->tree[b].n > 0) return fail(ctx, EASYSPEC_ESTATE, "draft_step: sequence %d holds a token tree (continue it with easyspec_draft_tree_step)", b);
     c.seq[c.n] = b; c.pos[c.n] = pos; c.tok_idx[c.n] = b; c.logit_row[c.n] = b; c.out_idx[c.n] = b;
+    c.rope_pos[c.n] = pos; c.vis_base[c.n] = pos + 1;  // causal: every earlier slot is visible
     ++c.n;
   }
   if (c.n == 0) return fail(ctx, EASYSPEC_ESTATE, "draft_step: no live sequence (calibrate a prompt first)");
   const int rc = forward(ctx, c, tokens_in, ctx->bounds, logits_out, tokens_out);
   if (rc != EASYSPEC_OK) return rc;
   for (int i = 0; i < c.n; ++i) ctx->fuzzy[c.seq[i]] += 1;
+  return EASYSPEC_OK;
+}
+
+extern "C" int easyspec_draft_tree_step(easyspec_ctx* ctx, const int32_t* tokens_in, const int32_t* n_nodes, const int32_t* parents,
+                                        int32_t* tokens_out, float* logits_out) {
+  if (!ctx) return fail(nullptr, EASYSPEC_EINVAL, "ctx is NULL");
+  if (!ctx->weights_loaded) return fail(ctx, EASYSPEC_ESTATE, "draft_tree_step: no weights loaded");
+  if (!tokens_in || !n_nodes || !parents || !tokens_out) return fail(ctx, EASYSPEC_EINVAL, "draft_tree_step: NULL argument");
+  const Shape& s = ctx->s;
+  const int W = EASYSPEC_MAX_TREE_WIDTH;
+  Cols c;
+  memset(&c, 0, sizeof c);
+  for (int b = 0; b < s.B; ++b) {
+    const int n = n_nodes[b];
+    if (n == 0) continue;
+    const easyspec_ctx::Tree& t = ctx->tree[b];
+    if (n < 0 || n > W) return fail(ctx, EASYSPEC_EINVAL, "draft_tree_step: n_nodes[%d] = %d outside 0..%d", b, n, W);
+    if (ctx->precise[b] == 0) return fail(ctx, EASYSPEC_ESTATE, "draft_tree_step: sequence %d has no context (calibrate a prompt first)", b);
+    if (ctx->fuzzy[b] != t.n) return fail(ctx, EASYSPEC_ESTATE, "draft_tree_step: sequence %d holds chain-drafted slots; calibrate first", b);
+    if (t.n + n > EASYSPEC_MAX_TREE_NODES) return fail(ctx, EASYSPEC_ECAPACITY, "draft_tree_step: sequence %d would hold %d > %d tree nodes", b, t.n + n, EASYSPEC_MAX_TREE_NODES);
+    if (ctx->precise[b] + t.n + n > s.max_ctx) return fail(ctx, EASYSPEC_ECAPACITY, "draft_tree_step: sequence %d is full (%d slots)", b, s.max_ctx);
+    if (c.n + n > kMaxCols) return fail(ctx, EASYSPEC_ECAPACITY, "draft_tree_step: more than %d nodes in one call", kMaxCols);
+    for (int j = 0; j < n; ++j) {
+      const int par = parents[b * W + j];
+      if (par < -1 || par >= t.n) return fail(ctx, EASYSPEC_EINVAL, "draft_tree_step: parent %d of node %d of sequence %d is not a node of an earlier level", par, j, b);
+      const int node = t.n + j;
+      const int depth = par < 0 ? 0 : t.depth[par] + 1;
+      c.seq[c.n] = b;
+      c.pos[c.n] = ctx->precise[b] + node;
+      c.rope_pos[c.n] = ctx->precise[b] + depth;
+      c.vis_base[c.n] = ctx->precise[b];
+      c.vis_mask[c.n] = (par < 0 ? 0ull : t.line[par]) | (1ull << node);
+      c.tok_idx[c.n] = b * W + j; c.logit_row[c.n] = b * W + j; c.out_idx[c.n] = b * W + j;
+      ++c.n;
+    }
+  }
+  if (c.n == 0) return fail(ctx, EASYSPEC_EINVAL, "draft_tree_step: no nodes");
+  const int rc = forward(ctx, c, tokens_in, ctx->bounds, logits_out, tokens_out);
+  if (rc != EASYSPEC_OK) return rc;
+  for (int i = 0; i < c.n; ++i) {
+    easyspec_ctx::Tree& t = ctx->tree[c.seq[i]];
+    const int node = c.pos[i] - ctx->precise[c.seq[i]];
+    t.depth[node] = c.rope_pos[i] - ctx->precise[c.seq[i]];
+    t.line[node] = c.vis_mask[i];
+  }
+  for (int b = 0; b < s.B; ++b) {
+    ctx->tree[b].n += n_nodes[b];
+    ctx->fuzzy[b] += n_nodes[b];
+  }
   return EASYSPEC_OK;
 }
 
@@ -422,6 +481,8 @@ extern "C" int easyspec_calibrate(easyspec_ctx* ctx, const int32_t* tokens, cons
         const bool last = r == n - 1;
         c.seq[c.n] = b;
         c.pos[c.n] = ctx->precise[b] + r;  // fuzzy slots are dropped: positions restart at the precise length
+        c.rope_pos[c.n] = c.pos[c.n];
+        c.vis_base[c.n] = c.pos[c.n] + 1;  // causal among the tokens of the pass
         c.tok_idx[c.n] = b * mc + r;
         c.logit_row[c.n] = logits_rows ? b * mc + r : (last ? b : -1);
         c.out_idx[c.n] = last ? b : -1;
@@ -436,6 +497,7 @@ extern "C" int easyspec_calibrate(easyspec_ctx* ctx, const int32_t* tokens, cons
   for (int q = 0; q < s.B; ++q)
     if (n_tokens[q] > 0) {
       ctx->fuzzy[q] = 0;
+      ctx->tree[q].n = 0;
       ctx->precise[q] += n_tokens[q];
     }
   return EASYSPEC_OK;
@@ -501,6 +563,7 @@ extern "C" int easyspec_truncate(easyspec_ctx* ctx, int32_t b, int32_t new_len) 
   if (new_len < 0 || new_len > ctx->precise[b]) return fail(ctx, EASYSPEC_EINVAL, "truncate: length %d outside 0..%d", new_len, ctx->precise[b]);
   ctx->precise[b] = new_len;
   ctx->fuzzy[b] = 0;
+  ctx->tree[b].n = 0;
   return EASYSPEC_OK;
 }
 
@@ -544,6 +607,7 @@ extern "C" int easyspec_kv_import(easyspec_ctx* ctx, int32_t b, const void* k, c
   if (rc != EASYSPEC_OK) return rc;
   ctx->precise[b] = n_slots;
   ctx->fuzzy[b] = 0;
+  ctx->tree[b].n = 0;
   return EASYSPEC_OK;
 }
 

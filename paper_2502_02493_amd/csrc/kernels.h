@@ -13,7 +13,12 @@ constexpr int kMaxChunks = 64;  // split-KV chunks per (column, head)
 struct Cols {
   int32_t n;
   int32_t seq[kMaxCols];
-  int32_t pos[kMaxCols];        // slot the column writes; it attends to slots 0..pos
+  int32_t pos[kMaxCols];        // slot the column writes; the highest slot it attends to
+  int32_t rope_pos[kMaxCols];   // its rotary position (= pos except for the nodes of a token tree)
+  // Visibility of slots 0..pos: every slot below vis_base, and slot vis_base + i iff bit i of
+  // vis_mask (pos < vis_base + 64).  Causal columns: vis_base = pos + 1.
+  int32_t vis_base[kMaxCols];
+  unsigned long long vis_mask[kMaxCols];
   int32_t tok_idx[kMaxCols];    // index into the caller's token array
   int32_t logit_row[kMaxCols];  // row of logits_out to write, or -1
   int32_t out_idx[kMaxCols];    // index of tokens_out to write, or -1

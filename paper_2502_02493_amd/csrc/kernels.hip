@@ -392,7 +392,7 @@ __global__ __launch_bounds__(1024) void qkv_kernel(QkvArgs a, Cols c) {
       b_hi = *reinterpret_cast<const f32x4*>(a.bias + (size_t)li * RQKV + head * a.hd + e0 + half);
     }
     if (head < a.Hq + a.Hkv) {
-      const f32x4* rp = reinterpret_cast<const f32x4*>(a.rope + (size_t)pos * half + e0);  // 4 x (cos, sin)
+      const f32x4* rp = reinterpret_cast<const f32x4*>(a.rope + (size_t)c.rope_pos[col] * half + e0);  // 4 x (cos, sin)
       cs01 = rp[0];
       cs23 = rp[1];
     }
@@ -710,13 +710,19 @@ struct AttnGeom {
 
 extern __shared__ float dyn_f[];
 
-template <typename T, int HD, int G>
+// TREE: the columns are nodes of token trees and carry a visibility mask; without it every
+// slot up to the column's own is visible and the mask logic costs no registers.
+template <typename T, int HD, int G, bool TREE>
 __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
   typedef AttnGeom<T, HD> Geo;
   constexpr int EPL = Geo::EPL, LPS = Geo::LPS, SPW = Geo::SPW, IT = kAttnIT;
   const int chunk = blockIdx.x, kvh = blockIdx.y;
   const int li = blockIdx.z / c.n, col = blockIdx.z % c.n;
   const int n_slots = c.pos[col] + 1;
+  // slots below vis_base are all visible; slot vis_base + i (i < 64) only if bit i is set (the
+  // column's row of a token tree's mask).  Causal columns have vis_base = n_slots.
+  const int vbase = c.vis_base[col];
+  const unsigned long long vmask = c.vis_mask[col];
   const int s0 = chunk * a.CH;
   if (s0 >= n_slots) return;
   const int s1 = min(s0 + a.CH, n_slots);
@@ -755,10 +761,11 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
       const int s = base + j * SPW + sub;
       vr[j] = s < s1 ? *reinterpret_cast<const u32x4*>(vb + (size_t)s * HD) : zero;
     }
-    float sc[IT][G];
+    float sc[IT][G], m_use[G];
 #pragma unroll
     for (int j = 0; j < IT; ++j) {
-      const bool valid = base + j * SPW + sub < s1;
+      const int s = base + j * SPW + sub;
+      const bool valid = s < s1 && (!TREE || s < vbase || ((vmask >> (s - vbase)) & 1ull));
       float kv[EPL];
       unpack<T>(kr[j], kv);
 #pragma unroll
@@ -778,10 +785,13 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
       for (int j = 1; j < IT; ++j) bm = fmaxf(bm, sc[j][g]);
 #pragma unroll
       for (int off = LPS; off < 64; off <<= 1) bm = fmaxf(bm, __shfl_xor(bm, off, 64));
-      // the first slot of a batch is always valid, so bm is finite
+      // a batch that lies wholly among masked tree slots leaves the maximum at -inf: the
+      // exponentials then take 0 as reference, so that they give 0 instead of exp(-inf + inf)
       const float m_new = fmaxf(m_run[g], bm);
-      const float alpha = __expf(m_run[g] - m_new);  // exp(-inf) = 0 on the first batch
+      const float m_ref = (TREE && m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = __expf(m_run[g] - m_ref);  // exp(-inf) = 0 on the first batch
       m_run[g] = m_new;
+      m_use[g] = m_ref;
       l_run[g] *= alpha;
 #pragma unroll
       for (int e = 0; e < EPL; ++e) acc[g][e] *= alpha;
@@ -792,7 +802,7 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
       unpack<T>(vr[j], vv);
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        const float p = __expf(sc[j][g] - m_run[g]);  // 0 for slots past the end
+        const float p = __expf(sc[j][g] - m_use[g]);  // 0 for slots past the end or masked
         l_run[g] += p;
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc[g][e] += p * vv[e];
@@ -1046,16 +1056,16 @@ void launch_qkv(const Shape& s, const Buffers& b, const Cols& c, int layer0, int
                hipLaunchKernelGGL((qkv_kernel<T, NB>), dim3(grid), dim3(64 * nw), red_bytes(nw, 2), st, a, c));
 }
 
-template <typename T, int HD>
+template <typename T, int HD, bool TREE>
 static void launch_attn_g(int G, dim3 grid, int nwv, hipStream_t st, const AttnArgs& a, const Cols& c) {
   const size_t lds = (size_t)(nwv * G * HD + 2 * nwv * G) * sizeof(float);
   const dim3 blk(64 * nwv);
   switch (G) {
-    case 1: hipLaunchKernelGGL((attn_kernel<T, HD, 1>), grid, blk, lds, st, a, c); break;
-    case 2: hipLaunchKernelGGL((attn_kernel<T, HD, 2>), grid, blk, lds, st, a, c); break;
-    case 4: hipLaunchKernelGGL((attn_kernel<T, HD, 4>), grid, blk, lds, st, a, c); break;
-    case 7: hipLaunchKernelGGL((attn_kernel<T, HD, 7>), grid, blk, lds, st, a, c); break;
-    case 8: hipLaunchKernelGGL((attn_kernel<T, HD, 8>), grid, blk, lds, st, a, c); break;
+    case 1: hipLaunchKernelGGL((attn_kernel<T, HD, 1, TREE>), grid, blk, lds, st, a, c); break;
+    case 2: hipLaunchKernelGGL((attn_kernel<T, HD, 2, TREE>), grid, blk, lds, st, a, c); break;
+    case 4: hipLaunchKernelGGL((attn_kernel<T, HD, 4, TREE>), grid, blk, lds, st, a, c); break;
+    case 7: hipLaunchKernelGGL((attn_kernel<T, HD, 7, TREE>), grid, blk, lds, st, a, c); break;
+    case 8: hipLaunchKernelGGL((attn_kernel<T, HD, 8, TREE>), grid, blk, lds, st, a, c); break;
     default: break;  // rejected at create
   }
 }
@@ -1076,9 +1086,13 @@ void launch_attn(const Shape& s, const Buffers& b, const Cols& c, int layer0, in
   // one chunk per context: eight waves share the whole context of a (layer, column, KV head) and
   // no merge launch is needed; several chunks: four waves per chunk
   const int nwv = n_chunks == 1 ? 8 : 4;
+  bool tree = false;  // any column that does not see every slot up to its own
+  for (int i = 0; i < c.n; ++i) tree = tree || c.vis_base[i] <= c.pos[i];
   DISPATCH_T(s.dtype, {
-    if (s.hd == 128) launch_attn_g<T, 128>(G, grid, nwv, st, a, c);
-    else launch_attn_g<T, 64>(G, grid, nwv, st, a, c);
+    if (s.hd == 128 && tree) launch_attn_g<T, 128, true>(G, grid, nwv, st, a, c);
+    else if (s.hd == 128) launch_attn_g<T, 128, false>(G, grid, nwv, st, a, c);
+    else if (tree) launch_attn_g<T, 64, true>(G, grid, nwv, st, a, c);
+    else launch_attn_g<T, 64, false>(G, grid, nwv, st, a, c);
   });
   if (n_chunks > 1) {
     const dim3 mgrid(n_set * c.n, s.Hkv);

@@ -87,6 +87,27 @@ class GpuDrafter:
         torch.cuda.synchronize()
         return self.tok_out.cpu().numpy().copy(), self.logits.cpu().numpy().copy()
 
+    def draft_tree_step(self, nodes_by_seq: dict):
+        """nodes_by_seq: {b: ([token ids], [parents])}.  Returns ({b: argmax ids [n]}, {b: logits [n, V]})."""
+        W, V = es.EASYSPEC_MAX_TREE_WIDTH, self.cfg["vocab"]
+        if not hasattr(self, "tree_in"):
+            self.tree_in = torch.zeros(self.B, W, dtype=torch.int32, device=self.dev)
+            self.tree_out = torch.zeros(self.B, W, dtype=torch.int32, device=self.dev)
+            self.tree_logits = torch.zeros(self.B, W, V, dtype=torch.float32, device=self.dev)
+        n = np.zeros(self.B, np.int32)
+        host = np.zeros((self.B, W), np.int32)
+        par = np.full((self.B, W), -1, np.int32)
+        for b, (t, p) in nodes_by_seq.items():
+            n[b] = len(t)
+            host[b, : len(t)] = t
+            par[b, : len(p)] = p
+        self.tree_in.copy_(torch.from_numpy(host))
+        self.tree_out.fill_(-1)
+        es.easyspec_draft_tree_step(self.ctx, self.tree_in, n, par, self.tree_out, self.tree_logits)
+        torch.cuda.synchronize()
+        toks, lg = self.tree_out.cpu().numpy(), self.tree_logits.cpu().numpy()
+        return ({b: toks[b, : n[b]].copy() for b in nodes_by_seq}, {b: lg[b, : n[b]].copy() for b in nodes_by_seq})
+
     def hidden(self):
         out = torch.zeros(16, self.cfg["d_model"], dtype=torch.float32, device=self.dev)
         n = es.easyspec_get_hidden(self.ctx, out, 16)
