@@ -76,7 +76,7 @@ def main():
     M = gamma + 1
     policy = es.EASYSPEC_POLICY_ALIGNED if wl["group_policy"] == "aligned" else es.EASYSPEC_POLICY_PACKED
     bounds = es.easyspec_default_groups(cfg["n_layers"], wl["group_size"], policy)
-    max_ctx = ctx_len + M + gamma + 8
+    max_ctx = ctx_len + M + max(gamma, 4 * 12) + 8      # room for the chain and for the widest tree timed below
 
     t0 = time.time()
     weights = synth.make_weights(cfg, args.seed)
@@ -181,6 +181,33 @@ def main():
     torch.cuda.synchronize()
     accept_us = 1e3 * sa[0].elapsed_time(sa[1]) / n_acc
 
+    # one level of a token tree per forward (tree widths of the paper's ablation), same context
+    tree = {}
+    W = es.EASYSPEC_MAX_TREE_WIDTH
+    tree_in = torch.from_numpy(synth.make_tokens(args.seed + 8, W, cfg["vocab"]).reshape(1, W)).to(dev)
+    tree_out = torch.zeros(1, W, dtype=torch.int32, device=dev)
+    for width in (4, 8, 12):
+        levels = 4
+        evs_t = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        reps = max(2, args.steps // 4)
+        tot = 0.0
+        for rep in range(reps + 1):
+            es.easyspec_truncate(ctx, 0, ctx_len)
+            es.easyspec_calibrate(ctx, calib_tok, n_tok, dptr, None, 0)
+            evs_t[0].record()
+            for lvl in range(levels):
+                par = np.full((1, W), -1, np.int32)
+                if lvl:
+                    par[0, :width] = (lvl - 1) * width + np.arange(width) // 2      # two children per node, half the nodes are leaves
+                es.easyspec_draft_tree_step(ctx, tree_in, np.array([width], np.int32), par, tree_out, None)
+            evs_t[1].record()
+            torch.cuda.synchronize()
+            if rep:
+                tot += evs_t[0].elapsed_time(evs_t[1])
+        us = 1e3 * tot / (reps * levels)
+        tree[f"width_{width}"] = {"us_per_level": round(us, 1), "hbm_frac": round(step_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
+    es.easyspec_truncate(ctx, 0, ctx_len)
+
     traffic_kib = args.traffic_kib if args.traffic_kib is not None else (
         None if args.layers else MEASURED_TRAFFIC_KIB.get(args.workload))
     out = {
@@ -205,6 +232,7 @@ def main():
                      "event_pair_us": round(1e3 * gu_raw_ms, 2), "empty_event_pair_us": round(1e3 * null_ms, 2),
                      "launches_timed": n_timed},
         "kernel_time": per_op,
+        "tree_step": tree,
         "sample_accept": {"us": round(accept_us, 1), "temperature": 0.8, "gamma": gamma, "vocab": V, "dtype": "f64",
                           "logit_bytes": (2 * gamma + 1) * V * 4},
     }

@@ -46,15 +46,18 @@ struct Buffers {
   float2 *rope;                          // [max_ctx][hd/2] (cos, sin)
   // cache
   void *kc, *vc;  // [L][B][Hkv][max_ctx][hd] T
-  // workspaces (per forward pass; column-major activations [.][kMaxCols][width])
+  // workspaces (per forward pass).  fp32 arrays are [.][kMaxCols][width].  Arrays in T are operands of
+  // the next weight contraction: per part either plain rows [column][width] (passes of one or two
+  // columns) or 1 KB tiles of KT consecutive k holding [k-group][column][EPL elements], the order of
+  // a wave's B fragments (see xoff() in kernels.hip); a slot of XA / AO is PARTS * 16 * width elements.
   float *H;     // [16][d]      residual stream
   float *ssp;   // [16][d/16]   per-row-tile partial sums of squares of the vector to be normed next
-  void *XA;     // [MAX_SET][16][d] T   H * g_attn(layer) for the layers of the coming set (or g_final)
-  void *XM;     // [16][d] T            H' * g_mlp(layer)
+  void *XA;     // [MAX_SET] x (16 x d) T   H * g_attn(layer) for the layers of the coming set (or g_final)
+  void *XM;     // (16 x d) T               H' * g_mlp(layer)
   float *Q;     // [MAX_SET][16][HQ]    rotated queries
-  void *AO;     // [MAX_SET][16][HQ] T  attention output (rounded to T)
+  void *AO;     // [MAX_SET] x (16 x HQ) T  attention output (rounded to T)
   float *A;     // [MAX_SET][16][d]     Attnoutput_i
-  void *ACT;    // [16][F] T            SiLU(gate)*up
+  void *ACT;    // (16 x F) T               SiLU(gate)*up
   float *PO;    // [MAX_SET*16*Hq][kMaxChunks][hd]  split-KV partial outputs
   float *PM, *PL;  // [MAX_SET*16*Hq][kMaxChunks]   partial max / sum
   float *amax_val; // [16][n_head_blocks]
