@@ -171,7 +171,7 @@ def main():
     tl = torch.from_numpy(synth.make_logits(args.seed + 5, gamma + 1, V)).to(dev)
     dl = (tl[:gamma] + 0.7 * torch.from_numpy(synth.make_logits(args.seed + 6, gamma, V, std=1.0)).to(dev)).contiguous()
     ru = torch.from_numpy(synth.make_uniforms(args.seed + 7, gamma + 1)).to(dev)
-    ws = torch.empty(es.easyspec_accept_workspace_bytes(1, gamma) // 8, dtype=torch.float64, device=dev)
+    ws = torch.empty(es.easyspec_accept_workspace_bytes(1, gamma, V) // 8, dtype=torch.float64, device=dev)
     sa = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     n_acc = 50
     for k in range(n_acc + 5):

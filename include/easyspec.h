@@ -183,7 +183,8 @@ int easyspec_greedy_accept(const int32_t *draft, const int32_t *target_argmax, i
  *   bonus          dev [batch]  drawn from max(0, p_m - p'_m) normalised if m < gamma (the distributions
  *                               at the first rejected position), from p_gamma otherwise: the lowest token v
  *                               whose running sum over tokens 0..v exceeds u times the total
- *   workspace      dev, easyspec_accept_workspace_bytes(batch, gamma) bytes, 8-byte aligned;
+ *   workspace      dev, easyspec_accept_workspace_bytes(batch, gamma, vocab) bytes, 8-byte aligned
+ *                  (about 8 bytes per vocabulary entry and sequence: the bonus weights);
  *                  contents need not be kept between calls
  *   hip_stream     the hipStream_t to launch on (NULL = the null stream); nothing is synchronised
  * gamma may be 0 (plain sampling from p_0).  A drafted token outside 0..vocab-1 at or before
@@ -194,7 +195,7 @@ int easyspec_greedy_accept(const int32_t *draft, const int32_t *target_argmax, i
 int easyspec_accept(const int32_t *draft, const float *draft_logits, const float *target_logits, const float *r,
                     const float *u, int32_t batch, int32_t gamma, int32_t vocab, float temperature,
                     int32_t *accept_len, int32_t *bonus, void *workspace, void *hip_stream);
-int64_t easyspec_accept_workspace_bytes(int32_t batch, int32_t gamma); /* -1 for bad arguments */
+int64_t easyspec_accept_workspace_bytes(int32_t batch, int32_t gamma, int32_t vocab); /* -1 for bad arguments */
 
 /* Host copies of the per-sequence lengths; each of precise, fuzzy: host [max_batch] or NULL. */
 int easyspec_get_lens(const easyspec_ctx *ctx, int32_t *precise, int32_t *fuzzy);

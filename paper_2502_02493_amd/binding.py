@@ -70,7 +70,7 @@ def load_library():
         L.easyspec_draft_tree_step.argtypes = [vp, vp, vp, vp, vp, vp]
         L.easyspec_greedy_accept.argtypes = [vp, vp, i32, i32, vp, vp, vp]
         L.easyspec_accept.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, C.c_float, vp, vp, vp, vp]
-        L.easyspec_accept_workspace_bytes.argtypes = [i32, i32]
+        L.easyspec_accept_workspace_bytes.argtypes = [i32, i32, i32]
         L.easyspec_accept_workspace_bytes.restype = C.c_int64
         L.easyspec_get_lens.argtypes = [vp, vp, vp]
         L.easyspec_truncate.argtypes = [vp, i32, i32]
@@ -186,8 +186,8 @@ def easyspec_accept(draft, draft_logits, target_logits, r, u, batch, gamma, voca
                                           _ptr(hip_stream)), None)
 
 
-def easyspec_accept_workspace_bytes(batch: int, gamma: int) -> int:
-    return int(load_library().easyspec_accept_workspace_bytes(batch, gamma))
+def easyspec_accept_workspace_bytes(batch: int, gamma: int, vocab: int) -> int:
+    return int(load_library().easyspec_accept_workspace_bytes(batch, gamma, vocab))
 
 
 def easyspec_get_lens(ctx, max_batch: int):

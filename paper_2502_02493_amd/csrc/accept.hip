@@ -8,15 +8,23 @@
 //   bonus ~ max(0, p_m - p'_m) / sum  (m < gamma),  p_gamma  (m = gamma), drawn by inverse CDF in
 //   index order with the given uniform u: the lowest v whose running sum exceeds u * sum.
 //
-// Two launches: (1) the maximum and the normaliser of each of the 2*gamma+1 logit rows of each
-// sequence, one workgroup per row; (2) one workgroup per sequence takes the decisions and draws
-// the bonus token with a block-wide scan over the vocabulary.  The work is 2 passes over
-// (2*gamma+1) * V floats per sequence, once per drafting-verification iteration.
+// Three launches, all spread over the vocabulary so that no single workgroup has to evaluate
+// 10^5 double-precision exponentials:
+//   (1) accept_stats_kernel    per logit row and vocabulary slice: slice maximum and
+//                              sum exp((l - max) / T)  (combined by the readers);
+//   (2) accept_weights_kernel  every workgroup repeats the gamma accept decisions (a few dozen
+//                              exponentials), then writes the unnormalised bonus weights q(v) of its
+//                              vocabulary chunk and the chunk's sum;
+//   (3) accept_draw_kernel     one workgroup per sequence: running sum over the chunk sums in
+//                              index order, then inside the chunk the draw lands in.
 #include "kernels.h"
 
 namespace es {
 
-constexpr int kAcceptThreads = 1024;
+constexpr int kStatSlices = 8;     // workgroups per logit row in (1)
+constexpr int kChunk = 2048;       // vocabulary entries per workgroup in (2) = 2 per thread in (3)
+constexpr int kAcceptThreads = 256;
+constexpr int kDrawThreads = kChunk / 2;
 
 __device__ __forceinline__ double block_sum(double v, double* sh) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -42,136 +50,222 @@ __device__ __forceinline__ float block_max(float v, float* sh) {
   return t;
 }
 
-// stats: [batch][2*gamma+1][2] = (row maximum, sum_v exp((logit_v - maximum) / T)); rows 0..gamma
-// are the target's, rows gamma+1..2*gamma the draft's.
+// Workspace of one sequence (doubles): [rows][kStatSlices][2] slice statistics, then one double
+// per vocabulary chunk (chunk sums), then q[V], then one slot holding m.
+struct AcceptWs {
+  double* stats;
+  double* chunk_sum;
+  double* q;
+  double* m_slot;
+};
+__host__ __device__ inline size_t accept_ws_doubles(int gamma, int V) {
+  const size_t rows = 2 * (size_t)gamma + 1, nchunk = ((size_t)V + kChunk - 1) / kChunk;
+  return rows * kStatSlices * 2 + nchunk + (size_t)V + 1;
+}
+__device__ __forceinline__ AcceptWs accept_ws(double* base, int b, int gamma, int V) {
+  const size_t rows = 2 * (size_t)gamma + 1, nchunk = ((size_t)V + kChunk - 1) / kChunk;
+  AcceptWs w;
+  w.stats = base + (size_t)b * accept_ws_doubles(gamma, V);
+  w.chunk_sum = w.stats + rows * kStatSlices * 2;
+  w.q = w.chunk_sum + nchunk;
+  w.m_slot = w.q + V;
+  return w;
+}
+
+// rows 0..gamma are the target's, rows gamma+1..2*gamma the draft's.  grid (kStatSlices, rows, batch)
 __global__ __launch_bounds__(kAcceptThreads) void accept_stats_kernel(const float* __restrict__ draft_logits,
                                                                        const float* __restrict__ target_logits, int gamma, int V,
-                                                                       double T, double* __restrict__ stats) {
+                                                                       double T, double* __restrict__ ws) {
   __shared__ double sh_d[kAcceptThreads / 64];
   __shared__ float sh_f[kAcceptThreads / 64];
-  const int j = blockIdx.x, b = blockIdx.y;
+  const int slice = blockIdx.x, j = blockIdx.y, b = blockIdx.z;
   const float* row = j <= gamma ? target_logits + ((size_t)b * (gamma + 1) + j) * V
                                 : draft_logits + ((size_t)b * gamma + (j - gamma - 1)) * V;
+  const int per = (V + kStatSlices - 1) / kStatSlices;
+  const int v0 = min(V, slice * per), v1 = min(V, v0 + per);
   float mx = -INFINITY;
-  for (int v = threadIdx.x; v < V; v += blockDim.x) mx = fmaxf(mx, row[v]);
+  for (int v = v0 + threadIdx.x; v < v1; v += blockDim.x) mx = fmaxf(mx, row[v]);
   mx = block_max(mx, sh_f);
   double z = 0.0;
-  for (int v = threadIdx.x; v < V; v += blockDim.x) z += exp(((double)row[v] - (double)mx) / T);
+  for (int v = v0 + threadIdx.x; v < v1; v += blockDim.x) z += exp(((double)row[v] - (double)mx) / T);
   z = block_sum(z, sh_d);
   if (threadIdx.x == 0) {
-    double* o = stats + ((size_t)b * (2 * gamma + 1) + j) * 2;
-    o[0] = (double)mx;
+    double* o = accept_ws(ws, b, gamma, V).stats + ((size_t)j * kStatSlices + slice) * 2;
+    o[0] = (double)mx;  // -inf for an empty slice; its sum is 0
     o[1] = z;
   }
 }
 
-struct BonusDist {
-  const float* t;   // target row
-  const float* d;   // draft row, or null (plain target distribution)
-  double tm, tz, dm, dz, T;
-  __device__ __forceinline__ double operator()(int v) const {
-    const double p = exp(((double)t[v] - tm) / T) / tz;
-    if (!d) return p;
-    const double q = p - exp(((double)d[v] - dm) / T) / dz;
-    return q > 0.0 ? q : 0.0;
-  }
-};
+// maximum and normaliser of a row from its slice statistics (slices in order)
+__device__ __forceinline__ void row_stats(const double* stats, int row, double T, double* mx, double* z) {
+  const double* s = stats + (size_t)row * kStatSlices * 2;
+  double m = s[0];
+  for (int i = 1; i < kStatSlices; ++i) m = fmax(m, s[2 * i]);
+  double t = 0.0;
+  for (int i = 0; i < kStatSlices; ++i)
+    if (s[2 * i + 1] > 0.0) t += s[2 * i + 1] * exp((s[2 * i] - m) / T);
+  *mx = m;
+  *z = t;
+}
 
-__global__ __launch_bounds__(kAcceptThreads) void accept_decide_kernel(const int32_t* __restrict__ draft,
-                                                                        const float* __restrict__ draft_logits,
-                                                                        const float* __restrict__ target_logits,
-                                                                        const float* __restrict__ r, const float* __restrict__ u,
-                                                                        int gamma, int V, double T, const double* __restrict__ stats,
-                                                                        int32_t* __restrict__ accept_len, int32_t* __restrict__ bonus) {
+// grid (chunks, batch).  Every workgroup takes the same decisions from the same numbers.
+__global__ __launch_bounds__(kAcceptThreads) void accept_weights_kernel(const int32_t* __restrict__ draft,
+                                                                         const float* __restrict__ draft_logits,
+                                                                         const float* __restrict__ target_logits,
+                                                                         const float* __restrict__ r, int gamma, int V, double T,
+                                                                         double* __restrict__ ws_base) {
   __shared__ double sh_d[kAcceptThreads / 64];
-  __shared__ double s_incl[kAcceptThreads];
-  __shared__ int s_m, s_pick;
-  const int b = blockIdx.x, tid = threadIdx.x;
-  const double* st = stats + (size_t)b * (2 * gamma + 1) * 2;
+  __shared__ double s_par[4];
+  __shared__ int s_m;
+  const int chunk = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  const AcceptWs ws = accept_ws(ws_base, b, gamma, V);
   const float* tl = target_logits + (size_t)b * (gamma + 1) * V;
   const float* dl = draft_logits + (size_t)b * gamma * V;
   if (tid == 0) {
     int m = 0;
+    double tm = 0.0, tz = 1.0, dm = 0.0, dz = 1.0;
     for (; m < gamma; ++m) {
       const int x = draft[(size_t)b * gamma + m];
       if (x < 0 || x >= V) { m = -1; break; }  // not a token: reported as accept_len = bonus = -1
-      const double p = exp(((double)tl[(size_t)m * V + x] - st[2 * m]) / T) / st[2 * m + 1];
-      const double pd = exp(((double)dl[(size_t)m * V + x] - st[2 * (gamma + 1 + m)]) / T) / st[2 * (gamma + 1 + m) + 1];
+      row_stats(ws.stats, m, T, &tm, &tz);
+      row_stats(ws.stats, gamma + 1 + m, T, &dm, &dz);
+      const double p = exp(((double)tl[(size_t)m * V + x] - tm) / T) / tz;
+      const double pd = exp(((double)dl[(size_t)m * V + x] - dm) / T) / dz;
       if ((double)r[(size_t)b * gamma + m] * pd > p) break;
     }
+    if (m == gamma) row_stats(ws.stats, gamma, T, &tm, &tz);
     s_m = m;
-    s_pick = -1;
+    s_par[0] = tm; s_par[1] = tz; s_par[2] = dm; s_par[3] = dz;
+    if (chunk == 0) *ws.m_slot = (double)m;
   }
   __syncthreads();
   const int m = s_m;
+  if (m < 0) return;
+  const double tm = s_par[0], tz = s_par[1], dm = s_par[2], dz = s_par[3];
+  const float* trow = tl + (size_t)m * V;
+  const float* drow = m < gamma ? dl + (size_t)m * V : nullptr;
+  // each thread owns a contiguous run, so that every sum below is in index order
+  constexpr int PER = kChunk / kAcceptThreads;
+  const int v0 = chunk * kChunk + tid * PER;
+  double mine = 0.0;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int v = v0 + i;
+    if (v < V) {
+      double q = exp(((double)trow[v] - tm) / T) / tz;
+      if (drow) {
+        q -= exp(((double)drow[v] - dm) / T) / dz;
+        q = q > 0.0 ? q : 0.0;
+      }
+      ws.q[v] = q;
+      mine += q;
+    }
+  }
+  const double tot = block_sum(mine, sh_d);
+  if (tid == 0) ws.chunk_sum[chunk] = tot;
+}
+
+// grid (batch), kDrawThreads threads (two vocabulary entries each inside the chosen chunk).
+__global__ __launch_bounds__(kDrawThreads) void accept_draw_kernel(const float* __restrict__ target_logits,
+                                                                    const float* __restrict__ u, int gamma, int V, double T,
+                                                                    double* __restrict__ ws_base, int32_t* __restrict__ accept_len,
+                                                                    int32_t* __restrict__ bonus) {
+  __shared__ double s_incl[kDrawThreads];
+  __shared__ double s_thr, s_before;
+  __shared__ int s_chunk, s_pick;
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const AcceptWs ws = accept_ws(ws_base, b, gamma, V);
+  const int m = (int)*ws.m_slot;
   if (m < 0) {
     if (tid == 0) { accept_len[b] = -1; bonus[b] = -1; }
     return;
   }
-  BonusDist q;
-  q.t = tl + (size_t)m * V;
-  q.tm = st[2 * m]; q.tz = st[2 * m + 1]; q.T = T;
-  q.d = m < gamma ? dl + (size_t)m * V : nullptr;
-  q.dm = m < gamma ? st[2 * (gamma + 1 + m)] : 0.0;
-  q.dz = m < gamma ? st[2 * (gamma + 1 + m) + 1] : 1.0;
-
-  // each thread owns a contiguous run of the vocabulary, so that the running sum is in index order
-  const int seg = (V + (int)blockDim.x - 1) / (int)blockDim.x;
-  const int v0 = min(V, tid * seg), v1 = min(V, v0 + seg);
-  double mine = 0.0;
-  for (int v = v0; v < v1; ++v) mine += q(v);
-  double total = block_sum(mine, sh_d);
-  if (q.d && !(total > 0.0)) {
-    // identical distributions leave no residual (a rejection is then impossible for r < 1): fall
-    // back to the target distribution of that position
-    q.d = nullptr;
-    mine = 0.0;
-    for (int v = v0; v < v1; ++v) mine += q(v);
-    total = block_sum(mine, sh_d);
-  }
-  // inclusive scan of the per-thread sums (Hillis-Steele over LDS; 1024 entries, 10 rounds)
-  s_incl[tid] = mine;
-  __syncthreads();
-  for (int off = 1; off < (int)blockDim.x; off <<= 1) {
-    const double add = tid >= off ? s_incl[tid - off] : 0.0;
+  const int nchunk = (V + kChunk - 1) / kChunk;
+  double total = 0.0;
+  for (int c0 = 0; c0 < nchunk; c0 += kDrawThreads) {  // chunk sums through LDS: loaded side by side, added in order
+    s_incl[tid] = c0 + tid < nchunk ? ws.chunk_sum[c0 + tid] : 0.0;
     __syncthreads();
-    s_incl[tid] += add;
+    if (tid == 0)
+      for (int c = 0; c < min(kDrawThreads, nchunk - c0); ++c) total += s_incl[c];
     __syncthreads();
   }
-  const double thr = (double)u[b] * total;
-  const double incl = s_incl[tid], excl = tid ? s_incl[tid - 1] : 0.0;
-  if (excl <= thr && thr < incl) {
-    // the draw lands in this thread's run; at most one thread gets here (incl is non-decreasing)
-    double run = excl;
-    int pick = -1, last_pos = v0;
-    for (int v = v0; v < v1; ++v) {
-      const double qv = q(v);
-      if (qv > 0.0) last_pos = v;
-      run += qv;
-      if (run > thr) { pick = v; break; }
+  if (tid == 0) {
+    if (!(total > 0.0)) {
+      // identical distributions leave no residual (a rejection is then impossible for r < 1): fall
+      // back to the target distribution of that position, evaluated here (rare, slow, correct)
+      double tm, tz;
+      row_stats(ws.stats, m, T, &tm, &tz);
+      const float* trow = target_logits + ((size_t)b * (gamma + 1) + m) * V;
+      total = 0.0;
+      for (int c = 0; c < nchunk; ++c) {
+        double cs = 0.0;
+        for (int v = c * kChunk; v < min(V, (c + 1) * kChunk); ++v) {
+          const double q = exp(((double)trow[v] - tm) / T) / tz;
+          ws.q[v] = q;
+          cs += q;
+        }
+        ws.chunk_sum[c] = cs;
+        total += cs;
+      }
     }
-    s_pick = pick >= 0 ? pick : last_pos;  // the scan and the walk may differ in the last bit
+    const double thr = (double)u[b] * total;
+    double run = 0.0;
+    int pick = -1;
+    for (int c = 0; c < nchunk; ++c) {
+      const double next = run + ws.chunk_sum[c];
+      if (next > thr) { pick = c; break; }
+      run = next;
+    }
+    s_thr = thr;
+    s_before = run;
+    s_chunk = pick;  // -1: u * total rounded up to the total
+    s_pick = -1;
   }
   __syncthreads();
+  const int chunk = s_chunk;
+  if (chunk >= 0) {
+    const int v0 = chunk * kChunk + 2 * tid;
+    const double q0 = v0 < V ? ws.q[v0] : 0.0, q1 = v0 + 1 < V ? ws.q[v0 + 1] : 0.0;
+    s_incl[tid] = q0 + q1;
+    __syncthreads();
+    for (int off = 1; off < kDrawThreads; off <<= 1) {  // inclusive scan, Hillis-Steele
+      const double add = tid >= off ? s_incl[tid - off] : 0.0;
+      __syncthreads();
+      s_incl[tid] += add;
+      __syncthreads();
+    }
+    const double thr = s_thr;
+    const double excl = s_before + (tid ? s_incl[tid - 1] : 0.0), incl = s_before + s_incl[tid];
+    if (excl <= thr && thr < incl) s_pick = (excl + q0 > thr || !(q1 > 0.0)) ? v0 : v0 + 1;  // at most one thread
+    __syncthreads();
+  }
   if (tid == 0) {
     int pick = s_pick;
     if (pick < 0) {
-      // u * total rounded up to the total: take the last token with positive mass
-      pick = V - 1;
-      while (pick > 0 && !(q(pick) > 0.0)) --pick;
+      // the scans disagreed in the last bit, or the threshold reached the total: the last token
+      // with positive weight of the chunk (of the vocabulary)
+      pick = min(V, chunk >= 0 ? (chunk + 1) * kChunk : V) - 1;
+      while (pick > 0 && !(ws.q[pick] > 0.0)) --pick;
     }
     accept_len[b] = m;
     bonus[b] = pick;
   }
 }
 
+size_t sample_accept_workspace_bytes(int batch, int gamma, int V) {
+  return (size_t)batch * accept_ws_doubles(gamma, V) * sizeof(double);
+}
+
 void launch_sample_accept(const int32_t* draft, const float* draft_logits, const float* target_logits, const float* r,
-                          const float* u, int batch, int gamma, int V, double T, double* stats, int32_t* accept_len,
+                          const float* u, int batch, int gamma, int V, double T, double* ws, int32_t* accept_len,
                           int32_t* bonus, hipStream_t st) {
-  hipLaunchKernelGGL(accept_stats_kernel, dim3(2 * gamma + 1, batch), dim3(kAcceptThreads), 0, st, draft_logits, target_logits,
-                     gamma, V, T, stats);
-  hipLaunchKernelGGL(accept_decide_kernel, dim3(batch), dim3(kAcceptThreads), 0, st, draft, draft_logits, target_logits, r, u, gamma,
-                     V, T, stats, accept_len, bonus);
+  const int nchunk = (V + kChunk - 1) / kChunk;
+  hipLaunchKernelGGL(accept_stats_kernel, dim3(kStatSlices, 2 * gamma + 1, batch), dim3(kAcceptThreads), 0, st, draft_logits,
+                     target_logits, gamma, V, T, ws);
+  hipLaunchKernelGGL(accept_weights_kernel, dim3(nchunk, batch), dim3(kAcceptThreads), 0, st, draft, draft_logits, target_logits, r,
+                     gamma, V, T, ws);
+  hipLaunchKernelGGL(accept_draw_kernel, dim3(batch), dim3(kDrawThreads), 0, st, target_logits, u, gamma, V, T, ws, accept_len,
+                     bonus);
 }
 
 }  // namespace es

@@ -527,9 +527,9 @@ extern "C" int easyspec_greedy_accept(const int32_t* draft, const int32_t* targe
   return EASYSPEC_OK;
 }
 
-extern "C" int64_t easyspec_accept_workspace_bytes(int32_t batch, int32_t gamma) {
-  if (batch < 1 || gamma < 0) return -1;
-  return (int64_t)batch * (2 * (int64_t)gamma + 1) * 2 * (int64_t)sizeof(double);
+extern "C" int64_t easyspec_accept_workspace_bytes(int32_t batch, int32_t gamma, int32_t vocab) {
+  if (batch < 1 || gamma < 0 || vocab < 1) return -1;
+  return (int64_t)sample_accept_workspace_bytes(batch, gamma, vocab);
 }
 
 extern "C" int easyspec_accept(const int32_t* draft, const float* draft_logits, const float* target_logits, const float* r,

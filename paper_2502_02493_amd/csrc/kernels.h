@@ -85,9 +85,10 @@ void launch_head(const Shape& s, const Buffers& b, const Cols& c, float* logits_
                  hipStream_t st);
 void launch_accept(const int32_t* draft, const int32_t* target, int batch, int gamma, int32_t* accept_len,
                    int32_t* bonus, hipStream_t st);
-// Acceptance by speculative sampling; stats: [batch][2*gamma+1][2] doubles of scratch.
+// Acceptance by speculative sampling; ws: sample_accept_workspace_bytes() of scratch.
+size_t sample_accept_workspace_bytes(int batch, int gamma, int V);
 void launch_sample_accept(const int32_t* draft, const float* draft_logits, const float* target_logits, const float* r,
-                          const float* u, int batch, int gamma, int V, double T, double* stats, int32_t* accept_len,
+                          const float* u, int batch, int gamma, int V, double T, double* ws, int32_t* accept_len,
                           int32_t* bonus, hipStream_t st);
 void launch_kv_copy(const Shape& s, const Buffers& b, int seq, void* k_user, void* v_user, int n_slots,
                     int to_cache, hipStream_t st);

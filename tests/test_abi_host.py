@@ -137,8 +137,9 @@ def test_accept_rejects_bad_arguments_on_the_host():
         with pytest.raises(es.EasySpecError) as e:
             es.easyspec_accept(**dict(ok, **over))
         assert e.value.code == es.EASYSPEC_EINVAL, over
-    assert es.easyspec_accept_workspace_bytes(4, 5) == 4 * 11 * 16
-    assert es.easyspec_accept_workspace_bytes(0, 5) == -1
+    assert es.easyspec_accept_workspace_bytes(4, 5, 1000) >= 4 * (11 * 16 + 1000 * 8)
+    assert es.easyspec_accept_workspace_bytes(0, 5, 1000) == -1
+    assert es.easyspec_accept_workspace_bytes(1, 5, 0) == -1
     import torch
     if not torch.cuda.is_available():
         with pytest.raises(es.EasySpecError) as e:      # valid arguments, no device: refused, never computed on the CPU

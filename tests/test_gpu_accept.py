@@ -48,7 +48,7 @@ def run_gpu(es, draft, dl, tl, r, u, T):
     d_draft, d_dl, d_tl, d_r, d_u = t(draft), t(dl), t(tl), t(r), t(u)
     acc = torch.full((batch,), -7, dtype=torch.int32, device=dev)
     bon = torch.full((batch,), -7, dtype=torch.int32, device=dev)
-    ws = torch.empty(es.easyspec_accept_workspace_bytes(batch, gamma) // 8, dtype=torch.float64, device=dev)
+    ws = torch.empty(es.easyspec_accept_workspace_bytes(batch, gamma, V) // 8, dtype=torch.float64, device=dev)
     es.easyspec_accept(d_draft if gamma else None, d_dl if gamma else None, d_tl, d_r if gamma else None, d_u, batch, gamma, V, T,
                        acc, bon, ws, torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()

@@ -105,6 +105,38 @@ def test_tree_8b_shape_reduced_depth_long_context(oracle, gpu):
     tree_parity(oracle, gpu, cfg, 530, [0, 1, 3], 5, [8, 8, 8], kv_prefix=2048)
 
 
+def test_tree_two_sequences_ragged(oracle, gpu):
+    """Two sequences with different contexts grow different trees in the same calls (3 + 2 nodes,
+    then 4 + 5 nodes); a third call extends only the second sequence."""
+    cfg = synth.model_shape("tiny", dtype="bf16")
+    bounds = [0, 1, 3, 4]
+    tol = TOL["bf16"]
+    w = synth.make_weights(cfg, 540)
+    model = oracle.Model(cfg, w, 160)
+    so = [oracle.Sequence(model), oracle.Sequence(model)]
+    g = gpu.GpuDrafter(cfg, w, max_batch=2, max_ctx=160, max_calib=16)
+    g.set_groups(bounds)
+    try:
+        for b, n in ((0, 11), (1, 70)):
+            prompt = synth.make_tokens(541 + b, n, cfg["vocab"])
+            so[b].calibrate(prompt)
+            g.prefill(b, prompt)
+        calls = [{0: ([5, 6, 7], [-1, -1, -1]), 1: ([8, 9], [-1, -1])},
+                 {0: ([1, 2, 3, 4], [0, 0, 2, 2]), 1: ([11, 12, 13, 14, 15], [0, 1, 1, 1, 0])},
+                 {1: ([21, 22, 23], [2, 6, 6])}]
+        for call in calls:
+            gt, gl = g.draft_tree_step(call)
+            for b, (toks, parents) in call.items():
+                wl = so[b].fuzzy_tree_step(bounds, toks, parents)
+                assert gpu.rel_l2(gl[b], wl) < tol, f"sequence {b}"
+        p, f = g.lens()
+        for b in (0, 1):
+            assert (p[b], f[b]) == (so[b].precise, so[b].fuzzy)
+            kv_check(gpu, g, so[b], b, so[b].precise + so[b].fuzzy, tol)
+    finally:
+        g.close()
+
+
 def test_tree_error_paths(gpu):
     import paper_2502_02493_amd as es
     cfg = synth.model_shape("tiny")
