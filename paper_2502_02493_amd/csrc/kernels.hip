@@ -725,6 +725,25 @@ struct AttnArgs {
 
 constexpr int kAttnIT = 8;  // loads in flight per operand per lane
 
+// Sum over aligned groups of N lanes (8, 16 or 32), every lane of a group receiving the total,
+// with data-parallel-primitive operand swizzles (lane^1 and lane^2 inside quads, then the
+// mirrored lane of the other half of 8 and of 16 lanes) instead of LDS permutes.  Same operand
+// pairs as an xor butterfly, hence the same bits.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+template <int N>
+__device__ __forceinline__ float group_sum(float v) {
+  static_assert(N == 8 || N == 16 || N == 32, "group size");
+  v += dpp_f32<0xB1>(v);   // quad_perm [1,0,3,2]
+  v += dpp_f32<0x4E>(v);   // quad_perm [2,3,0,1]
+  v += dpp_f32<0x141>(v);  // row_half_mirror
+  if (N >= 16) v += dpp_f32<0x140>(v);  // row_mirror
+  if (N >= 32) v += __shfl_xor(v, 16, 64);
+  return v;
+}
+
 template <typename T, int HD>
 struct AttnGeom {
   static constexpr int EPL = Tr<T>::EPL, LPS = HD / EPL, SPW = 64 / LPS;
@@ -778,12 +797,12 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
 #pragma unroll
     for (int j = 0; j < IT; ++j) {
       const int s = base + j * SPW + sub;
-      kr[j] = s < s1 ? *reinterpret_cast<const u32x4*>(kb + (size_t)s * HD) : zero;
+      kr[j] = s < s1 ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kb + (size_t)s * HD)) : zero;
     }
 #pragma unroll
     for (int j = 0; j < IT; ++j) {
       const int s = base + j * SPW + sub;
-      vr[j] = s < s1 ? *reinterpret_cast<const u32x4*>(vb + (size_t)s * HD) : zero;
+      vr[j] = s < s1 ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vb + (size_t)s * HD)) : zero;
     }
     float sc[IT][G], m_use[G];
 #pragma unroll
@@ -797,8 +816,7 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
         float dot = 0.f;
 #pragma unroll
         for (int e = 0; e < EPL; ++e) dot += q[g][e] * kv[e];
-#pragma unroll
-        for (int off = 1; off < LPS; off <<= 1) dot += __shfl_xor(dot, off, 64);
+        dot = group_sum<LPS>(dot);
         sc[j][g] = valid ? dot * a.scale : -INFINITY;
       }
     }
@@ -807,12 +825,12 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
       float bm = sc[0][g];
 #pragma unroll
       for (int j = 1; j < IT; ++j) bm = fmaxf(bm, sc[j][g]);
-#pragma unroll
-      for (int off = LPS; off < 64; off <<= 1) bm = fmaxf(bm, __shfl_xor(bm, off, 64));
-      // a batch that lies wholly among masked tree slots leaves the maximum at -inf: the
-      // exponentials then take 0 as reference, so that they give 0 instead of exp(-inf + inf)
+      // The running maximum belongs to the slot group (the LPS lanes that share slots), not to the
+      // wave: no cross-lane traffic per batch; the groups are brought to a common reference once,
+      // after the loop.  A group whose slots so far were all past the end or masked still has
+      // -inf: the exponentials then take 0 as reference and give 0 instead of exp(-inf + inf).
       const float m_new = fmaxf(m_run[g], bm);
-      const float m_ref = (TREE && m_new == -INFINITY) ? 0.f : m_new;
+      const float m_ref = m_new == -INFINITY ? 0.f : m_new;
       const float alpha = __expf(m_run[g] - m_ref);  // exp(-inf) = 0 on the first batch
       m_run[g] = m_new;
       m_use[g] = m_ref;
@@ -834,10 +852,18 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
     }
   }
 
-  // combine the slot groups of the wave (l_run counts each slot once per group, every lane of a
-  // group holds the same value)
+  // combine the slot groups of the wave: common reference maximum first (l_run counts each slot
+  // once per group, every lane of a group holds the same value)
 #pragma unroll
   for (int g = 0; g < G; ++g) {
+    float mw = m_run[g];
+#pragma unroll
+    for (int off = LPS; off < 64; off <<= 1) mw = fmaxf(mw, __shfl_xor(mw, off, 64));
+    const float rescale = m_run[g] == -INFINITY ? 0.f : __expf(m_run[g] - mw);  // a group without slots has l = acc = 0
+    m_run[g] = mw;
+    l_run[g] *= rescale;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[g][e] *= rescale;
 #pragma unroll
     for (int off = LPS; off < 64; off <<= 1) {
       l_run[g] += __shfl_xor(l_run[g], off, 64);
