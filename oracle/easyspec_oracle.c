@@ -76,6 +76,13 @@ typedef struct {
    * slot precise + t, with its parent node (-1: child of the last precise token) and depth */
   int32_t n_tree;
   int32_t tree_parent[ESO_MAX_TREE], tree_depth[ESO_MAX_TREE];
+  /* 0: layer-parallel attention only (Alg. 2).  1: full-layer parallel (the ablation of App. B):
+   * every layer of a set, attention AND MLP, works from the set's input h_1, and the set's
+   * output is h_1 plus the sum of what each layer adds:
+   *   a_i = Attn_i(h_1),  m_i = MLP_i(h_1 + a_i),  h_out = h_1 + sum_i (a_i + m_i).
+   * The paper names the variant without defining it; this is the reading "each layer of the set
+   * runs whole, on its own device, from the same input".  With sets of one layer it is Alg. 1. */
+  int32_t full_layer;
 } eso_seq;
 
 /* ---------------------------------------------------------------- storage formats */
@@ -234,6 +241,7 @@ float *eso_seq_k(eso_seq *s) { return s->K; }
 float *eso_seq_v(eso_seq *s) { return s->V; }
 int32_t eso_seq_precise(const eso_seq *s) { return s->precise; }
 int32_t eso_seq_fuzzy(const eso_seq *s) { return s->fuzzy; }
+void eso_seq_set_full_layer(eso_seq *s, int32_t on) { s->full_layer = on ? 1 : 0; }
 void eso_seq_set_lens(eso_seq *s, int32_t precise, int32_t fuzzy) { s->precise = precise; s->fuzzy = fuzzy; s->n_tree = 0; }
 double *eso_seq_enable_attn_tap(eso_seq *s) {
   if (!s->attn_tap) s->attn_tap = (double *)calloc((size_t)s->m->cfg.n_layers * (size_t)s->m->cfg.d_model, sizeof(double));
@@ -361,6 +369,21 @@ int eso_sequential_step(eso_seq *s, int32_t token, double *logits, double *hidde
   return 0;
 }
 
+/* Full-layer parallel set (the ablation of App. B; see eso_seq.full_layer): with the Attnoutputs
+ * a[i] = Attn_i(h_1) of the set [lo, hi) known, every MLP reads h_1 plus its own layer's
+ * Attnoutput, and all contributions are added to h_1.  On entry h == h1.  mo: scratch. */
+static void full_layer_set(const eso_seq *s, int lo, int hi, const double *h1, const double *a, double *h, double *mo) {
+  const int d = s->m->cfg.d_model;
+  double *t = (double *)malloc(sizeof(double) * (size_t)d);
+  for (int i = lo; i < hi; ++i) {
+    const double *ai = a + (size_t)i * d;
+    for (int e = 0; e < d; ++e) t[e] = h1[e] + ai[e];          /* this layer's own h' = h_1 + Attnoutput_i */
+    mlp_block(s->m, i, t, mo);                                  /* MLP_i(h_1 + Attnoutput_i) */
+    for (int e = 0; e < d; ++e) h[e] = (h[e] + ai[e]) + mo[e];  /* h_out = h_1 + sum_i (a_i + m_i), added in layer order */
+  }
+  free(t);
+}
+
 /* ---------------------------------------------------------------- paper Alg. 2 */
 
 /* One layer-parallel fuzzy forward of one token.  bounds[0]=0 < ... < bounds[n_sets]=L;
@@ -383,11 +406,15 @@ int eso_fuzzy_step(eso_seq *s, const int32_t *bounds, int32_t n_sets, int32_t to
     int lo = bounds[j], hi = bounds[j + 1];
     memcpy(h1, h, sizeof(double) * (size_t)d);                                 /* h_1 = h */
     for (int i = lo; i < hi; ++i) attn_block(s, i, h1, pos, a + (size_t)i * d); /* Attn_i(h_1), parallel */
-    for (int i = lo; i < hi; ++i) {
-      const double *ai = a + (size_t)i * d;
-      for (int e = 0; e < d; ++e) h[e] = h[e] + ai[e];  /* h'_i = h_i + Attnoutput_i */
-      mlp_block(s->m, i, h, mo);                        /* MLPoutput_i = MLP_i(h'_i) */
-      for (int e = 0; e < d; ++e) h[e] = h[e] + mo[e];  /* h_{i+1} = h'_i + MLPoutput_i */
+    if (s->full_layer) {
+      full_layer_set(s, lo, hi, h1, a, h, mo); /* App. B ablation */
+    } else {
+      for (int i = lo; i < hi; ++i) {
+        const double *ai = a + (size_t)i * d;
+        for (int e = 0; e < d; ++e) h[e] = h[e] + ai[e];  /* h'_i = h_i + Attnoutput_i */
+        mlp_block(s->m, i, h, mo);                        /* MLPoutput_i = MLP_i(h'_i) */
+        for (int e = 0; e < d; ++e) h[e] = h[e] + mo[e];  /* h_{i+1} = h'_i + MLPoutput_i */
+      }
     }
   }
   if (s->attn_tap) memcpy(s->attn_tap, a, sizeof(double) * (size_t)d * (size_t)c->n_layers);
@@ -437,11 +464,15 @@ int eso_fuzzy_tree_step(eso_seq *s, const int32_t *bounds, int32_t n_sets, int32
       int lo = bounds[g], hi = bounds[g + 1];
       memcpy(h1, h, sizeof(double) * (size_t)d);                                                      /* h_1 = h */
       for (int i = lo; i < hi; ++i) attn_block_vis(s, i, h1, slot, P + depth, vis, nv, a + (size_t)i * d); /* Attn_i(h_1) */
-      for (int i = lo; i < hi; ++i) {
-        const double *ai = a + (size_t)i * d;
-        for (int e = 0; e < d; ++e) h[e] = h[e] + ai[e];  /* h'_i = h_i + Attnoutput_i */
-        mlp_block(s->m, i, h, mo);                        /* MLPoutput_i = MLP_i(h'_i) */
-        for (int e = 0; e < d; ++e) h[e] = h[e] + mo[e];  /* h_{i+1} = h'_i + MLPoutput_i */
+      if (s->full_layer) {
+        full_layer_set(s, lo, hi, h1, a, h, mo); /* App. B ablation */
+      } else {
+        for (int i = lo; i < hi; ++i) {
+          const double *ai = a + (size_t)i * d;
+          for (int e = 0; e < d; ++e) h[e] = h[e] + ai[e];  /* h'_i = h_i + Attnoutput_i */
+          mlp_block(s->m, i, h, mo);                        /* MLPoutput_i = MLP_i(h'_i) */
+          for (int e = 0; e < d; ++e) h[e] = h[e] + mo[e];  /* h_{i+1} = h'_i + MLPoutput_i */
+        }
       }
     }
     if (hidden_out) memcpy(hidden_out + (size_t)j * d, h, sizeof(double) * (size_t)d);

@@ -69,6 +69,7 @@ def lib():
         L.eso_seq_fuzzy.restype = i32
         L.eso_seq_fuzzy.argtypes = [vp]
         L.eso_seq_set_lens.argtypes = [vp, i32, i32]
+        L.eso_seq_set_full_layer.argtypes = [vp, i32]
         L.eso_seq_enable_attn_tap.restype = dp
         L.eso_seq_enable_attn_tap.argtypes = [vp]
         L.eso_sequential_step.argtypes = [vp, i32, dp, dp]
@@ -270,11 +271,18 @@ class Sequence:
         self.V[:, :, :n, :] = v
         self.set_lens(n, 0)
 
+    def set_full_layer(self, on: bool):
+        """Fuzzy steps run every layer of a set, attention and MLP, from the set's input (the
+        full-layer ablation of paper App. B) instead of Alg. 2."""
+        self.full_layer = bool(on)
+        lib().eso_seq_set_full_layer(self._h, int(self.full_layer))
+
     def clone(self):
         s = Sequence(self.model)
         s.K[...] = self.K
         s.V[...] = self.V
         s.set_lens(self.precise, self.fuzzy)
+        s.set_full_layer(getattr(self, "full_layer", False))
         return s
 
     def attn_tap(self):

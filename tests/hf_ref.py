@@ -80,3 +80,24 @@ def hf_fuzzy_step(model, cache, token, bounds):
             h = h + layer.mlp(layer.post_attention_layernorm(h))
     logits = model.lm_head(model.model.norm(h))
     return logits[0, 0].numpy(), np.stack(attn_outs)
+
+
+@torch.no_grad()
+def hf_full_layer_step(model, cache, token, bounds):
+    """Full-layer-parallel forward of one token (the ablation of the paper's App. B) composed from the
+    library's blocks: within a set every layer, attention and MLP, starts from the hidden state
+    that enters the set, and the set's output is that state plus what every layer adds."""
+    pos = cache.get_seq_length()
+    h = model.model.embed_tokens(torch.tensor([[int(token)]]))
+    pe = model.model.rotary_emb(h, torch.tensor([[pos]]))
+    for j in range(len(bounds) - 1):
+        h1 = h
+        for i in range(bounds[j], bounds[j + 1]):
+            layer = model.model.layers[i]
+            a = layer.self_attn(hidden_states=layer.input_layernorm(h1), position_embeddings=pe,
+                                attention_mask=None, past_key_values=cache,
+                                cache_position=torch.tensor([pos]))[0]
+            m = layer.mlp(layer.post_attention_layernorm(h1 + a))
+            h = h + a + m
+    logits = model.lm_head(model.model.norm(h))
+    return logits[0, 0].numpy(), h[0, 0].numpy()
