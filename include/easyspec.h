@@ -116,6 +116,19 @@ int easyspec_set_groups(easyspec_ctx *ctx, const int32_t *bounds, int32_t n_sets
  * n_layers + 1 entries; *n_sets receives the number of sets.  Pure host function. */
 int easyspec_default_groups(int32_t n_layers, int32_t N, int32_t policy, int32_t *bounds, int32_t *n_sets);
 
+/* What the layers of a set share in fuzzy steps (easyspec_draft_step, easyspec_draft_tree_step).
+ *   EASYSPEC_PARALLEL_ATTENTION (default)  Alg. 2: the attention layers of a set read the set's
+ *       input; the MLPs run in layer order on the running residual.
+ *   EASYSPEC_PARALLEL_FULL_LAYER  the ablation of App. B: attention AND MLP of every layer of the
+ *       set work from the set's input h_1: a_i = Attn_i(h_1), m_i = MLP_i(h_1 + a_i),
+ *       output = h_1 + sum_i (a_i + m_i).  The paper reports this variant as worse and does not
+ *       define it; this is the reading "each layer of the set runs whole from the same input".
+ * Sets of one layer are Alg. 1 in both modes.  Calibration is unaffected.  EASYSPEC_EINVAL for
+ * an unknown mode. */
+#define EASYSPEC_PARALLEL_ATTENTION 0
+#define EASYSPEC_PARALLEL_FULL_LAYER 1
+int easyspec_set_parallel_mode(easyspec_ctx *ctx, int32_t mode);
+
 /* One fuzzy forward (Alg. 2) for every live sequence (precise length > 0), one token each.
  *   tokens_in  dev [max_batch]  token fed to sequence b (ignored for idle sequences)
  *   tokens_out dev [max_batch]  argmax of the logits, lowest index on ties (idle: untouched)

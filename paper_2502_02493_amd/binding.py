@@ -16,10 +16,11 @@ EASYSPEC_DTYPE_F32, EASYSPEC_DTYPE_BF16 = 0, 1
 EASYSPEC_POLICY_ALIGNED, EASYSPEC_POLICY_PACKED = 0, 1
 EASYSPEC_MAX_BATCH, EASYSPEC_MAX_CALIB_TOKENS, EASYSPEC_MAX_SET = 16, 16, 8
 EASYSPEC_MAX_TREE_WIDTH, EASYSPEC_MAX_TREE_NODES = 16, 64
+EASYSPEC_PARALLEL_ATTENTION, EASYSPEC_PARALLEL_FULL_LAYER = 0, 1
 
 EXPORTS = ["easyspec_create", "easyspec_destroy", "easyspec_load_weights", "easyspec_set_groups",
            "easyspec_default_groups", "easyspec_draft_step", "easyspec_calibrate", "easyspec_greedy_accept",
-           "easyspec_accept", "easyspec_accept_workspace_bytes", "easyspec_draft_tree_step",
+           "easyspec_accept", "easyspec_accept_workspace_bytes", "easyspec_draft_tree_step", "easyspec_set_parallel_mode",
            "easyspec_get_lens", "easyspec_truncate", "easyspec_kv_import", "easyspec_kv_export",
            "easyspec_get_hidden", "easyspec_step_bytes", "easyspec_profile_begin", "easyspec_profile_end",
            "easyspec_last_error"]
@@ -66,6 +67,7 @@ def load_library():
         L.easyspec_set_groups.argtypes = [vp, vp, i32]
         L.easyspec_default_groups.argtypes = [i32, i32, i32, vp, C.POINTER(i32)]
         L.easyspec_draft_step.argtypes = [vp, vp, vp, vp]
+        L.easyspec_set_parallel_mode.argtypes = [vp, i32]
         L.easyspec_calibrate.argtypes = [vp, vp, vp, vp, vp, i32]
         L.easyspec_draft_tree_step.argtypes = [vp, vp, vp, vp, vp, vp]
         L.easyspec_greedy_accept.argtypes = [vp, vp, i32, i32, vp, vp, vp]
@@ -165,6 +167,10 @@ def easyspec_calibrate(ctx, tokens, n_tokens, next_token_out, logits_out=None, l
     n = np.ascontiguousarray(n_tokens, dtype=np.int32)
     _check(load_library().easyspec_calibrate(ctx, _ptr(tokens), _ptr(n), _ptr(next_token_out), _ptr(logits_out),
                                              int(logits_rows)), ctx)
+
+
+def easyspec_set_parallel_mode(ctx, mode: int):
+    _check(load_library().easyspec_set_parallel_mode(ctx, int(mode)), ctx)
 
 
 def easyspec_draft_tree_step(ctx, tokens_in, n_nodes, parents, tokens_out, logits_out=None):

@@ -34,6 +34,7 @@ struct easyspec_ctx {
   std::vector<int32_t> single;  // every layer alone (Alg. 1 order)
   std::vector<void*> allocs;
   int32_t last_rows;
+  int32_t parallel_mode;  // EASYSPEC_PARALLEL_*
   // per-kernel timing (easyspec_profile_*)
   int32_t prof_op;
   size_t prof_used;
@@ -113,6 +114,7 @@ extern "C" int easyspec_create(const easyspec_config* cfg, void* hip_stream, eas
   ctx->last_rows = 0;
   ctx->prof_op = -1;
   ctx->prof_used = 0;
+  ctx->parallel_mode = EASYSPEC_PARALLEL_ATTENTION;
   Shape& s = ctx->s;
   s.dtype = cfg->dtype; s.L = cfg->n_layers; s.d = cfg->d_model; s.Hq = cfg->n_q_heads; s.Hkv = cfg->n_kv_heads;
   s.hd = cfg->head_dim; s.F = cfg->d_ffn; s.V = cfg->vocab; s.HQ = s.Hq * s.hd; s.RQKV = (s.Hq + 2 * s.Hkv) * s.hd;
@@ -146,11 +148,12 @@ extern "C" int easyspec_create(const easyspec_config* cfg, void* hip_stream, eas
     ALLOC(ctx, b.H, (size_t)kMaxCols * s.d * sizeof(float));
     ALLOC(ctx, b.ssp, (size_t)kMaxCols * (s.d / 16) * sizeof(float));
     ALLOC(ctx, b.XA, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.d * act_);
-    ALLOC(ctx, b.XM, (size_t)kMaxCols * s.d * act_);
+    ALLOC(ctx, b.ssp_set, (size_t)EASYSPEC_MAX_SET * kMaxCols * (s.d / 16) * sizeof(float));
+    ALLOC(ctx, b.XM, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.d * act_);
     ALLOC(ctx, b.Q, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.HQ * sizeof(float));
     ALLOC(ctx, b.AO, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.HQ * act_);
     ALLOC(ctx, b.A, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.d * sizeof(float));
-    ALLOC(ctx, b.ACT, (size_t)kMaxCols * s.F * act_);
+    ALLOC(ctx, b.ACT, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.F * act_);
     const size_t prow = (size_t)EASYSPEC_MAX_SET * kMaxCols * s.Hq;
     ALLOC(ctx, b.PO, prow * kMaxChunks * s.hd * sizeof(float));
     ALLOC(ctx, b.PM, prow * kMaxChunks * sizeof(float));
@@ -348,7 +351,7 @@ struct ProfScope {
 };
 
 static int forward(easyspec_ctx* ctx, const Cols& c, const int32_t* tokens, const std::vector<int32_t>& bounds,
-                   float* logits_out, int32_t* tokens_out) {
+                   bool full_layer, float* logits_out, int32_t* tokens_out) {
   const Shape& s = ctx->s;
   const Buffers& b = ctx->b;
   hipStream_t st = ctx->stream;
@@ -361,10 +364,20 @@ static int forward(easyspec_ctx* ctx, const Cols& c, const int32_t* tokens, cons
     // every attention layer of the set reads the hidden state that enters the set
     { ProfScope p(ctx, EASYSPEC_OP_QKV); launch_qkv(s, b, c, lo, k, st); }
     { ProfScope p(ctx, EASYSPEC_OP_ATTN); launch_attn(s, b, c, lo, k, chunk, n_chunks, st); }
+    if (full_layer && k > 1) {
+      // App. B ablation: the MLPs of the set also work from the set's input, each behind its own
+      // layer's attention; one launch per operation for the whole set
+      { ProfScope p(ctx, EASYSPEC_OP_OPROJ); launch_oproj_full(s, b, c, lo, k, st); }
+      { ProfScope p(ctx, EASYSPEC_OP_GATEUP); launch_gateup(s, b, c, lo, k, b.ssp_set, st); }
+      ProfScope p(ctx, EASYSPEC_OP_DOWN);
+      if (hi < s.L) launch_down_full(s, b, c, lo, k, b.g_attn + (size_t)hi * s.d, bounds[j + 2] - hi, b.XA, st);
+      else launch_down_full(s, b, c, lo, k, b.g_final, 1, b.XA, st);
+      continue;
+    }
     { ProfScope p(ctx, EASYSPEC_OP_OPROJ); launch_oproj(s, b, c, lo, k, st); }
     // the MLPs run in layer order on the running residual
     for (int i = lo; i < hi; ++i) {
-      { ProfScope p(ctx, EASYSPEC_OP_GATEUP); launch_gateup(s, b, c, i, st); }
+      { ProfScope p(ctx, EASYSPEC_OP_GATEUP); launch_gateup(s, b, c, i, 1, b.ssp, st); }
       ProfScope p(ctx, EASYSPEC_OP_DOWN);
       if (i + 1 < hi) {
         launch_down(s, b, c, i, i + 1 - lo, b.g_mlp + (size_t)(i + 1) * s.d, 1, b.XM, st);
@@ -378,6 +391,14 @@ static int forward(easyspec_ctx* ctx, const Cols& c, const int32_t* tokens, cons
   { ProfScope p(ctx, EASYSPEC_OP_HEAD); launch_head(s, b, c, logits_out, tokens_out, st); }
   HIPCHK(ctx, hipGetLastError());
   ctx->last_rows = c.n;
+  return EASYSPEC_OK;
+}
+
+extern "C" int easyspec_set_parallel_mode(easyspec_ctx* ctx, int32_t mode) {
+  if (!ctx) return fail(nullptr, EASYSPEC_EINVAL, "ctx is NULL");
+  if (mode != EASYSPEC_PARALLEL_ATTENTION && mode != EASYSPEC_PARALLEL_FULL_LAYER)
+    return fail(ctx, EASYSPEC_EINVAL, "set_parallel_mode: unknown mode %d", mode);
+  ctx->parallel_mode = mode;
   return EASYSPEC_OK;
 }
 
@@ -398,7 +419,7 @@ extern "C" int easyspec_draft_step(easyspec_ctx* ctx, const int32_t* tokens_in, 
     ++c.n;
   }
   if (c.n == 0) return fail(ctx, EASYSPEC_ESTATE, "draft_step: no live sequence (calibrate a prompt first)");
-  const int rc = forward(ctx, c, tokens_in, ctx->bounds, logits_out, tokens_out);
+  const int rc = forward(ctx, c, tokens_in, ctx->bounds, ctx->parallel_mode == EASYSPEC_PARALLEL_FULL_LAYER, logits_out, tokens_out);
   if (rc != EASYSPEC_OK) return rc;
   for (int i = 0; i < c.n; ++i) ctx->fuzzy[c.seq[i]] += 1;
   return EASYSPEC_OK;
@@ -438,7 +459,7 @@ extern "C" int easyspec_draft_tree_step(easyspec_ctx* ctx, const int32_t* tokens
     }
   }
   if (c.n == 0) return fail(ctx, EASYSPEC_EINVAL, "draft_tree_step: no nodes");
-  const int rc = forward(ctx, c, tokens_in, ctx->bounds, logits_out, tokens_out);
+  const int rc = forward(ctx, c, tokens_in, ctx->bounds, ctx->parallel_mode == EASYSPEC_PARALLEL_FULL_LAYER, logits_out, tokens_out);
   if (rc != EASYSPEC_OK) return rc;
   for (int i = 0; i < c.n; ++i) {
     easyspec_ctx::Tree& t = ctx->tree[c.seq[i]];
@@ -491,7 +512,7 @@ extern "C" int easyspec_calibrate(easyspec_ctx* ctx, const int32_t* tokens, cons
       ++b;
     }
     if (c.n == 0) continue;
-    const int rc = forward(ctx, c, tokens, ctx->single, logits_out, next_token_out);
+    const int rc = forward(ctx, c, tokens, ctx->single, false, logits_out, next_token_out);
     if (rc != EASYSPEC_OK) return rc;
   }
   for (int q = 0; q < s.B; ++q)

@@ -52,12 +52,13 @@ struct Buffers {
   // a wave's B fragments (see xoff() in kernels.hip); a slot of XA / AO is PARTS * 16 * width elements.
   float *H;     // [16][d]      residual stream
   float *ssp;   // [16][d/16]   per-row-tile partial sums of squares of the vector to be normed next
+  float *ssp_set;  // [MAX_SET][16][d/16]  the same per layer of a set (full-layer mode: one MLP input per layer)
   void *XA;     // [MAX_SET] x (16 x d) T   H * g_attn(layer) for the layers of the coming set (or g_final)
-  void *XM;     // (16 x d) T               H' * g_mlp(layer)
+  void *XM;     // [MAX_SET] x (16 x d) T   H' * g_mlp(layer); one slot outside full-layer mode
   float *Q;     // [MAX_SET][16][HQ]    rotated queries
   void *AO;     // [MAX_SET] x (16 x HQ) T  attention output (rounded to T)
   float *A;     // [MAX_SET][16][d]     Attnoutput_i
-  void *ACT;    // (16 x F) T               SiLU(gate)*up
+  void *ACT;    // [MAX_SET] x (16 x F) T   SiLU(gate)*up; one slot outside full-layer mode
   float *PO;    // [MAX_SET*16*Hq][kMaxChunks][hd]  split-KV partial outputs
   float *PM, *PL;  // [MAX_SET*16*Hq][kMaxChunks]   partial max / sum
   float *amax_val; // [16][n_head_blocks]
@@ -75,7 +76,15 @@ void launch_attn(const Shape& s, const Buffers& b, const Cols& c, int layer0, in
                  hipStream_t st);
 // O projection of the set's layers; the first layer's result goes straight into the residual.
 void launch_oproj(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st);
-void launch_gateup(const Shape& s, const Buffers& b, const Cols& c, int layer, hipStream_t st);
+// Gate/up of n_layers consecutive layers, layer i on operand slot i of XM with partial sums slot i
+// of ssp ([n_layers][16][d/16]) into operand slot i of ACT.  n_layers = 1 outside full-layer mode.
+void launch_gateup(const Shape& s, const Buffers& b, const Cols& c, int layer, int n_layers, const float* ssp, hipStream_t st);
+// Full-layer-parallel mode (App. B ablation), per set: the O projections (every layer parks its
+// Attnoutput and writes its own MLP's input into XM / ssp_set) and the down projections (summed
+// over the set's layers and added to the residual together with the Attnoutputs).
+void launch_oproj_full(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st);
+void launch_down_full(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, const float* gain, int n_gain,
+                      void* xout, hipStream_t st);
 // Down projection + residual.  a_next: Attnoutput of the next layer of the same set to add, or
 // -1.  The normed-input vectors for what comes next are written with gains
 // gain[0..n_gain) (stride d) into xout (stride 16*d elements of T).

@@ -523,14 +523,85 @@ __global__ __launch_bounds__(1024) void proj_resid_kernel(ProjArgs a, Cols c) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Gate and up projections + SiLU(gate) * up.  grid = F/16.
+// The two projections of full-layer-parallel mode (the ablation of App. B: every layer of a set,
+// attention and MLP, works from the set's input h_1 = H; the set's output is
+// H + sum_i (Attnoutput_i + MLPoutput_i)).
+//   down == 0, O projections of the set, grid = k * d/16: layer li parks Attnoutput_li in A[li]
+//     and writes the input of its own MLP, T((H + Attnoutput_li) * gain_li), into operand slot li
+//     of xout with the partial sums of squares in slot li of ssp; H is left alone.
+//   down == 1, down projections of the set, grid = d/16: a workgroup adds up the k layers'
+//     contractions for its row tile (operand slot li of x against layer li of w), then
+//     h = H + that sum + A[0] + ... + A[k-1]; writes H, the partial sums of squares of h and
+//     T(h * gain_j) for the n_gain consumers that come next, like proj_resid_kernel.
+// ------------------------------------------------------------------------------------------
+struct ProjFullArgs {
+  const u32x4* w;
+  size_t w_layer_stride;
+  const void* x;  // k operand slots of 16 x K in T
+  int K, d, k, down;
+  float* H;
+  float* A;       // [MAX_SET][16][d]
+  const float* gain;  // down == 0: [k][d]; down == 1: [n_gain][d]
+  int n_gain;
+  void* xout;
+  float* ssp;     // down == 0: [k][16][d/16]; down == 1: [16][d/16]
+};
+
+template <typename T, int NB>
+__global__ __launch_bounds__(1024) void proj_full_kernel(ProjFullArgs a, Cols c) {
+  const int nkt = a.K / Tr<T>::KT;
+  const int ntile = a.d / 16;
+  const int li = a.down ? 0 : blockIdx.x / ntile, t = blockIdx.x % ntile;
+  const int lane = threadIdx.x & 63, col = lane & 15;
+  const bool ok = col < c.n;
+  const int r0 = t * 16 + (lane >> 4) * 4;
+  f32x4 acc[1] = {{0.f, 0.f, 0.f, 0.f}};
+  const int n_sum = a.down ? a.k : 1;
+  for (int j = 0; j < n_sum; ++j) {  // uniform over the workgroup
+    const int l = li + j;
+    const u32x4* const w[1] = {a.w + (size_t)l * a.w_layer_stride + (size_t)t * nkt * 64};
+    gemm_accumulate<T, 1, NB>(w, reinterpret_cast<const T*>(a.x) + (size_t)l * Tr<T>::PARTS * kMaxCols * a.K, a.K, c.n, acc);
+  }
+  if (!reduce_waves<1>(acc, dyn_red)) return;
+  fold_columns<T, 1>(acc, c.n);
+
+  float ss = 0.f;
+  if (ok) {
+    f32x4 h = *reinterpret_cast<const f32x4*>(a.H + (size_t)col * a.d + r0);
+    h += acc[0];
+    if (a.down) {
+      for (int j = 0; j < a.k; ++j) h += *reinterpret_cast<const f32x4*>(a.A + ((size_t)j * kMaxCols + col) * a.d + r0);
+      *reinterpret_cast<f32x4*>(a.H + (size_t)col * a.d + r0) = h;
+      for (int j = 0; j < a.n_gain; ++j) {
+        const f32x4 g = *reinterpret_cast<const f32x4*>(a.gain + (size_t)j * a.d + r0);
+        T* xo = reinterpret_cast<T*>(a.xout) + (size_t)j * Tr<T>::PARTS * kMaxCols * a.d + xoff<T>(c.n, a.d, col, r0);
+        store_act4<T>(xo, (size_t)kMaxCols * a.d, h[0] * g[0], h[1] * g[1], h[2] * g[2], h[3] * g[3]);
+      }
+    } else {
+      store4<float>(a.A + ((size_t)li * kMaxCols + col) * a.d + r0, acc[0][0], acc[0][1], acc[0][2], acc[0][3]);
+      const f32x4 g = *reinterpret_cast<const f32x4*>(a.gain + (size_t)li * a.d + r0);
+      T* xo = reinterpret_cast<T*>(a.xout) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.d + xoff<T>(c.n, a.d, col, r0);
+      store_act4<T>(xo, (size_t)kMaxCols * a.d, h[0] * g[0], h[1] * g[1], h[2] * g[2], h[3] * g[3]);
+    }
+    ss = h[0] * h[0] + h[1] * h[1] + h[2] * h[2] + h[3] * h[3];
+  }
+  ss += __shfl_xor(ss, 16, 64);
+  ss += __shfl_xor(ss, 32, 64);
+  if (ok && lane < 16) a.ssp[(size_t)li * kMaxCols * ntile + col * ntile + t] = ss;
+}
+
+// ------------------------------------------------------------------------------------------
+// Gate and up projections + SiLU(gate) * up of one layer, or of the k layers of a set each on
+// its own input (full-layer mode): layer li of the launch reads operand slot li of x with
+// partial sums slot li and writes operand slot li of act.  grid = k * F/16.
 // ------------------------------------------------------------------------------------------
 struct GateUpArgs {
   const u32x4* wg;
   const u32x4* wu;
-  const void* x;  // XM: operand of 16 x d
-  const float* ssp;
-  void* act;  // operand of 16 x F in T
+  size_t w_layer_stride;
+  const void* x;  // XM: k operand slots of 16 x d
+  const float* ssp;  // [k][16][d/16]
+  void* act;  // k operand slots of 16 x F in T
   int d, F;
   float inv_d, eps;
 };
@@ -539,13 +610,16 @@ template <typename T, int NB>
 __global__ __launch_bounds__(1024) void gateup_kernel(GateUpArgs a, Cols c) {
   __shared__ float s_rstd[kMaxCols];
   const int nkt = a.d / Tr<T>::KT;
-  const int t = blockIdx.x;
-  const u32x4* const w[2] = {a.wg + (size_t)t * nkt * 64, a.wu + (size_t)t * nkt * 64};
+  const int ntile = a.F / 16;
+  const int li = blockIdx.x / ntile, t = blockIdx.x % ntile;
+  const size_t wl = (size_t)li * a.w_layer_stride + (size_t)t * nkt * 64;
+  const u32x4* const w[2] = {a.wg + wl, a.wu + wl};
+  const float* ssp = a.ssp + (size_t)li * kMaxCols * (a.d / 16);
   RstdPre pre;
-  rstd_issue(a.ssp, a.d / 16, c.n, pre);
+  rstd_issue(ssp, a.d / 16, c.n, pre);
   f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-  gemm_accumulate<T, 2, NB>(w, reinterpret_cast<const T*>(a.x), a.d, c.n, acc);
-  rstd_finish(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
+  gemm_accumulate<T, 2, NB>(w, reinterpret_cast<const T*>(a.x) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.d, a.d, c.n, acc);
+  rstd_finish(ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
   if (!reduce_waves<2>(acc, dyn_red)) return;
   fold_columns<T, 2>(acc, c.n);
   const int lane = threadIdx.x & 63, col = lane & 15;
@@ -557,7 +631,7 @@ __global__ __launch_bounds__(1024) void gateup_kernel(GateUpArgs a, Cols c) {
     const float g = acc[0][i] * r, u = acc[1][i] * r;
     o[i] = (g / (1.0f + expf(-g))) * u;
   }
-  T* dst = reinterpret_cast<T*>(a.act) + xoff<T>(c.n, a.F, col, t * 16 + (lane >> 4) * 4);
+  T* dst = reinterpret_cast<T*>(a.act) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.F + xoff<T>(c.n, a.F, col, t * 16 + (lane >> 4) * 4);
   store_act4<T>(dst, (size_t)kMaxCols * a.F, o[0], o[1], o[2], o[3]);
 }
 
@@ -1172,14 +1246,15 @@ void launch_oproj(const Shape& s, const Buffers& b, const Cols& c, int layer0, i
                hipLaunchKernelGGL((proj_resid_kernel<T, NB>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
 }
 
-void launch_gateup(const Shape& s, const Buffers& b, const Cols& c, int layer, hipStream_t st) {
+void launch_gateup(const Shape& s, const Buffers& b, const Cols& c, int layer, int n_layers, const float* ssp, hipStream_t st) {
   GateUpArgs a;
   const size_t stride = tile_stride(s.F, s.d, s.dtype);
   a.wg = (const u32x4*)b.wg + (size_t)layer * stride;
   a.wu = (const u32x4*)b.wu + (size_t)layer * stride;
-  a.x = b.XM; a.ssp = b.ssp; a.act = b.ACT; a.d = s.d; a.F = s.F;
+  a.w_layer_stride = stride;
+  a.x = b.XM; a.ssp = ssp; a.act = b.ACT; a.d = s.d; a.F = s.F;
   a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
-  const int grid = s.F / 16;
+  const int grid = n_layers * (s.F / 16);
   const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
   const int nw = pick_waves(8, nkt, "EASYSPEC_NW_GU");
   DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
@@ -1201,6 +1276,42 @@ void launch_down(const Shape& s, const Buffers& b, const Cols& c, int layer, int
   const int nw = pick_waves(8, nkt, "EASYSPEC_NW_DOWN");
   DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
                hipLaunchKernelGGL((proj_resid_kernel<T, NB>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+}
+
+void launch_oproj_full(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st) {
+  ProjFullArgs a;
+  const size_t stride = tile_stride(s.d, s.HQ, s.dtype);
+  a.w = (const u32x4*)b.wo + (size_t)layer0 * stride;
+  a.w_layer_stride = stride;
+  a.x = b.AO;
+  a.K = s.HQ; a.d = s.d; a.k = n_set; a.down = 0;
+  a.H = b.H; a.A = b.A;
+  a.gain = b.g_mlp + (size_t)layer0 * s.d;
+  a.n_gain = 0;
+  a.xout = b.XM;
+  a.ssp = b.ssp_set;
+  const int grid = n_set * (s.d / 16);
+  const int nkt = s.HQ / (s.dtype == 1 ? 32 : 16);
+  const int nw = pick_waves(grid < 512 ? 8 : 4, nkt, "EASYSPEC_NW_O");
+  DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
+               hipLaunchKernelGGL((proj_full_kernel<T, NB>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+}
+
+void launch_down_full(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, const float* gain, int n_gain,
+                      void* xout, hipStream_t st) {
+  ProjFullArgs a;
+  const size_t stride = tile_stride(s.d, s.F, s.dtype);
+  a.w = (const u32x4*)b.wd + (size_t)layer0 * stride;
+  a.w_layer_stride = stride;
+  a.x = b.ACT;
+  a.K = s.F; a.d = s.d; a.k = n_set; a.down = 1;
+  a.H = b.H; a.A = b.A;
+  a.gain = gain; a.n_gain = n_gain; a.xout = xout; a.ssp = b.ssp;
+  const int grid = s.d / 16;
+  const int nkt = s.F / (s.dtype == 1 ? 32 : 16);
+  const int nw = pick_waves(8, nkt, "EASYSPEC_NW_DOWN");
+  DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
+               hipLaunchKernelGGL((proj_full_kernel<T, NB>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
 }
 
 void launch_head(const Shape& s, const Buffers& b, const Cols& c, float* logits_out, int32_t* tokens_out, hipStream_t st) {

@@ -43,6 +43,9 @@ class GpuDrafter:
     def set_groups(self, bounds):
         es.easyspec_set_groups(self.ctx, bounds)
 
+    def set_full_layer(self, on: bool):
+        es.easyspec_set_parallel_mode(self.ctx, es.EASYSPEC_PARALLEL_FULL_LAYER if on else es.EASYSPEC_PARALLEL_ATTENTION)
+
     def lens(self):
         return es.easyspec_get_lens(self.ctx, self.B)
 
