@@ -208,6 +208,25 @@ def main():
         tree[f"width_{width}"] = {"us_per_level": round(us, 1), "hbm_frac": round(step_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
     es.easyspec_truncate(ctx, 0, ctx_len)
 
+    # the full-layer-parallel ablation (paper App. B) on the same sets: 6 launches per set instead of 4 + 2k
+    es.easyspec_set_parallel_mode(ctx, es.EASYSPEC_PARALLEL_FULL_LAYER)
+    fl = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    reps = max(2, args.steps // 4)
+    tot = 0.0
+    for rep in range(reps + 1):
+        es.easyspec_truncate(ctx, 0, ctx_len)
+        es.easyspec_calibrate(ctx, calib_tok, n_tok, dptr, None, 0)
+        fl[0].record()
+        for j in range(1, gamma):
+            es.easyspec_draft_step(ctx, dptr + (j - 1) * esz, dptr + j * esz, None)
+        fl[1].record()
+        torch.cuda.synchronize()
+        if rep:
+            tot += fl[0].elapsed_time(fl[1])
+    full_us = 1e3 * tot / (reps * (gamma - 1))
+    es.easyspec_set_parallel_mode(ctx, es.EASYSPEC_PARALLEL_ATTENTION)
+    es.easyspec_truncate(ctx, 0, ctx_len)
+
     traffic_kib = args.traffic_kib if args.traffic_kib is not None else (
         None if args.layers else MEASURED_TRAFFIC_KIB.get(args.workload))
     out = {
@@ -233,6 +252,7 @@ def main():
                      "launches_timed": n_timed},
         "kernel_time": per_op,
         "tree_step": tree,
+        "full_layer_step": {"us": round(full_us, 1), "hbm_frac": round(step_bytes / (full_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)},
         "sample_accept": {"us": round(accept_us, 1), "temperature": 0.8, "gamma": gamma, "vocab": V, "dtype": "f64",
                           "logit_bytes": (2 * gamma + 1) * V * 4},
     }
