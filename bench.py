@@ -227,6 +227,19 @@ def main():
     es.easyspec_set_parallel_mode(ctx, es.EASYSPEC_PARALLEL_ATTENTION)
     es.easyspec_truncate(ctx, 0, ctx_len)
 
+    # what a kernel that only reads reaches on this device (same loads as the weight stream), 4 GiB per pass
+    probe = torch.empty(1 << 30, dtype=torch.int32, device=dev)
+    probe.zero_()
+    sink = torch.empty(es.easyspec_stream_read_sink_floats(), dtype=torch.float32, device=dev)
+    pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for k in range(8):
+        if k == 3: pe[0].record()
+        es.easyspec_stream_read(probe, probe.numel() * 4, sink, stream)
+    pe[1].record()
+    torch.cuda.synchronize()
+    stream_gbs = 5 * probe.numel() * 4 / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e9
+    del probe
+
     traffic_kib = args.traffic_kib if args.traffic_kib is not None else (
         None if args.layers else MEASURED_TRAFFIC_KIB.get(args.workload))
     out = {
@@ -241,7 +254,8 @@ def main():
                    "shape": cfg["name"], "context": ctx_len, "batch": B,
                    "group_size": wl["group_size"], "sets": [int(x) for x in bounds], "gamma": gamma, "calib_tokens": M},
         "draft_step": {"us": round(step_us, 1), "tokens_per_s": round(1e6 / step_us, 2), "bytes": int(step_bytes),
-                       "hbm_frac": round(step_bytes / (step_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)},
+                       "hbm_frac": round(step_bytes / (step_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                       "frac_of_stream_read": round(step_bytes / (step_us * 1e-6) / 1e9 / stream_gbs, 4)},
         "calibrate": {"us": round(calib_us, 1), "tokens": M, "bytes": int(calib_bytes),
                       "hbm_frac": round(calib_bytes / (calib_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)},
         "roofline": {"bound": "hbm", "kernel": "gateup_kernel", "achieved": round(gu_gbs, 1), "peak": HBM_PEAK_GBS,
@@ -249,7 +263,8 @@ def main():
                      "traffic": traffic_kib * 1024 if traffic_kib else None,
                      "bytes_per_launch": int(gu_bytes), "avg_launch_us": round(1e3 * gu_ms, 2),
                      "event_pair_us": round(1e3 * gu_raw_ms, 2), "empty_event_pair_us": round(1e3 * null_ms, 2),
-                     "launches_timed": n_timed},
+                     "launches_timed": n_timed, "stream_read_gbs": round(stream_gbs, 1),
+                     "frac_of_stream_read": round(gu_gbs / stream_gbs, 4)},
         "kernel_time": per_op,
         "tree_step": tree,
         "full_layer_step": {"us": round(full_us, 1), "hbm_frac": round(step_bytes / (full_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)},

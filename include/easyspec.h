@@ -235,6 +235,15 @@ int easyspec_get_hidden(easyspec_ctx *ctx, float *out, int32_t max_rows, int32_t
  * KV slots each live sequence reads.  Pure host arithmetic, for roofline reports. */
 int64_t easyspec_step_bytes(const easyspec_ctx *ctx);
 
+/* Streaming-read probe for roofline reports: reads `bytes` (a positive multiple of 16) of the
+ * caller's device buffer once, with the loads the weight stream uses (16-byte, non-temporal,
+ * 8 in flight per lane), on hip_stream (NULL = the null stream).  The caller times it; the rate
+ * is what a kernel that only reads can reach on this device, against which the share of the
+ * nominal 8 TB/s can be judged.  sink: dev, easyspec_stream_read_sink_floats() floats, receives
+ * checksums so that the reads cannot be dropped.  EASYSPEC_EINVAL for NULL or a bad size. */
+int easyspec_stream_read(const void *buf, int64_t bytes, float *sink, void *hip_stream);
+int32_t easyspec_stream_read_sink_floats(void);
+
 /* Per-kernel timing for roofline reports.  Between profile_begin and profile_end every launch
  * of the kernel class `op` made by draft steps and calibrations is bracketed by a pair of HIP
  * events on the context's stream (at most max_launches pairs; later launches run untimed).

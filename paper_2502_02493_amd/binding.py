@@ -20,7 +20,7 @@ EASYSPEC_PARALLEL_ATTENTION, EASYSPEC_PARALLEL_FULL_LAYER = 0, 1
 
 EXPORTS = ["easyspec_create", "easyspec_destroy", "easyspec_load_weights", "easyspec_set_groups",
            "easyspec_default_groups", "easyspec_draft_step", "easyspec_calibrate", "easyspec_greedy_accept",
-           "easyspec_accept", "easyspec_accept_workspace_bytes", "easyspec_draft_tree_step", "easyspec_set_parallel_mode",
+           "easyspec_accept", "easyspec_accept_workspace_bytes", "easyspec_draft_tree_step", "easyspec_set_parallel_mode", "easyspec_stream_read", "easyspec_stream_read_sink_floats",
            "easyspec_get_lens", "easyspec_truncate", "easyspec_kv_import", "easyspec_kv_export",
            "easyspec_get_hidden", "easyspec_step_bytes", "easyspec_profile_begin", "easyspec_profile_end",
            "easyspec_last_error"]
@@ -80,6 +80,8 @@ def load_library():
         L.easyspec_kv_export.argtypes = [vp, i32, vp, vp, i32]
         L.easyspec_get_hidden.argtypes = [vp, vp, i32, C.POINTER(i32)]
         L.easyspec_step_bytes.argtypes = [vp]
+        L.easyspec_stream_read.argtypes = [vp, C.c_int64, vp, vp]
+        L.easyspec_stream_read_sink_floats.argtypes = []
         L.easyspec_step_bytes.restype = C.c_int64
         L.easyspec_profile_begin.argtypes = [vp, i32, i32]
         L.easyspec_profile_end.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_float)]
@@ -194,6 +196,14 @@ def easyspec_accept(draft, draft_logits, target_logits, r, u, batch, gamma, voca
 
 def easyspec_accept_workspace_bytes(batch: int, gamma: int, vocab: int) -> int:
     return int(load_library().easyspec_accept_workspace_bytes(batch, gamma, vocab))
+
+
+def easyspec_stream_read(buf, nbytes: int, sink, hip_stream=None):
+    _check(load_library().easyspec_stream_read(_ptr(buf), int(nbytes), _ptr(sink), _ptr(hip_stream)), None)
+
+
+def easyspec_stream_read_sink_floats() -> int:
+    return int(load_library().easyspec_stream_read_sink_floats())
 
 
 def easyspec_get_lens(ctx, max_batch: int):

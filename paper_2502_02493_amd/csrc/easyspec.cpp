@@ -682,6 +682,18 @@ extern "C" int easyspec_profile_end(easyspec_ctx* ctx, int32_t* n_launches, floa
   return EASYSPEC_OK;
 }
 
+extern "C" int easyspec_stream_read(const void* buf, int64_t bytes, float* sink, void* hip_stream) {
+  if (!buf || !sink) return fail(nullptr, EASYSPEC_EINVAL, "stream_read: NULL argument");
+  if (bytes < 16 || bytes % 16 != 0) return fail(nullptr, EASYSPEC_EINVAL, "stream_read: bytes must be a positive multiple of 16");
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) return fail(nullptr, EASYSPEC_EHIP, "no HIP device available (this library has no CPU path)");
+  launch_stream_read(buf, (size_t)bytes, sink, (hipStream_t)hip_stream);
+  HIPCHK(nullptr, hipGetLastError());
+  return EASYSPEC_OK;
+}
+
+extern "C" int32_t easyspec_stream_read_sink_floats(void) { return stream_read_sink_floats(); }
+
 extern "C" int64_t easyspec_step_bytes(const easyspec_ctx* ctx) {
   if (!ctx) return 0;
   const Shape& s = ctx->s;

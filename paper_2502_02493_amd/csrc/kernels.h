@@ -99,6 +99,9 @@ size_t sample_accept_workspace_bytes(int batch, int gamma, int V);
 void launch_sample_accept(const int32_t* draft, const float* draft_logits, const float* target_logits, const float* r,
                           const float* u, int batch, int gamma, int V, double T, double* ws, int32_t* accept_len,
                           int32_t* bonus, hipStream_t st);
+// Reads `bytes` (multiple of 16) of buf once; sink: stream_read_sink_floats() floats.
+void launch_stream_read(const void* buf, size_t bytes, float* sink, hipStream_t st);
+int stream_read_sink_floats();
 void launch_kv_copy(const Shape& s, const Buffers& b, int seq, void* k_user, void* v_user, int n_slots,
                     int to_cache, hipStream_t st);
 

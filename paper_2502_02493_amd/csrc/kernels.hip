@@ -1327,6 +1327,42 @@ void launch_head(const Shape& s, const Buffers& b, const Cols& c, float* logits_
   hipLaunchKernelGGL(argmax_final_kernel, dim3(c.n), dim3(1024), 0, st, a.cand_val, a.cand_idx, a.nblk, tokens_out, c);
 }
 
+// Streaming-read probe: the same non-temporal 16-byte loads as the weight stream, 8 in flight per
+// lane, summed so that nothing is optimised away.  sink: one float per workgroup.
+constexpr int kProbeBlocks = 4096, kProbeThreads = 256;
+__global__ __launch_bounds__(kProbeThreads) void stream_read_kernel(const u32x4* __restrict__ p, size_t n16, float* sink) {
+  // a workgroup reads 8 consecutive 4 KB pieces (32 KB contiguous) per round, as the waves of a
+  // weight-streaming workgroup do
+  const size_t stride = (size_t)gridDim.x * blockDim.x * 8;
+  size_t i = (size_t)blockIdx.x * blockDim.x * 8 + threadIdx.x;
+  uint32_t acc = 0;
+  for (; i + 7 * (size_t)blockDim.x < n16; i += stride) {
+    u32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(p + i + (size_t)u * blockDim.x);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc += v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+  }
+  for (int u = 0; u < 8; ++u) {  // ragged end: the last, partial round
+    const size_t j = i + (size_t)u * blockDim.x;
+    if (j < n16) {
+      const u32x4 v = __builtin_nontemporal_load(p + j);
+      acc += v.x ^ v.y ^ v.z ^ v.w;
+    }
+  }
+  __shared__ uint32_t sh[kProbeThreads / 64];
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) sink[blockIdx.x] = (float)(sh[0] + sh[1] + sh[2] + sh[3]);
+}
+
+void launch_stream_read(const void* buf, size_t bytes, float* sink, hipStream_t st) {
+  hipLaunchKernelGGL(stream_read_kernel, dim3(kProbeBlocks), dim3(kProbeThreads), 0, st, (const u32x4*)buf, bytes / 16, sink);
+}
+int stream_read_sink_floats() { return kProbeBlocks; }
+
 void launch_accept(const int32_t* draft, const int32_t* target, int batch, int gamma, int32_t* accept_len, int32_t* bonus,
                    hipStream_t st) {
   hipLaunchKernelGGL(accept_kernel, dim3((batch + 63) / 64), dim3(64), 0, st, draft, target, batch, gamma, accept_len, bonus);

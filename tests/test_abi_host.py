@@ -145,3 +145,12 @@ def test_accept_rejects_bad_arguments_on_the_host():
         with pytest.raises(es.EasySpecError) as e:      # valid arguments, no device: refused, never computed on the CPU
             es.easyspec_accept(**ok)
         assert e.value.code == es.EASYSPEC_EHIP
+
+
+def test_stream_read_rejects_bad_arguments_on_the_host():
+    a = np.zeros(64, np.float32)
+    for buf, n, sink in ((None, 64, a), (a, 64, None), (a, 0, a), (a, 24, a), (a, -16, a)):
+        with pytest.raises(es.EasySpecError) as e:
+            es.easyspec_stream_read(buf, n, sink)
+        assert e.value.code == es.EASYSPEC_EINVAL
+    assert es.easyspec_stream_read_sink_floats() >= 1
