@@ -316,8 +316,9 @@ static void pick_chunk(const Shape& s, const Cols& c, int n_set, int* chunk, int
   int max_len = 1;
   for (int i = 0; i < c.n; ++i)
     if (c.pos[i] + 1 > max_len) max_len = c.pos[i] + 1;
-  const int unit = attn_block_slots(s);
-  // Short contexts: one workgroup per (layer, column, KV head) walks the whole context, which
+  int units, unit, per_wg;
+  attn_plan(s, c, &units, &unit, &per_wg);
+  // Short contexts: one piece of work per (layer, column, KV head) walks the whole context, which
   // saves the merge launch; two dependent launches cost more than the narrower launch loses.
   static const int single_max = getenv("EASYSPEC_ATTN_SINGLE") ? atoi(getenv("EASYSPEC_ATTN_SINGLE")) : 256;
   if (max_len <= single_max) {
@@ -325,12 +326,12 @@ static void pick_chunk(const Shape& s, const Cols& c, int n_set, int* chunk, int
     *n_chunks = 1;
     return;
   }
-  // Long contexts: chunks are multiples of what one workgroup covers per batch; grow them until the
+  // Long contexts: chunks are multiples of what one piece covers per batch; grow them until the
   // chunk count fits the partial buffers and the launch is not cut finer than two workgroups per CU.
   static const long max_wg = getenv("EASYSPEC_ATTN_WG") ? atol(getenv("EASYSPEC_ATTN_WG")) : 512;
   int ch = unit;
   auto nch = [&](int ch_) { return (max_len + ch_ - 1) / ch_; };
-  while (ch < 1024 && (nch(ch) > kMaxChunks || (long)nch(ch) * s.Hkv * n_set * c.n > max_wg)) ch *= 2;
+  while (ch < 1024 && (nch(ch) > kMaxChunks || (long)nch(ch) * s.Hkv * n_set * units > max_wg * per_wg)) ch *= 2;
   *chunk = ch;
   *n_chunks = nch(ch);
 }

@@ -23,6 +23,8 @@
 // rsqrt(mean(h^2) + eps).  Both sides of the parity tests use this order of roundings.
 #include "kernels.h"
 
+#include <algorithm>
+
 namespace es {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -989,6 +991,198 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Attention on the matrix cores (bf16 caches).  The query rows that share one KV head — the G
+// heads of up to 16/G columns of one sequence (the tokens of a calibration, the nodes of a tree
+// level; a single column in a plain draft step) — are the 16 columns of MFMA tiles, so K and V
+// are read once per group of columns and the per-slot arithmetic leaves the vector ALUs:
+//   S^T[slot][row]  = K[slot][:] . Q[row][:]      A = K (rows = slots), B = Q^T, two-term bf16 q
+//   O^T[e][row]    += V^T[e][slot] P^T[slot][row]  A = V^T, B = P^T, two-term bf16 p
+// Each wave walks its own sub-chunk of the context in super tiles of 64 slots and leaves one
+// split-KV partial per query row (merged by attn_merge_kernel; written out directly if the
+// column's whole context is one sub-chunk).  The slots of a super tile are dealt to the four
+// S^T tiles so that lane (row r, quarter q) ends up with the 16 CONSECUTIVE slots q*16 .. q*16+15:
+// the accumulator layout of S^T is then the B-operand layout of the P.V instruction, and a
+// V^T fragment is 8 consecutive slots.  V is stored [slot][head_dim]; a wave transposes its
+// 64 x head_dim tile through its own piece of LDS (XOR-swizzled pieces: conflict-free 2-byte
+// gathers).  grid = (ceil(sub-chunks / waves), Hkv, k * groups), block = 64 * waves.
+// ------------------------------------------------------------------------------------------
+struct ColGroups {
+  int32_t n;                // groups
+  int32_t first[kMaxCols];  // first column of group i
+  int32_t count[kMaxCols];  // its columns (consecutive, same sequence); count * G <= 16
+};
+constexpr int kMfmaAttnWaves = 4;
+
+__device__ __forceinline__ bf16x8 pack_bf16x8(const uint32_t (&b)[8]) {
+  u32x4 v = {b[0] | (b[1] << 16), b[2] | (b[3] << 16), b[4] | (b[5] << 16), b[6] | (b[7] << 16)};
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+template <int HD, bool TREE>
+__global__ __launch_bounds__(64 * kMfmaAttnWaves) void attn_mfma_kernel(AttnArgs a, Cols c, ColGroups cg, int G) {
+  constexpr int KT = HD / 32, ET = HD / 16, PIECES = HD / 8;
+  extern __shared__ u32x4 dyn_v[];  // [waves][64 slots][PIECES] 16-byte pieces, pieces swizzled
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, NWV = blockDim.x >> 6;
+  const int chunk = blockIdx.x * NWV + wave, kvh = blockIdx.y;
+  const int li = blockIdx.z / cg.n, grp = blockIdx.z % cg.n;
+  const int first = cg.first[grp], cnt = cg.count[grp];
+  const int r = lane & 15, q4 = lane >> 4;  // query row (MFMA column) and quarter / k-group
+  const bool row_ok = r < cnt * G;
+  const int col = first + (row_ok ? r / G : 0), g = row_ok ? r % G : 0;
+  int n_max = 0;  // slots the longest column of the group attends to
+  for (int i = 0; i < cnt; ++i) n_max = max(n_max, c.pos[first + i] + 1);
+  const int ws0 = chunk * a.CH;
+  if (ws0 >= n_max) return;  // whole wave; nothing below synchronises across waves
+  const int ws1 = min(ws0 + a.CH, n_max);
+  const int n_slots = c.pos[col] + 1;  // of this lane's row
+  const int vbase = c.vis_base[col];
+  const unsigned long long vmask = c.vis_mask[col];
+  const int HQ = a.Hq * HD;
+  const size_t rowbase = (((size_t)(a.layer0 + li) * a.B + c.seq[first]) * a.Hkv + kvh) * (size_t)a.max_ctx;
+  const bf16_t* kc = reinterpret_cast<const bf16_t*>(a.kc) + rowbase * HD;
+  const u32x4* vc = reinterpret_cast<const u32x4*>(reinterpret_cast<const bf16_t*>(a.vc) + rowbase * HD);
+  u32x4* vt = dyn_v + (size_t)wave * 64 * PIECES;
+  const uint16_t* vt16 = reinterpret_cast<const uint16_t*>(vt);
+
+  // B operands of S^T: this row's query, hi and lo bf16 terms, k-group q4 of every k-tile
+  bf16x8 qh[KT], ql[KT];
+  {
+    const float* qp = a.Q + ((size_t)li * kMaxCols + col) * HQ + (kvh * G + g) * HD + q4 * 8;
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+      uint32_t hb[8], lb[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float x = row_ok ? qp[kt * 32 + e] : 0.f;
+        hb[e] = float_to_bf16_bits(x);
+        lb[e] = float_to_bf16_bits(x - bf16_bits_to_float(hb[e]));
+      }
+      qh[kt] = pack_bf16x8(hb);
+      ql[kt] = pack_bf16x8(lb);
+    }
+  }
+
+  f32x4 o[ET];
+#pragma unroll
+  for (int et = 0; et < ET; ++et) o[et] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_run = -INFINITY, l_run = 0.f;  // l_run: this lane's 16 slots per super tile only
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  const int swz = q4 * (PIECES / 4);
+
+  for (int base = ws0; base < ws1; base += 64) {
+    // K fragments: S^T tile t, A row m = lane % 16 <-> slot base + (m/4)*16 + t*4 + m%4
+    u32x4 kf[4][KT];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int slot = base + (r >> 2) * 16 + t * 4 + (r & 3);
+#pragma unroll
+      for (int kt = 0; kt < KT; ++kt)
+        kf[t][kt] = slot < ws1 ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kc + (size_t)slot * HD + kt * 32 + q4 * 8)) : zero;
+    }
+    // V tile, row-major from memory (coalesced), into LDS with the pieces of slot s XORed by (s/16)*(PIECES/4)
+    u32x4 vf[PIECES];
+#pragma unroll
+    for (int it = 0; it < PIECES; ++it) {
+      const int f = it * 64 + lane, sl = f / PIECES;
+      vf[it] = base + sl < ws1 ? __builtin_nontemporal_load(vc + (size_t)base * PIECES + f) : zero;
+    }
+#pragma unroll
+    for (int it = 0; it < PIECES; ++it) {
+      const int f = it * 64 + lane, sl = f / PIECES, piece = f % PIECES;
+      vt[sl * PIECES + (piece ^ ((sl >> 4) * (PIECES / 4)))] = vf[it];
+    }
+    // scores of this lane's row against its 16 slots base + q4*16 + t*4 + i
+    float sc[4][4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kt = 0; kt < KT; ++kt) {
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[t][kt]), qh[kt], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[t][kt]), ql[kt], acc, 0, 0, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int slot = base + q4 * 16 + t * 4 + i;
+        const bool valid = row_ok && slot < n_slots && (!TREE || slot < vbase || ((vmask >> (slot - vbase)) & 1ull));
+        sc[t][i] = valid ? acc[i] * a.scale : -INFINITY;
+      }
+    }
+    float bm = -INFINITY;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) bm = fmaxf(bm, sc[t][i]);
+    bm = fmaxf(bm, __shfl_xor(bm, 16, 64));  // the four quarters of a row must share the reference:
+    bm = fmaxf(bm, __shfl_xor(bm, 32, 64));  // their slots are summed by one instruction below
+    const float m_new = fmaxf(m_run, bm);
+    const float m_ref = m_new == -INFINITY ? 0.f : m_new;  // nothing visible so far: exponentials give 0
+    const float alpha = __expf(m_run - m_ref);
+    m_run = m_new;
+    l_run *= alpha;
+#pragma unroll
+    for (int et = 0; et < ET; ++et) o[et] *= alpha;
+    // B operands of P.V: MFMA number h takes slots q4*16 + h*8 .. +8 of this lane = tiles 2h, 2h+1
+    bf16x8 ph[2], pl[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      uint32_t hb[8], lb[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float pv = __expf(sc[2 * h + (j >> 2)][j & 3] - m_ref);
+        l_run += pv;
+        hb[j] = float_to_bf16_bits(pv);
+        lb[j] = float_to_bf16_bits(pv - bf16_bits_to_float(hb[j]));
+      }
+      ph[h] = pack_bf16x8(hb);
+      pl[h] = pack_bf16x8(lb);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // this wave's LDS stores have landed
+    __builtin_amdgcn_wave_barrier();
+    // A operands: V^T row e = et*16 + lane%16, the 8 slots q4*16 + h*8 + j, gathered from LDS
+#pragma unroll
+    for (int et = 0; et < ET; ++et) {
+      const int e = et * 16 + r;
+      const int pofs = ((e >> 3) ^ swz) * 8 + (e & 7);  // 2-byte index inside a slot's row
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        uint32_t vb[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) vb[j] = vt16[(q4 * 16 + h * 8 + j) * HD + pofs];
+        const bf16x8 va = pack_bf16x8(vb);
+        o[et] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, ph[h], o[et], 0, 0, 0);
+        o[et] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pl[h], o[et], 0, 0, 0);
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    __builtin_amdgcn_wave_barrier();  // the gathers are done before the next tile overwrites the piece of LDS
+  }
+
+  l_run += __shfl_xor(l_run, 16, 64);
+  l_run += __shfl_xor(l_run, 32, 64);
+  if (!row_ok || ws0 >= n_slots) return;  // padding rows; columns that end before this sub-chunk
+  const int nch = (n_slots + a.CH - 1) / a.CH;
+  const int head = kvh * G + g;
+  if (nch == 1) {
+#pragma unroll
+    for (int et = 0; et < ET; ++et) {
+      const int e = et * 16 + q4 * 4;
+      bf16_t* dst = reinterpret_cast<bf16_t*>(a.AO) + (size_t)li * 2 * kMaxCols * HQ + xoff<bf16_t>(c.n, HQ, col, head * HD + e);
+      store_act4<bf16_t>(dst, (size_t)kMaxCols * HQ, o[et][0] / l_run, o[et][1] / l_run, o[et][2] / l_run, o[et][3] / l_run);
+    }
+  } else {
+    const size_t row = ((size_t)li * kMaxCols + col) * a.Hq + head;
+#pragma unroll
+    for (int et = 0; et < ET; ++et)
+      *reinterpret_cast<f32x4*>(a.PO + (row * kMaxChunks + chunk) * HD + et * 16 + q4 * 4) = o[et];
+    if (q4 == 0) {
+      a.PM[row * kMaxChunks + chunk] = m_run;
+      a.PL[row * kMaxChunks + chunk] = l_run;
+    }
+  }
+}
+
 // Merge the chunk partials of one (layer, column, KV head): all G query heads, chunks in
 // order.  Runs as its own launch: the kernel boundary is what makes the partials written by
 // workgroups on other XCDs visible (a device-scope fence inside the attention kernel costs an
@@ -1194,9 +1388,40 @@ static void launch_attn_g(int G, dim3 grid, int nwv, hipStream_t st, const AttnA
   }
 }
 
-int attn_block_slots(const Shape& s) {
+// Matrix-core attention: bf16 caches, switched by EASYSPEC_ATTN_MFMA.
+static bool attn_use_mfma(const Shape& s) {
+  static const int on = env_int("EASYSPEC_ATTN_MFMA", 0);
+  return on != 0 && s.dtype == 1;
+}
+
+// Runs of consecutive columns of one sequence, cut so that a group's query rows (columns x G
+// heads per KV head) fill at most the 16 columns of an MFMA tile.
+static void group_columns(const Cols& c, int G, ColGroups& cg) {
+  const int most = std::max(1, 16 / G);
+  cg.n = 0;
+  for (int i = 0; i < c.n;) {
+    int j = i + 1;
+    while (j < c.n && c.seq[j] == c.seq[i] && j - i < most) ++j;
+    cg.first[cg.n] = i;
+    cg.count[cg.n] = j - i;
+    ++cg.n;
+    i = j;
+  }
+}
+
+void attn_plan(const Shape& s, const Cols& c, int* units, int* chunk_unit, int* units_per_workgroup) {
+  if (attn_use_mfma(s)) {
+    ColGroups cg;
+    group_columns(c, s.Hq / s.Hkv, cg);
+    *units = cg.n;       // one wave per group of columns, sub-chunk and KV head
+    *chunk_unit = 64;    // it walks its sub-chunk in super tiles of 64 slots
+    *units_per_workgroup = kMfmaAttnWaves;
+    return;
+  }
   const int lps = s.hd * (s.dtype == 1 ? 2 : 4) / 16;
-  return 4 * kAttnIT * (64 / lps);
+  *units = c.n;
+  *chunk_unit = 4 * kAttnIT * (64 / lps);  // four waves side by side, one batch each
+  *units_per_workgroup = 1;
 }
 
 void launch_attn(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, int chunk, int n_chunks,
@@ -1212,6 +1437,17 @@ void launch_attn(const Shape& s, const Buffers& b, const Cols& c, int layer0, in
   const int nwv = n_chunks == 1 ? 8 : 4;
   bool tree = false;  // any column that does not see every slot up to its own
   for (int i = 0; i < c.n; ++i) tree = tree || c.vis_base[i] <= c.pos[i];
+  if (attn_use_mfma(s)) {
+    ColGroups cg;
+    group_columns(c, G, cg);
+    const dim3 mg((n_chunks + kMfmaAttnWaves - 1) / kMfmaAttnWaves, s.Hkv, n_set * cg.n);
+    const dim3 blk(64 * kMfmaAttnWaves);
+    const size_t lds = (size_t)kMfmaAttnWaves * 64 * (s.hd / 8) * sizeof(u32x4);
+    if (s.hd == 128 && tree) hipLaunchKernelGGL((attn_mfma_kernel<128, true>), mg, blk, lds, st, a, c, cg, G);
+    else if (s.hd == 128) hipLaunchKernelGGL((attn_mfma_kernel<128, false>), mg, blk, lds, st, a, c, cg, G);
+    else if (tree) hipLaunchKernelGGL((attn_mfma_kernel<64, true>), mg, blk, lds, st, a, c, cg, G);
+    else hipLaunchKernelGGL((attn_mfma_kernel<64, false>), mg, blk, lds, st, a, c, cg, G);
+  } else
   DISPATCH_T(s.dtype, {
     if (s.hd == 128 && tree) launch_attn_g<T, 128, true>(G, grid, nwv, st, a, c);
     else if (s.hd == 128) launch_attn_g<T, 128, false>(G, grid, nwv, st, a, c);
