@@ -1022,7 +1022,7 @@ __device__ __forceinline__ bf16x8 pack_bf16x8(const uint32_t (&b)[8]) {
 template <int HD, bool TREE>
 __global__ __launch_bounds__(64 * kMfmaAttnWaves) void attn_mfma_kernel(AttnArgs a, Cols c, ColGroups cg, int G) {
   constexpr int KT = HD / 32, ET = HD / 16, PIECES = HD / 8;
-  extern __shared__ u32x4 dyn_v[];  // [waves][64 slots][PIECES] 16-byte pieces, pieces swizzled
+  extern __shared__ u32x4 dyn_v[];  // per wave: V tile [64 slots][PIECES] then K tile [16 slots][PIECES], 16-byte pieces, swizzled
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, NWV = blockDim.x >> 6;
   const int chunk = blockIdx.x * NWV + wave, kvh = blockIdx.y;
   const int li = blockIdx.z / cg.n, grp = blockIdx.z % cg.n;
@@ -1042,8 +1042,10 @@ __global__ __launch_bounds__(64 * kMfmaAttnWaves) void attn_mfma_kernel(AttnArgs
   const size_t rowbase = (((size_t)(a.layer0 + li) * a.B + c.seq[first]) * a.Hkv + kvh) * (size_t)a.max_ctx;
   const bf16_t* kc = reinterpret_cast<const bf16_t*>(a.kc) + rowbase * HD;
   const u32x4* vc = reinterpret_cast<const u32x4*>(reinterpret_cast<const bf16_t*>(a.vc) + rowbase * HD);
-  u32x4* vt = dyn_v + (size_t)wave * 64 * PIECES;
+  u32x4* vt = dyn_v + (size_t)wave * 80 * PIECES;
+  u32x4* kt_lds = vt + 64 * PIECES;
   const uint16_t* vt16 = reinterpret_cast<const uint16_t*>(vt);
+  const u32x4* kc4 = reinterpret_cast<const u32x4*>(kc);
 
   // B operands of S^T: this row's query, hi and lo bf16 terms, k-group q4 of every k-tile
   bf16x8 qh[KT], ql[KT];
@@ -1071,14 +1073,13 @@ __global__ __launch_bounds__(64 * kMfmaAttnWaves) void attn_mfma_kernel(AttnArgs
   const int swz = q4 * (PIECES / 4);
 
   for (int base = ws0; base < ws1; base += 64) {
-    // K fragments: S^T tile t, A row m = lane % 16 <-> slot base + (m/4)*16 + t*4 + m%4
-    u32x4 kf[4][KT];
+    // K rows as they lie in memory (coalesced: a load instruction covers 4 KB / PIECES... consecutive
+    // bytes): fragment f = it*64 + lane of the 64 x PIECES pieces of the super tile
+    u32x4 kf[PIECES];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const int slot = base + (r >> 2) * 16 + t * 4 + (r & 3);
-#pragma unroll
-      for (int kt = 0; kt < KT; ++kt)
-        kf[t][kt] = slot < ws1 ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kc + (size_t)slot * HD + kt * 32 + q4 * 8)) : zero;
+    for (int it = 0; it < PIECES; ++it) {
+      const int f = it * 64 + lane, sl = f / PIECES;
+      kf[it] = base + sl < ws1 ? __builtin_nontemporal_load(kc4 + (size_t)base * PIECES + f) : zero;
     }
     // V tile, row-major from memory (coalesced), into LDS with the pieces of slot s XORed by (s/16)*(PIECES/4)
     u32x4 vf[PIECES];
@@ -1092,16 +1093,31 @@ __global__ __launch_bounds__(64 * kMfmaAttnWaves) void attn_mfma_kernel(AttnArgs
       const int f = it * 64 + lane, sl = f / PIECES, piece = f % PIECES;
       vt[sl * PIECES + (piece ^ ((sl >> 4) * (PIECES / 4)))] = vf[it];
     }
-    // scores of this lane's row against its 16 slots base + q4*16 + t*4 + i
+    // scores of this lane's row against its 16 slots base + q4*16 + t*4 + i.  S^T tile t takes
+    // the slots (m/4)*16 + t*4 + m%4, m = 0..15, as its A rows: their pieces go through LDS
+    // (piece p of A row m stored at p ^ m, so that the 16 rows of one piece hit 16 different banks)
     float sc[4][4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
+#pragma unroll
+      for (int it = 0; it < PIECES; ++it) {
+        const int f = it * 64 + lane, sl = f / PIECES, piece = f % PIECES;
+        if (((sl >> 2) & 3) == t) {  // slot sl belongs to tile t
+          const int m = (sl >> 4) * 4 + (sl & 3);
+          kt_lds[m * PIECES + (piece ^ (m & (PIECES - 1)))] = kf[it];
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      __builtin_amdgcn_wave_barrier();
       f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int kt = 0; kt < KT; ++kt) {
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[t][kt]), qh[kt], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[t][kt]), ql[kt], acc, 0, 0, 0);
+        const u32x4 ka = kt_lds[r * PIECES + ((kt * 4 + q4) ^ (r & (PIECES - 1)))];
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka), qh[kt], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka), ql[kt], acc, 0, 0, 0);
       }
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+      __builtin_amdgcn_wave_barrier();
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int slot = base + q4 * 16 + t * 4 + i;
@@ -1388,10 +1404,24 @@ static void launch_attn_g(int G, dim3 grid, int nwv, hipStream_t st, const AttnA
   }
 }
 
-// Matrix-core attention: bf16 caches, switched by EASYSPEC_ATTN_MFMA.
-static bool attn_use_mfma(const Shape& s) {
-  static const int on = env_int("EASYSPEC_ATTN_MFMA", 0);
-  return on != 0 && s.dtype == 1;
+// Matrix-core attention or the vector-ALU kernel?  The MFMA kernel reads K and V once per group
+// of columns of a sequence and does the per-slot arithmetic on the matrix cores, but its
+// per-wave chain (LDS transposes between the two products) is longer; measured, it wins once a
+// launch holds several columns of a sequence and enough (column, layer, slot) work: tree levels,
+// long calibrations.  Single columns (plain draft steps) and short 1-layer launches stay on the
+// vector kernel.  EASYSPEC_ATTN_MFMA = 0 / 2 forces never / always (bf16 only).
+static bool attn_use_mfma(const Shape& s, const Cols& c, int n_set) {
+  const int mode = env_int("EASYSPEC_ATTN_MFMA", 1);  // read at every call: tests switch it between contexts
+  const long min_work = env_int("EASYSPEC_ATTN_MFMA_MIN", 32768);
+  if (mode == 0 || s.dtype != 1) return false;
+  if (mode == 2) return true;
+  bool shared = false;
+  int max_len = 1;
+  for (int i = 0; i < c.n; ++i) {
+    shared = shared || (i > 0 && c.seq[i] == c.seq[i - 1]);
+    max_len = std::max(max_len, c.pos[i] + 1);
+  }
+  return shared && (long)n_set * c.n * max_len >= min_work;
 }
 
 // Runs of consecutive columns of one sequence, cut so that a group's query rows (columns x G
@@ -1409,23 +1439,24 @@ static void group_columns(const Cols& c, int G, ColGroups& cg) {
   }
 }
 
-void attn_plan(const Shape& s, const Cols& c, int* units, int* chunk_unit, int* units_per_workgroup) {
-  if (attn_use_mfma(s)) {
+bool attn_plan(const Shape& s, const Cols& c, int n_set, int* units, int* chunk_unit, int* units_per_workgroup) {
+  if (attn_use_mfma(s, c, n_set)) {
     ColGroups cg;
     group_columns(c, s.Hq / s.Hkv, cg);
     *units = cg.n;       // one wave per group of columns, sub-chunk and KV head
     *chunk_unit = 64;    // it walks its sub-chunk in super tiles of 64 slots
     *units_per_workgroup = kMfmaAttnWaves;
-    return;
+    return true;
   }
   const int lps = s.hd * (s.dtype == 1 ? 2 : 4) / 16;
   *units = c.n;
   *chunk_unit = 4 * kAttnIT * (64 / lps);  // four waves side by side, one batch each
   *units_per_workgroup = 1;
+  return false;
 }
 
 void launch_attn(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, int chunk, int n_chunks,
-                 hipStream_t st) {
+                 bool mfma, hipStream_t st) {
   AttnArgs a;
   a.Q = b.Q; a.kc = b.kc; a.vc = b.vc; a.PO = b.PO; a.PM = b.PM; a.PL = b.PL; a.AO = b.AO;
   a.layer0 = layer0; a.Hq = s.Hq; a.Hkv = s.Hkv; a.B = s.B; a.max_ctx = s.max_ctx; a.CH = chunk;
@@ -1437,12 +1468,12 @@ void launch_attn(const Shape& s, const Buffers& b, const Cols& c, int layer0, in
   const int nwv = n_chunks == 1 ? 8 : 4;
   bool tree = false;  // any column that does not see every slot up to its own
   for (int i = 0; i < c.n; ++i) tree = tree || c.vis_base[i] <= c.pos[i];
-  if (attn_use_mfma(s)) {
+  if (mfma) {
     ColGroups cg;
     group_columns(c, G, cg);
     const dim3 mg((n_chunks + kMfmaAttnWaves - 1) / kMfmaAttnWaves, s.Hkv, n_set * cg.n);
     const dim3 blk(64 * kMfmaAttnWaves);
-    const size_t lds = (size_t)kMfmaAttnWaves * 64 * (s.hd / 8) * sizeof(u32x4);
+    const size_t lds = (size_t)kMfmaAttnWaves * 80 * (s.hd / 8) * sizeof(u32x4);  // per wave a 64-slot V tile and a 16-slot K tile
     if (s.hd == 128 && tree) hipLaunchKernelGGL((attn_mfma_kernel<128, true>), mg, blk, lds, st, a, c, cg, G);
     else if (s.hd == 128) hipLaunchKernelGGL((attn_mfma_kernel<128, false>), mg, blk, lds, st, a, c, cg, G);
     else if (tree) hipLaunchKernelGGL((attn_mfma_kernel<64, true>), mg, blk, lds, st, a, c, cg, G);
