@@ -1047,6 +1047,26 @@ __global__ __launch_bounds__(64 * kMfmaAttnWaves) void attn_mfma_kernel(AttnArgs
   const uint16_t* vt16 = reinterpret_cast<const uint16_t*>(vt);
   const u32x4* kc4 = reinterpret_cast<const u32x4*>(kc);
 
+  // K and V rows of a super tile as they lie in memory (coalesced): fragment f = it*64 + lane of its
+  // 64 x PIECES 16-byte pieces.  The registers are free again once their contents sit in LDS, so
+  // the next super tile is requested while the current one is still being worked on; the first
+  // one before the queries are fetched.
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  u32x4 kf[PIECES], vf[PIECES];
+  auto request = [&](int base) {
+#pragma unroll
+    for (int it = 0; it < PIECES; ++it) {
+      const int f = it * 64 + lane, sl = f / PIECES;
+      kf[it] = base + sl < ws1 ? __builtin_nontemporal_load(kc4 + (size_t)base * PIECES + f) : zero;
+    }
+#pragma unroll
+    for (int it = 0; it < PIECES; ++it) {
+      const int f = it * 64 + lane, sl = f / PIECES;
+      vf[it] = base + sl < ws1 ? __builtin_nontemporal_load(vc + (size_t)base * PIECES + f) : zero;
+    }
+  };
+  request(ws0);
+
   // B operands of S^T: this row's query, hi and lo bf16 terms, k-group q4 of every k-tile
   bf16x8 qh[KT], ql[KT];
   {
@@ -1069,25 +1089,10 @@ __global__ __launch_bounds__(64 * kMfmaAttnWaves) void attn_mfma_kernel(AttnArgs
 #pragma unroll
   for (int et = 0; et < ET; ++et) o[et] = f32x4{0.f, 0.f, 0.f, 0.f};
   float m_run = -INFINITY, l_run = 0.f;  // l_run: this lane's 16 slots per super tile only
-  const u32x4 zero = {0u, 0u, 0u, 0u};
   const int swz = q4 * (PIECES / 4);
 
   for (int base = ws0; base < ws1; base += 64) {
-    // K rows as they lie in memory (coalesced: a load instruction covers 4 KB / PIECES... consecutive
-    // bytes): fragment f = it*64 + lane of the 64 x PIECES pieces of the super tile
-    u32x4 kf[PIECES];
-#pragma unroll
-    for (int it = 0; it < PIECES; ++it) {
-      const int f = it * 64 + lane, sl = f / PIECES;
-      kf[it] = base + sl < ws1 ? __builtin_nontemporal_load(kc4 + (size_t)base * PIECES + f) : zero;
-    }
-    // V tile, row-major from memory (coalesced), into LDS with the pieces of slot s XORed by (s/16)*(PIECES/4)
-    u32x4 vf[PIECES];
-#pragma unroll
-    for (int it = 0; it < PIECES; ++it) {
-      const int f = it * 64 + lane, sl = f / PIECES;
-      vf[it] = base + sl < ws1 ? __builtin_nontemporal_load(vc + (size_t)base * PIECES + f) : zero;
-    }
+    // V tile into LDS with the pieces of slot s XORed by (s/16)*(PIECES/4)
 #pragma unroll
     for (int it = 0; it < PIECES; ++it) {
       const int f = it * 64 + lane, sl = f / PIECES, piece = f % PIECES;
@@ -1107,8 +1112,7 @@ __global__ __launch_bounds__(64 * kMfmaAttnWaves) void attn_mfma_kernel(AttnArgs
           kt_lds[m * PIECES + (piece ^ (m & (PIECES - 1)))] = kf[it];
         }
       }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_wave_barrier();  // LDS operations of one wave execute in order: no wait is needed
       f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int kt = 0; kt < KT; ++kt) {
@@ -1116,7 +1120,6 @@ __global__ __launch_bounds__(64 * kMfmaAttnWaves) void attn_mfma_kernel(AttnArgs
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka), qh[kt], acc, 0, 0, 0);
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka), ql[kt], acc, 0, 0, 0);
       }
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -1125,6 +1128,7 @@ __global__ __launch_bounds__(64 * kMfmaAttnWaves) void attn_mfma_kernel(AttnArgs
         sc[t][i] = valid ? acc[i] * a.scale : -INFINITY;
       }
     }
+    if (base + 64 < ws1) request(base + 64);  // both register sets are in LDS / consumed by now
     float bm = -INFINITY;
 #pragma unroll
     for (int t = 0; t < 4; ++t)
@@ -1154,7 +1158,6 @@ __global__ __launch_bounds__(64 * kMfmaAttnWaves) void attn_mfma_kernel(AttnArgs
       ph[h] = pack_bf16x8(hb);
       pl[h] = pack_bf16x8(lb);
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // this wave's LDS stores have landed
     __builtin_amdgcn_wave_barrier();
     // A operands: V^T row e = et*16 + lane%16, the 8 slots q4*16 + h*8 + j, gathered from LDS
 #pragma unroll
@@ -1171,8 +1174,7 @@ __global__ __launch_bounds__(64 * kMfmaAttnWaves) void attn_mfma_kernel(AttnArgs
         o[et] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pl[h], o[et], 0, 0, 0);
       }
     }
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    __builtin_amdgcn_wave_barrier();  // the gathers are done before the next tile overwrites the piece of LDS
+    __builtin_amdgcn_wave_barrier();  // the gathers are issued before the next tile's stores into the same piece of LDS
   }
 
   l_run += __shfl_xor(l_run, 16, 64);
@@ -1412,7 +1414,7 @@ static void launch_attn_g(int G, dim3 grid, int nwv, hipStream_t st, const AttnA
 // vector kernel.  EASYSPEC_ATTN_MFMA = 0 / 2 forces never / always (bf16 only).
 static bool attn_use_mfma(const Shape& s, const Cols& c, int n_set) {
   const int mode = env_int("EASYSPEC_ATTN_MFMA", 1);  // read at every call: tests switch it between contexts
-  const long min_work = env_int("EASYSPEC_ATTN_MFMA_MIN", 32768);
+  const long min_work = env_int("EASYSPEC_ATTN_MFMA_MIN", 20000);
   if (mode == 0 || s.dtype != 1) return false;
   if (mode == 2) return true;
   bool shared = false;
