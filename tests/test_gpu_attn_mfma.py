@@ -10,6 +10,7 @@ import pytest
 import easyspec_synth as synth
 from test_gpu_parity import iteration_parity
 from test_gpu_tree import tree_parity
+from test_gpu_tree import test_tree_two_sequences_ragged as _two_sequences_ragged
 from test_gpu_full_layer import full_layer_parity
 
 pytestmark = pytest.mark.gpu
@@ -74,3 +75,35 @@ def test_tree_8b_shape_long_context(oracle, gpu):
 
 def test_full_layer_batch2(oracle, gpu):
     full_layer_parity(oracle, gpu, synth.model_shape("tiny_qwen", dtype="bf16"), 770, [0, 1, 4, 5], 37, 3, batch=2)
+
+
+def test_tree_two_sequences_ragged(oracle, gpu):
+    """Several groups per launch: two sequences of different length growing different trees."""
+    _two_sequences_ragged(oracle, gpu)
+
+
+def test_calibration_of_two_sequences_in_one_call(oracle, gpu):
+    """Causal columns of two sequences in one pass (5 + 9 tokens: groups of 8, 1 and 5 columns at
+    2 query heads per KV head), after fuzzy steps that must leave no trace."""
+    from test_gpu_parity import TOL
+    cfg = synth.model_shape("tiny", dtype="bf16")
+    w = synth.make_weights(cfg, 780)
+    model = oracle.Model(cfg, w, 200)
+    so = [oracle.Sequence(model), oracle.Sequence(model)]
+    g = gpu.GpuDrafter(cfg, w, max_batch=2, max_ctx=200, max_calib=16)
+    g.set_groups([0, 1, 3, 4])
+    try:
+        for b, n in ((0, 90), (1, 131)):
+            prompt = synth.make_tokens(781 + b, n, cfg["vocab"])
+            so[b].calibrate(prompt)
+            g.prefill(b, prompt)
+        for t in (3, 4):
+            g.draft_step({0: t, 1: t + 10})
+            so[0].fuzzy_step([0, 1, 3, 4], t)
+            so[1].fuzzy_step([0, 1, 3, 4], t + 10)
+        toks = {0: [1, 2, 3, 4, 5], 1: [6, 7, 8, 9, 10, 11, 12, 13, 14]}
+        _, gl = g.calibrate(toks)
+        for b in (0, 1):
+            assert gpu.rel_l2(gl[b], so[b].calibrate(toks[b])) < TOL["bf16"], f"sequence {b}"
+    finally:
+        g.close()
