@@ -177,17 +177,19 @@ def test_batch4_ragged_long_contexts(oracle, gpu):
         g.close()
 
 
-def test_full_size_llama3_8b_sampled(oracle, gpu):
-    """The benchmark configuration itself (32 layers, context 2048, aligned N=4 sets, gamma 5,
-    6-token calibration): one calibration and two fuzzy steps checked against the oracle."""
+def full_size_sampled(oracle, gpu, shape, ctx_len, N, want_bounds=None, tree_width=0):
+    """A benchmark configuration itself (full depth, aligned sets, gamma 5, 6-token calibration): one
+    calibration and two fuzzy steps checked against the oracle; optionally one tree level of the
+    given width on top (the calibration is redone first, so the chain's fuzzy slots are gone)."""
     import paper_2502_02493_amd as es
-    cfg = synth.model_shape("llama3_8b")
-    print("drawing 8B-shape weights ...", flush=True)
+    cfg = synth.model_shape(shape)
+    print(f"drawing {shape} weights ...", flush=True)
     w = synth.make_weights(cfg, 2025)
-    ctx_len, bounds = 2048, groups(es, cfg, 4)
-    assert list(bounds) == [0, 1, 4, 8, 12, 16, 20, 24, 28, 31, 32]
-    so = oracle.Sequence(oracle.Model(cfg, w, ctx_len + 32))
-    g = gpu.GpuDrafter(cfg, w, max_batch=1, max_ctx=ctx_len + 32, max_calib=16)
+    bounds = groups(es, cfg, N)
+    if want_bounds is not None:
+        assert list(bounds) == want_bounds
+    so = oracle.Sequence(oracle.Model(cfg, w, ctx_len + 48))
+    g = gpu.GpuDrafter(cfg, w, max_batch=1, max_ctx=ctx_len + 48, max_calib=16)
     stats = [0, 0]
     try:
         g.set_groups(bounds)
@@ -209,5 +211,25 @@ def test_full_size_llama3_8b_sampled(oracle, gpu):
             assert err < TOL["bf16"]
             tok = check_ids(oracle, "bf16", gtok[0], wl, stats)
         assert stats[0] >= 2, stats
+        if tree_width:
+            so.calibrate([tok])
+            g.calibrate({0: [tok]}, all_rows=False)
+            toks = [int(t) for t in synth.make_tokens(2028, tree_width, cfg["vocab"])]
+            print("oracle tree level ...", flush=True)
+            wl = so.fuzzy_tree_step(bounds, toks, [-1] * tree_width)
+            _, gl = g.draft_tree_step({0: (toks, [-1] * tree_width)})
+            err = gpu.rel_l2(gl[0], wl)
+            print("tree level rel-L2", err, flush=True)
+            assert err < TOL["bf16"]
     finally:
         g.close()
+
+
+def test_full_size_llama3_8b_sampled(oracle, gpu):
+    """32 layers, context 2048, sets of 4; then a tree level of width 4 (matrix-core attention at full size)."""
+    full_size_sampled(oracle, gpu, "llama3_8b", 2048, 4, [0, 1, 4, 8, 12, 16, 20, 24, 28, 31, 32], tree_width=4)
+
+
+def test_full_size_qwen2_7b_sampled(oracle, gpu):
+    """28 layers, context 4096, sets of 4, 7 query heads per KV head, QKV bias."""
+    full_size_sampled(oracle, gpu, "qwen2_7b", 4096, 4)
