@@ -312,32 +312,6 @@ extern "C" int easyspec_set_groups(easyspec_ctx* ctx, const int32_t* bounds, int
 // one forward pass over the columns `c` (launch sequence of Alg. 1 / Alg. 2)
 // ---------------------------------------------------------------------------------------------
 
-// Returns whether the matrix-core attention kernel takes these columns.
-static bool pick_chunk(const Shape& s, const Cols& c, int n_set, int* chunk, int* n_chunks) {
-  int max_len = 1;
-  for (int i = 0; i < c.n; ++i)
-    if (c.pos[i] + 1 > max_len) max_len = c.pos[i] + 1;
-  int units, unit, per_wg;
-  const bool mfma = attn_plan(s, c, n_set, &units, &unit, &per_wg);
-  // Short contexts: one piece of work per (layer, column, KV head) walks the whole context, which
-  // saves the merge launch; two dependent launches cost more than the narrower launch loses.
-  static const int single_max = getenv("EASYSPEC_ATTN_SINGLE") ? atoi(getenv("EASYSPEC_ATTN_SINGLE")) : 256;
-  if (max_len <= single_max) {
-    *chunk = (max_len + unit - 1) / unit * unit;
-    *n_chunks = 1;
-    return mfma;
-  }
-  // Long contexts: chunks are multiples of what one piece covers per batch; grow them until the
-  // chunk count fits the partial buffers and the launch is not cut finer than two workgroups per CU.
-  static const long max_wg = getenv("EASYSPEC_ATTN_WG") ? atol(getenv("EASYSPEC_ATTN_WG")) : 512;
-  int ch = unit;
-  auto nch = [&](int ch_) { return (max_len + ch_ - 1) / ch_; };
-  while (ch < 1024 && (nch(ch) > kMaxChunks || (long)nch(ch) * s.Hkv * n_set * units > max_wg * per_wg)) ch *= 2;
-  *chunk = ch;
-  *n_chunks = nch(ch);
-  return mfma;
-}
-
 // Brackets the launches of one kernel class with an event pair while profiling is on.
 struct ProfScope {
   easyspec_ctx* ctx;
@@ -362,11 +336,10 @@ static int forward(easyspec_ctx* ctx, const Cols& c, const int32_t* tokens, cons
   launch_embed(s, b, c, tokens, 0, bounds[1] - bounds[0], st);
   for (int j = 0; j < n_sets; ++j) {
     const int lo = bounds[j], hi = bounds[j + 1], k = hi - lo;
-    int chunk, n_chunks;
-    const bool mfma = pick_chunk(s, c, k, &chunk, &n_chunks);
+    const AttnCut cut = attn_cut(s, c, k);
     // every attention layer of the set reads the hidden state that enters the set
     { ProfScope p(ctx, EASYSPEC_OP_QKV); launch_qkv(s, b, c, lo, k, st); }
-    { ProfScope p(ctx, EASYSPEC_OP_ATTN); launch_attn(s, b, c, lo, k, chunk, n_chunks, mfma, st); }
+    { ProfScope p(ctx, EASYSPEC_OP_ATTN); launch_attn(s, b, c, lo, k, cut, st); }
     if (full_layer && k > 1) {
       // App. B ablation: the MLPs of the set also work from the set's input, each behind its own
       // layer's attention; one launch per operation for the whole set

@@ -70,13 +70,15 @@ void launch_repack(int dtype, const void* src, void* dst, int rows, int K, hipSt
 void launch_embed(const Shape& s, const Buffers& b, const Cols& c, const int32_t* tokens, int layer0, int n_set,
                   hipStream_t st);
 void launch_qkv(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st);
-// How launch_attn will cut the work of these columns over n_set layers: `units` independent pieces
-// per (chunk, KV head, layer) — one per column, or one per group of columns of a sequence on the
-// matrix-core path (return value true; pass it on to launch_attn) — `units_per_workgroup` of them
-// per workgroup; chunk sizes must be multiples of `chunk_unit` slots.
-bool attn_plan(const Shape& s, const Cols& c, int n_set, int* units, int* chunk_unit, int* units_per_workgroup);
-void launch_attn(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, int chunk, int n_chunks,
-                 bool mfma, hipStream_t st);
+// How an attention launch over n_set layers cuts the contexts of these columns into split-KV chunks.
+struct AttnCut {
+  bool mfma;     // the matrix-core kernel takes the launch (groups of columns of one sequence)
+  int n_chunks;  // chunks of the longest column = grid extent; 1: every context in one piece, no merge launch
+  int chunk;     // matrix-core kernel: slots per chunk (fixed length)
+  int nb_ref;    // vector kernel: batches of the longest column; shorter columns get proportionally fewer chunks
+};
+AttnCut attn_cut(const Shape& s, const Cols& c, int n_set);
+void launch_attn(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, const AttnCut& cut, hipStream_t st);
 // O projection of the set's layers; the first layer's result goes straight into the residual.
 void launch_oproj(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st);
 // Gate/up of n_layers consecutive layers, layer i on operand slot i of XM with partial sums slot i

@@ -795,11 +795,37 @@ struct AttnArgs {
   float* PM;
   float* PL;
   void* AO;
-  int layer0, Hq, Hkv, B, max_ctx, CH;
+  int layer0, Hq, Hkv, B, max_ctx;
+  int CH;       // fixed-length cut (matrix-core kernel): slots per chunk
+  int nch_ref;  // even cut (vector kernel, nb_ref > 0): chunks of a column of nb_ref batches
+  int nb_ref;
+  int direct;   // vector kernel: LDS holds the state of every slot group (see the kernel's last part)
   float scale;
 };
 
+// The split-KV cut of one column: its chunk count and the slot range [s0, s1) of chunk `chunk`
+// (empty for chunk >= nch).  Fixed-length cut: chunks of CH slots.  Even cut: the column's
+// batches (of `wave_slots` slots, what one wave fetches at a time) are dealt to
+// round(nb * nch_ref / nb_ref) chunks whose batch counts differ by at most one, so that a
+// context of a power-of-two length plus a few drafted tokens does not leave a sliver of a chunk.
+__device__ __forceinline__ void chunk_range(const AttnArgs& a, int n_slots, int wave_slots, int chunk, int& nch, int& s0,
+                                            int& s1) {
+  if (a.nb_ref == 0) {
+    nch = (n_slots + a.CH - 1) / a.CH;
+    s0 = chunk * a.CH;
+    s1 = min(s0 + a.CH, n_slots);
+  } else {
+    const int nb = (n_slots + wave_slots - 1) / wave_slots;
+    nch = max(1, min(nb, (nb * a.nch_ref + a.nb_ref / 2) / a.nb_ref));
+    s0 = (int)((long)chunk * nb / nch) * wave_slots;
+    s1 = min((int)((long)(chunk + 1) * nb / nch) * wave_slots, n_slots);
+  }
+}
+
 constexpr int kAttnIT = 8;  // loads in flight per operand per lane
+// whether the registers allow a second set of K/V fragments (next batch requested early)
+template <int G, bool TREE>
+constexpr bool kAttnPrefetch = G <= 2 || (G <= 4 && !TREE);
 
 // Sum over aligned groups of N lanes (8, 16 or 32), every lane of a group receiving the total,
 // with data-parallel-primitive operand swizzles (lane^1 and lane^2 inside quads, then the
@@ -842,16 +868,18 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
   // column's row of a token tree's mask).  Causal columns have vis_base = n_slots.
   const int vbase = c.vis_base[col];
   const unsigned long long vmask = c.vis_mask[col];
-  const int s0 = chunk * a.CH;
-  if (s0 >= n_slots) return;
-  const int s1 = min(s0 + a.CH, n_slots);
-  const int nch = (n_slots + a.CH - 1) / a.CH;
+  int nch, s0, s1;
+  chunk_range(a, n_slots, Geo::WAVE_SLOTS, chunk, nch, s0, s1);
+  if (chunk >= nch) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, NWV = blockDim.x >> 6;  // 4 or 8 waves
   const int sub = lane / LPS, e0 = (lane % LPS) * EPL;
 
   const size_t rowbase = (((size_t)(a.layer0 + li) * a.B + c.seq[col]) * a.Hkv + kvh) * (size_t)a.max_ctx;
-  const T* kb = reinterpret_cast<const T*>(a.kc) + rowbase * HD + e0;
-  const T* vb = reinterpret_cast<const T*>(a.vc) + rowbase * HD + e0;
+  // wave-uniform row bases; a lane's fragment of slot s lies s * HD + e0 elements further (32-bit offsets)
+  const char* kb = reinterpret_cast<const char*>(reinterpret_cast<const T*>(a.kc) + rowbase * HD);
+  const char* vb = reinterpret_cast<const char*>(reinterpret_cast<const T*>(a.vc) + rowbase * HD);
+  constexpr uint32_t ROW_BYTES = HD * sizeof(T);
+  const uint32_t lane_byte = e0 * sizeof(T);
   const int HQ = a.Hq * HD;
 
   float q[G][EPL], acc[G][EPL], m_run[G], l_run[G];
@@ -867,19 +895,23 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
     l_run[g] = 0.f;
   }
 
-  const u32x4 zero = {0u, 0u, 0u, 0u};
-  for (int base = s0 + wave * Geo::WAVE_SLOTS; base < s1; base += NWV * Geo::WAVE_SLOTS) {  // wave-uniform
-    u32x4 kr[IT], vr[IT];
+  // The K and V fragments of a batch: IT loads per operand, all issued before the first is used.
+  // Slots past the end of the chunk fetch the chunk's last row instead (their scores are
+  // discarded below), so the loads are unconditional and the wait counts exact: a wave asks
+  // for its next batch before it works on the current one and waits only for the older loads.
+  auto fetch = [&](u32x4 (&kr)[IT], u32x4 (&vr)[IT], int base) {
 #pragma unroll
     for (int j = 0; j < IT; ++j) {
-      const int s = base + j * SPW + sub;
-      kr[j] = s < s1 ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kb + (size_t)s * HD)) : zero;
+      const int s = min(base + j * SPW + sub, s1 - 1);
+      kr[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kb + ((uint32_t)s * ROW_BYTES + lane_byte)));
     }
 #pragma unroll
     for (int j = 0; j < IT; ++j) {
-      const int s = base + j * SPW + sub;
-      vr[j] = s < s1 ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vb + (size_t)s * HD)) : zero;
+      const int s = min(base + j * SPW + sub, s1 - 1);
+      vr[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vb + ((uint32_t)s * ROW_BYTES + lane_byte)));
     }
+  };
+  auto work = [&](const u32x4 (&kr)[IT], const u32x4 (&vr)[IT], int base) {
     float sc[IT][G], m_use[G];
 #pragma unroll
     for (int j = 0; j < IT; ++j) {
@@ -926,67 +958,137 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
         for (int e = 0; e < EPL; ++e) acc[g][e] += p * vv[e];
       }
     }
-  }
-
-  // combine the slot groups of the wave: common reference maximum first (l_run counts each slot
-  // once per group, every lane of a group holds the same value)
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-    float mw = m_run[g];
-#pragma unroll
-    for (int off = LPS; off < 64; off <<= 1) mw = fmaxf(mw, __shfl_xor(mw, off, 64));
-    const float rescale = m_run[g] == -INFINITY ? 0.f : __expf(m_run[g] - mw);  // a group without slots has l = acc = 0
-    m_run[g] = mw;
-    l_run[g] *= rescale;
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) acc[g][e] *= rescale;
-#pragma unroll
-    for (int off = LPS; off < 64; off <<= 1) {
-      l_run[g] += __shfl_xor(l_run[g], off, 64);
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) acc[g][e] += __shfl_xor(acc[g][e], off, 64);
+  };
+  const int stride = NWV * Geo::WAVE_SLOTS;
+  int base = s0 + wave * Geo::WAVE_SLOTS;  // wave-uniform, like the branches below
+  if constexpr (kAttnPrefetch<G, TREE>) {
+    // two register sets in turn; the last request of a wave is never used
+    u32x4 kr0[IT], vr0[IT], kr1[IT], vr1[IT];
+    if (base < s1) {
+      fetch(kr0, vr0, base);
+      for (;;) {
+        fetch(kr1, vr1, base + stride);
+        work(kr0, vr0, base);
+        base += stride;
+        if (base >= s1) break;
+        fetch(kr0, vr0, base + stride);
+        work(kr1, vr1, base);
+        base += stride;
+        if (base >= s1) break;
+      }
+    }
+  } else {
+    for (; base < s1; base += stride) {
+      u32x4 kr[IT], vr[IT];
+      fetch(kr, vr, base);
+      work(kr, vr, base);
     }
   }
-  float* w_acc = dyn_f;                 // [NWV][G][HD]
-  float* w_m = dyn_f + NWV * G * HD;    // [NWV][G]
-  float* w_l = w_m + NWV * G;           // [NWV][G]
-  if (sub == 0) {
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) w_acc[(wave * G + g) * HD + e0 + e] = acc[g][e];
-  }
-  if (lane == 0) {
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      w_m[wave * G + g] = m_run[g];  // -inf for a wave that had no slots
-      w_l[wave * G + g] = l_run[g];
-    }
-  }
-  __syncthreads();
 
+  // Combine the NWV * SPW slot groups of the workgroup (l_run counts each slot once per group,
+  // every lane of a group holds the same value).  A group, or a whole chunk of a tree column,
+  // may have seen no visible slot: its maximum is -inf, its sums 0, and its weight below 0.
   const size_t arow = (size_t)li * kMaxCols + col;
-  for (int idx = tid; idx < G * HD; idx += blockDim.x) {
-    const int g = idx / HD, e = idx % HD;
-    float m = w_m[g];
-    for (int w = 1; w < NWV; ++w) m = fmaxf(m, w_m[w * G + g]);
-    float l = 0.f, o = 0.f;
-    for (int w = 0; w < NWV; ++w) {
-      const float wgt = __expf(w_m[w * G + g] - m);
-      l += w_l[w * G + g] * wgt;
-      o += w_acc[(w * G + g) * HD + e] * wgt;
-    }
+  auto emit = [&](int g, int e, float m, float l, float o0, float o1) {  // outputs e, e + 1 of head g
     const int head = kvh * G + g;
     if (nch == 1) {
-      store_act1<T>(reinterpret_cast<T*>(a.AO) + (size_t)li * Tr<T>::PARTS * kMaxCols * HQ + xoff<T>(c.n, HQ, col, head * HD + e),
-                    (size_t)kMaxCols * HQ, o / l);
+      T* dst = reinterpret_cast<T*>(a.AO) + (size_t)li * Tr<T>::PARTS * kMaxCols * HQ;
+      store_act1<T>(dst + xoff<T>(c.n, HQ, col, head * HD + e), (size_t)kMaxCols * HQ, o0 / l);
+      store_act1<T>(dst + xoff<T>(c.n, HQ, col, head * HD + e + 1), (size_t)kMaxCols * HQ, o1 / l);
     } else {
       const size_t row = arow * a.Hq + head;
-      a.PO[(row * kMaxChunks + chunk) * HD + e] = o;
+      *reinterpret_cast<float2*>(a.PO + (row * kMaxChunks + chunk) * HD + e) = make_float2(o0, o1);
       if (e == 0) {
         a.PM[row * kMaxChunks + chunk] = m;
         a.PL[row * kMaxChunks + chunk] = l;
       }
+    }
+  };
+  if (a.direct) {
+    // every group's state goes to LDS as it stands; each thread then folds all groups for two
+    // adjacent outputs (no cross-lane traffic at all)
+    const int P = NWV * SPW, p = wave * SPW + sub;
+    float* w_acc = dyn_f;              // [P][G][HD]
+    float* w_m = dyn_f + P * G * HD;   // [G][P]
+    float* w_l = w_m + G * P;          // [G][P]
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+#pragma unroll
+      for (int e = 0; e < EPL; e += 4)
+        *reinterpret_cast<f32x4*>(w_acc + (p * G + g) * HD + e0 + e) = f32x4{acc[g][e], acc[g][e + 1], acc[g][e + 2], acc[g][e + 3]};
+    }
+    if (lane % LPS == 0) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        w_m[g * P + p] = m_run[g];
+        w_l[g * P + p] = l_run[g];
+      }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < G * HD / 2; idx += blockDim.x) {
+      const int g = idx / (HD / 2), e = (idx % (HD / 2)) * 2;
+      float m = w_m[g * P];
+      for (int q = 1; q < P; ++q) m = fmaxf(m, w_m[g * P + q]);
+      const float m_ref = m == -INFINITY ? 0.f : m;
+      float l = 0.f, o0 = 0.f, o1 = 0.f;
+      for (int q = 0; q < P; ++q) {  // in group order: the result does not depend on timing
+        const float wgt = __expf(w_m[g * P + q] - m_ref);
+        const float2 v = *reinterpret_cast<const float2*>(w_acc + (q * G + g) * HD + e);
+        l += w_l[g * P + q] * wgt;
+        o0 += v.x * wgt;
+        o1 += v.y * wgt;
+      }
+      emit(g, e, m, l, o0, o1);
+    }
+  } else {
+    // LDS too small for every group: the groups of a wave are combined with shuffles first
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float mw = m_run[g];
+#pragma unroll
+      for (int off = LPS; off < 64; off <<= 1) mw = fmaxf(mw, __shfl_xor(mw, off, 64));
+      const float rescale = m_run[g] == -INFINITY ? 0.f : __expf(m_run[g] - mw);
+      m_run[g] = mw;
+      l_run[g] *= rescale;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[g][e] *= rescale;
+#pragma unroll
+      for (int off = LPS; off < 64; off <<= 1) {
+        l_run[g] += __shfl_xor(l_run[g], off, 64);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[g][e] += __shfl_xor(acc[g][e], off, 64);
+      }
+    }
+    float* w_acc = dyn_f;                 // [NWV][G][HD]
+    float* w_m = dyn_f + NWV * G * HD;    // [NWV][G]
+    float* w_l = w_m + NWV * G;           // [NWV][G]
+    if (sub == 0) {
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) w_acc[(wave * G + g) * HD + e0 + e] = acc[g][e];
+    }
+    if (lane == 0) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        w_m[wave * G + g] = m_run[g];
+        w_l[wave * G + g] = l_run[g];
+      }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < G * HD / 2; idx += blockDim.x) {
+      const int g = idx / (HD / 2), e = (idx % (HD / 2)) * 2;
+      float m = w_m[g];
+      for (int w = 1; w < NWV; ++w) m = fmaxf(m, w_m[w * G + g]);
+      const float m_ref = m == -INFINITY ? 0.f : m;
+      float l = 0.f, o0 = 0.f, o1 = 0.f;
+      for (int w = 0; w < NWV; ++w) {
+        const float wgt = __expf(w_m[w * G + g] - m_ref);
+        l += w_l[w * G + g] * wgt;
+        o0 += w_acc[(w * G + g) * HD + e] * wgt;
+        o1 += w_acc[(w * G + g) * HD + e + 1] * wgt;
+      }
+      emit(g, e, m, l, o0, o1);
     }
   }
 }
@@ -1213,7 +1315,8 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, Cols c) {
   const int li = blockIdx.x / c.n, col = blockIdx.x % c.n, kvh = blockIdx.y, tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int n_slots = c.pos[col] + 1;
-  const int nch = (n_slots + a.CH - 1) / a.CH;
+  int nch, s0_unused, s1_unused;
+  chunk_range(a, n_slots, AttnGeom<T, HD>::WAVE_SLOTS, 0, nch, s0_unused, s1_unused);
   if (nch == 1) return;
   const int G = a.Hq / a.Hkv, HQ = a.Hq * HD;
   const size_t arow = (size_t)li * kMaxCols + col;
@@ -1393,8 +1496,13 @@ void launch_qkv(const Shape& s, const Buffers& b, const Cols& c, int layer0, int
 }
 
 template <typename T, int HD, bool TREE>
-static void launch_attn_g(int G, dim3 grid, int nwv, hipStream_t st, const AttnArgs& a, const Cols& c) {
-  const size_t lds = (size_t)(nwv * G * HD + 2 * nwv * G) * sizeof(float);
+static void launch_attn_g(int G, dim3 grid, int nwv, hipStream_t st, AttnArgs a, const Cols& c) {
+  // partial state of every slot group of the workgroup if that fits the default 64 KB of
+  // dynamic LDS, else of every wave
+  const int groups = nwv * AttnGeom<T, HD>::SPW;
+  a.direct = (size_t)groups * G * (HD + 2) * sizeof(float) <= 65536 ? 1 : 0;
+  const int sets = a.direct ? groups : nwv;
+  const size_t lds = (size_t)sets * G * (HD + 2) * sizeof(float);
   const dim3 blk(64 * nwv);
   switch (G) {
     case 1: hipLaunchKernelGGL((attn_kernel<T, HD, 1, TREE>), grid, blk, lds, st, a, c); break;
@@ -1441,27 +1549,79 @@ static void group_columns(const Cols& c, int G, ColGroups& cg) {
   }
 }
 
-bool attn_plan(const Shape& s, const Cols& c, int n_set, int* units, int* chunk_unit, int* units_per_workgroup) {
-  if (attn_use_mfma(s, c, n_set)) {
+AttnCut attn_cut(const Shape& s, const Cols& c, int n_set) {
+  AttnCut cut;
+  cut.mfma = attn_use_mfma(s, c, n_set);
+  cut.chunk = 0;
+  cut.nb_ref = 0;
+  int max_len = 1;
+  for (int i = 0; i < c.n; ++i) max_len = std::max(max_len, c.pos[i] + 1);
+  // Short contexts: one piece of work per (layer, column, KV head) walks the whole context, which
+  // saves the merge launch; two dependent launches cost more than the narrower launch loses.
+  static const int single_max = env_int("EASYSPEC_ATTN_SINGLE", 256);
+  if (cut.mfma) {
+    // one wave per (group of columns, sub-chunk, KV head), kMfmaAttnWaves of them per workgroup,
+    // walking its sub-chunk in super tiles of 64 slots: sub-chunks of a fixed length, grown until
+    // their count fits the partial buffers and the launch is not cut finer than two workgroups per CU
     ColGroups cg;
     group_columns(c, s.Hq / s.Hkv, cg);
-    *units = cg.n;       // one wave per group of columns, sub-chunk and KV head
-    *chunk_unit = 64;    // it walks its sub-chunk in super tiles of 64 slots
-    *units_per_workgroup = kMfmaAttnWaves;
-    return true;
+    const int unit = 64;
+    if (max_len <= single_max) {
+      cut.chunk = (max_len + unit - 1) / unit * unit;
+      cut.n_chunks = 1;
+      return cut;
+    }
+    static const long max_wg = env_int("EASYSPEC_ATTN_WG", 512);
+    int ch = unit;
+    auto nch = [&](int ch_) { return (max_len + ch_ - 1) / ch_; };
+    while (ch < 1024 && (nch(ch) > kMaxChunks || (long)nch(ch) * s.Hkv * n_set * cg.n > max_wg * kMfmaAttnWaves)) ch *= 2;
+    cut.chunk = ch;
+    cut.n_chunks = nch(ch);
+    return cut;
   }
+  // Vector kernel: one workgroup of four waves per (chunk, KV head, layer, column); a wave works in
+  // batches of `ws` slots.  Every column's batches are dealt evenly to its chunks (chunk_range).
+  // The chunk count of the longest column is the one that minimises the batches the busiest SIMD
+  // has to work through — (workgroups per CU, rounded up) x (batches of the busiest wave of a
+  // workgroup) — and among equals the smallest (fewer partials to merge).
   const int lps = s.hd * (s.dtype == 1 ? 2 : 4) / 16;
-  *units = c.n;
-  *chunk_unit = 4 * kAttnIT * (64 / lps);  // four waves side by side, one batch each
-  *units_per_workgroup = 1;
-  return false;
+  const int ws = kAttnIT * (64 / lps);
+  const int nb_max = (max_len + ws - 1) / ws;
+  cut.nb_ref = nb_max;
+  cut.n_chunks = 1;
+  if (max_len <= single_max) return cut;
+  const int forced = env_int("EASYSPEC_ATTN_NCH", 0);  // tests: a fixed count for the longest column, read at every call
+  static const int n_cu = [] {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+    return n;
+  }();
+  long best = -1;
+  for (int nch = forced > 0 ? forced : 2; nch <= std::min(kMaxChunks, nb_max); ++nch) {
+    long wgs = 0;
+    for (int i = 0; i < c.n; ++i) {
+      const int nb = (c.pos[i] + 1 + ws - 1) / ws;
+      wgs += std::max(1, std::min(nb, (nb * nch + nb_max / 2) / nb_max));
+    }
+    wgs *= (long)s.Hkv * n_set;
+    const long per_cu = (wgs + n_cu - 1) / n_cu;
+    const long per_wave = ((nb_max + nch - 1) / nch + 3) / 4;
+    const long score = per_cu * per_wave;
+    if (best < 0 || score < best) {
+      best = score;
+      cut.n_chunks = nch;
+    }
+    if (forced > 0) break;
+  }
+  return cut;
 }
 
-void launch_attn(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, int chunk, int n_chunks,
-                 bool mfma, hipStream_t st) {
+void launch_attn(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, const AttnCut& cut, hipStream_t st) {
+  const int n_chunks = cut.n_chunks;
   AttnArgs a;
   a.Q = b.Q; a.kc = b.kc; a.vc = b.vc; a.PO = b.PO; a.PM = b.PM; a.PL = b.PL; a.AO = b.AO;
-  a.layer0 = layer0; a.Hq = s.Hq; a.Hkv = s.Hkv; a.B = s.B; a.max_ctx = s.max_ctx; a.CH = chunk;
+  a.layer0 = layer0; a.Hq = s.Hq; a.Hkv = s.Hkv; a.B = s.B; a.max_ctx = s.max_ctx;
+  a.CH = cut.chunk; a.nch_ref = cut.n_chunks; a.nb_ref = cut.nb_ref;
   a.scale = 1.0f / sqrtf((float)s.hd);
   const int G = s.Hq / s.Hkv;
   const dim3 grid(n_chunks, s.Hkv, n_set * c.n);
@@ -1470,7 +1630,7 @@ void launch_attn(const Shape& s, const Buffers& b, const Cols& c, int layer0, in
   const int nwv = n_chunks == 1 ? 8 : 4;
   bool tree = false;  // any column that does not see every slot up to its own
   for (int i = 0; i < c.n; ++i) tree = tree || c.vis_base[i] <= c.pos[i];
-  if (mfma) {
+  if (cut.mfma) {
     ColGroups cg;
     group_columns(c, G, cg);
     const dim3 mg((n_chunks + kMfmaAttnWaves - 1) / kMfmaAttnWaves, s.Hkv, n_set * cg.n);
@@ -1650,3 +1810,4 @@ void launch_kv_copy(const Shape& s, const Buffers& b, int seq, void* k_user, voi
 }
 
 }  // namespace es
+

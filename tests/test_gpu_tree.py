@@ -37,7 +37,7 @@ def make_tree(seed, widths, vocab):
     return levels
 
 
-def tree_parity(oracle, gpu, cfg, seed, bounds, prompt_len, widths, max_ctx=None, kv_prefix=0):
+def tree_parity(oracle, gpu, cfg, seed, bounds, prompt_len, widths, max_ctx=None, kv_prefix=0, make_levels=make_tree):
     tol = TOL[cfg["dtype"]]
     w = synth.make_weights(cfg, seed)
     total = sum(widths)
@@ -56,7 +56,7 @@ def tree_parity(oracle, gpu, cfg, seed, bounds, prompt_len, widths, max_ctx=None
         g.prefill(0, prompt)
         P = so.precise
         for it in range(2):
-            levels = make_tree(seed + 10 * it, widths, cfg["vocab"])
+            levels = make_levels(seed + 10 * it, widths, cfg["vocab"])
             for toks, parents in levels:
                 wl, wh = so.fuzzy_tree_step(bounds, toks, parents, want_hidden=True)
                 gt, gl = g.draft_tree_step({0: (toks, parents)})
@@ -103,6 +103,24 @@ def test_tree_8b_shape_reduced_depth_long_context(oracle, gpu):
     """8B layer shape at 3 layers, 2048-slot synthetic prefix (split-KV attention with a merge), width 8."""
     cfg = synth.model_shape("llama3_8b", n_layers=3, vocab=4096)
     tree_parity(oracle, gpu, cfg, 530, [0, 1, 3], 5, [8, 8, 8], kv_prefix=2048)
+
+
+def test_tree_chunk_without_visible_slot(oracle, gpu, monkeypatch):
+    """Fresh roots added after two levels see none of the earlier nodes: with the tree region starting on
+    a batch boundary and one batch per split-KV chunk, the chunk that holds the first 32 nodes has no
+    visible slot for them (a partial with maximum -inf that the merge must weigh with 0)."""
+    monkeypatch.setenv("EASYSPEC_ATTN_MFMA", "0")
+    monkeypatch.setenv("EASYSPEC_ATTN_NCH", "64")
+
+    def levels_with_late_roots(seed, widths, vocab):
+        levels = make_tree(seed, widths, vocab)
+        toks, _ = levels[2]
+        levels[2] = (toks, [-1] * len(toks))
+        return levels
+
+    for dtype, prompt_len in (("fp32", 288), ("bf16", 320)):      # 32 / 64 slots per batch at head_dim 64
+        cfg = synth.model_shape("tiny", dtype=dtype)
+        tree_parity(oracle, gpu, cfg, 540, [0, 1, 3, 4], prompt_len, [16, 16, 16, 16], make_levels=levels_with_late_roots)
 
 
 def test_tree_two_sequences_ragged(oracle, gpu):
