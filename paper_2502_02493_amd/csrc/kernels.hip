@@ -823,9 +823,6 @@ __device__ __forceinline__ void chunk_range(const AttnArgs& a, int n_slots, int 
 }
 
 constexpr int kAttnIT = 8;  // loads in flight per operand per lane
-// whether the registers allow a second set of K/V fragments (next batch requested early)
-template <int G, bool TREE>
-constexpr bool kAttnPrefetch = G <= 2 || (G <= 4 && !TREE);
 
 // Sum over aligned groups of N lanes (8, 16 or 32), every lane of a group receiving the total,
 // with data-parallel-primitive operand swizzles (lane^1 and lane^2 inside quads, then the
@@ -895,11 +892,11 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
     l_run[g] = 0.f;
   }
 
-  // The K and V fragments of a batch: IT loads per operand, all issued before the first is used.
-  // Slots past the end of the chunk fetch the chunk's last row instead (their scores are
-  // discarded below), so the loads are unconditional and the wait counts exact: a wave asks
-  // for its next batch before it works on the current one and waits only for the older loads.
-  auto fetch = [&](u32x4 (&kr)[IT], u32x4 (&vr)[IT], int base) {
+  // A wave works in batches: IT loads per operand, all issued before the first is used.  Slots
+  // past the end of the chunk fetch the chunk's last row instead (their scores are discarded
+  // below): unconditional loads, no branch per load.
+  for (int base = s0 + wave * Geo::WAVE_SLOTS; base < s1; base += NWV * Geo::WAVE_SLOTS) {  // wave-uniform
+    u32x4 kr[IT], vr[IT];
 #pragma unroll
     for (int j = 0; j < IT; ++j) {
       const int s = min(base + j * SPW + sub, s1 - 1);
@@ -910,8 +907,6 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
       const int s = min(base + j * SPW + sub, s1 - 1);
       vr[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vb + ((uint32_t)s * ROW_BYTES + lane_byte)));
     }
-  };
-  auto work = [&](const u32x4 (&kr)[IT], const u32x4 (&vr)[IT], int base) {
     float sc[IT][G], m_use[G];
 #pragma unroll
     for (int j = 0; j < IT; ++j) {
@@ -957,31 +952,6 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc[g][e] += p * vv[e];
       }
-    }
-  };
-  const int stride = NWV * Geo::WAVE_SLOTS;
-  int base = s0 + wave * Geo::WAVE_SLOTS;  // wave-uniform, like the branches below
-  if constexpr (kAttnPrefetch<G, TREE>) {
-    // two register sets in turn; the last request of a wave is never used
-    u32x4 kr0[IT], vr0[IT], kr1[IT], vr1[IT];
-    if (base < s1) {
-      fetch(kr0, vr0, base);
-      for (;;) {
-        fetch(kr1, vr1, base + stride);
-        work(kr0, vr0, base);
-        base += stride;
-        if (base >= s1) break;
-        fetch(kr0, vr0, base + stride);
-        work(kr1, vr1, base);
-        base += stride;
-        if (base >= s1) break;
-      }
-    }
-  } else {
-    for (; base < s1; base += stride) {
-      u32x4 kr[IT], vr[IT];
-      fetch(kr, vr, base);
-      work(kr, vr, base);
     }
   }
 
