@@ -24,6 +24,7 @@
 #include "kernels.h"
 
 #include <algorithm>
+#include <type_traits>
 
 namespace es {
 
@@ -805,24 +806,24 @@ struct AttnArgs {
 
 // The split-KV cut of one column: its chunk count and the slot range [s0, s1) of chunk `chunk`
 // (empty for chunk >= nch).  Fixed-length cut: chunks of CH slots.  Even cut: the column's
-// batches (of `wave_slots` slots, what one wave fetches at a time) are dealt to
-// round(nb * nch_ref / nb_ref) chunks whose batch counts differ by at most one, so that a
-// context of a power-of-two length plus a few drafted tokens does not leave a sliver of a chunk.
-__device__ __forceinline__ void chunk_range(const AttnArgs& a, int n_slots, int wave_slots, int chunk, int& nch, int& s0,
-                                            int& s1) {
+// units (of `unit` slots, the smallest step of a wave) are dealt to round(nb * nch_ref / nb_ref)
+// chunks whose unit counts differ by at most one, so that a context of a power-of-two length
+// plus a few drafted tokens does not leave a sliver of a chunk.
+__device__ __forceinline__ void chunk_range(const AttnArgs& a, int n_slots, int unit, int chunk, int& nch, int& s0, int& s1) {
   if (a.nb_ref == 0) {
     nch = (n_slots + a.CH - 1) / a.CH;
     s0 = chunk * a.CH;
     s1 = min(s0 + a.CH, n_slots);
   } else {
-    const int nb = (n_slots + wave_slots - 1) / wave_slots;
+    const int nb = (n_slots + unit - 1) / unit;
     nch = max(1, min(nb, (nb * a.nch_ref + a.nb_ref / 2) / a.nb_ref));
-    s0 = (int)((long)chunk * nb / nch) * wave_slots;
-    s1 = min((int)((long)(chunk + 1) * nb / nch) * wave_slots, n_slots);
+    s0 = (int)((long)chunk * nb / nch) * unit;
+    s1 = min((int)((long)(chunk + 1) * nb / nch) * unit, n_slots);
   }
 }
 
-constexpr int kAttnIT = 8;  // loads in flight per operand per lane
+constexpr int kAttnIT = 8;       // loads in flight per operand per lane
+constexpr int kAttnSmallIT = 2;  // the same for the short steps that finish a wave's share
 
 // Sum over aligned groups of N lanes (8, 16 or 32), every lane of a group receiving the total,
 // with data-parallel-primitive operand swizzles (lane^1 and lane^2 inside quads, then the
@@ -847,6 +848,7 @@ template <typename T, int HD>
 struct AttnGeom {
   static constexpr int EPL = Tr<T>::EPL, LPS = HD / EPL, SPW = 64 / LPS;
   static constexpr int WAVE_SLOTS = kAttnIT * SPW;    // slots one wave covers per batch
+  static constexpr int UNIT = kAttnSmallIT * SPW;     // and per small step: the granularity of the split
   static constexpr int BLOCK_SLOTS = 4 * WAVE_SLOTS;  // chunk sizes are multiples of this (4-wave launches)
 };
 
@@ -866,7 +868,7 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
   const int vbase = c.vis_base[col];
   const unsigned long long vmask = c.vis_mask[col];
   int nch, s0, s1;
-  chunk_range(a, n_slots, Geo::WAVE_SLOTS, chunk, nch, s0, s1);
+  chunk_range(a, n_slots, Geo::UNIT, chunk, nch, s0, s1);
   if (chunk >= nch) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, NWV = blockDim.x >> 6;  // 4 or 8 waves
   const int sub = lane / LPS, e0 = (lane % LPS) * EPL;
@@ -892,26 +894,32 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
     l_run[g] = 0.f;
   }
 
-  // A wave works in batches: IT loads per operand, all issued before the first is used.  Slots
-  // past the end of the chunk fetch the chunk's last row instead (their scores are discarded
+  // The chunk's units are dealt evenly to the waves, each taking a contiguous run [w0, w1): full
+  // batches of IT loads per operand (all issued before the first is used) while more than two
+  // small steps' worth is left, then small steps, so that a wave's arithmetic follows its share
+  // of the slots.  Slots past w1 fetch the run's last row instead (their scores are discarded
   // below): unconditional loads, no branch per load.
-  for (int base = s0 + wave * Geo::WAVE_SLOTS; base < s1; base += NWV * Geo::WAVE_SLOTS) {  // wave-uniform
-    u32x4 kr[IT], vr[IT];
+  const int n_units = (s1 - s0 + Geo::UNIT - 1) / Geo::UNIT;
+  const int w0 = s0 + wave * n_units / NWV * Geo::UNIT;
+  const int w1 = min(s0 + (wave + 1) * n_units / NWV * Geo::UNIT, s1);
+  auto process = [&](auto n_loads, int base) {
+    constexpr int N = decltype(n_loads)::value;
+    u32x4 kr[N], vr[N];
 #pragma unroll
-    for (int j = 0; j < IT; ++j) {
-      const int s = min(base + j * SPW + sub, s1 - 1);
+    for (int j = 0; j < N; ++j) {
+      const int s = min(base + j * SPW + sub, w1 - 1);
       kr[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kb + ((uint32_t)s * ROW_BYTES + lane_byte)));
     }
 #pragma unroll
-    for (int j = 0; j < IT; ++j) {
-      const int s = min(base + j * SPW + sub, s1 - 1);
+    for (int j = 0; j < N; ++j) {
+      const int s = min(base + j * SPW + sub, w1 - 1);
       vr[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vb + ((uint32_t)s * ROW_BYTES + lane_byte)));
     }
-    float sc[IT][G], m_use[G];
+    float sc[N][G], m_use[G];
 #pragma unroll
-    for (int j = 0; j < IT; ++j) {
+    for (int j = 0; j < N; ++j) {
       const int s = base + j * SPW + sub;
-      const bool valid = s < s1 && (!TREE || s < vbase || ((vmask >> (s - vbase)) & 1ull));
+      const bool valid = s < w1 && (!TREE || s < vbase || ((vmask >> (s - vbase)) & 1ull));
       float kv[EPL];
       unpack<T>(kr[j], kv);
 #pragma unroll
@@ -927,7 +935,7 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
     for (int g = 0; g < G; ++g) {
       float bm = sc[0][g];
 #pragma unroll
-      for (int j = 1; j < IT; ++j) bm = fmaxf(bm, sc[j][g]);
+      for (int j = 1; j < N; ++j) bm = fmaxf(bm, sc[j][g]);
       // The running maximum belongs to the slot group (the LPS lanes that share slots), not to the
       // wave: no cross-lane traffic per batch; the groups are brought to a common reference once,
       // after the loop.  A group whose slots so far were all past the end or masked still has
@@ -942,7 +950,7 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
       for (int e = 0; e < EPL; ++e) acc[g][e] *= alpha;
     }
 #pragma unroll
-    for (int j = 0; j < IT; ++j) {
+    for (int j = 0; j < N; ++j) {
       float vv[EPL];
       unpack<T>(vr[j], vv);
 #pragma unroll
@@ -953,7 +961,10 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
         for (int e = 0; e < EPL; ++e) acc[g][e] += p * vv[e];
       }
     }
-  }
+  };
+  int base = w0;  // wave-uniform, like the loop conditions
+  for (; w1 - base > 2 * Geo::UNIT; base += Geo::WAVE_SLOTS) process(std::integral_constant<int, IT>{}, base);
+  for (; base < w1; base += Geo::UNIT) process(std::integral_constant<int, kAttnSmallIT>{}, base);
 
   // Combine the NWV * SPW slot groups of the workgroup (l_run counts each slot once per group,
   // every lane of a group holds the same value).  A group, or a whole chunk of a tree column,
@@ -1286,7 +1297,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, Cols c) {
   const int lane = tid & 63, wave = tid >> 6;
   const int n_slots = c.pos[col] + 1;
   int nch, s0_unused, s1_unused;
-  chunk_range(a, n_slots, AttnGeom<T, HD>::WAVE_SLOTS, 0, nch, s0_unused, s1_unused);
+  chunk_range(a, n_slots, AttnGeom<T, HD>::UNIT, 0, nch, s0_unused, s1_unused);
   if (nch == 1) return;
   const int G = a.Hq / a.Hkv, HQ = a.Hq * HD;
   const size_t arow = (size_t)li * kMaxCols + col;
@@ -1549,14 +1560,15 @@ AttnCut attn_cut(const Shape& s, const Cols& c, int n_set) {
     cut.n_chunks = nch(ch);
     return cut;
   }
-  // Vector kernel: one workgroup of four waves per (chunk, KV head, layer, column); a wave works in
-  // batches of `ws` slots.  Every column's batches are dealt evenly to its chunks (chunk_range).
-  // The chunk count of the longest column is the one that minimises the batches the busiest SIMD
-  // has to work through — (workgroups per CU, rounded up) x (batches of the busiest wave of a
-  // workgroup) — and among equals the smallest (fewer partials to merge).
+  // Vector kernel: one workgroup of four waves per (chunk, KV head, layer, column).  Every column's
+  // units (the slots of a wave's small step) are dealt evenly to its chunks (chunk_range) and a
+  // chunk's units evenly to its waves, which work through them in full batches of four units and
+  // up to two small steps.  The chunk count of the longest column is the one that minimises the
+  // arithmetic of the busiest SIMD — (workgroups per CU, rounded up) x (cost of the busiest wave
+  // of a workgroup) — and among equals the smallest (fewer partials to merge).
   const int lps = s.hd * (s.dtype == 1 ? 2 : 4) / 16;
-  const int ws = kAttnIT * (64 / lps);
-  const int nb_max = (max_len + ws - 1) / ws;
+  const int unit = kAttnSmallIT * (64 / lps);
+  const int nb_max = (max_len + unit - 1) / unit;
   cut.nb_ref = nb_max;
   cut.n_chunks = 1;
   if (max_len <= single_max) return cut;
@@ -1566,17 +1578,24 @@ AttnCut attn_cut(const Shape& s, const Cols& c, int n_set) {
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
     return n;
   }();
+  // cost of a wave with u units, in tenths of a full batch: a small step does a quarter of a
+  // batch's slots at about a third of its time
+  constexpr int per_batch = kAttnIT / kAttnSmallIT;
+  auto wave_cost = [](long u) {
+    const long full = u / per_batch, rest = u % per_batch;
+    return 10 * full + (rest == 0 ? 0 : rest <= 2 ? 3 * rest + 1 : 10);
+  };
   long best = -1;
-  for (int nch = forced > 0 ? forced : 2; nch <= std::min(kMaxChunks, nb_max); ++nch) {
+  for (int nch = forced > 0 ? std::min(forced, nb_max) : 2; nch <= std::min(kMaxChunks, nb_max); ++nch) {
     long wgs = 0;
     for (int i = 0; i < c.n; ++i) {
-      const int nb = (c.pos[i] + 1 + ws - 1) / ws;
+      const int nb = (c.pos[i] + 1 + unit - 1) / unit;
       wgs += std::max(1, std::min(nb, (nb * nch + nb_max / 2) / nb_max));
     }
     wgs *= (long)s.Hkv * n_set;
     const long per_cu = (wgs + n_cu - 1) / n_cu;
-    const long per_wave = ((nb_max + nch - 1) / nch + 3) / 4;
-    const long score = per_cu * per_wave;
+    const long per_wave = ((nb_max + nch - 1) / nch + 3) / 4;  // units of the busiest wave
+    const long score = per_cu * wave_cost(per_wave);
     if (best < 0 || score < best) {
       best = score;
       cut.n_chunks = nch;
@@ -1780,4 +1799,5 @@ void launch_kv_copy(const Shape& s, const Buffers& b, int seq, void* k_user, voi
 }
 
 }  // namespace es
+
 
