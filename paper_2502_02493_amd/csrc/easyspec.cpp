@@ -62,7 +62,7 @@ static int fail(easyspec_ctx* ctx, int code, const char* fmt, ...) {
   } while (0)
 
 static size_t esize(const Shape& s) { return s.dtype == EASYSPEC_DTYPE_BF16 ? 2 : 4; }
-static size_t packed_bytes(const Shape& s, int rows, int K) { return (size_t)((rows + 15) / 16) * 16 * (size_t)K * esize(s); }
+static size_t packed_bytes(const Shape& s, int rows, int K, int R = 16) { return es::packed_bytes(s.dtype, rows, K, R); }
 
 static int dev_alloc(easyspec_ctx* ctx, void** p, size_t bytes) {
   *p = nullptr;
@@ -119,6 +119,7 @@ extern "C" int easyspec_create(const easyspec_config* cfg, void* hip_stream, eas
   s.dtype = cfg->dtype; s.L = cfg->n_layers; s.d = cfg->d_model; s.Hq = cfg->n_q_heads; s.Hkv = cfg->n_kv_heads;
   s.hd = cfg->head_dim; s.F = cfg->d_ffn; s.V = cfg->vocab; s.HQ = s.Hq * s.hd; s.RQKV = (s.Hq + 2 * s.Hkv) * s.hd;
   s.B = cfg->max_batch; s.max_ctx = cfg->max_ctx; s.eps = cfg->rms_eps; s.has_bias = cfg->qkv_bias ? 1 : 0;
+  s.R_ffn = tile_rows(s.F);
   ctx->precise.assign(s.B, 0);
   ctx->fuzzy.assign(s.B, 0);
   ctx->tree.assign(s.B, easyspec_ctx::Tree());
@@ -132,8 +133,8 @@ extern "C" int easyspec_create(const easyspec_config* cfg, void* hip_stream, eas
     const size_t act_ = es_ * (s.dtype == EASYSPEC_DTYPE_BF16 ? 2 : 1);  // bf16 activations: hi and lo arrays
     ALLOC(ctx, b.wqkv, (size_t)s.L * packed_bytes(s, s.RQKV, s.d));
     ALLOC(ctx, b.wo, (size_t)s.L * packed_bytes(s, s.d, s.HQ));
-    ALLOC(ctx, b.wg, (size_t)s.L * packed_bytes(s, s.F, s.d));
-    ALLOC(ctx, b.wu, (size_t)s.L * packed_bytes(s, s.F, s.d));
+    ALLOC(ctx, b.wg, (size_t)s.L * packed_bytes(s, s.F, s.d, s.R_ffn));
+    ALLOC(ctx, b.wu, (size_t)s.L * packed_bytes(s, s.F, s.d, s.R_ffn));
     ALLOC(ctx, b.wd, (size_t)s.L * packed_bytes(s, s.d, s.F));
     ALLOC(ctx, b.wlm, packed_bytes(s, s.V, s.d));
     ALLOC(ctx, b.embed, (size_t)s.V * s.d * es_);
@@ -226,8 +227,8 @@ extern "C" int easyspec_load_weights(easyspec_ctx* ctx, const easyspec_weights* 
     auto put = [&](const void* src, size_t elems, size_t off_elems) -> hipError_t {
       return hipMemcpyAsync((char*)stage + off_elems * es_, src, elems * es_, hipMemcpyDefault, st);
     };
-    auto pack = [&](void* dst_base, size_t layer, int rows, int K) -> hipError_t {
-      launch_repack(s.dtype, stage, (char*)dst_base + layer * packed_bytes(s, rows, K), rows, K, st);
+    auto pack = [&](void* dst_base, size_t layer, int rows, int K, int R = 16) -> hipError_t {
+      launch_repack(s.dtype, stage, (char*)dst_base + layer * packed_bytes(s, rows, K, R), rows, K, R, st);
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
       return hipStreamSynchronize(st);  // staging is reused
@@ -241,9 +242,9 @@ extern "C" int easyspec_load_weights(easyspec_ctx* ctx, const easyspec_weights* 
       HIPCHK(ctx, put(lw.wo, (size_t)s.d * s.HQ, 0));
       HIPCHK(ctx, pack(b.wo, l, s.d, s.HQ));
       HIPCHK(ctx, put(lw.wg, (size_t)s.F * s.d, 0));
-      HIPCHK(ctx, pack(b.wg, l, s.F, s.d));
+      HIPCHK(ctx, pack(b.wg, l, s.F, s.d, s.R_ffn));
       HIPCHK(ctx, put(lw.wu, (size_t)s.F * s.d, 0));
-      HIPCHK(ctx, pack(b.wu, l, s.F, s.d));
+      HIPCHK(ctx, pack(b.wu, l, s.F, s.d, s.R_ffn));
       HIPCHK(ctx, put(lw.wd, (size_t)s.d * s.F, 0));
       HIPCHK(ctx, pack(b.wd, l, s.d, s.F));
       if (s.has_bias) {

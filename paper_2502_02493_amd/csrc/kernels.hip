@@ -195,12 +195,13 @@ __device__ __forceinline__ bool folded(int ncols) {
 
 template <typename T, int RT, int NB>
 __device__ __forceinline__ void gemm_loop(const u32x4* const (&w)[RT], const u32x4* const (&xp)[NB], int xs, bool colok,
-                                          int nkt, f32x4 (&acc)[RT]) {
+                                          int nkt, f32x4 (&acc)[RT], int w_lane, int w_stride) {
   constexpr int U = 8 / RT;  // k-tiles per batch: 8 KB of weights in flight per wave
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, NW = blockDim.x >> 6;
+  const int wave = threadIdx.x >> 6, NW = blockDim.x >> 6;
+  // w_lane: the lane's 16-byte piece of a weight fragment, w_stride: pieces per fragment (lane and 64 for tiles of 16 rows)
   const u32x4* wp[RT];
 #pragma unroll
-  for (int r = 0; r < RT; ++r) wp[r] = w[r] + lane;
+  for (int r = 0; r < RT; ++r) wp[r] = w[r] + w_lane;
   const u32x4 zero = {0u, 0u, 0u, 0u};
   int kt = wave;
   for (; kt + (U - 1) * NW < nkt; kt += U * NW) {
@@ -208,7 +209,7 @@ __device__ __forceinline__ void gemm_loop(const u32x4* const (&w)[RT], const u32
 #pragma unroll
     for (int u = 0; u < U; ++u) {
 #pragma unroll
-      for (int r = 0; r < RT; ++r) a[r][u] = __builtin_nontemporal_load(wp[r] + (size_t)(kt + u * NW) * 64);
+      for (int r = 0; r < RT; ++r) a[r][u] = __builtin_nontemporal_load(wp[r] + (size_t)(kt + u * NW) * w_stride);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -232,7 +233,7 @@ __device__ __forceinline__ void gemm_loop(const u32x4* const (&w)[RT], const u32
     for (int u = 0; u < U; ++u) {
       const bool in = kt + u * NW < nkt;
 #pragma unroll
-      for (int r = 0; r < RT; ++r) a[r][u] = in ? __builtin_nontemporal_load(wp[r] + (size_t)(kt + u * NW) * 64) : zero;
+      for (int r = 0; r < RT; ++r) a[r][u] = in ? __builtin_nontemporal_load(wp[r] + (size_t)(kt + u * NW) * w_stride) : zero;
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -256,12 +257,13 @@ __device__ __forceinline__ void gemm_loop(const u32x4* const (&w)[RT], const u32
 // free of the second path's registers.
 template <typename T, int RT, int NB>
 __device__ __forceinline__ void gemm_accumulate(const u32x4* const (&w)[RT], const T* __restrict__ x, int K, int ncols,
-                                                f32x4 (&acc)[RT]) {
+                                                f32x4 (&acc)[RT], int w_lane = -1, int w_stride = 64) {
   constexpr int EPL = Tr<T>::EPL, KT = Tr<T>::KT, PARTS = Tr<T>::PARTS;
   const int lane = threadIdx.x & 63;
   const int col = lane & 15, kg = lane >> 4;
   const int nkt = K / KT;
   const size_t part = (size_t)kMaxCols * K;  // elements between the hi and lo arrays
+  if (w_lane < 0) w_lane = lane;  // full tiles: fragment piece i belongs to lane i
   if (NB == 1) {
     // lane column c < ncols reads the hi term of column c, column ncols + c its lo term
     const bool is_lo = PARTS == 2 && col >= ncols;
@@ -269,12 +271,12 @@ __device__ __forceinline__ void gemm_accumulate(const u32x4* const (&w)[RT], con
     const bool colok = src < ncols;
     const u32x4* const xp[1] = {
         reinterpret_cast<const u32x4*>(x + (is_lo ? part : 0) + xoff<T>(ncols, K, colok ? src : 0, kg * EPL))};
-    gemm_loop<T, RT, 1>(w, xp, xtile_stride<T>(ncols), colok, nkt, acc);
+    gemm_loop<T, RT, 1>(w, xp, xtile_stride<T>(ncols), colok, nkt, acc, w_lane, w_stride);
   } else {
     const bool colok = col < ncols;
     const T* base = x + xoff<T>(ncols, K, colok ? col : 0, kg * EPL);
     const u32x4* const xp[2] = {reinterpret_cast<const u32x4*>(base), reinterpret_cast<const u32x4*>(base + part)};
-    gemm_loop<T, RT, 2>(w, xp, xtile_stride<T>(ncols), colok, nkt, acc);
+    gemm_loop<T, RT, 2>(w, xp, xtile_stride<T>(ncols), colok, nkt, acc, w_lane, w_stride);
   }
 }
 
@@ -606,6 +608,7 @@ struct GateUpArgs {
   const float* ssp;  // [k][16][d/16]
   void* act;  // k operand slots of 16 x F in T
   int d, F;
+  int R;      // rows per weight tile (tile_rows() of F), ntile = ceil(F / R) workgroups per layer
   float inv_d, eps;
 };
 
@@ -613,15 +616,18 @@ template <typename T, int NB>
 __global__ __launch_bounds__(1024) void gateup_kernel(GateUpArgs a, Cols c) {
   __shared__ float s_rstd[kMaxCols];
   const int nkt = a.d / Tr<T>::KT;
-  const int ntile = a.F / 16;
+  const int R = a.R, ntile = (a.F + R - 1) / R;
   const int li = blockIdx.x / ntile, t = blockIdx.x % ntile;
-  const size_t wl = (size_t)li * a.w_layer_stride + (size_t)t * nkt * 64;
+  const size_t wl = (size_t)li * a.w_layer_stride + (size_t)t * nkt * (4 * R);
   const u32x4* const w[2] = {a.wg + wl, a.wu + wl};
   const float* ssp = a.ssp + (size_t)li * kMaxCols * (a.d / 16);
   RstdPre pre;
   rstd_issue(ssp, a.d / 16, c.n, pre);
   f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-  gemm_accumulate<T, 2, NB>(w, reinterpret_cast<const T*>(a.x) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.d, a.d, c.n, acc);
+  // a tile of R < 16 rows: the lanes of the missing rows re-read the last row (their results are dropped)
+  const int m = threadIdx.x & 15, kg = (threadIdx.x & 63) >> 4;
+  gemm_accumulate<T, 2, NB>(w, reinterpret_cast<const T*>(a.x) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.d, a.d, c.n, acc,
+                            kg * R + min(m, R - 1), 4 * R);
   rstd_finish(ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
   if (!reduce_waves<2>(acc, dyn_red)) return;
   fold_columns<T, 2>(acc, c.n);
@@ -634,8 +640,17 @@ __global__ __launch_bounds__(1024) void gateup_kernel(GateUpArgs a, Cols c) {
     const float g = acc[0][i] * r, u = acc[1][i] * r;
     o[i] = (g / (1.0f + expf(-g))) * u;
   }
-  T* dst = reinterpret_cast<T*>(a.act) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.F + xoff<T>(c.n, a.F, col, t * 16 + (lane >> 4) * 4);
-  store_act4<T>(dst, (size_t)kMaxCols * a.F, o[0], o[1], o[2], o[3]);
+  T* dst = reinterpret_cast<T*>(a.act) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.F;
+  const int row0 = (lane >> 4) * 4;  // of the tile
+  if (R == 16) {
+    store_act4<T>(dst + xoff<T>(c.n, a.F, col, t * 16 + row0), (size_t)kMaxCols * a.F, o[0], o[1], o[2], o[3]);
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int f = t * R + row0 + i;
+      if (row0 + i < R && f < a.F) store_act1<T>(dst + xoff<T>(c.n, a.F, col, f), (size_t)kMaxCols * a.F, o[i]);
+    }
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1356,20 +1371,22 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, Cols c) {
 // Small utilities.
 // ------------------------------------------------------------------------------------------
 
-// Row-major [rows][K] -> 1 KB tiles; rows padded with zeros up to a multiple of 16.
+// Row-major [rows][K] -> tiles of R <= 16 rows, per k-tile a fragment of [k-group 4][R rows] 16-byte
+// pieces (1 KB for R = 16: piece i is lane i's share of an MFMA A operand); rows padded with zeros
+// up to a multiple of R.
 template <typename T>
-__global__ void repack_kernel(const T* __restrict__ src, u32x4* __restrict__ dst, int rows, int K, size_t n_frag) {
+__global__ void repack_kernel(const T* __restrict__ src, u32x4* __restrict__ dst, int rows, int K, int R, size_t n_frag) {
   constexpr int EPL = Tr<T>::EPL, KT = Tr<T>::KT;
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n_frag) return;
   const int nkt = K / KT;
-  const int lane = (int)(i & 63);
-  const size_t tile = i >> 6;
+  const int piece = (int)(i % (4 * R));
+  const size_t tile = i / (4 * R);
   const int kt = (int)(tile % nkt);
   const size_t rt = tile / nkt;
-  const size_t row = rt * 16 + (lane & 15);
+  const size_t row = rt * R + piece % R;
   u32x4 v = {0u, 0u, 0u, 0u};
-  if (row < (size_t)rows) v = *reinterpret_cast<const u32x4*>(src + row * K + (size_t)kt * KT + (lane >> 4) * EPL);
+  if (row < (size_t)rows) v = *reinterpret_cast<const u32x4*>(src + row * K + (size_t)kt * KT + (piece / R) * EPL);
   dst[i] = v;
 }
 
@@ -1437,15 +1454,41 @@ static bool two_fragments(int dtype, const Cols& c) { return dtype == 1 && 2 * c
     else { typedef float T; __VA_ARGS__; }        \
   } while (0)
 
-static size_t tile_stride(int rows, int K, int dtype) {  // u32x4 per matrix
+static size_t tile_stride(int rows, int K, int dtype, int R = 16) {  // u32x4 per matrix
   const int kt = dtype == 1 ? 32 : 16;
-  return (size_t)((rows + 15) / 16) * (K / kt) * 64;
+  return (size_t)((rows + R - 1) / R) * (K / kt) * (4 * R);
 }
 
-void launch_repack(int dtype, const void* src, void* dst, int rows, int K, hipStream_t st) {
-  const size_t n_frag = tile_stride(rows, K, dtype);
+size_t packed_bytes(int dtype, int rows, int K, int R) { return tile_stride(rows, K, dtype, R) * sizeof(u32x4); }
+
+// Rows per weight tile of a matrix whose launch is one workgroup per row tile.  The hardware hands
+// workgroups to CUs as they free up, so a launch costs as many rounds as its busiest CU gets
+// workgroups: 896 tiles of 16 rows on 256 CUs cost 4 rounds for 3.5 rounds of work.  A slightly
+// lower tile (the MFMA's spare rows idle) can make the count a multiple of the CU count: 1024
+// tiles of 14 rows.  More workgroups also cost more prologues and activation reads, so the tile
+// is lowered only for a gain in balance of more than a tenth (measured: 14 rows at F = 14336
+// take 1.5 us off a 37 us launch; 15 rows at F = 18944, balance 0.925 -> 0.987, gain nothing).
+int tile_rows(int rows) {
+  const int forced = env_int("EASYSPEC_TILE_ROWS", 0);  // tests: read at every create
+  if (forced >= 8 && forced <= 16) return forced;
+  int dev = 0, n_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
+    n_cu = 256;
+  if ((rows + 15) / 16 <= n_cu) return 16;  // less than one round anyway
+  auto balance = [&](int R) {
+    const int tiles = (rows + R - 1) / R;
+    return (double)tiles / ((double)n_cu * ((tiles + n_cu - 1) / n_cu));
+  };
+  int best = 16;
+  for (int R = 15; R >= 12; --R)
+    if (balance(R) > balance(16) + 0.10 && balance(R) > balance(best)) best = R;
+  return best;
+}
+
+void launch_repack(int dtype, const void* src, void* dst, int rows, int K, int R, hipStream_t st) {
+  const size_t n_frag = tile_stride(rows, K, dtype, R);
   const unsigned grid = (unsigned)((n_frag + 255) / 256);
-  DISPATCH_T(dtype, hipLaunchKernelGGL(repack_kernel<T>, dim3(grid), dim3(256), 0, st, (const T*)src, (u32x4*)dst, rows, K, n_frag));
+  DISPATCH_T(dtype, hipLaunchKernelGGL(repack_kernel<T>, dim3(grid), dim3(256), 0, st, (const T*)src, (u32x4*)dst, rows, K, R, n_frag));
 }
 
 void launch_embed(const Shape& s, const Buffers& b, const Cols& c, const int32_t* tokens, int layer0, int n_set,
@@ -1666,13 +1709,13 @@ void launch_oproj(const Shape& s, const Buffers& b, const Cols& c, int layer0, i
 
 void launch_gateup(const Shape& s, const Buffers& b, const Cols& c, int layer, int n_layers, const float* ssp, hipStream_t st) {
   GateUpArgs a;
-  const size_t stride = tile_stride(s.F, s.d, s.dtype);
+  const size_t stride = tile_stride(s.F, s.d, s.dtype, s.R_ffn);
   a.wg = (const u32x4*)b.wg + (size_t)layer * stride;
   a.wu = (const u32x4*)b.wu + (size_t)layer * stride;
   a.w_layer_stride = stride;
-  a.x = b.XM; a.ssp = ssp; a.act = b.ACT; a.d = s.d; a.F = s.F;
+  a.x = b.XM; a.ssp = ssp; a.act = b.ACT; a.d = s.d; a.F = s.F; a.R = s.R_ffn;
   a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
-  const int grid = n_layers * (s.F / 16);
+  const int grid = n_layers * ((s.F + s.R_ffn - 1) / s.R_ffn);
   const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
   const int nw = pick_waves(8, nkt, "EASYSPEC_NW_GU");
   DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),

@@ -93,6 +93,17 @@ def test_llama3_8b_layer_shape_reduced_depth(oracle, gpu):
     one_iteration(oracle, gpu, cfg, 500, b, 256, 5, accept=3)
 
 
+@pytest.mark.parametrize("rows", [13, 15])
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_gate_up_weight_tiles_of_fewer_rows(oracle, gpu, monkeypatch, rows, dtype):
+    """The gate and up matrices packed in tiles of 13 / 15 rows instead of 16 (what the library picks
+    by itself when that evens out the workgroups per CU: 14 rows at the 8B width, 15 at Qwen2-7B's):
+    1024 rows leave a ragged last tile either way."""
+    monkeypatch.setenv("EASYSPEC_TILE_ROWS", str(rows))
+    cfg = synth.model_shape("tiny", dtype=dtype)
+    one_iteration(oracle, gpu, cfg, 560 + rows, [0, 1, 3, 4], 40, 4, accept=2)
+
+
 @pytest.mark.parametrize("N", [2, 4, 7])
 def test_qwen2_7b_layer_shape_reduced_depth(oracle, gpu, N):
     """Qwen2-7B layer shape (7 query heads per KV head, QKV bias), 9 layers, group sizes 2/4/7,
