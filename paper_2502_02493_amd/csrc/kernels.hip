@@ -897,6 +897,10 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
   const int HQ = a.Hq * HD;
 
   float q[G][EPL], acc[G][EPL], m_run[G], l_run[G];
+  // one head per lane (see the batch code): running maximum and sum of that head only
+  constexpr bool kHeadPerLane = G == 4 && LPS == 16;
+  float m1 = -INFINITY, l1 = 0.f;
+  const bool odd1 = lane & 1, odd2 = lane & 2;
 #pragma unroll
   for (int g = 0; g < G; ++g) {
     const float* qp = a.Q + ((size_t)li * kMaxCols + col) * HQ + (kvh * G + g) * HD + e0;
@@ -929,6 +933,61 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
     for (int j = 0; j < N; ++j) {
       const int s = min(base + j * SPW + sub, w1 - 1);
       vr[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vb + ((uint32_t)s * ROW_BYTES + lane_byte)));
+    }
+    if constexpr (kHeadPerLane) {
+      // Four query heads over a 16-lane row: instead of four row-wide sums per slot, the lanes
+      // trade partial dot products pairwise so that lane l ends up with the row's total for head
+      // 2 (l & 1) + ((l >> 1) & 1) alone; the softmax arithmetic is then done once per lane
+      // (one head) and the probability of head g comes back to the row's other lanes as a
+      // quad broadcast on its way into the P.V products.
+      float sc1[N];
+#pragma unroll
+      for (int j = 0; j < N; ++j) {
+        const int s = base + j * SPW + sub;
+        const bool valid = s < w1 && (!TREE || s < vbase || ((vmask >> (s - vbase)) & 1ull));
+        float kv[EPL];
+        unpack<T>(kr[j], kv);
+        float d[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          d[g] = 0.f;
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) d[g] += q[g][e] * kv[e];
+        }
+        const float t0 = (odd1 ? d[2] : d[0]) + dpp_f32<0xB1>(odd1 ? d[0] : d[2]);  // lane ^ 1
+        const float t1 = (odd1 ? d[3] : d[1]) + dpp_f32<0xB1>(odd1 ? d[1] : d[3]);
+        float v = (odd2 ? t1 : t0) + dpp_f32<0x4E>(odd2 ? t0 : t1);                  // lane ^ 2
+        v += dpp_f32<0x124>(v);  // row_ror:4
+        v += dpp_f32<0x128>(v);  // row_ror:8
+        sc1[j] = valid ? v * a.scale : -INFINITY;
+      }
+      float bm = sc1[0];
+#pragma unroll
+      for (int j = 1; j < N; ++j) bm = fmaxf(bm, sc1[j]);
+      const float m_new = fmaxf(m1, bm);
+      const float m_ref = m_new == -INFINITY ? 0.f : m_new;  // see the general path below
+      const float alpha = __expf(m1 - m_ref);
+      m1 = m_new;
+      l1 *= alpha;
+      const float al[4] = {dpp_f32<0x00>(alpha), dpp_f32<0xAA>(alpha), dpp_f32<0x55>(alpha), dpp_f32<0xFF>(alpha)};
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[g][e] *= al[g];
+#pragma unroll
+      for (int j = 0; j < N; ++j) {
+        float vv[EPL];
+        unpack<T>(vr[j], vv);
+        const float p = __expf(sc1[j] - m_ref);  // 0 for slots past the end or masked
+        l1 += p;
+        // head g sits in quad lane 0, 2, 1, 3 for g = 0 .. 3
+        const float pg[4] = {dpp_f32<0x00>(p), dpp_f32<0xAA>(p), dpp_f32<0x55>(p), dpp_f32<0xFF>(p)};
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) acc[g][e] += pg[g] * vv[e];
+      }
+      return;
     }
     float sc[N][G], m_use[G];
 #pragma unroll
@@ -980,6 +1039,16 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
   int base = w0;  // wave-uniform, like the loop conditions
   for (; w1 - base > 2 * Geo::UNIT; base += Geo::WAVE_SLOTS) process(std::integral_constant<int, IT>{}, base);
   for (; base < w1; base += Geo::UNIT) process(std::integral_constant<int, kAttnSmallIT>{}, base);
+
+  if constexpr (kHeadPerLane) {  // back to every lane holding all four heads' maximum and sum
+    const float mm[4] = {dpp_f32<0x00>(m1), dpp_f32<0xAA>(m1), dpp_f32<0x55>(m1), dpp_f32<0xFF>(m1)};
+    const float ll[4] = {dpp_f32<0x00>(l1), dpp_f32<0xAA>(l1), dpp_f32<0x55>(l1), dpp_f32<0xFF>(l1)};
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      m_run[g] = mm[g & 3];
+      l_run[g] = ll[g & 3];
+    }
+  }
 
   // Combine the NWV * SPW slot groups of the workgroup (l_run counts each slot once per group,
   // every lane of a group holds the same value).  A group, or a whole chunk of a tree column,
