@@ -188,10 +188,10 @@ def test_batch4_ragged_long_contexts(oracle, gpu):
         g.close()
 
 
-def full_size_sampled(oracle, gpu, shape, ctx_len, N, want_bounds=None, tree_width=0):
-    """A benchmark configuration itself (full depth, aligned sets, gamma 5, 6-token calibration): one
-    calibration and two fuzzy steps checked against the oracle; optionally one tree level of the
-    given width on top (the calibration is redone first, so the chain's fuzzy slots are gone)."""
+def full_size_sampled(oracle, gpu, shape, ctx_len, N, want_bounds=None, tree_width=0, calib_tokens=6):
+    """A benchmark configuration itself (full depth, aligned sets): one calibration of `calib_tokens`
+    tokens and two fuzzy steps checked against the oracle; optionally one tree level of the given
+    width on top (the calibration is redone first, so the chain's fuzzy slots are gone)."""
     import paper_2502_02493_amd as es
     cfg = synth.model_shape(shape)
     print(f"drawing {shape} weights ...", flush=True)
@@ -206,7 +206,7 @@ def full_size_sampled(oracle, gpu, shape, ctx_len, N, want_bounds=None, tree_wid
         g.set_groups(bounds)
         k, v = synth.make_kv_prefix(cfg, 2026, ctx_len)
         so.import_kv(k, v); g.import_kv(0, k, v)
-        calib = [int(t) for t in synth.make_tokens(2027, 6, cfg["vocab"])]
+        calib = [int(t) for t in synth.make_tokens(2027, calib_tokens, cfg["vocab"])]
         print("oracle calibration ...", flush=True)
         wl = so.calibrate(calib, all_rows=False)
         gt, gl = g.calibrate({0: calib}, all_rows=False)
@@ -237,8 +237,16 @@ def full_size_sampled(oracle, gpu, shape, ctx_len, N, want_bounds=None, tree_wid
 
 
 def test_full_size_llama3_8b_sampled(oracle, gpu):
-    """32 layers, context 2048, sets of 4; then a tree level of width 4 (matrix-core attention at full size)."""
-    full_size_sampled(oracle, gpu, "llama3_8b", 2048, 4, [0, 1, 4, 8, 12, 16, 20, 24, 28, 31, 32], tree_width=4)
+    """32 layers, context 2048, sets of 4, 6-token calibration; then a tree level of width 8 (matrix-core
+    attention at full size)."""
+    full_size_sampled(oracle, gpu, "llama3_8b", 2048, 4, [0, 1, 4, 8, 12, 16, 20, 24, 28, 31, 32], tree_width=8)
+
+
+def test_full_size_llama3_8b_long_calibration_sampled(oracle, gpu):
+    """The calibration-dominant configuration: 32 layers, context 8192, a 9-token calibration (more than 8
+    columns: two activation fragments per weight tile, matrix-core attention over 9 columns), then fuzzy
+    steps and a 4-wide tree level (the vector kernel with the tree mask at full size)."""
+    full_size_sampled(oracle, gpu, "llama3_8b", 8192, 4, tree_width=4, calib_tokens=9)
 
 
 def test_full_size_qwen2_7b_sampled(oracle, gpu):
