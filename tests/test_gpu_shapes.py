@@ -188,6 +188,43 @@ def test_batch4_ragged_long_contexts(oracle, gpu):
         g.close()
 
 
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_batch16_ragged_contexts(oracle, gpu, dtype):
+    """Sixteen sequences whose contexts run from 1 slot to several split-KV chunks in one launch: every
+    column gets its own number of chunks (one for the short ones) and its own ragged last batch."""
+    cfg = synth.model_shape("tiny", dtype=dtype)
+    w = synth.make_weights(cfg, 570)
+    rng = np.random.Generator(np.random.Philox(key=[571, 0]))
+    ctxs = [1, 2, 31, 33, 63, 64, 65, 255, 256, 257] + [int(x) for x in rng.integers(258, 1500, 6)]
+    max_ctx = 1536
+    model = oracle.Model(cfg, w, max_ctx)
+    seqs = [oracle.Sequence(model) for _ in ctxs]
+    g = gpu.GpuDrafter(cfg, w, max_batch=16, max_ctx=max_ctx, max_calib=4)
+    bounds = np.array([0, 1, 3, 4], np.int32)
+    try:
+        g.set_groups(bounds)
+        for b, n in enumerate(ctxs):
+            k, v = synth.make_kv_prefix(cfg, 572, n, seq=b)
+            seqs[b].import_kv(k, v); g.import_kv(b, k, v)
+        toks = synth.make_tokens(573, 16 * 8, cfg["vocab"]).reshape(16, 8)
+        for step in range(3):
+            feed = {b: int(toks[b, step]) for b in range(16)}
+            gt, gl = g.draft_step(feed)
+            for b in range(16):
+                wl = seqs[b].fuzzy_step(bounds, feed[b])
+                assert gpu.rel_l2(gl[b], wl) < TOL[dtype], f"fuzzy logits, sequence {b} (context {ctxs[b]}), step {step}"
+        # calibration of a few of them (4 + 4 + 4 + 4 columns), the others keep their fuzzy slots
+        calib = {b: [int(t) for t in toks[b, 4:8]] for b in (0, 5, 9, 15)}
+        gt, gl = g.calibrate(calib, all_rows=True)
+        for b, t in calib.items():
+            wl = seqs[b].calibrate(t, all_rows=True)
+            assert gpu.rel_l2(gl[b], wl) < TOL[dtype], f"calibration logits, sequence {b}"
+        p, f = g.lens()
+        assert [int(x) for x in p] == [s.precise for s in seqs] and [int(x) for x in f] == [s.fuzzy for s in seqs]
+    finally:
+        g.close()
+
+
 def full_size_sampled(oracle, gpu, shape, ctx_len, N, want_bounds=None, tree_width=0, calib_tokens=6):
     """A benchmark configuration itself (full depth, aligned sets): one calibration of `calib_tokens`
     tokens and two fuzzy steps checked against the oracle; optionally one tree level of the given
