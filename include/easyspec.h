@@ -244,6 +244,19 @@ int64_t easyspec_step_bytes(const easyspec_ctx *ctx);
 int easyspec_stream_read(const void *buf, int64_t bytes, float *sink, void *hip_stream);
 int32_t easyspec_stream_read_sink_floats(void);
 
+/* How a decode-attention launch over n_layers_in_set layers would cut the contexts of n_cols
+ * columns among workgroups and waves (the split-KV cut of the vector-ALU attention kernel): host
+ * arithmetic only, evaluated with the kernels' own index functions, no device needed.  For tests
+ * of that arithmetic (every slot of every column must fall to exactly one wave) and for tuning.
+ *   ctx_lens  host [n_cols]  slots column i attends to (1 .. max_ctx), n_cols 1 .. 16
+ *   n_chunks  host [n_cols]  receives the chunks of column i (1 .. EASYSPEC_MAX_CHUNKS)
+ *   ranges    host [n_cols][EASYSPEC_MAX_CHUNKS][8][2] or NULL: receives the slots [from, to) of
+ *             wave w of chunk c of column i; (0, 0) beyond the column's chunks or the launch's waves
+ * Returns the waves per workgroup of the launch (4 or 8), or a negative error code. */
+#define EASYSPEC_MAX_CHUNKS 64
+int easyspec_attention_cut(const easyspec_config *cfg, const int32_t *ctx_lens, int32_t n_cols, int32_t n_layers_in_set,
+                           int32_t *n_chunks, int32_t *ranges);
+
 /* Per-kernel timing for roofline reports.  Between profile_begin and profile_end every launch
  * of the kernel class `op` made by draft steps and calibrations is bracketed by a pair of HIP
  * events on the context's stream (at most max_launches pairs; later launches run untimed).

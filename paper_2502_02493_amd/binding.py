@@ -16,11 +16,12 @@ EASYSPEC_DTYPE_F32, EASYSPEC_DTYPE_BF16 = 0, 1
 EASYSPEC_POLICY_ALIGNED, EASYSPEC_POLICY_PACKED = 0, 1
 EASYSPEC_MAX_BATCH, EASYSPEC_MAX_CALIB_TOKENS, EASYSPEC_MAX_SET = 16, 16, 8
 EASYSPEC_MAX_TREE_WIDTH, EASYSPEC_MAX_TREE_NODES = 16, 64
+EASYSPEC_MAX_CHUNKS = 64
 EASYSPEC_PARALLEL_ATTENTION, EASYSPEC_PARALLEL_FULL_LAYER = 0, 1
 
 EXPORTS = ["easyspec_create", "easyspec_destroy", "easyspec_load_weights", "easyspec_set_groups",
            "easyspec_default_groups", "easyspec_draft_step", "easyspec_calibrate", "easyspec_greedy_accept",
-           "easyspec_accept", "easyspec_accept_workspace_bytes", "easyspec_draft_tree_step", "easyspec_set_parallel_mode", "easyspec_stream_read", "easyspec_stream_read_sink_floats",
+           "easyspec_accept", "easyspec_accept_workspace_bytes", "easyspec_draft_tree_step", "easyspec_set_parallel_mode", "easyspec_stream_read", "easyspec_stream_read_sink_floats", "easyspec_attention_cut",
            "easyspec_get_lens", "easyspec_truncate", "easyspec_kv_import", "easyspec_kv_export",
            "easyspec_get_hidden", "easyspec_step_bytes", "easyspec_profile_begin", "easyspec_profile_end",
            "easyspec_last_error"]
@@ -82,6 +83,7 @@ def load_library():
         L.easyspec_step_bytes.argtypes = [vp]
         L.easyspec_stream_read.argtypes = [vp, C.c_int64, vp, vp]
         L.easyspec_stream_read_sink_floats.argtypes = []
+        L.easyspec_attention_cut.argtypes = [C.POINTER(easyspec_config), vp, i32, i32, vp, vp]
         L.easyspec_step_bytes.restype = C.c_int64
         L.easyspec_profile_begin.argtypes = [vp, i32, i32]
         L.easyspec_profile_end.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_float)]
@@ -204,6 +206,18 @@ def easyspec_stream_read(buf, nbytes: int, sink, hip_stream=None):
 
 def easyspec_stream_read_sink_floats() -> int:
     return int(load_library().easyspec_stream_read_sink_floats())
+
+
+def easyspec_attention_cut(cfg: easyspec_config, ctx_lens, n_layers_in_set: int, with_ranges=True):
+    """(waves per workgroup, n_chunks[n_cols], ranges[n_cols][EASYSPEC_MAX_CHUNKS][8][2] or None)."""
+    lens = np.ascontiguousarray(ctx_lens, dtype=np.int32)
+    n_chunks = np.zeros(len(lens), np.int32)
+    ranges = np.zeros((len(lens), EASYSPEC_MAX_CHUNKS, 8, 2), np.int32) if with_ranges else None
+    rc = load_library().easyspec_attention_cut(C.byref(cfg), _ptr(lens), len(lens), int(n_layers_in_set), _ptr(n_chunks),
+                                               _ptr(ranges))
+    if rc < 0:
+        _check(rc, None)
+    return rc, n_chunks, ranges
 
 
 def easyspec_get_lens(ctx, max_batch: int):

@@ -671,6 +671,46 @@ extern "C" int easyspec_stream_read(const void* buf, int64_t bytes, float* sink,
 
 extern "C" int32_t easyspec_stream_read_sink_floats(void) { return stream_read_sink_floats(); }
 
+static_assert(EASYSPEC_MAX_CHUNKS == kMaxChunks, "header and kernels disagree on the chunk limit");
+
+extern "C" int easyspec_attention_cut(const easyspec_config* cfg, const int32_t* ctx_lens, int32_t n_cols, int32_t n_layers_in_set,
+                                      int32_t* n_chunks, int32_t* ranges) {
+  int rc = check_config(cfg);
+  if (rc != EASYSPEC_OK) return rc;
+  if (!ctx_lens || !n_chunks) return fail(nullptr, EASYSPEC_EINVAL, "attention_cut: NULL argument");
+  if (n_cols < 1 || n_cols > kMaxCols) return fail(nullptr, EASYSPEC_EINVAL, "attention_cut: n_cols must be 1..%d", kMaxCols);
+  if (n_layers_in_set < 1 || n_layers_in_set > EASYSPEC_MAX_SET)
+    return fail(nullptr, EASYSPEC_EINVAL, "attention_cut: n_layers_in_set must be 1..%d", EASYSPEC_MAX_SET);
+  Shape s;
+  memset(&s, 0, sizeof s);
+  s.dtype = cfg->dtype; s.Hq = cfg->n_q_heads; s.Hkv = cfg->n_kv_heads; s.hd = cfg->head_dim; s.max_ctx = cfg->max_ctx;
+  Cols c;
+  memset(&c, 0, sizeof c);
+  c.n = n_cols;
+  for (int i = 0; i < n_cols; ++i) {
+    if (ctx_lens[i] < 1 || ctx_lens[i] > cfg->max_ctx)
+      return fail(nullptr, EASYSPEC_EINVAL, "attention_cut: ctx_lens[%d] = %d outside 1..%d", i, ctx_lens[i], cfg->max_ctx);
+    c.pos[i] = ctx_lens[i] - 1;
+  }
+  const AttnCut cut = attn_cut_vector(s, c, n_layers_in_set);
+  const int nwv = attn_waves(cut);
+  if (ranges) memset(ranges, 0, sizeof(int32_t) * (size_t)n_cols * EASYSPEC_MAX_CHUNKS * 8 * 2);
+  for (int i = 0; i < n_cols; ++i) {
+    int nch = 0, w0 = 0, w1 = 0;
+    attn_ranges(s, cut, ctx_lens[i], 0, 0, &nch, &w0, &w1);
+    n_chunks[i] = nch;
+    if (!ranges) continue;
+    for (int ch = 0; ch < nch && ch < EASYSPEC_MAX_CHUNKS; ++ch)
+      for (int w = 0; w < nwv; ++w) {
+        attn_ranges(s, cut, ctx_lens[i], ch, w, &nch, &w0, &w1);
+        int32_t* r = ranges + (((size_t)i * EASYSPEC_MAX_CHUNKS + ch) * 8 + w) * 2;
+        r[0] = w0;
+        r[1] = w1;
+      }
+  }
+  return nwv;
+}
+
 extern "C" int64_t easyspec_step_bytes(const easyspec_ctx* ctx) {
   if (!ctx) return 0;
   const Shape& s = ctx->s;

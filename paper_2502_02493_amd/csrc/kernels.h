@@ -82,6 +82,12 @@ struct AttnCut {
   int nb_ref;    // vector kernel: batches of the longest column; shorter columns get proportionally fewer chunks
 };
 AttnCut attn_cut(const Shape& s, const Cols& c, int n_set);
+AttnCut attn_cut_vector(const Shape& s, const Cols& c, int n_set);  // the cut the vector kernel would get
+// Host evaluation of the kernels' own index arithmetic for a vector-kernel cut: the chunk count of a
+// column of n_slots slots and the slots [w0, w1) that wave `wave` of chunk `chunk` works through
+// (empty beyond the column's chunks); attn_waves: waves per workgroup of the launch.
+int attn_waves(const AttnCut& cut);
+void attn_ranges(const Shape& s, const AttnCut& cut, int n_slots, int chunk, int wave, int* nch, int* w0, int* w1);
 void launch_attn(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, const AttnCut& cut, hipStream_t st);
 // O projection of the set's layers; the first layer's result goes straight into the residual.
 void launch_oproj(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st);

@@ -824,17 +824,29 @@ struct AttnArgs {
 // units (of `unit` slots, the smallest step of a wave) are dealt to round(nb * nch_ref / nb_ref)
 // chunks whose unit counts differ by at most one, so that a context of a power-of-two length
 // plus a few drafted tokens does not leave a sliver of a chunk.
-__device__ __forceinline__ void chunk_range(const AttnArgs& a, int n_slots, int unit, int chunk, int& nch, int& s0, int& s1) {
+__host__ __device__ __forceinline__ void chunk_range(const AttnArgs& a, int n_slots, int unit, int chunk, int& nch, int& s0,
+                                                     int& s1) {
   if (a.nb_ref == 0) {
     nch = (n_slots + a.CH - 1) / a.CH;
     s0 = chunk * a.CH;
-    s1 = min(s0 + a.CH, n_slots);
+    s1 = s0 + a.CH < n_slots ? s0 + a.CH : n_slots;
   } else {
     const int nb = (n_slots + unit - 1) / unit;
-    nch = max(1, min(nb, (nb * a.nch_ref + a.nb_ref / 2) / a.nb_ref));
+    nch = (nb * a.nch_ref + a.nb_ref / 2) / a.nb_ref;
+    nch = nch > nb ? nb : nch;
+    nch = nch < 1 ? 1 : nch;
     s0 = (int)((long)chunk * nb / nch) * unit;
-    s1 = min((int)((long)(chunk + 1) * nb / nch) * unit, n_slots);
+    s1 = (int)((long)(chunk + 1) * nb / nch) * unit;
+    s1 = s1 < n_slots ? s1 : n_slots;
   }
+}
+
+// The run [w0, w1) of wave `wave` of `nwv` inside the chunk [s0, s1): the chunk's units dealt evenly.
+__host__ __device__ __forceinline__ void wave_range(int s0, int s1, int unit, int wave, int nwv, int& w0, int& w1) {
+  const int n_units = (s1 - s0 + unit - 1) / unit;
+  w0 = s0 + wave * n_units / nwv * unit;
+  w1 = s0 + (wave + 1) * n_units / nwv * unit;
+  w1 = w1 < s1 ? w1 : s1;
 }
 
 constexpr int kAttnIT = 8;       // loads in flight per operand per lane
@@ -918,9 +930,8 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
   // small steps' worth is left, then small steps, so that a wave's arithmetic follows its share
   // of the slots.  Slots past w1 fetch the run's last row instead (their scores are discarded
   // below): unconditional loads, no branch per load.
-  const int n_units = (s1 - s0 + Geo::UNIT - 1) / Geo::UNIT;
-  const int w0 = s0 + wave * n_units / NWV * Geo::UNIT;
-  const int w1 = min(s0 + (wave + 1) * n_units / NWV * Geo::UNIT, s1);
+  int w0, w1;
+  wave_range(s0, s1, Geo::UNIT, wave, NWV, w0, w1);
   auto process = [&](auto n_loads, int base) {
     constexpr int N = decltype(n_loads)::value;
     u32x4 kr[N], vr[N];
@@ -1672,6 +1683,16 @@ AttnCut attn_cut(const Shape& s, const Cols& c, int n_set) {
     cut.n_chunks = nch(ch);
     return cut;
   }
+  return attn_cut_vector(s, c, n_set);
+}
+
+AttnCut attn_cut_vector(const Shape& s, const Cols& c, int n_set) {
+  AttnCut cut;
+  cut.mfma = false;
+  cut.chunk = 0;
+  int max_len = 1;
+  for (int i = 0; i < c.n; ++i) max_len = std::max(max_len, c.pos[i] + 1);
+  static const int single_max = env_int("EASYSPEC_ATTN_SINGLE", 256);
   // Vector kernel: one workgroup of four waves per (chunk, KV head, layer, column).  Every column's
   // units (the slots of a wave's small step) are dealt evenly to its chunks (chunk_range) and a
   // chunk's units evenly to its waves, which work through them in full batches of four units and
@@ -1717,6 +1738,22 @@ AttnCut attn_cut(const Shape& s, const Cols& c, int n_set) {
   return cut;
 }
 
+int attn_waves(const AttnCut& cut) { return cut.n_chunks == 1 ? 8 : 4; }
+
+void attn_ranges(const Shape& s, const AttnCut& cut, int n_slots, int chunk, int wave, int* nch, int* w0, int* w1) {
+  AttnArgs a;
+  a.CH = cut.chunk; a.nch_ref = cut.n_chunks; a.nb_ref = cut.nb_ref;
+  const int lps = s.hd * (s.dtype == 1 ? 2 : 4) / 16;
+  const int unit = kAttnSmallIT * (64 / lps);
+  int s0, s1;
+  chunk_range(a, n_slots, unit, chunk, *nch, s0, s1);
+  if (chunk >= *nch) {
+    *w0 = *w1 = 0;
+    return;
+  }
+  wave_range(s0, s1, unit, wave, attn_waves(cut), *w0, *w1);
+}
+
 void launch_attn(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, const AttnCut& cut, hipStream_t st) {
   const int n_chunks = cut.n_chunks;
   AttnArgs a;
@@ -1728,7 +1765,7 @@ void launch_attn(const Shape& s, const Buffers& b, const Cols& c, int layer0, in
   const dim3 grid(n_chunks, s.Hkv, n_set * c.n);
   // one chunk per context: eight waves share the whole context of a (layer, column, KV head) and
   // no merge launch is needed; several chunks: four waves per chunk
-  const int nwv = n_chunks == 1 ? 8 : 4;
+  const int nwv = attn_waves(cut);
   bool tree = false;  // any column that does not see every slot up to its own
   for (int i = 0; i < c.n; ++i) tree = tree || c.vis_base[i] <= c.pos[i];
   if (cut.mfma) {

@@ -8,6 +8,7 @@ import re
 import numpy as np
 import pytest
 
+import easyspec_synth as synth
 import paper_2502_02493_amd as es
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -154,3 +155,54 @@ def test_stream_read_rejects_bad_arguments_on_the_host():
             es.easyspec_stream_read(buf, n, sink)
         assert e.value.code == es.EASYSPEC_EINVAL
     assert es.easyspec_stream_read_sink_floats() >= 1
+
+
+def test_attention_cut_gives_every_slot_to_exactly_one_wave():
+    """The split-KV cut of the vector attention kernel, evaluated on the host with the kernels' own index
+    functions: whatever the mix of context lengths, the chunks of a column tile its context in order, the
+    waves of a chunk tile the chunk, chunk counts respect the partial buffers, and contexts that all fit
+    one piece are not split."""
+    import paper_2502_02493_amd as es
+    rng = np.random.default_rng(77)
+    shapes = [("llama3_8b", "bf16"), ("qwen2_7b", "bf16"), ("tiny", "fp32"), ("tiny", "bf16"), ("tiny_qwen", "bf16")]
+    special = [1, 2, 7, 8, 9, 31, 32, 33, 255, 256, 257, 511, 513, 2047, 2048, 2049, 2055, 4097, 8191, 32768, 65535, 65536]
+    cases = 0
+    for shape, dtype in shapes:
+        cfg = es.make_config(synth.model_shape(shape, dtype=dtype), 16, 65536, 16)
+        for trial in range(60):
+            n_cols = int(rng.integers(1, 17))
+            if trial % 3 == 0:
+                lens = [int(rng.choice(special)) for _ in range(n_cols)]
+            elif trial % 3 == 1:
+                base = int(rng.choice(special))
+                lens = [max(1, min(65536, base + i)) for i in range(n_cols)]          # a calibration: consecutive lengths
+            else:
+                lens = [int(x) for x in np.exp(rng.uniform(0, np.log(65536), n_cols)).astype(int).clip(1, 65536)]
+            for n_set in (1, 3, 4, 8):
+                nwv, n_chunks, ranges = es.easyspec_attention_cut(cfg, lens, n_set)
+                assert nwv in (4, 8)
+                if max(lens) <= 256:
+                    assert nwv == 8 and all(n == 1 for n in n_chunks)
+                for i, n in enumerate(lens):
+                    assert 1 <= n_chunks[i] <= es.EASYSPEC_MAX_CHUNKS
+                    at = 0
+                    for ch in range(n_chunks[i]):
+                        for w in range(nwv):
+                            lo, hi = (int(x) for x in ranges[i, ch, w])
+                            assert lo == at or hi == lo, (shape, lens, n_set, i, ch, w, lo, hi, at)   # in order, no gap
+                            assert hi >= lo
+                            if hi > lo:
+                                at = hi
+                        assert not ranges[i, ch, nwv:].any()
+                    assert at == n, (shape, lens, n_set, i, at)
+                    assert not ranges[i, n_chunks[i]:].any()
+                cases += 1
+    assert cases == len(shapes) * 60 * 4
+
+
+def test_attention_cut_rejects_bad_arguments():
+    import paper_2502_02493_amd as es
+    cfg = es.make_config(synth.model_shape("tiny", dtype="fp32"), 4, 512, 8)
+    for lens, n_set in (([0], 1), ([513], 1), ([5] * 17, 1), ([5], 0), ([5], 9)):
+        with pytest.raises(es.EasySpecError):
+            es.easyspec_attention_cut(cfg, lens, n_set)
