@@ -876,7 +876,6 @@ struct AttnGeom {
   static constexpr int EPL = Tr<T>::EPL, LPS = HD / EPL, SPW = 64 / LPS;
   static constexpr int WAVE_SLOTS = kAttnIT * SPW;    // slots one wave covers per batch
   static constexpr int UNIT = kAttnSmallIT * SPW;     // and per small step: the granularity of the split
-  static constexpr int BLOCK_SLOTS = 4 * WAVE_SLOTS;  // chunk sizes are multiples of this (4-wave launches)
 };
 
 extern __shared__ float dyn_f[];
