@@ -1625,7 +1625,7 @@ static void launch_attn_g(int G, dim3 grid, int nwv, hipStream_t st, AttnArgs a,
 // vector kernel.  EASYSPEC_ATTN_MFMA = 0 / 2 forces never / always (bf16 only).
 static bool attn_use_mfma(const Shape& s, const Cols& c, int n_set) {
   const int mode = env_int("EASYSPEC_ATTN_MFMA", 1);  // read at every call: tests switch it between contexts
-  const long min_work = env_int("EASYSPEC_ATTN_MFMA_MIN", 40000);
+  const long min_work = env_int("EASYSPEC_ATTN_MFMA_MIN", 30000);
   if (mode == 0 || s.dtype != 1) return false;
   if (mode == 2) return true;
   bool shared = false;
