@@ -1,6 +1,6 @@
 // Host side of the EasySpec C ABI (include/easyspec.h): argument checks, the per-sequence
 // precise / fuzzy length state machine, weight repacking, and the launch sequence of one
-// forward pass.  All arithmetic of the method runs in the kernels of kernels.hip.
+// forward pass.  All arithmetic of the method runs in the kernels of gemv.hip, attention.hip and accept.hip.
 #include "../../include/easyspec.h"
 
 #include <math.h>

@@ -1,0 +1,584 @@
+// Weight-streaming kernels of the EasySpec draft hot path (gfx950): QKV, O / down projection with
+// the residual update, gate/up, LM head, embedding; and their launch wrappers.  The shared core
+// (tile layouts, the MFMA loop, wave reduction, split RMSNorm) is in device_common.hpp.
+#include "launch_common.hpp"
+
+namespace es {
+
+// ------------------------------------------------------------------------------------------
+// QKV projection of the k layers of a set + bias + rotary + KV-cache write.
+// Unit of work: two row tiles of one head, rows e and e + hd/2, so that the rotation pairs
+// sit in the same lane.  grid = k * (Hq + 2 Hkv) * (hd/32).
+// ------------------------------------------------------------------------------------------
+struct QkvArgs {
+  const u32x4* w;  // layer layer0
+  size_t w_layer_stride;
+  const void* x;  // XA: k operand slots of 16 x d
+  const float* ssp;
+  const float* bias;  // layer layer0, or null
+  const float2* rope;
+  float* q;
+  void* kc;
+  void* vc;
+  int layer0, d, Hq, Hkv, hd, B, max_ctx;
+  float inv_d, eps;
+};
+
+template <typename T, int NB>
+__global__ __launch_bounds__(1024) void qkv_kernel(QkvArgs a, Cols c) {
+  __shared__ float s_rstd[kMaxCols];
+  const int KT = Tr<T>::KT;
+  const int nkt = a.d / KT;
+  const int pairs = a.hd / 32;
+  const int units = (a.Hq + 2 * a.Hkv) * pairs;
+  const int li = blockIdx.x / units, u = blockIdx.x % units;
+  const int head = u / pairs, p = u % pairs;
+  const int rt0 = head * (a.hd / 16) + p, rt1 = rt0 + pairs;
+  const u32x4* wl = a.w + (size_t)li * a.w_layer_stride;
+  const u32x4* const w[2] = {wl + (size_t)rt0 * nkt * 64, wl + (size_t)rt1 * nkt * 64};
+  const T* x = reinterpret_cast<const T*>(a.x) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.d;
+  // operands of the epilogue (wave 0 only) and of the norm scale are fetched before the weight
+  // stream starts, so that their latency does not sit in the tail of the kernel
+  const int lane = threadIdx.x & 63, col = lane & 15;
+  const int e0 = p * 16 + (lane >> 4) * 4;  // element inside the head, < hd/2
+  const int half = a.hd / 2;
+  const int RQKV = (a.Hq + 2 * a.Hkv) * a.hd;
+  const bool epi = threadIdx.x < 64 && col < c.n;
+  const int pos = epi ? c.pos[col] : 0, seq = epi ? c.seq[col] : 0;
+  f32x4 b_lo = {0.f, 0.f, 0.f, 0.f}, b_hi = {0.f, 0.f, 0.f, 0.f}, cs01 = {1.f, 0.f, 1.f, 0.f}, cs23 = {1.f, 0.f, 1.f, 0.f};
+  if (epi) {
+    if (a.bias) {
+      b_lo = *reinterpret_cast<const f32x4*>(a.bias + (size_t)li * RQKV + head * a.hd + e0);
+      b_hi = *reinterpret_cast<const f32x4*>(a.bias + (size_t)li * RQKV + head * a.hd + e0 + half);
+    }
+    if (head < a.Hq + a.Hkv) {
+      const f32x4* rp = reinterpret_cast<const f32x4*>(a.rope + (size_t)c.rope_pos[col] * half + e0);  // 4 x (cos, sin)
+      cs01 = rp[0];
+      cs23 = rp[1];
+    }
+  }
+  RstdPre pre;
+  rstd_issue(a.ssp, a.d / 16, c.n, pre);
+
+  f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+  gemm_accumulate<T, 2, NB>(w, x, a.d, c.n, acc);
+  rstd_finish(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
+  if (!reduce_waves<2>(acc, dyn_red)) return;
+  fold_columns<T, 2>(acc, c.n);
+
+  if (col >= c.n) return;
+  const float r = s_rstd[col];
+  const float cosv[4] = {cs01[0], cs01[2], cs23[0], cs23[2]}, sinv[4] = {cs01[1], cs01[3], cs23[1], cs23[3]};
+  float lo[4], hi[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    // identity rotation (cos 1, sin 0) for the V rows; bias 0 without bias
+    const float v0 = acc[0][i] * r + b_lo[i], v1 = acc[1][i] * r + b_hi[i];
+    lo[i] = v0 * cosv[i] - v1 * sinv[i];
+    hi[i] = v1 * cosv[i] + v0 * sinv[i];
+  }
+  if (head < a.Hq) {
+    float* q = a.q + ((size_t)li * kMaxCols + col) * (a.Hq * a.hd) + head * a.hd + e0;
+    store4<float>(q, lo[0], lo[1], lo[2], lo[3]);
+    store4<float>(q + half, hi[0], hi[1], hi[2], hi[3]);
+  } else {
+    const bool is_k = head < a.Hq + a.Hkv;
+    const int kvh = is_k ? head - a.Hq : head - a.Hq - a.Hkv;
+    T* base = reinterpret_cast<T*>(is_k ? a.kc : a.vc);
+    T* row = base + ((((size_t)(a.layer0 + li) * a.B + seq) * a.Hkv + kvh) * a.max_ctx + pos) * a.hd + e0;
+    store4<T>(row, lo[0], lo[1], lo[2], lo[3]);
+    store4<T>(row + half, hi[0], hi[1], hi[2], hi[3]);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Projection back into the residual stream: the O projections of a set's layers in one
+// launch (k > 1), or one down projection (k = 1).  Layer 0 of the launch updates the
+// residual: h = H + acc (+ Attnoutput of the next layer), writes H, the sum of squares of h
+// and T(h * gain_j) for the consumer(s) that come next; the other layers only store their
+// Attnoutput for later.  grid = k * d/16.
+// ------------------------------------------------------------------------------------------
+struct ProjArgs {
+  const u32x4* w;
+  size_t w_layer_stride;
+  const void* x;  // k operand slots of 16 x K in T
+  int K, d;
+  float* H;
+  float* A;      // [MAX_SET][16][d]
+  int a_add;     // slot of A to add to the residual after acc, or -1
+  const float* gain;
+  int n_gain;
+  void* xout;    // n_gain operand slots of 16 x d in T
+  float* ssp;
+};
+
+template <typename T, int NB>
+__global__ __launch_bounds__(1024) void proj_resid_kernel(ProjArgs a, Cols c) {
+  const int KT = Tr<T>::KT;
+  const int nkt = a.K / KT;
+  const int ntile = a.d / 16;
+  const int li = blockIdx.x / ntile, t = blockIdx.x % ntile;
+  const u32x4* const w[1] = {a.w + (size_t)li * a.w_layer_stride + (size_t)t * nkt * 64};
+  const T* x = reinterpret_cast<const T*>(a.x) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.K;
+  // residual-update operands (wave 0 of a layer-0 workgroup) are fetched before the weight stream
+  const int lane = threadIdx.x & 63, col = lane & 15;
+  const bool ok = col < c.n;
+  const int r0 = t * 16 + (lane >> 4) * 4;
+  f32x4 h_in = {0.f, 0.f, 0.f, 0.f}, a_in = {0.f, 0.f, 0.f, 0.f}, g_in = {0.f, 0.f, 0.f, 0.f};
+  if (threadIdx.x < 64 && li == 0 && ok) {
+    h_in = *reinterpret_cast<const f32x4*>(a.H + (size_t)col * a.d + r0);
+    if (a.a_add >= 0) a_in = *reinterpret_cast<const f32x4*>(a.A + ((size_t)a.a_add * kMaxCols + col) * a.d + r0);
+    g_in = *reinterpret_cast<const f32x4*>(a.gain + r0);
+  }
+  f32x4 acc[1] = {{0.f, 0.f, 0.f, 0.f}};
+  gemm_accumulate<T, 1, NB>(w, x, a.K, c.n, acc);
+  if (!reduce_waves<1>(acc, dyn_red)) return;
+  fold_columns<T, 1>(acc, c.n);
+
+  if (li > 0) {
+    if (ok) store4<float>(a.A + ((size_t)li * kMaxCols + col) * a.d + r0, acc[0][0], acc[0][1], acc[0][2], acc[0][3]);
+    return;
+  }
+  float ss = 0.f;
+  if (ok) {
+    float* hp = a.H + (size_t)col * a.d + r0;
+    f32x4 h = h_in;
+    h += acc[0];
+    if (a.a_add >= 0) h += a_in;
+    *reinterpret_cast<f32x4*>(hp) = h;
+    for (int j = 0; j < a.n_gain; ++j) {
+      const f32x4 g = j == 0 ? g_in : *reinterpret_cast<const f32x4*>(a.gain + (size_t)j * a.d + r0);
+      T* xo = reinterpret_cast<T*>(a.xout) + (size_t)j * Tr<T>::PARTS * kMaxCols * a.d + xoff<T>(c.n, a.d, col, r0);
+      store_act4<T>(xo, (size_t)kMaxCols * a.d, h[0] * g[0], h[1] * g[1], h[2] * g[2], h[3] * g[3]);
+    }
+    ss = h[0] * h[0] + h[1] * h[1] + h[2] * h[2] + h[3] * h[3];
+  }
+  ss += __shfl_xor(ss, 16, 64);
+  ss += __shfl_xor(ss, 32, 64);
+  if (ok && lane < 16) a.ssp[col * ntile + t] = ss;
+}
+
+// ------------------------------------------------------------------------------------------
+// The two projections of full-layer-parallel mode (the ablation of App. B: every layer of a set,
+// attention and MLP, works from the set's input h_1 = H; the set's output is
+// H + sum_i (Attnoutput_i + MLPoutput_i)).
+//   down == 0, O projections of the set, grid = k * d/16: layer li parks Attnoutput_li in A[li]
+//     and writes the input of its own MLP, T((H + Attnoutput_li) * gain_li), into operand slot li
+//     of xout with the partial sums of squares in slot li of ssp; H is left alone.
+//   down == 1, down projections of the set, grid = d/16: a workgroup adds up the k layers'
+//     contractions for its row tile (operand slot li of x against layer li of w), then
+//     h = H + that sum + A[0] + ... + A[k-1]; writes H, the partial sums of squares of h and
+//     T(h * gain_j) for the n_gain consumers that come next, like proj_resid_kernel.
+// ------------------------------------------------------------------------------------------
+struct ProjFullArgs {
+  const u32x4* w;
+  size_t w_layer_stride;
+  const void* x;  // k operand slots of 16 x K in T
+  int K, d, k, down;
+  float* H;
+  float* A;       // [MAX_SET][16][d]
+  const float* gain;  // down == 0: [k][d]; down == 1: [n_gain][d]
+  int n_gain;
+  void* xout;
+  float* ssp;     // down == 0: [k][16][d/16]; down == 1: [16][d/16]
+};
+
+template <typename T, int NB>
+__global__ __launch_bounds__(1024) void proj_full_kernel(ProjFullArgs a, Cols c) {
+  const int nkt = a.K / Tr<T>::KT;
+  const int ntile = a.d / 16;
+  const int li = a.down ? 0 : blockIdx.x / ntile, t = blockIdx.x % ntile;
+  const int lane = threadIdx.x & 63, col = lane & 15;
+  const bool ok = col < c.n;
+  const int r0 = t * 16 + (lane >> 4) * 4;
+  f32x4 acc[1] = {{0.f, 0.f, 0.f, 0.f}};
+  const int n_sum = a.down ? a.k : 1;
+  for (int j = 0; j < n_sum; ++j) {  // uniform over the workgroup
+    const int l = li + j;
+    const u32x4* const w[1] = {a.w + (size_t)l * a.w_layer_stride + (size_t)t * nkt * 64};
+    gemm_accumulate<T, 1, NB>(w, reinterpret_cast<const T*>(a.x) + (size_t)l * Tr<T>::PARTS * kMaxCols * a.K, a.K, c.n, acc);
+  }
+  if (!reduce_waves<1>(acc, dyn_red)) return;
+  fold_columns<T, 1>(acc, c.n);
+
+  float ss = 0.f;
+  if (ok) {
+    f32x4 h = *reinterpret_cast<const f32x4*>(a.H + (size_t)col * a.d + r0);
+    h += acc[0];
+    if (a.down) {
+      for (int j = 0; j < a.k; ++j) h += *reinterpret_cast<const f32x4*>(a.A + ((size_t)j * kMaxCols + col) * a.d + r0);
+      *reinterpret_cast<f32x4*>(a.H + (size_t)col * a.d + r0) = h;
+      for (int j = 0; j < a.n_gain; ++j) {
+        const f32x4 g = *reinterpret_cast<const f32x4*>(a.gain + (size_t)j * a.d + r0);
+        T* xo = reinterpret_cast<T*>(a.xout) + (size_t)j * Tr<T>::PARTS * kMaxCols * a.d + xoff<T>(c.n, a.d, col, r0);
+        store_act4<T>(xo, (size_t)kMaxCols * a.d, h[0] * g[0], h[1] * g[1], h[2] * g[2], h[3] * g[3]);
+      }
+    } else {
+      store4<float>(a.A + ((size_t)li * kMaxCols + col) * a.d + r0, acc[0][0], acc[0][1], acc[0][2], acc[0][3]);
+      const f32x4 g = *reinterpret_cast<const f32x4*>(a.gain + (size_t)li * a.d + r0);
+      T* xo = reinterpret_cast<T*>(a.xout) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.d + xoff<T>(c.n, a.d, col, r0);
+      store_act4<T>(xo, (size_t)kMaxCols * a.d, h[0] * g[0], h[1] * g[1], h[2] * g[2], h[3] * g[3]);
+    }
+    ss = h[0] * h[0] + h[1] * h[1] + h[2] * h[2] + h[3] * h[3];
+  }
+  ss += __shfl_xor(ss, 16, 64);
+  ss += __shfl_xor(ss, 32, 64);
+  if (ok && lane < 16) a.ssp[(size_t)li * kMaxCols * ntile + col * ntile + t] = ss;
+}
+
+// ------------------------------------------------------------------------------------------
+// Gate and up projections + SiLU(gate) * up of one layer, or of the k layers of a set each on
+// its own input (full-layer mode): layer li of the launch reads operand slot li of x with
+// partial sums slot li and writes operand slot li of act.  grid = k * F/16.
+// ------------------------------------------------------------------------------------------
+struct GateUpArgs {
+  const u32x4* wg;
+  const u32x4* wu;
+  size_t w_layer_stride;
+  const void* x;  // XM: k operand slots of 16 x d
+  const float* ssp;  // [k][16][d/16]
+  void* act;  // k operand slots of 16 x F in T
+  int d, F;
+  int R;      // rows per weight tile (tile_rows() of F), ntile = ceil(F / R) workgroups per layer
+  float inv_d, eps;
+};
+
+template <typename T, int NB>
+__global__ __launch_bounds__(1024) void gateup_kernel(GateUpArgs a, Cols c) {
+  __shared__ float s_rstd[kMaxCols];
+  const int nkt = a.d / Tr<T>::KT;
+  const int R = a.R, ntile = (a.F + R - 1) / R;
+  const int li = blockIdx.x / ntile, t = blockIdx.x % ntile;
+  const size_t wl = (size_t)li * a.w_layer_stride + (size_t)t * nkt * (4 * R);
+  const u32x4* const w[2] = {a.wg + wl, a.wu + wl};
+  const float* ssp = a.ssp + (size_t)li * kMaxCols * (a.d / 16);
+  RstdPre pre;
+  rstd_issue(ssp, a.d / 16, c.n, pre);
+  f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+  // a tile of R < 16 rows: the lanes of the missing rows re-read the last row (their results are dropped)
+  const int m = threadIdx.x & 15, kg = (threadIdx.x & 63) >> 4;
+  gemm_accumulate<T, 2, NB>(w, reinterpret_cast<const T*>(a.x) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.d, a.d, c.n, acc,
+                            kg * R + min(m, R - 1), 4 * R);
+  rstd_finish(ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
+  if (!reduce_waves<2>(acc, dyn_red)) return;
+  fold_columns<T, 2>(acc, c.n);
+  const int lane = threadIdx.x & 63, col = lane & 15;
+  if (col >= c.n) return;
+  const float r = s_rstd[col];
+  float o[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float g = acc[0][i] * r, u = acc[1][i] * r;
+    o[i] = (g / (1.0f + expf(-g))) * u;
+  }
+  T* dst = reinterpret_cast<T*>(a.act) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.F;
+  const int row0 = (lane >> 4) * 4;  // of the tile
+  if (R == 16) {
+    store_act4<T>(dst + xoff<T>(c.n, a.F, col, t * 16 + row0), (size_t)kMaxCols * a.F, o[0], o[1], o[2], o[3]);
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int f = t * R + row0 + i;
+      if (row0 + i < R && f < a.F) store_act1<T>(dst + xoff<T>(c.n, a.F, col, f), (size_t)kMaxCols * a.F, o[i]);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// LM head: logits + per-workgroup argmax candidates (lowest index wins ties).  grid = ceil(V/16).
+// ------------------------------------------------------------------------------------------
+struct HeadArgs {
+  const u32x4* w;
+  const void* x;  // XA slot 0: T(h * g_final)
+  const float* ssp;
+  float* logits;  // or null
+  float* cand_val;
+  int32_t* cand_idx;
+  int d, V, nblk;
+  float inv_d, eps;
+};
+
+__device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
+
+template <typename T, int NB>
+__global__ __launch_bounds__(1024) void head_kernel(HeadArgs a, Cols c) {
+  __shared__ float s_rstd[kMaxCols];
+  const int nkt = a.d / Tr<T>::KT;
+  const int t = blockIdx.x;
+  const u32x4* const w[1] = {a.w + (size_t)t * nkt * 64};
+  RstdPre pre;
+  rstd_issue(a.ssp, a.d / 16, c.n, pre);
+  f32x4 acc[1] = {{0.f, 0.f, 0.f, 0.f}};
+  gemm_accumulate<T, 1, NB>(w, reinterpret_cast<const T*>(a.x), a.d, c.n, acc);
+  rstd_finish(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
+  if (!reduce_waves<1>(acc, dyn_red)) return;
+  fold_columns<T, 1>(acc, c.n);
+  const int lane = threadIdx.x & 63, col = lane & 15;
+  const bool ok = col < c.n;
+  const float r = ok ? s_rstd[col] : 0.f;
+  const int r0 = t * 16 + (lane >> 4) * 4;
+  float bv = -INFINITY;
+  int bi = 0x7FFFFFFF;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = r0 + i;
+    const float v = acc[0][i] * r;
+    if (ok && row < a.V) {
+      if (a.logits && c.logit_row[col] >= 0) a.logits[(size_t)c.logit_row[col] * a.V + row] = v;
+      if (better(v, row, bv, bi)) { bv = v; bi = row; }
+    }
+  }
+#pragma unroll
+  for (int off = 16; off <= 32; off <<= 1) {
+    const float ov = __shfl_xor(bv, off, 64);
+    const int oi = __shfl_xor(bi, off, 64);
+    if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+  }
+  if (ok && lane < 16) {
+    a.cand_val[(size_t)col * a.nblk + t] = bv;
+    a.cand_idx[(size_t)col * a.nblk + t] = bi;
+  }
+}
+
+__global__ __launch_bounds__(1024) void argmax_final_kernel(const float* cand_val, const int32_t* cand_idx, int nblk,
+                                                            int32_t* tokens_out, Cols c) {
+  __shared__ float sv[16];
+  __shared__ int si[16];
+  const int col = blockIdx.x, tid = threadIdx.x;
+  float bv = -INFINITY;
+  int bi = 0x7FFFFFFF;
+  for (int j0 = tid; j0 < nblk; j0 += 8 * 1024) {
+    float v[8];
+    int ix[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {  // independent loads, issued together
+      const int j = j0 + u * 1024;
+      const bool in = j < nblk;
+      v[u] = in ? cand_val[(size_t)col * nblk + j] : -INFINITY;
+      ix[u] = in ? cand_idx[(size_t)col * nblk + j] : 0x7FFFFFFF;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (better(v[u], ix[u], bv, bi)) { bv = v[u]; bi = ix[u]; }
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const float ov = __shfl_xor(bv, off, 64);
+    const int oi = __shfl_xor(bi, off, 64);
+    if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+  }
+  if ((tid & 63) == 0) { sv[tid >> 6] = bv; si[tid >> 6] = bi; }
+  __syncthreads();
+  if (tid == 0) {
+    for (int w = 1; w < 16; ++w)
+      if (better(sv[w], si[w], bv, bi)) { bv = sv[w]; bi = si[w]; }
+    if (c.out_idx[col] >= 0) tokens_out[c.out_idx[col]] = bi;
+  }
+}
+
+// four consecutive elements as floats, p aligned to 4 elements
+template <typename T>
+__device__ __forceinline__ f32x4 load4(const T* p);
+template <>
+__device__ __forceinline__ f32x4 load4<float>(const float* p) {
+  return *reinterpret_cast<const f32x4*>(p);
+}
+template <>
+__device__ __forceinline__ f32x4 load4<bf16_t>(const bf16_t* p) {
+  const u32x2 r = *reinterpret_cast<const u32x2*>(p);
+  f32x4 v = {__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xFFFF0000u), __uint_as_float(r.y << 16),
+             __uint_as_float(r.y & 0xFFFF0000u)};
+  return v;
+}
+
+// ------------------------------------------------------------------------------------------
+// Embedding gather: H = E[token]; sum of squares; T(H * g_attn) for the layers of the first set.
+// grid = columns, 1024 threads, four elements per thread and pass.
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(1024) void embed_kernel(const T* __restrict__ E, const int32_t* __restrict__ tokens,
+                                                     const float* __restrict__ gain, int n_gain, int d, int V, float* H,
+                                                     T* xa, float* ssp, Cols c) {
+  __shared__ float red[16];
+  const int col = blockIdx.x, tid = threadIdx.x;
+  const int tok = min(max(tokens[c.tok_idx[col]], 0), V - 1);  // ids outside the vocabulary are clamped
+  float ss = 0.f;
+  for (int j = tid * 4; j < d; j += 4096) {
+    const f32x4 h = load4<T>(E + (size_t)tok * d + j);
+    *reinterpret_cast<f32x4*>(H + (size_t)col * d + j) = h;
+    for (int i = 0; i < n_gain; ++i) {
+      const f32x4 g = *reinterpret_cast<const f32x4*>(gain + (size_t)i * d + j);
+      store_act4<T>(xa + (size_t)i * Tr<T>::PARTS * kMaxCols * d + xoff<T>(c.n, d, col, j), (size_t)kMaxCols * d, h[0] * g[0], h[1] * g[1],
+                    h[2] * g[2], h[3] * g[3]);
+    }
+    ss += (h[0] * h[0] + h[1] * h[1]) + (h[2] * h[2] + h[3] * h[3]);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+  if ((tid & 63) == 0) red[tid >> 6] = ss;
+  __syncthreads();
+  const int ntile = d / 16;
+  float total = 0.f;
+  for (int w = 0; w < 16; ++w) total += red[w];
+  for (int t = tid; t < ntile; t += 1024) ssp[col * ntile + t] = (t == 0) ? total : 0.f;
+}
+
+size_t packed_bytes(int dtype, int rows, int K, int R) { return tile_stride(rows, K, dtype, R) * sizeof(u32x4); }
+
+// Rows per weight tile of a matrix whose launch is one workgroup per row tile.  The hardware hands
+// workgroups to CUs as they free up, so a launch costs as many rounds as its busiest CU gets
+// workgroups: 896 tiles of 16 rows on 256 CUs cost 4 rounds for 3.5 rounds of work.  A slightly
+// lower tile (the MFMA's spare rows idle) can make the count a multiple of the CU count: 1024
+// tiles of 14 rows.  More workgroups also cost more prologues and activation reads, so the tile
+// is lowered only for a gain in balance of more than a tenth (measured: 14 rows at F = 14336
+// take 1.5 us off a 37 us launch; 15 rows at F = 18944, balance 0.925 -> 0.987, gain nothing).
+int tile_rows(int rows) {
+  const int forced = env_int("EASYSPEC_TILE_ROWS", 0);  // tests: read at every create
+  if (forced >= 8 && forced <= 16) return forced;
+  int dev = 0, n_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
+    n_cu = 256;
+  if ((rows + 15) / 16 <= n_cu) return 16;  // less than one round anyway
+  auto balance = [&](int R) {
+    const int tiles = (rows + R - 1) / R;
+    return (double)tiles / ((double)n_cu * ((tiles + n_cu - 1) / n_cu));
+  };
+  int best = 16;
+  for (int R = 15; R >= 12; --R)
+    if (balance(R) > balance(16) + 0.10 && balance(R) > balance(best)) best = R;
+  return best;
+}
+void launch_embed(const Shape& s, const Buffers& b, const Cols& c, const int32_t* tokens, int layer0, int n_set,
+                  hipStream_t st) {
+  DISPATCH_T(s.dtype, hipLaunchKernelGGL(embed_kernel<T>, dim3(c.n), dim3(1024), 0, st, (const T*)b.embed, tokens,
+                                         b.g_attn + (size_t)layer0 * s.d, n_set, s.d, s.V, b.H, (T*)b.XA, b.ssp, c));
+}
+
+void launch_qkv(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st) {
+  QkvArgs a;
+  const size_t stride = tile_stride(s.RQKV, s.d, s.dtype);
+  a.w = (const u32x4*)b.wqkv + (size_t)layer0 * stride;
+  a.w_layer_stride = stride;
+  a.x = b.XA;
+  a.ssp = b.ssp;
+  a.bias = s.has_bias ? b.bqkv + (size_t)layer0 * s.RQKV : nullptr;
+  a.rope = b.rope;
+  a.q = b.Q;
+  a.kc = b.kc;
+  a.vc = b.vc;
+  a.layer0 = layer0; a.d = s.d; a.Hq = s.Hq; a.Hkv = s.Hkv; a.hd = s.hd; a.B = s.B; a.max_ctx = s.max_ctx;
+  a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
+  const int grid = n_set * (s.Hq + 2 * s.Hkv) * (s.hd / 32);
+  const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
+  // few workgroups (a set of one layer): more waves per workgroup
+  const int nw = pick_waves(grid < 512 ? 8 : 4, nkt, "EASYSPEC_NW_QKV");
+  DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
+               hipLaunchKernelGGL((qkv_kernel<T, NB>), dim3(grid), dim3(64 * nw), red_bytes(nw, 2), st, a, c));
+}
+
+void launch_oproj(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st) {
+  ProjArgs a;
+  const size_t stride = tile_stride(s.d, s.HQ, s.dtype);
+  a.w = (const u32x4*)b.wo + (size_t)layer0 * stride;
+  a.w_layer_stride = stride;
+  a.x = b.AO;
+  a.K = s.HQ; a.d = s.d;
+  a.H = b.H; a.A = b.A; a.a_add = -1;
+  a.gain = b.g_mlp + (size_t)layer0 * s.d;
+  a.n_gain = 1;
+  a.xout = b.XM;
+  a.ssp = b.ssp;
+  const int grid = n_set * (s.d / 16);
+  const int nkt = s.HQ / (s.dtype == 1 ? 32 : 16);
+  const int nw = pick_waves(grid < 512 ? 8 : 4, nkt, "EASYSPEC_NW_O");
+  DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
+               hipLaunchKernelGGL((proj_resid_kernel<T, NB>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+}
+
+void launch_gateup(const Shape& s, const Buffers& b, const Cols& c, int layer, int n_layers, const float* ssp, hipStream_t st) {
+  GateUpArgs a;
+  const size_t stride = tile_stride(s.F, s.d, s.dtype, s.R_ffn);
+  a.wg = (const u32x4*)b.wg + (size_t)layer * stride;
+  a.wu = (const u32x4*)b.wu + (size_t)layer * stride;
+  a.w_layer_stride = stride;
+  a.x = b.XM; a.ssp = ssp; a.act = b.ACT; a.d = s.d; a.F = s.F; a.R = s.R_ffn;
+  a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
+  const int grid = n_layers * ((s.F + s.R_ffn - 1) / s.R_ffn);
+  const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
+  const int nw = pick_waves(8, nkt, "EASYSPEC_NW_GU");
+  DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
+               hipLaunchKernelGGL((gateup_kernel<T, NB>), dim3(grid), dim3(64 * nw), red_bytes(nw, 2), st, a, c));
+}
+
+void launch_down(const Shape& s, const Buffers& b, const Cols& c, int layer, int a_next, const float* gain, int n_gain,
+                 void* xout, hipStream_t st) {
+  ProjArgs a;
+  const size_t stride = tile_stride(s.d, s.F, s.dtype);
+  a.w = (const u32x4*)b.wd + (size_t)layer * stride;
+  a.w_layer_stride = stride;
+  a.x = b.ACT;
+  a.K = s.F; a.d = s.d;
+  a.H = b.H; a.A = b.A; a.a_add = a_next;
+  a.gain = gain; a.n_gain = n_gain; a.xout = xout; a.ssp = b.ssp;
+  const int grid = s.d / 16;
+  const int nkt = s.F / (s.dtype == 1 ? 32 : 16);
+  // Seven waves when that cuts K into whole batches of 8 tiles per wave (F = 14336: 8 batches each) and
+  // the pass has one activation fragment: measured 11 us per step faster than eight at the 8B shape
+  // (a wave's tiles are then 7 KB apart instead of a power of two); slower where K does not divide
+  // (Qwen2-7B's F = 18944) or with two fragments.
+  const bool seven = !two_fragments(s.dtype, c) && nkt % 56 == 0;
+  const int nw = pick_waves(seven ? 7 : 8, nkt, "EASYSPEC_NW_DOWN");
+  DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
+               hipLaunchKernelGGL((proj_resid_kernel<T, NB>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+}
+
+void launch_oproj_full(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st) {
+  ProjFullArgs a;
+  const size_t stride = tile_stride(s.d, s.HQ, s.dtype);
+  a.w = (const u32x4*)b.wo + (size_t)layer0 * stride;
+  a.w_layer_stride = stride;
+  a.x = b.AO;
+  a.K = s.HQ; a.d = s.d; a.k = n_set; a.down = 0;
+  a.H = b.H; a.A = b.A;
+  a.gain = b.g_mlp + (size_t)layer0 * s.d;
+  a.n_gain = 0;
+  a.xout = b.XM;
+  a.ssp = b.ssp_set;
+  const int grid = n_set * (s.d / 16);
+  const int nkt = s.HQ / (s.dtype == 1 ? 32 : 16);
+  const int nw = pick_waves(grid < 512 ? 8 : 4, nkt, "EASYSPEC_NW_O");
+  DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
+               hipLaunchKernelGGL((proj_full_kernel<T, NB>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+}
+
+void launch_down_full(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, const float* gain, int n_gain,
+                      void* xout, hipStream_t st) {
+  ProjFullArgs a;
+  const size_t stride = tile_stride(s.d, s.F, s.dtype);
+  a.w = (const u32x4*)b.wd + (size_t)layer0 * stride;
+  a.w_layer_stride = stride;
+  a.x = b.ACT;
+  a.K = s.F; a.d = s.d; a.k = n_set; a.down = 1;
+  a.H = b.H; a.A = b.A;
+  a.gain = gain; a.n_gain = n_gain; a.xout = xout; a.ssp = b.ssp;
+  const int grid = s.d / 16;
+  const int nkt = s.F / (s.dtype == 1 ? 32 : 16);
+  const int nw = pick_waves(8, nkt, "EASYSPEC_NW_DOWN");
+  DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
+               hipLaunchKernelGGL((proj_full_kernel<T, NB>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+}
+
+void launch_head(const Shape& s, const Buffers& b, const Cols& c, float* logits_out, int32_t* tokens_out, hipStream_t st) {
+  HeadArgs a;
+  a.w = (const u32x4*)b.wlm; a.x = b.XA; a.ssp = b.ssp; a.logits = logits_out;
+  a.cand_val = b.amax_val; a.cand_idx = b.amax_idx;
+  a.d = s.d; a.V = s.V; a.nblk = (s.V + 15) / 16;
+  a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
+  const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
+  const int nw = pick_waves(4, nkt, "EASYSPEC_NW_HEAD");
+  DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
+               hipLaunchKernelGGL((head_kernel<T, NB>), dim3(a.nblk), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+  hipLaunchKernelGGL(argmax_final_kernel, dim3(c.n), dim3(1024), 0, st, a.cand_val, a.cand_idx, a.nblk, tokens_out, c);
+}
+
+}  // namespace es

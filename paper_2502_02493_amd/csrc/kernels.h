@@ -1,5 +1,5 @@
 // Internal interface between the host state machine (easyspec.cpp) and the gfx950 kernels
-// (kernels.hip).  Plain structs and launch functions; no device code in this header.
+// (gemv.hip, attention.hip, util.hip, accept.hip).  Plain structs and launch functions; no device code in this header.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -37,7 +37,7 @@ struct Shape {
 
 // Device buffers of a context.  "T" = storage dtype.  Activation arrays in T hold two parts
 // [hi | lo] per slot when T is bf16 (the value is hi + lo), one part when T is fp32.  Packed matrices are arrays of 1 KB tiles
-// (16 rows x 16 bytes per lane-group, see kernels.hip) ordered [layer][row tile][k tile].
+// (16 rows x 16 bytes per lane-group, see device_common.hpp) ordered [layer][row tile][k tile].
 struct Buffers {
   // weights
   void *wqkv, *wo, *wg, *wu, *wd, *wlm;  // packed tiles
@@ -50,7 +50,7 @@ struct Buffers {
   // workspaces (per forward pass).  fp32 arrays are [.][kMaxCols][width].  Arrays in T are operands of
   // the next weight contraction: per part either plain rows [column][width] (passes of one or two
   // columns) or 1 KB tiles of KT consecutive k holding [k-group][column][EPL elements], the order of
-  // a wave's B fragments (see xoff() in kernels.hip); a slot of XA / AO is PARTS * 16 * width elements.
+  // a wave's B fragments (see xoff() in device_common.hpp); a slot of XA / AO is PARTS * 16 * width elements.
   float *H;     // [16][d]      residual stream
   float *ssp;   // [16][d/16]   per-row-tile partial sums of squares of the vector to be normed next
   float *ssp_set;  // [MAX_SET][16][d/16]  the same per layer of a set (full-layer mode: one MLP input per layer)

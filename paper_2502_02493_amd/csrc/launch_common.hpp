@@ -1,0 +1,47 @@
+// Host-side helpers shared by the launch wrappers of the kernel files.
+#pragma once
+#include "device_common.hpp"
+
+#include <stdlib.h>
+
+namespace es {
+
+static inline int env_int(const char* name, int dflt) {
+  const char* v = getenv(name);
+  return v ? atoi(v) : dflt;
+}
+
+// Waves per workgroup (they split K).  `dflt` is the value measured best at the 8B shape for
+// that operation; a wave always keeps at least 8 k-tiles.  EASYSPEC_NW_* overrides for sweeps.
+static inline int pick_waves(int dflt, int nkt, const char* env) {
+  const int forced = env_int(env, 0);
+  int nw = forced > 0 ? forced : dflt;
+  if (nw > 16) nw = 16;
+  while (nw > 1 && nkt / nw < 8) nw /= 2;
+  return nw;
+}
+
+static inline size_t red_bytes(int nw, int rt) { return (size_t)(nw > 1 ? nw - 1 : 0) * rt * 64 * sizeof(f32x4); }
+
+// bf16 with more than 8 columns: hi and lo activation terms take a fragment each
+static inline bool two_fragments(int dtype, const Cols& c) { return dtype == 1 && 2 * c.n > kMaxCols; }
+
+#define DISPATCH_TNB(dtype, two, ...)                                         \
+  do {                                                                        \
+    if ((dtype) == 1 && (two)) { typedef bf16_t T; constexpr int NB = 2; __VA_ARGS__; } \
+    else if ((dtype) == 1) { typedef bf16_t T; constexpr int NB = 1; __VA_ARGS__; }     \
+    else { typedef float T; constexpr int NB = 1; __VA_ARGS__; }              \
+  } while (0)
+
+#define DISPATCH_T(dtype, ...)                    \
+  do {                                            \
+    if ((dtype) == 1) { typedef bf16_t T; __VA_ARGS__; } \
+    else { typedef float T; __VA_ARGS__; }        \
+  } while (0)
+
+static inline size_t tile_stride(int rows, int K, int dtype, int R = 16) {  // u32x4 per matrix
+  const int kt = dtype == 1 ? 32 : 16;
+  return (size_t)((rows + R - 1) / R) * (K / kt) * (4 * R);
+}
+
+}  // namespace es
