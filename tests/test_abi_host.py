@@ -206,3 +206,12 @@ def test_attention_cut_rejects_bad_arguments():
     for lens, n_set in (([0], 1), ([513], 1), ([5] * 17, 1), ([5], 0), ([5], 9)):
         with pytest.raises(es.EasySpecError):
             es.easyspec_attention_cut(cfg, lens, n_set)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: `bench.py --gpus 2` must say so and exit without touching a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
