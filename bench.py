@@ -157,10 +157,22 @@ def main():
     esz = 4
     dptr = draft.data_ptr()
 
+    # Calibration length per iteration: gamma + 1 tokens (every drafted token accepted, the costliest case), or,
+    # for the calibration-dominant workload, accepted-length + 1 with the accepted length drawn uniformly from
+    # 0 .. gamma by the seeded generator (partial rewrites of the fuzzy slots).
+    draw_m = wl.get("calib_tokens") == "uniform"
+    m_rng = np.random.Generator(np.random.Philox(key=[args.seed, 77]))
+    m_used = []
+    n_tok_iter = n_tok.copy()
+
     def iteration(ev=None):
         es.easyspec_truncate(ctx, 0, ctx_len)
-        if ev: ev[0].record()
-        es.easyspec_calibrate(ctx, calib_tok, n_tok, dptr, None, 0)       # first draft token -> draft[0]
+        if draw_m:
+            n_tok_iter[0] = int(m_rng.integers(1, M + 1))
+        if ev:
+            m_used.append(int(n_tok_iter[0]))
+            ev[0].record()
+        es.easyspec_calibrate(ctx, calib_tok, n_tok_iter, dptr, None, 0)  # first draft token -> draft[0]
         if ev: ev[1].record()
         for j in range(1, gamma):
             es.easyspec_draft_step(ctx, dptr + (j - 1) * esz, dptr + j * esz, None)
@@ -191,7 +203,8 @@ def main():
     es.easyspec_truncate(ctx, 0, ctx_len)
     step_bytes = es.easyspec_step_bytes(ctx)              # one draft step at this context
     e = 2 if cfg["dtype"] == "bf16" else 4
-    calib_bytes = step_bytes + (M - 1) * cfg["n_layers"] * 2 * cfg["n_kv_heads"] * cfg["head_dim"] * e
+    m_mean = float(np.mean(m_used)) if m_used else float(M)
+    calib_bytes = step_bytes + (m_mean - 1) * cfg["n_layers"] * 2 * cfg["n_kv_heads"] * cfg["head_dim"] * e
     gu_bytes = 2 * cfg["d_ffn"] * cfg["d_model"] * e
 
     # dominant kernel (gate/up projection: 2*F*d weights per launch), HIP events around each launch,
@@ -312,7 +325,8 @@ def main():
         "draft_step": {"us": round(step_us, 1), "tokens_per_s": round(1e6 / step_us, 2), "bytes": int(step_bytes),
                        "hbm_frac": round(step_bytes / (step_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
                        "frac_of_stream_read": round(step_bytes / (step_us * 1e-6) / 1e9 / stream_gbs, 4)},
-        "calibrate": {"us": round(calib_us, 1), "tokens": M, "bytes": int(calib_bytes),
+        "calibrate": {"us": round(calib_us, 1), "tokens": M if not draw_m else round(m_mean, 2),
+                      "tokens_drawn": "uniform 1..%d" % M if draw_m else "fixed", "bytes": int(calib_bytes),
                       "hbm_frac": round(calib_bytes / (calib_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)},
         "roofline": {"bound": "hbm", "kernel": "gateup_kernel", "achieved": round(gu_gbs, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(gu_gbs / HBM_PEAK_GBS, 4),

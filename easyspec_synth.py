@@ -222,7 +222,7 @@ WORKLOADS = {
     "qwen2_7b_ctx4096": dict(model="qwen2_7b", group_policy="aligned", group_size=4, gamma=5,
                              context=4096, batch=1),
     "llama3_8b_calib_ctx8192": dict(model="llama3_8b", group_policy="aligned", group_size=4, gamma=8,
-                                    context=8192, batch=1),
+                                    context=8192, batch=1, calib_tokens="uniform"),
     "llama3_8b_batch4_long": dict(model="llama3_8b", group_policy="aligned", group_size=4, gamma=5,
                                   context=(4096, 8192, 16384, 32768), batch=4),
 }
