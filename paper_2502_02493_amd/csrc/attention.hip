@@ -403,6 +403,7 @@ struct ColGroups {
   int32_t count[kMaxCols];  // its columns (consecutive, same sequence); count * G <= 16
 };
 constexpr int kMfmaAttnWaves = 4;
+typedef short v4i16 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ bf16x8 pack_bf16x8(const uint32_t (&b)[8]) {
   u32x4 v = {b[0] | (b[1] << 16), b[2] | (b[3] << 16), b[4] | (b[5] << 16), b[6] | (b[7] << 16)};
@@ -434,7 +435,6 @@ __global__ __launch_bounds__(64 * kMfmaAttnWaves) void attn_mfma_kernel(AttnArgs
   const u32x4* vc = reinterpret_cast<const u32x4*>(reinterpret_cast<const bf16_t*>(a.vc) + rowbase * HD);
   u32x4* vt = dyn_v + (size_t)wave * 80 * PIECES;
   u32x4* kt_lds = vt + 64 * PIECES;
-  const uint16_t* vt16 = reinterpret_cast<const uint16_t*>(vt);
   const u32x4* kc4 = reinterpret_cast<const u32x4*>(kc);
 
   // K and V rows of a super tile as they lie in memory (coalesced): fragment f = it*64 + lane of its
@@ -479,14 +479,14 @@ __global__ __launch_bounds__(64 * kMfmaAttnWaves) void attn_mfma_kernel(AttnArgs
 #pragma unroll
   for (int et = 0; et < ET; ++et) o[et] = f32x4{0.f, 0.f, 0.f, 0.f};
   float m_run = -INFINITY, l_run = 0.f;  // l_run: this lane's 16 slots per super tile only
-  const int swz = q4 * (PIECES / 4);
 
   for (int base = ws0; base < ws1; base += 64) {
-    // V tile into LDS with the pieces of slot s XORed by (s/16)*(PIECES/4)
+    // V tile into LDS, the 32-byte blocks of slot s XORed by s % 4: the transposing reads below take
+    // the same block of four consecutive slots at once, which then lie in different banks
 #pragma unroll
     for (int it = 0; it < PIECES; ++it) {
       const int f = it * 64 + lane, sl = f / PIECES, piece = f % PIECES;
-      vt[sl * PIECES + (piece ^ ((sl >> 4) * (PIECES / 4)))] = vf[it];
+      vt[sl * PIECES + (piece ^ ((sl & 3) << 1))] = vf[it];
     }
     // scores of this lane's row against its 16 slots base + q4*16 + t*4 + i.  S^T tile t takes
     // the slots (m/4)*16 + t*4 + m%4, m = 0..15, as its A rows: their pieces go through LDS
@@ -549,17 +549,26 @@ __global__ __launch_bounds__(64 * kMfmaAttnWaves) void attn_mfma_kernel(AttnArgs
       pl[h] = pack_bf16x8(lb);
     }
     __builtin_amdgcn_wave_barrier();
-    // A operands: V^T row e = et*16 + lane%16, the 8 slots q4*16 + h*8 + j, gathered from LDS
+    // A operands: V^T row e = et*16 + lane%16, the 8 slots q4*16 + h*8 + j, by the LDS transposing
+    // read (ds_read_b64_tr_b16): in a group of 16 lanes, lane i offers the 8 bytes at its address
+    // (4 elements of "row" i) and receives element i%4 of rows i/4, i/4 + 4, i/4 + 8, i/4 + 12.
+    // With row 4j + c = (slot s0 + j, elements e0 + 4c .. +3), lane i receives V[s0 + j][e0 + i],
+    // j = 0..3: four consecutive slots of its own V^T row.  Two reads per 8-slot k-group.
 #pragma unroll
     for (int et = 0; et < ET; ++et) {
-      const int e = et * 16 + r;
-      const int pofs = ((e >> 3) ^ swz) * 8 + (e & 7);  // 2-byte index inside a slot's row
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
-        uint32_t vb[8];
+        v4i16 half[2];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) vb[j] = vt16[(q4 * 16 + h * 8 + j) * HD + pofs];
-        const bf16x8 va = pack_bf16x8(vb);
+        for (int t2 = 0; t2 < 2; ++t2) {
+          const int slot = q4 * 16 + h * 8 + t2 * 4 + (r >> 2);  // this lane's row of the transposed block
+          const int piece = (et * 2 + ((r & 3) >> 1)) ^ ((slot & 3) << 1);
+          const char* src = reinterpret_cast<const char*>(vt) + slot * (HD * 2) + piece * 16 + (r & 1) * 8;
+          half[t2] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4i16*)(src));
+        }
+        typedef short v8i16 __attribute__((ext_vector_type(8)));
+        const v8i16 both = {half[0][0], half[0][1], half[0][2], half[0][3], half[1][0], half[1][1], half[1][2], half[1][3]};
+        const bf16x8 va = __builtin_bit_cast(bf16x8, both);
         o[et] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, ph[h], o[et], 0, 0, 0);
         o[et] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pl[h], o[et], 0, 0, 0);
       }
