@@ -120,6 +120,7 @@ extern "C" int easyspec_create(const easyspec_config* cfg, void* hip_stream, eas
   s.hd = cfg->head_dim; s.F = cfg->d_ffn; s.V = cfg->vocab; s.HQ = s.Hq * s.hd; s.RQKV = (s.Hq + 2 * s.Hkv) * s.hd;
   s.B = cfg->max_batch; s.max_ctx = cfg->max_ctx; s.eps = cfg->rms_eps; s.has_bias = cfg->qkv_bias ? 1 : 0;
   s.R_ffn = tile_rows(s.F);
+  s.R_qkv = qkv_tile_rows(s.RQKV / 2);
   ctx->precise.assign(s.B, 0);
   ctx->fuzzy.assign(s.B, 0);
   ctx->tree.assign(s.B, easyspec_ctx::Tree());
@@ -131,7 +132,7 @@ extern "C" int easyspec_create(const easyspec_config* cfg, void* hip_stream, eas
     memset(&b, 0, sizeof b);
     const size_t es_ = esize(s);
     const size_t act_ = es_ * (s.dtype == EASYSPEC_DTYPE_BF16 ? 2 : 1);  // bf16 activations: hi and lo arrays
-    ALLOC(ctx, b.wqkv, (size_t)s.L * packed_bytes(s, s.RQKV, s.d));
+    ALLOC(ctx, b.wqkv, (size_t)s.L * 2 * packed_bytes(s, s.RQKV / 2, s.d, s.R_qkv));
     ALLOC(ctx, b.wo, (size_t)s.L * packed_bytes(s, s.d, s.HQ));
     ALLOC(ctx, b.wg, (size_t)s.L * packed_bytes(s, s.F, s.d, s.R_ffn));
     ALLOC(ctx, b.wu, (size_t)s.L * packed_bytes(s, s.F, s.d, s.R_ffn));
@@ -228,17 +229,27 @@ extern "C" int easyspec_load_weights(easyspec_ctx* ctx, const easyspec_weights* 
       return hipMemcpyAsync((char*)stage + off_elems * es_, src, elems * es_, hipMemcpyDefault, st);
     };
     auto pack = [&](void* dst_base, size_t layer, int rows, int K, int R = 16) -> hipError_t {
-      launch_repack(s.dtype, stage, (char*)dst_base + layer * packed_bytes(s, rows, K, R), rows, K, R, st);
+      launch_repack(s.dtype, stage, (char*)dst_base + layer * packed_bytes(s, rows, K, R), rows, K, R, 0, 0, st);
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
       return hipStreamSynchronize(st);  // staging is reused
+    };
+    // stacked [Wq; Wk; Wv]: the first halves of all heads, then the second halves (the rotation pairs)
+    auto pack_qkv = [&](size_t layer) -> hipError_t {
+      const size_t half_bytes = packed_bytes(s, s.RQKV / 2, s.d, s.R_qkv);
+      char* dst = (char*)b.wqkv + layer * 2 * half_bytes;
+      launch_repack(s.dtype, stage, dst, s.RQKV / 2, s.d, s.R_qkv, s.hd / 2, 0, st);
+      launch_repack(s.dtype, stage, dst + half_bytes, s.RQKV / 2, s.d, s.R_qkv, s.hd / 2, s.hd / 2, st);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+      return hipStreamSynchronize(st);
     };
     for (int l = 0; l < s.L; ++l) {
       const easyspec_layer_weights& lw = w->layers[l];
       HIPCHK(ctx, put(lw.wq, (size_t)s.HQ * s.d, 0));
       HIPCHK(ctx, put(lw.wk, (size_t)s.Hkv * s.hd * s.d, (size_t)s.HQ * s.d));
       HIPCHK(ctx, put(lw.wv, (size_t)s.Hkv * s.hd * s.d, (size_t)(s.HQ + s.Hkv * s.hd) * s.d));
-      HIPCHK(ctx, pack(b.wqkv, l, s.RQKV, s.d));
+      HIPCHK(ctx, pack_qkv(l));
       HIPCHK(ctx, put(lw.wo, (size_t)s.d * s.HQ, 0));
       HIPCHK(ctx, pack(b.wo, l, s.d, s.HQ));
       HIPCHK(ctx, put(lw.wg, (size_t)s.F * s.d, 0));

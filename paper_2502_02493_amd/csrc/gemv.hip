@@ -7,8 +7,11 @@ namespace es {
 
 // ------------------------------------------------------------------------------------------
 // QKV projection of the k layers of a set + bias + rotary + KV-cache write.
-// Unit of work: two row tiles of one head, rows e and e + hd/2, so that the rotation pairs
-// sit in the same lane.  grid = k * (Hq + 2 Hkv) * (hd/32).
+// The rotation pairs (row e of a head and row e + hd/2) are numbered through all heads of a layer,
+// pair = head * hd/2 + e, and packed as two matrices of (Hq + 2 Hkv) * hd/2 rows each (first and
+// second halves).  Unit of work: the same tile of R pairs of both, so that a pair sits in one
+// lane.  R is 16, or 12 where that fills the CUs better (qkv_tile_rows); a lane's four rows stay
+// inside one head because R and hd/2 are multiples of 4.  grid = k * ceil(pairs / R).
 // ------------------------------------------------------------------------------------------
 struct QkvArgs {
   const u32x4* w;  // layer layer0
@@ -21,6 +24,7 @@ struct QkvArgs {
   void* kc;
   void* vc;
   int layer0, d, Hq, Hkv, hd, B, max_ctx;
+  int R;  // pairs per tile
   float inv_d, eps;
 };
 
@@ -29,21 +33,22 @@ __global__ __launch_bounds__(1024) void qkv_kernel(QkvArgs a, Cols c) {
   __shared__ float s_rstd[kMaxCols];
   const int KT = Tr<T>::KT;
   const int nkt = a.d / KT;
-  const int pairs = a.hd / 32;
-  const int units = (a.Hq + 2 * a.Hkv) * pairs;
+  const int half = a.hd / 2;
+  const int R = a.R, n_pairs = (a.Hq + 2 * a.Hkv) * half, units = (n_pairs + R - 1) / R;
   const int li = blockIdx.x / units, u = blockIdx.x % units;
-  const int head = u / pairs, p = u % pairs;
-  const int rt0 = head * (a.hd / 16) + p, rt1 = rt0 + pairs;
   const u32x4* wl = a.w + (size_t)li * a.w_layer_stride;
-  const u32x4* const w[2] = {wl + (size_t)rt0 * nkt * 64, wl + (size_t)rt1 * nkt * 64};
+  const u32x4* const w[2] = {wl + (size_t)u * nkt * (4 * R), wl + (size_t)(units + u) * nkt * (4 * R)};
   const T* x = reinterpret_cast<const T*>(a.x) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.d;
   // operands of the epilogue (wave 0 only) and of the norm scale are fetched before the weight
   // stream starts, so that their latency does not sit in the tail of the kernel
   const int lane = threadIdx.x & 63, col = lane & 15;
-  const int e0 = p * 16 + (lane >> 4) * 4;  // element inside the head, < hd/2
-  const int half = a.hd / 2;
+  const int row0 = (lane >> 4) * 4;       // of the tile
+  const int pair0 = u * R + row0;         // first of the lane's four pairs
+  const bool rows_ok = row0 < R && pair0 < n_pairs;
+  const int head = rows_ok ? pair0 / half : 0;
+  const int e0 = rows_ok ? pair0 % half : 0;  // element inside the head, < hd/2
   const int RQKV = (a.Hq + 2 * a.Hkv) * a.hd;
-  const bool epi = threadIdx.x < 64 && col < c.n;
+  const bool epi = threadIdx.x < 64 && col < c.n && rows_ok;
   const int pos = epi ? c.pos[col] : 0, seq = epi ? c.seq[col] : 0;
   f32x4 b_lo = {0.f, 0.f, 0.f, 0.f}, b_hi = {0.f, 0.f, 0.f, 0.f}, cs01 = {1.f, 0.f, 1.f, 0.f}, cs23 = {1.f, 0.f, 1.f, 0.f};
   if (epi) {
@@ -61,12 +66,13 @@ __global__ __launch_bounds__(1024) void qkv_kernel(QkvArgs a, Cols c) {
   rstd_issue(a.ssp, a.d / 16, c.n, pre);
 
   f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-  gemm_accumulate<T, 2, NB>(w, x, a.d, c.n, acc);
+  // a tile of R < 16 pairs: the lanes of the missing rows re-read the last row (their results are dropped)
+  gemm_accumulate<T, 2, NB>(w, x, a.d, c.n, acc, (lane >> 4) * R + min(lane & 15, R - 1), 4 * R);
   rstd_finish(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
   if (!reduce_waves<2>(acc, dyn_red)) return;
   fold_columns<T, 2>(acc, c.n);
 
-  if (col >= c.n) return;
+  if (col >= c.n || !rows_ok) return;
   const float r = s_rstd[col];
   const float cosv[4] = {cs01[0], cs01[2], cs23[0], cs23[2]}, sinv[4] = {cs01[1], cs01[3], cs23[1], cs23[3]};
   float lo[4], hi[4];
@@ -448,6 +454,30 @@ int tile_rows(int rows) {
     if (balance(R) > balance(16) + 0.10 && balance(R) > balance(best)) best = R;
   return best;
 }
+
+// Rotation pairs per tile of the QKV matrices (16 or 12; the epilogue wants a multiple of 4).  A set
+// of k layers launches k * ceil(pairs / R) workgroups; the launch costs (workgroups per CU, rounded
+// up) * R rows' worth of streaming per CU.  Summed over sets of 1 to 4 layers, per layer: at the 8B
+// shape (3072 pairs) tiles of 16 cost 16 + 12 + 16 + 12 (192, 384, 576, 768 workgroups on 256 CUs),
+// tiles of 12 cost 12 each (256, 512, 768, 1024).
+int qkv_tile_rows(int n_pairs) {
+  const int forced = env_int("EASYSPEC_QKV_TILE_ROWS", 0);  // tests: read at every create
+  if (forced == 8 || forced == 12 || forced == 16) return forced;
+  int dev = 0, n_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
+    n_cu = 256;
+  if ((n_pairs + 15) / 16 < n_cu / 4) return 16;  // small models: never more than a fraction of a round
+  auto cost = [&](int R) {
+    double sum = 0.0;
+    for (int k = 1; k <= 4; ++k) {
+      const int wg = k * ((n_pairs + R - 1) / R);
+      sum += (double)((wg + n_cu - 1) / n_cu) * R / k;
+    }
+    return sum;
+  };
+  return cost(12) < 0.9 * cost(16) ? 12 : 16;
+}
+
 void launch_embed(const Shape& s, const Buffers& b, const Cols& c, const int32_t* tokens, int layer0, int n_set,
                   hipStream_t st) {
   DISPATCH_T(s.dtype, hipLaunchKernelGGL(embed_kernel<T>, dim3(c.n), dim3(1024), 0, st, (const T*)b.embed, tokens,
@@ -456,7 +486,7 @@ void launch_embed(const Shape& s, const Buffers& b, const Cols& c, const int32_t
 
 void launch_qkv(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st) {
   QkvArgs a;
-  const size_t stride = tile_stride(s.RQKV, s.d, s.dtype);
+  const size_t stride = 2 * tile_stride(s.RQKV / 2, s.d, s.dtype, s.R_qkv);  // first halves, second halves
   a.w = (const u32x4*)b.wqkv + (size_t)layer0 * stride;
   a.w_layer_stride = stride;
   a.x = b.XA;
@@ -467,8 +497,9 @@ void launch_qkv(const Shape& s, const Buffers& b, const Cols& c, int layer0, int
   a.kc = b.kc;
   a.vc = b.vc;
   a.layer0 = layer0; a.d = s.d; a.Hq = s.Hq; a.Hkv = s.Hkv; a.hd = s.hd; a.B = s.B; a.max_ctx = s.max_ctx;
+  a.R = s.R_qkv;
   a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
-  const int grid = n_set * (s.Hq + 2 * s.Hkv) * (s.hd / 32);
+  const int grid = n_set * ((s.RQKV / 2 + s.R_qkv - 1) / s.R_qkv);
   const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
   // few workgroups (a set of one layer): more waves per workgroup
   const int nw = pick_waves(grid < 512 ? 8 : 4, nkt, "EASYSPEC_NW_QKV");

@@ -32,7 +32,8 @@ struct Shape {
   int32_t B, max_ctx;
   float eps;
   int32_t has_bias;
-  int32_t R_ffn;  // rows per weight tile of the gate and up matrices (tile_rows(F)); every other matrix: 16
+  int32_t R_ffn;  // rows per weight tile of the gate and up matrices (tile_rows(F))
+  int32_t R_qkv;  // rotation pairs per tile of the QKV matrices (qkv_tile_rows); every other matrix: tiles of 16 rows
 };
 
 // Device buffers of a context.  "T" = storage dtype.  Activation arrays in T hold two parts
@@ -69,8 +70,10 @@ struct Buffers {
 // Launch wrappers (all asynchronous on `st`).
 // Packed matrices: row tiles of R <= 16 rows (see repack_kernel).
 int tile_rows(int rows);
+int qkv_tile_rows(int n_pairs);
 size_t packed_bytes(int dtype, int rows, int K, int R);
-void launch_repack(int dtype, const void* src, void* dst, int rows, int K, int R, hipStream_t st);
+// half = 0: packed row r is source row r; half > 0: source row (r / half) * 2 * half + r % half + row_add
+void launch_repack(int dtype, const void* src, void* dst, int rows, int K, int R, int half, int row_add, hipStream_t st);
 void launch_embed(const Shape& s, const Buffers& b, const Cols& c, const int32_t* tokens, int layer0, int n_set,
                   hipStream_t st);
 void launch_qkv(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st);

@@ -8,11 +8,14 @@ namespace es {
 // Small utilities.
 // ------------------------------------------------------------------------------------------
 
-// Row-major [rows][K] -> tiles of R <= 16 rows, per k-tile a fragment of [k-group 4][R rows] 16-byte
+// Row-major [.][K] -> tiles of R <= 16 rows, per k-tile a fragment of [k-group 4][R rows] 16-byte
 // pieces (1 KB for R = 16: piece i is lane i's share of an MFMA A operand); rows padded with zeros
-// up to a multiple of R.
+// up to a multiple of R.  Packed row r is source row r (half = 0), or, for the rotary halves of
+// stacked heads (half > 0), source row (r / half) * 2 * half + r % half + row_add: the first
+// (row_add = 0) or second (row_add = half) half of head r / half.
 template <typename T>
-__global__ void repack_kernel(const T* __restrict__ src, u32x4* __restrict__ dst, int rows, int K, int R, size_t n_frag) {
+__global__ void repack_kernel(const T* __restrict__ src, u32x4* __restrict__ dst, int rows, int K, int R, int half, int row_add,
+                              size_t n_frag) {
   constexpr int EPL = Tr<T>::EPL, KT = Tr<T>::KT;
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n_frag) return;
@@ -23,7 +26,10 @@ __global__ void repack_kernel(const T* __restrict__ src, u32x4* __restrict__ dst
   const size_t rt = tile / nkt;
   const size_t row = rt * R + piece % R;
   u32x4 v = {0u, 0u, 0u, 0u};
-  if (row < (size_t)rows) v = *reinterpret_cast<const u32x4*>(src + row * K + (size_t)kt * KT + (piece / R) * EPL);
+  if (row < (size_t)rows) {
+    const size_t srow = half > 0 ? (row / half) * 2 * half + row % half + row_add : row;
+    v = *reinterpret_cast<const u32x4*>(src + srow * K + (size_t)kt * KT + (piece / R) * EPL);
+  }
   dst[i] = v;
 }
 
@@ -54,10 +60,11 @@ __global__ void kv_copy_kernel(u32x4* cache, u32x4* user, int L, int B, int Hkv,
   else user[i] = cache[ci];
 }
 
-void launch_repack(int dtype, const void* src, void* dst, int rows, int K, int R, hipStream_t st) {
+void launch_repack(int dtype, const void* src, void* dst, int rows, int K, int R, int half, int row_add, hipStream_t st) {
   const size_t n_frag = tile_stride(rows, K, dtype, R);
   const unsigned grid = (unsigned)((n_frag + 255) / 256);
-  DISPATCH_T(dtype, hipLaunchKernelGGL(repack_kernel<T>, dim3(grid), dim3(256), 0, st, (const T*)src, (u32x4*)dst, rows, K, R, n_frag));
+  DISPATCH_T(dtype, hipLaunchKernelGGL(repack_kernel<T>, dim3(grid), dim3(256), 0, st, (const T*)src, (u32x4*)dst, rows, K, R, half,
+                                       row_add, n_frag));
 }
 // Streaming-read probe: the same non-temporal 16-byte loads as the weight stream, 8 in flight per
 // lane, summed so that nothing is optimised away.  sink: one float per workgroup.

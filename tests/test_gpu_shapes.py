@@ -104,6 +104,17 @@ def test_gate_up_weight_tiles_of_fewer_rows(oracle, gpu, monkeypatch, rows, dtyp
     one_iteration(oracle, gpu, cfg, 560 + rows, [0, 1, 3, 4], 40, 4, accept=2)
 
 
+@pytest.mark.parametrize("rows", [8, 12, 16])
+@pytest.mark.parametrize("shape", ["tiny", "tiny_qwen"])
+def test_qkv_weight_tiles_of_fewer_rotation_pairs(oracle, gpu, monkeypatch, rows, shape):
+    """The QKV matrices packed in tiles of 8 / 12 / 16 rotation pairs (12 is what the library picks
+    at the 8B and Qwen2-7B widths, 16 for small models), bf16, with and without QKV bias; tiles of 12
+    straddle head boundaries and leave a ragged last tile."""
+    monkeypatch.setenv("EASYSPEC_QKV_TILE_ROWS", str(rows))
+    cfg = synth.model_shape(shape, dtype="bf16")
+    one_iteration(oracle, gpu, cfg, 580 + rows, [0, 1, 3, cfg["n_layers"]], 40, 4, accept=2)
+
+
 @pytest.mark.parametrize("N", [2, 4, 7])
 def test_qwen2_7b_layer_shape_reduced_depth(oracle, gpu, N):
     """Qwen2-7B layer shape (7 query heads per KV head, QKV bias), 9 layers, group sizes 2/4/7,
