@@ -394,8 +394,8 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
 // S^T tiles so that lane (row r, quarter q) ends up with the 16 CONSECUTIVE slots q*16 .. q*16+15:
 // the accumulator layout of S^T is then the B-operand layout of the P.V instruction, and a
 // V^T fragment is 8 consecutive slots.  V is stored [slot][head_dim]; a wave transposes its
-// 64 x head_dim tile through its own piece of LDS (XOR-swizzled pieces: conflict-free 2-byte
-// gathers).  grid = (ceil(sub-chunks / waves), Hkv, k * groups), block = 64 * waves.
+// 64 x head_dim tile through its own piece of LDS (XOR-swizzled pieces, read back with the
+// transposing LDS read).  grid = (ceil(sub-chunks / waves), Hkv, k * groups), block = 64 * waves.
 // ------------------------------------------------------------------------------------------
 struct ColGroups {
   int32_t n;                // groups
