@@ -57,23 +57,34 @@ struct Tr<bf16_t> {
 // consumer both know:
 //   up to kPlainCols columns: plain rows, x[col][k] at col * K + k.  A wave's B fragments of one
 //     k-tile are then one 64-byte run per column: the fewest cache lines for one or two columns.
-//   more columns: 1 KB tiles of KT consecutive k, inside a tile [k-group (4)][column (16)][EPL
-//     elements] — the order in which the 64 lanes of a wave take their 16-byte fragments (lane =
-//     k-group * 16 + column) — so that a fragment load is one contiguous run per k-group and part
-//     instead of one cache line per column (measured: 6-column calibration 7 % faster, 8-wide tree
-//     level 12 %; with one column the tiles would touch four times the lines of plain rows).
+//   more columns: tiles of KT consecutive k, inside a tile [k-group (4)][column (pitch)][EPL
+//     elements] — the order in which the lanes of a wave take their 16-byte fragments (lane =
+//     k-group * 16 + column) — so that the fragment loads of one k-tile and part are contiguous
+//     runs instead of one cache line per column (measured: 6-column calibration 7 % faster, 8-wide
+//     tree level 12 %; with one column the tiles would touch four times the lines of plain rows).
+//     The pitch follows the column count (xpitch): what these loads cost is the number of 128-byte
+//     lines a wave asks the L2 for, and a 4-column pass with a pitch of 16 touches four half-used
+//     lines per k-tile and part where a pitch of 4 touches two.
 constexpr int kPlainCols = 2;
 
+// 16-byte fragments per k-group of a tile: the column count rounded up to an even number (tiles
+// are then whole 128-byte lines), except that 7, 8, 15 and 16 columns keep 16, where packing
+// saves no line and costs the spread over 256-byte blocks
+__device__ __forceinline__ int xpitch(int ncols) {
+  const int even = (ncols + 1) & ~1;
+  return (even & 7) == 0 ? kMaxCols : even;
+}
 template <typename T>
 __device__ __forceinline__ size_t xoff(int ncols, int K, int col, int k) {
   constexpr int EPL = Tr<T>::EPL, KT = Tr<T>::KT;
   if (ncols <= kPlainCols) return (size_t)col * K + k;
-  return (size_t)(k / KT) * (kMaxCols * KT) + (size_t)((k % KT) / EPL) * (kMaxCols * EPL) + col * EPL + (k % EPL);
+  const int pitch = xpitch(ncols);
+  return (size_t)(k / KT) * (pitch * KT) + (size_t)((k % KT) / EPL) * (pitch * EPL) + col * EPL + (k % EPL);
 }
 // u32x4 between the fragments of consecutive k-tiles
 template <typename T>
 __device__ __forceinline__ int xtile_stride(int ncols) {
-  return ncols <= kPlainCols ? 4 : 64;
+  return ncols <= kPlainCols ? 4 : 4 * xpitch(ncols);
 }
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
