@@ -28,72 +28,93 @@ struct QkvArgs {
   float inv_d, eps;
 };
 
-template <typename T, int NB>
-__global__ __launch_bounds__(1024) void qkv_kernel(QkvArgs a, Cols c) {
+// TP: tiles of R pairs per workgroup (two where a pass loads two fragments per k-tile, as for gate/up)
+template <typename T, int NB, int TP>
+__global__ __launch_bounds__(TP == 1 ? 1024 : 512) void qkv_kernel(QkvArgs a, Cols c) {
   __shared__ float s_rstd[kMaxCols];
   const int KT = Tr<T>::KT;
   const int nkt = a.d / KT;
   const int half = a.hd / 2;
-  const int R = a.R, n_pairs = (a.Hq + 2 * a.Hkv) * half, units = (n_pairs + R - 1) / R;
-  const int li = blockIdx.x / units, u = blockIdx.x % units;
+  const int R = a.R, n_pairs = (a.Hq + 2 * a.Hkv) * half, units = (n_pairs + R - 1) / R, nwg = (units + TP - 1) / TP;
+  const int li = blockIdx.x / nwg, u0 = (blockIdx.x % nwg) * TP;
   const u32x4* wl = a.w + (size_t)li * a.w_layer_stride;
-  const u32x4* const w[2] = {wl + (size_t)u * nkt * (4 * R), wl + (size_t)(units + u) * nkt * (4 * R)};
+  const u32x4* w[2 * TP];
+#pragma unroll
+  for (int p = 0; p < TP; ++p) {
+    const int u = min(u0 + p, units - 1);  // a missing last tile re-reads its neighbour (results dropped)
+    w[2 * p] = wl + (size_t)u * nkt * (4 * R);
+    w[2 * p + 1] = wl + (size_t)(units + u) * nkt * (4 * R);
+  }
   const T* x = reinterpret_cast<const T*>(a.x) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.d;
   // operands of the epilogue (wave 0 only) and of the norm scale are fetched before the weight
   // stream starts, so that their latency does not sit in the tail of the kernel
   const int lane = threadIdx.x & 63, col = lane & 15;
-  const int row0 = (lane >> 4) * 4;       // of the tile
-  const int pair0 = u * R + row0;         // first of the lane's four pairs
-  const bool rows_ok = row0 < R && pair0 < n_pairs;
-  const int head = rows_ok ? pair0 / half : 0;
-  const int e0 = rows_ok ? pair0 % half : 0;  // element inside the head, < hd/2
+  const int row0 = (lane >> 4) * 4;  // of the tile
   const int RQKV = (a.Hq + 2 * a.Hkv) * a.hd;
-  const bool epi = threadIdx.x < 64 && col < c.n && rows_ok;
-  const int pos = epi ? c.pos[col] : 0, seq = epi ? c.seq[col] : 0;
-  f32x4 b_lo = {0.f, 0.f, 0.f, 0.f}, b_hi = {0.f, 0.f, 0.f, 0.f}, cs01 = {1.f, 0.f, 1.f, 0.f}, cs23 = {1.f, 0.f, 1.f, 0.f};
-  if (epi) {
-    if (a.bias) {
-      b_lo = *reinterpret_cast<const f32x4*>(a.bias + (size_t)li * RQKV + head * a.hd + e0);
-      b_hi = *reinterpret_cast<const f32x4*>(a.bias + (size_t)li * RQKV + head * a.hd + e0 + half);
-    }
-    if (head < a.Hq + a.Hkv) {
-      const f32x4* rp = reinterpret_cast<const f32x4*>(a.rope + (size_t)c.rope_pos[col] * half + e0);  // 4 x (cos, sin)
-      cs01 = rp[0];
-      cs23 = rp[1];
+  const bool col_ok = threadIdx.x < 64 && col < c.n;
+  const int pos = col_ok ? c.pos[col] : 0, seq = col_ok ? c.seq[col] : 0;
+  bool rows_ok[TP];
+  int head[TP], e0[TP];
+  f32x4 b_lo[TP], b_hi[TP], cs01[TP], cs23[TP];
+#pragma unroll
+  for (int p = 0; p < TP; ++p) {
+    const int pair0 = (u0 + p) * R + row0;  // first of the lane's four pairs
+    rows_ok[p] = u0 + p < units && row0 < R && pair0 < n_pairs;
+    head[p] = rows_ok[p] ? pair0 / half : 0;
+    e0[p] = rows_ok[p] ? pair0 % half : 0;  // element inside the head, < hd/2
+    b_lo[p] = b_hi[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+    cs01[p] = cs23[p] = f32x4{1.f, 0.f, 1.f, 0.f};
+    if (col_ok && rows_ok[p]) {
+      if (a.bias) {
+        b_lo[p] = *reinterpret_cast<const f32x4*>(a.bias + (size_t)li * RQKV + head[p] * a.hd + e0[p]);
+        b_hi[p] = *reinterpret_cast<const f32x4*>(a.bias + (size_t)li * RQKV + head[p] * a.hd + e0[p] + half);
+      }
+      if (head[p] < a.Hq + a.Hkv) {
+        const f32x4* rp = reinterpret_cast<const f32x4*>(a.rope + (size_t)c.rope_pos[col] * half + e0[p]);  // 4 x (cos, sin)
+        cs01[p] = rp[0];
+        cs23[p] = rp[1];
+      }
     }
   }
   RstdPre pre;
   rstd_issue(a.ssp, a.d / 16, c.n, pre);
 
-  f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-  // a tile of R < 16 pairs: the lanes of the missing rows re-read the last row (their results are dropped)
-  gemm_accumulate<T, 2, NB>(w, x, a.d, c.n, acc, (lane >> 4) * R + min(lane & 15, R - 1), 4 * R);
-  rstd_finish(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
-  if (!reduce_waves<2>(acc, dyn_red)) return;
-  fold_columns<T, 2>(acc, c.n);
-
-  if (col >= c.n || !rows_ok) return;
-  const float r = s_rstd[col];
-  const float cosv[4] = {cs01[0], cs01[2], cs23[0], cs23[2]}, sinv[4] = {cs01[1], cs01[3], cs23[1], cs23[3]};
-  float lo[4], hi[4];
+  f32x4 acc[2 * TP];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    // identity rotation (cos 1, sin 0) for the V rows; bias 0 without bias
-    const float v0 = acc[0][i] * r + b_lo[i], v1 = acc[1][i] * r + b_hi[i];
-    lo[i] = v0 * cosv[i] - v1 * sinv[i];
-    hi[i] = v1 * cosv[i] + v0 * sinv[i];
-  }
-  if (head < a.Hq) {
-    float* q = a.q + ((size_t)li * kMaxCols + col) * (a.Hq * a.hd) + head * a.hd + e0;
-    store4<float>(q, lo[0], lo[1], lo[2], lo[3]);
-    store4<float>(q + half, hi[0], hi[1], hi[2], hi[3]);
-  } else {
-    const bool is_k = head < a.Hq + a.Hkv;
-    const int kvh = is_k ? head - a.Hq : head - a.Hq - a.Hkv;
-    T* base = reinterpret_cast<T*>(is_k ? a.kc : a.vc);
-    T* row = base + ((((size_t)(a.layer0 + li) * a.B + seq) * a.Hkv + kvh) * a.max_ctx + pos) * a.hd + e0;
-    store4<T>(row, lo[0], lo[1], lo[2], lo[3]);
-    store4<T>(row + half, hi[0], hi[1], hi[2], hi[3]);
+  for (int p = 0; p < 2 * TP; ++p) acc[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+  // a tile of R < 16 pairs: the lanes of the missing rows re-read the last row (their results are dropped)
+  const u32x4* const(&wc)[2 * TP] = w;
+  gemm_accumulate<T, 2 * TP, NB>(wc, x, a.d, c.n, acc, (lane >> 4) * R + min(lane & 15, R - 1), 4 * R);
+  rstd_finish(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
+  if (!reduce_waves<2 * TP>(acc, dyn_red)) return;
+  fold_columns<T, 2 * TP>(acc, c.n);
+
+  if (col >= c.n) return;
+  const float r = s_rstd[col];
+#pragma unroll
+  for (int p = 0; p < TP; ++p) {
+    if (!rows_ok[p]) continue;
+    const float cosv[4] = {cs01[p][0], cs01[p][2], cs23[p][0], cs23[p][2]}, sinv[4] = {cs01[p][1], cs01[p][3], cs23[p][1], cs23[p][3]};
+    float lo[4], hi[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      // identity rotation (cos 1, sin 0) for the V rows; bias 0 without bias
+      const float v0 = acc[2 * p][i] * r + b_lo[p][i], v1 = acc[2 * p + 1][i] * r + b_hi[p][i];
+      lo[i] = v0 * cosv[i] - v1 * sinv[i];
+      hi[i] = v1 * cosv[i] + v0 * sinv[i];
+    }
+    if (head[p] < a.Hq) {
+      float* q = a.q + ((size_t)li * kMaxCols + col) * (a.Hq * a.hd) + head[p] * a.hd + e0[p];
+      store4<float>(q, lo[0], lo[1], lo[2], lo[3]);
+      store4<float>(q + half, hi[0], hi[1], hi[2], hi[3]);
+    } else {
+      const bool is_k = head[p] < a.Hq + a.Hkv;
+      const int kvh = is_k ? head[p] - a.Hq : head[p] - a.Hq - a.Hkv;
+      T* base = reinterpret_cast<T*>(is_k ? a.kc : a.vc);
+      T* row = base + ((((size_t)(a.layer0 + li) * a.B + seq) * a.Hkv + kvh) * a.max_ctx + pos) * a.hd + e0[p];
+      store4<T>(row, lo[0], lo[1], lo[2], lo[3]);
+      store4<T>(row + half, hi[0], hi[1], hi[2], hi[3]);
+    }
   }
 }
 
@@ -118,50 +139,67 @@ struct ProjArgs {
   float* ssp;
 };
 
-template <typename T, int NB>
+// TP: row tiles per workgroup (two for the stacked O launches of two-fragment passes, as for gate/up)
+template <typename T, int NB, int TP>
 __global__ __launch_bounds__(1024) void proj_resid_kernel(ProjArgs a, Cols c) {
   const int KT = Tr<T>::KT;
   const int nkt = a.K / KT;
-  const int ntile = a.d / 16;
-  const int li = blockIdx.x / ntile, t = blockIdx.x % ntile;
-  const u32x4* const w[1] = {a.w + (size_t)li * a.w_layer_stride + (size_t)t * nkt * 64};
+  const int ntile = a.d / 16, nwg = (ntile + TP - 1) / TP;
+  const int li = blockIdx.x / nwg, t0 = (blockIdx.x % nwg) * TP;
+  const u32x4* w[TP];
+#pragma unroll
+  for (int p = 0; p < TP; ++p)  // a missing last tile re-reads its neighbour (results dropped)
+    w[p] = a.w + (size_t)li * a.w_layer_stride + (size_t)min(t0 + p, ntile - 1) * nkt * 64;
   const T* x = reinterpret_cast<const T*>(a.x) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.K;
   // residual-update operands (wave 0 of a layer-0 workgroup) are fetched before the weight stream
   const int lane = threadIdx.x & 63, col = lane & 15;
   const bool ok = col < c.n;
-  const int r0 = t * 16 + (lane >> 4) * 4;
-  f32x4 h_in = {0.f, 0.f, 0.f, 0.f}, a_in = {0.f, 0.f, 0.f, 0.f}, g_in = {0.f, 0.f, 0.f, 0.f};
-  if (threadIdx.x < 64 && li == 0 && ok) {
-    h_in = *reinterpret_cast<const f32x4*>(a.H + (size_t)col * a.d + r0);
-    if (a.a_add >= 0) a_in = *reinterpret_cast<const f32x4*>(a.A + ((size_t)a.a_add * kMaxCols + col) * a.d + r0);
-    g_in = *reinterpret_cast<const f32x4*>(a.gain + r0);
-  }
-  f32x4 acc[1] = {{0.f, 0.f, 0.f, 0.f}};
-  gemm_accumulate<T, 1, NB>(w, x, a.K, c.n, acc);
-  if (!reduce_waves<1>(acc, dyn_red)) return;
-  fold_columns<T, 1>(acc, c.n);
-
-  if (li > 0) {
-    if (ok) store4<float>(a.A + ((size_t)li * kMaxCols + col) * a.d + r0, acc[0][0], acc[0][1], acc[0][2], acc[0][3]);
-    return;
-  }
-  float ss = 0.f;
-  if (ok) {
-    float* hp = a.H + (size_t)col * a.d + r0;
-    f32x4 h = h_in;
-    h += acc[0];
-    if (a.a_add >= 0) h += a_in;
-    *reinterpret_cast<f32x4*>(hp) = h;
-    for (int j = 0; j < a.n_gain; ++j) {
-      const f32x4 g = j == 0 ? g_in : *reinterpret_cast<const f32x4*>(a.gain + (size_t)j * a.d + r0);
-      T* xo = reinterpret_cast<T*>(a.xout) + (size_t)j * Tr<T>::PARTS * kMaxCols * a.d + xoff<T>(c.n, a.d, col, r0);
-      store_act4<T>(xo, (size_t)kMaxCols * a.d, h[0] * g[0], h[1] * g[1], h[2] * g[2], h[3] * g[3]);
+  f32x4 h_in[TP], a_in[TP], g_in[TP];
+#pragma unroll
+  for (int p = 0; p < TP; ++p) {
+    h_in[p] = a_in[p] = g_in[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int r0 = (t0 + p) * 16 + (lane >> 4) * 4;
+    if (threadIdx.x < 64 && li == 0 && ok && t0 + p < ntile) {
+      h_in[p] = *reinterpret_cast<const f32x4*>(a.H + (size_t)col * a.d + r0);
+      if (a.a_add >= 0) a_in[p] = *reinterpret_cast<const f32x4*>(a.A + ((size_t)a.a_add * kMaxCols + col) * a.d + r0);
+      g_in[p] = *reinterpret_cast<const f32x4*>(a.gain + r0);
     }
-    ss = h[0] * h[0] + h[1] * h[1] + h[2] * h[2] + h[3] * h[3];
   }
-  ss += __shfl_xor(ss, 16, 64);
-  ss += __shfl_xor(ss, 32, 64);
-  if (ok && lane < 16) a.ssp[col * ntile + t] = ss;
+  f32x4 acc[TP];
+#pragma unroll
+  for (int p = 0; p < TP; ++p) acc[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const u32x4* const(&wc)[TP] = w;
+  gemm_accumulate<T, TP, NB>(wc, x, a.K, c.n, acc);
+  if (!reduce_waves<TP>(acc, dyn_red)) return;
+  fold_columns<T, TP>(acc, c.n);
+
+#pragma unroll
+  for (int p = 0; p < TP; ++p) {
+    const int t = t0 + p;
+    if (t >= ntile) break;
+    const int r0 = t * 16 + (lane >> 4) * 4;
+    if (li > 0) {
+      if (ok) store4<float>(a.A + ((size_t)li * kMaxCols + col) * a.d + r0, acc[p][0], acc[p][1], acc[p][2], acc[p][3]);
+      continue;
+    }
+    float ss = 0.f;
+    if (ok) {
+      float* hp = a.H + (size_t)col * a.d + r0;
+      f32x4 h = h_in[p];
+      h += acc[p];
+      if (a.a_add >= 0) h += a_in[p];
+      *reinterpret_cast<f32x4*>(hp) = h;
+      for (int j = 0; j < a.n_gain; ++j) {
+        const f32x4 g = j == 0 ? g_in[p] : *reinterpret_cast<const f32x4*>(a.gain + (size_t)j * a.d + r0);
+        T* xo = reinterpret_cast<T*>(a.xout) + (size_t)j * Tr<T>::PARTS * kMaxCols * a.d + xoff<T>(c.n, a.d, col, r0);
+        store_act4<T>(xo, (size_t)kMaxCols * a.d, h[0] * g[0], h[1] * g[1], h[2] * g[2], h[3] * g[3]);
+      }
+      ss = h[0] * h[0] + h[1] * h[1] + h[2] * h[2] + h[3] * h[3];
+    }
+    ss += __shfl_xor(ss, 16, 64);
+    ss += __shfl_xor(ss, 32, 64);
+    if (ok && lane < 16) a.ssp[col * ntile + t] = ss;
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -249,43 +287,59 @@ struct GateUpArgs {
   float inv_d, eps;
 };
 
-template <typename T, int NB>
+// TP: row tiles of each matrix per workgroup.  Two (four MFMA row tiles share every activation
+// fragment) halve the fragment loads per weight byte, which is what passes of many columns pay for.
+template <typename T, int NB, int TP>
 __global__ __launch_bounds__(1024) void gateup_kernel(GateUpArgs a, Cols c) {
   __shared__ float s_rstd[kMaxCols];
   const int nkt = a.d / Tr<T>::KT;
-  const int R = a.R, ntile = (a.F + R - 1) / R;
-  const int li = blockIdx.x / ntile, t = blockIdx.x % ntile;
-  const size_t wl = (size_t)li * a.w_layer_stride + (size_t)t * nkt * (4 * R);
-  const u32x4* const w[2] = {a.wg + wl, a.wu + wl};
+  const int R = a.R, ntile = (a.F + R - 1) / R, nunit = (ntile + TP - 1) / TP;
+  const int li = blockIdx.x / nunit, t0 = (blockIdx.x % nunit) * TP;
+  const u32x4* w[2 * TP];
+#pragma unroll
+  for (int p = 0; p < TP; ++p) {
+    const int t = min(t0 + p, ntile - 1);  // a missing last tile re-reads its neighbour (results dropped)
+    const size_t wl = (size_t)li * a.w_layer_stride + (size_t)t * nkt * (4 * R);
+    w[2 * p] = a.wg + wl;
+    w[2 * p + 1] = a.wu + wl;
+  }
   const float* ssp = a.ssp + (size_t)li * kMaxCols * (a.d / 16);
   RstdPre pre;
   rstd_issue(ssp, a.d / 16, c.n, pre);
-  f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+  f32x4 acc[2 * TP];
+#pragma unroll
+  for (int p = 0; p < 2 * TP; ++p) acc[p] = f32x4{0.f, 0.f, 0.f, 0.f};
   // a tile of R < 16 rows: the lanes of the missing rows re-read the last row (their results are dropped)
   const int m = threadIdx.x & 15, kg = (threadIdx.x & 63) >> 4;
-  gemm_accumulate<T, 2, NB>(w, reinterpret_cast<const T*>(a.x) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.d, a.d, c.n, acc,
-                            kg * R + min(m, R - 1), 4 * R);
+  const u32x4* const(&wc)[2 * TP] = w;
+  gemm_accumulate<T, 2 * TP, NB>(wc, reinterpret_cast<const T*>(a.x) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.d, a.d, c.n, acc,
+                                 kg * R + min(m, R - 1), 4 * R);
   rstd_finish(ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
-  if (!reduce_waves<2>(acc, dyn_red)) return;
-  fold_columns<T, 2>(acc, c.n);
+  if (!reduce_waves<2 * TP>(acc, dyn_red)) return;
+  fold_columns<T, 2 * TP>(acc, c.n);
   const int lane = threadIdx.x & 63, col = lane & 15;
   if (col >= c.n) return;
   const float r = s_rstd[col];
-  float o[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const float g = acc[0][i] * r, u = acc[1][i] * r;
-    o[i] = (g / (1.0f + expf(-g))) * u;
-  }
   T* dst = reinterpret_cast<T*>(a.act) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.F;
   const int row0 = (lane >> 4) * 4;  // of the tile
-  if (R == 16) {
-    store_act4<T>(dst + xoff<T>(c.n, a.F, col, t * 16 + row0), (size_t)kMaxCols * a.F, o[0], o[1], o[2], o[3]);
-  } else {
+#pragma unroll
+  for (int p = 0; p < TP; ++p) {
+    const int t = t0 + p;
+    if (t >= ntile) break;
+    float o[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int f = t * R + row0 + i;
-      if (row0 + i < R && f < a.F) store_act1<T>(dst + xoff<T>(c.n, a.F, col, f), (size_t)kMaxCols * a.F, o[i]);
+      const float g = acc[2 * p][i] * r, u = acc[2 * p + 1][i] * r;
+      o[i] = (g / (1.0f + expf(-g))) * u;
+    }
+    if (R == 16) {
+      store_act4<T>(dst + xoff<T>(c.n, a.F, col, t * 16 + row0), (size_t)kMaxCols * a.F, o[0], o[1], o[2], o[3]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int f = t * R + row0 + i;
+        if (row0 + i < R && f < a.F) store_act1<T>(dst + xoff<T>(c.n, a.F, col, f), (size_t)kMaxCols * a.F, o[i]);
+      }
     }
   }
 }
@@ -306,43 +360,54 @@ struct HeadArgs {
 
 __device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
 
-template <typename T, int NB>
+// TP: row tiles per workgroup (as for gate/up: more than one where a pass loads two fragments per k-tile)
+template <typename T, int NB, int TP>
 __global__ __launch_bounds__(1024) void head_kernel(HeadArgs a, Cols c) {
   __shared__ float s_rstd[kMaxCols];
   const int nkt = a.d / Tr<T>::KT;
-  const int t = blockIdx.x;
-  const u32x4* const w[1] = {a.w + (size_t)t * nkt * 64};
+  const int t0 = blockIdx.x * TP;
+  const u32x4* w[TP];
+#pragma unroll
+  for (int p = 0; p < TP; ++p) w[p] = a.w + (size_t)min(t0 + p, a.nblk - 1) * nkt * 64;  // a missing tile re-reads the last one
   RstdPre pre;
   rstd_issue(a.ssp, a.d / 16, c.n, pre);
-  f32x4 acc[1] = {{0.f, 0.f, 0.f, 0.f}};
-  gemm_accumulate<T, 1, NB>(w, reinterpret_cast<const T*>(a.x), a.d, c.n, acc);
+  f32x4 acc[TP];
+#pragma unroll
+  for (int p = 0; p < TP; ++p) acc[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const u32x4* const(&wc)[TP] = w;
+  gemm_accumulate<T, TP, NB>(wc, reinterpret_cast<const T*>(a.x), a.d, c.n, acc);
   rstd_finish(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
-  if (!reduce_waves<1>(acc, dyn_red)) return;
-  fold_columns<T, 1>(acc, c.n);
+  if (!reduce_waves<TP>(acc, dyn_red)) return;
+  fold_columns<T, TP>(acc, c.n);
   const int lane = threadIdx.x & 63, col = lane & 15;
   const bool ok = col < c.n;
   const float r = ok ? s_rstd[col] : 0.f;
-  const int r0 = t * 16 + (lane >> 4) * 4;
-  float bv = -INFINITY;
-  int bi = 0x7FFFFFFF;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int row = r0 + i;
-    const float v = acc[0][i] * r;
-    if (ok && row < a.V) {
-      if (a.logits && c.logit_row[col] >= 0) a.logits[(size_t)c.logit_row[col] * a.V + row] = v;
-      if (better(v, row, bv, bi)) { bv = v; bi = row; }
+  for (int p = 0; p < TP; ++p) {
+    const int t = t0 + p;
+    if (t >= a.nblk) break;
+    const int r0 = t * 16 + (lane >> 4) * 4;
+    float bv = -INFINITY;
+    int bi = 0x7FFFFFFF;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = r0 + i;
+      const float v = acc[p][i] * r;
+      if (ok && row < a.V) {
+        if (a.logits && c.logit_row[col] >= 0) a.logits[(size_t)c.logit_row[col] * a.V + row] = v;
+        if (better(v, row, bv, bi)) { bv = v; bi = row; }
+      }
     }
-  }
 #pragma unroll
-  for (int off = 16; off <= 32; off <<= 1) {
-    const float ov = __shfl_xor(bv, off, 64);
-    const int oi = __shfl_xor(bi, off, 64);
-    if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-  }
-  if (ok && lane < 16) {
-    a.cand_val[(size_t)col * a.nblk + t] = bv;
-    a.cand_idx[(size_t)col * a.nblk + t] = bi;
+    for (int off = 16; off <= 32; off <<= 1) {
+      const float ov = __shfl_xor(bv, off, 64);
+      const int oi = __shfl_xor(bi, off, 64);
+      if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+    }
+    if (ok && lane < 16) {
+      a.cand_val[(size_t)col * a.nblk + t] = bv;
+      a.cand_idx[(size_t)col * a.nblk + t] = bi;
+    }
   }
 }
 
@@ -499,12 +564,19 @@ void launch_qkv(const Shape& s, const Buffers& b, const Cols& c, int layer0, int
   a.layer0 = layer0; a.d = s.d; a.Hq = s.Hq; a.Hkv = s.Hkv; a.hd = s.hd; a.B = s.B; a.max_ctx = s.max_ctx;
   a.R = s.R_qkv;
   a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
-  const int grid = n_set * ((s.RQKV / 2 + s.R_qkv - 1) / s.R_qkv);
+  const int units = (s.RQKV / 2 + s.R_qkv - 1) / s.R_qkv;
+  const int grid = n_set * units;
   const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
   // few workgroups (a set of one layer): more waves per workgroup
   const int nw = pick_waves(grid < 512 ? 8 : 4, nkt, "EASYSPEC_NW_QKV");
-  DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
-               hipLaunchKernelGGL((qkv_kernel<T, NB>), dim3(grid), dim3(64 * nw), red_bytes(nw, 2), st, a, c));
+  if (two_fragments(s.dtype, c)) {
+    // two tiles per workgroup share every fragment load (12-wide tree level 3292 -> 3282 us)
+    const int grid2 = n_set * ((units + 1) / 2);
+    const int nw2 = nw > 8 ? 8 : nw;  // the instantiation is built for at most 8 waves
+    hipLaunchKernelGGL((qkv_kernel<bf16_t, 2, 2>), dim3(grid2), dim3(64 * nw2), red_bytes(nw2, 4), st, a, c);
+    return;
+  }
+  DISPATCH_T(s.dtype, hipLaunchKernelGGL((qkv_kernel<T, 1, 1>), dim3(grid), dim3(64 * nw), red_bytes(nw, 2), st, a, c));
 }
 
 void launch_oproj(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st) {
@@ -522,8 +594,15 @@ void launch_oproj(const Shape& s, const Buffers& b, const Cols& c, int layer0, i
   const int grid = n_set * (s.d / 16);
   const int nkt = s.HQ / (s.dtype == 1 ? 32 : 16);
   const int nw = pick_waves(grid < 512 ? 8 : 4, nkt, "EASYSPEC_NW_O");
+  if (two_fragments(s.dtype, c) && n_set > 1) {
+    // stacked launches of a two-fragment pass: two row tiles per workgroup share every fragment load
+    // (12-wide tree level 3284 -> 3259 us)
+    const int grid2 = n_set * ((s.d / 16 + 1) / 2);
+    hipLaunchKernelGGL((proj_resid_kernel<bf16_t, 2, 2>), dim3(grid2), dim3(64 * nw), red_bytes(nw, 2), st, a, c);
+    return;
+  }
   DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
-               hipLaunchKernelGGL((proj_resid_kernel<T, NB>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+               hipLaunchKernelGGL((proj_resid_kernel<T, NB, 1>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
 }
 
 void launch_gateup(const Shape& s, const Buffers& b, const Cols& c, int layer, int n_layers, const float* ssp, hipStream_t st) {
@@ -534,11 +613,19 @@ void launch_gateup(const Shape& s, const Buffers& b, const Cols& c, int layer, i
   a.w_layer_stride = stride;
   a.x = b.XM; a.ssp = ssp; a.act = b.ACT; a.d = s.d; a.F = s.F; a.R = s.R_ffn;
   a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
-  const int grid = n_layers * ((s.F + s.R_ffn - 1) / s.R_ffn);
+  const int ntile = (s.F + s.R_ffn - 1) / s.R_ffn;
   const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
   const int nw = pick_waves(8, nkt, "EASYSPEC_NW_GU");
-  DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
-               hipLaunchKernelGGL((gateup_kernel<T, NB>), dim3(grid), dim3(64 * nw), red_bytes(nw, 2), st, a, c));
+  if (two_fragments(s.dtype, c)) {
+    // two fragments per k-tile: two row tiles of each matrix per workgroup, so that four MFMA row tiles
+    // share every fragment load (measured: 12-wide tree level 3402 -> 3322 us; with one fragment the
+    // larger workgroups lose: 6-token calibration 3377 -> 3411 us, draft step 2676 -> 2731 us)
+    const int grid = n_layers * ((ntile + 1) / 2);
+    hipLaunchKernelGGL((gateup_kernel<bf16_t, 2, 2>), dim3(grid), dim3(64 * nw), red_bytes(nw, 4), st, a, c);
+    return;
+  }
+  const int grid = n_layers * ntile;
+  DISPATCH_T(s.dtype, hipLaunchKernelGGL((gateup_kernel<T, 1, 1>), dim3(grid), dim3(64 * nw), red_bytes(nw, 2), st, a, c));
 }
 
 void launch_down(const Shape& s, const Buffers& b, const Cols& c, int layer, int a_next, const float* gain, int n_gain,
@@ -560,7 +647,7 @@ void launch_down(const Shape& s, const Buffers& b, const Cols& c, int layer, int
   const bool seven = !two_fragments(s.dtype, c) && nkt % 56 == 0;
   const int nw = pick_waves(seven ? 7 : 8, nkt, "EASYSPEC_NW_DOWN");
   DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
-               hipLaunchKernelGGL((proj_resid_kernel<T, NB>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+               hipLaunchKernelGGL((proj_resid_kernel<T, NB, 1>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
 }
 
 void launch_oproj_full(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st) {
@@ -607,8 +694,12 @@ void launch_head(const Shape& s, const Buffers& b, const Cols& c, float* logits_
   a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
   const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
   const int nw = pick_waves(4, nkt, "EASYSPEC_NW_HEAD");
-  DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
-               hipLaunchKernelGGL((head_kernel<T, NB>), dim3(a.nblk), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+  if (two_fragments(s.dtype, c)) {
+    // two row tiles per workgroup share every fragment load (12-wide tree level 3309 -> 3276 us; four: the same)
+    hipLaunchKernelGGL((head_kernel<bf16_t, 2, 2>), dim3((a.nblk + 1) / 2), dim3(64 * nw), red_bytes(nw, 2), st, a, c);
+  } else {
+    DISPATCH_T(s.dtype, hipLaunchKernelGGL((head_kernel<T, 1, 1>), dim3(a.nblk), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+  }
   hipLaunchKernelGGL(argmax_final_kernel, dim3(c.n), dim3(1024), 0, st, a.cand_val, a.cand_idx, a.nblk, tokens_out, c);
 }
 

@@ -94,14 +94,16 @@ def test_llama3_8b_layer_shape_reduced_depth(oracle, gpu):
 
 
 @pytest.mark.parametrize("rows", [13, 15])
-@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
-def test_gate_up_weight_tiles_of_fewer_rows(oracle, gpu, monkeypatch, rows, dtype):
+@pytest.mark.parametrize("dtype,accept", [("fp32", 2), ("bf16", 2), ("bf16", 10)])
+def test_gate_up_weight_tiles_of_fewer_rows(oracle, gpu, monkeypatch, rows, dtype, accept):
     """The gate and up matrices packed in tiles of 13 / 15 rows instead of 16 (what the library picks
     by itself when that evens out the workgroups per CU: 14 rows at the 8B width, 15 at Qwen2-7B's):
-    1024 rows leave a ragged last tile either way."""
+    1024 rows leave a ragged last tile either way.  The 11-token calibration of the last case takes
+    the two-fragment kernel, whose workgroups hold two row tiles of each matrix: 79 and 69 tiles leave
+    the last workgroup with one."""
     monkeypatch.setenv("EASYSPEC_TILE_ROWS", str(rows))
     cfg = synth.model_shape("tiny", dtype=dtype)
-    one_iteration(oracle, gpu, cfg, 560 + rows, [0, 1, 3, 4], 40, 4, accept=2)
+    one_iteration(oracle, gpu, cfg, 560 + rows, [0, 1, 3, 4], 40, accept + 2, accept=accept)
 
 
 @pytest.mark.parametrize("rows", [8, 12, 16])
