@@ -569,14 +569,16 @@ void launch_qkv(const Shape& s, const Buffers& b, const Cols& c, int layer0, int
   const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
   // few workgroups (a set of one layer): more waves per workgroup
   const int nw = pick_waves(grid < 512 ? 8 : 4, nkt, "EASYSPEC_NW_QKV");
-  if (two_fragments(s.dtype, c)) {
-    // two tiles per workgroup share every fragment load (12-wide tree level 3292 -> 3282 us)
+  if (two_fragments(s.dtype, c) && n_set > 1) {
+    // stacked launches: two tiles per workgroup share every fragment load (12-wide tree level 3292 -> 3282 us);
+    // a single layer keeps one tile per workgroup, which fills the CUs
     const int grid2 = n_set * ((units + 1) / 2);
     const int nw2 = nw > 8 ? 8 : nw;  // the instantiation is built for at most 8 waves
     hipLaunchKernelGGL((qkv_kernel<bf16_t, 2, 2>), dim3(grid2), dim3(64 * nw2), red_bytes(nw2, 4), st, a, c);
     return;
   }
-  DISPATCH_T(s.dtype, hipLaunchKernelGGL((qkv_kernel<T, 1, 1>), dim3(grid), dim3(64 * nw), red_bytes(nw, 2), st, a, c));
+  DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
+               hipLaunchKernelGGL((qkv_kernel<T, NB, 1>), dim3(grid), dim3(64 * nw), red_bytes(nw, 2), st, a, c));
 }
 
 void launch_oproj(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st) {
