@@ -569,9 +569,8 @@ void launch_qkv(const Shape& s, const Buffers& b, const Cols& c, int layer0, int
   const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
   // few workgroups (a set of one layer): more waves per workgroup
   const int nw = pick_waves(grid < 512 ? 8 : 4, nkt, "EASYSPEC_NW_QKV");
-  if (two_fragments(s.dtype, c) && n_set > 1) {
-    // stacked launches: two tiles per workgroup share every fragment load (12-wide tree level 3292 -> 3282 us);
-    // a single layer keeps one tile per workgroup, which fills the CUs
+  if (pair_tiles(s.dtype, c, grid)) {
+    // two tiles per workgroup share every fragment load (12-wide tree level 3292 -> 3282 us)
     const int grid2 = n_set * ((units + 1) / 2);
     const int nw2 = nw > 8 ? 8 : nw;  // the instantiation is built for at most 8 waves
     hipLaunchKernelGGL((qkv_kernel<bf16_t, 2, 2>), dim3(grid2), dim3(64 * nw2), red_bytes(nw2, 4), st, a, c);
@@ -596,9 +595,8 @@ void launch_oproj(const Shape& s, const Buffers& b, const Cols& c, int layer0, i
   const int grid = n_set * (s.d / 16);
   const int nkt = s.HQ / (s.dtype == 1 ? 32 : 16);
   const int nw = pick_waves(grid < 512 ? 8 : 4, nkt, "EASYSPEC_NW_O");
-  if (two_fragments(s.dtype, c) && n_set > 1) {
-    // stacked launches of a two-fragment pass: two row tiles per workgroup share every fragment load
-    // (12-wide tree level 3284 -> 3259 us)
+  if (pair_tiles(s.dtype, c, grid)) {
+    // two row tiles per workgroup share every fragment load (12-wide tree level 3284 -> 3259 us)
     const int grid2 = n_set * ((s.d / 16 + 1) / 2);
     hipLaunchKernelGGL((proj_resid_kernel<bf16_t, 2, 2>), dim3(grid2), dim3(64 * nw), red_bytes(nw, 2), st, a, c);
     return;
@@ -618,7 +616,7 @@ void launch_gateup(const Shape& s, const Buffers& b, const Cols& c, int layer, i
   const int ntile = (s.F + s.R_ffn - 1) / s.R_ffn;
   const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
   const int nw = pick_waves(8, nkt, "EASYSPEC_NW_GU");
-  if (two_fragments(s.dtype, c)) {
+  if (pair_tiles(s.dtype, c, n_layers * ntile)) {
     // two fragments per k-tile: two row tiles of each matrix per workgroup, so that four MFMA row tiles
     // share every fragment load (measured: 12-wide tree level 3402 -> 3322 us; with one fragment the
     // larger workgroups lose: 6-token calibration 3377 -> 3411 us, draft step 2676 -> 2731 us)
@@ -627,7 +625,8 @@ void launch_gateup(const Shape& s, const Buffers& b, const Cols& c, int layer, i
     return;
   }
   const int grid = n_layers * ntile;
-  DISPATCH_T(s.dtype, hipLaunchKernelGGL((gateup_kernel<T, 1, 1>), dim3(grid), dim3(64 * nw), red_bytes(nw, 2), st, a, c));
+  DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
+               hipLaunchKernelGGL((gateup_kernel<T, NB, 1>), dim3(grid), dim3(64 * nw), red_bytes(nw, 2), st, a, c));
 }
 
 void launch_down(const Shape& s, const Buffers& b, const Cols& c, int layer, int a_next, const float* gain, int n_gain,
@@ -696,11 +695,12 @@ void launch_head(const Shape& s, const Buffers& b, const Cols& c, float* logits_
   a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
   const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
   const int nw = pick_waves(4, nkt, "EASYSPEC_NW_HEAD");
-  if (two_fragments(s.dtype, c)) {
+  if (pair_tiles(s.dtype, c, a.nblk)) {
     // two row tiles per workgroup share every fragment load (12-wide tree level 3309 -> 3276 us; four: the same)
     hipLaunchKernelGGL((head_kernel<bf16_t, 2, 2>), dim3((a.nblk + 1) / 2), dim3(64 * nw), red_bytes(nw, 2), st, a, c);
   } else {
-    DISPATCH_T(s.dtype, hipLaunchKernelGGL((head_kernel<T, 1, 1>), dim3(a.nblk), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+    DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
+                 hipLaunchKernelGGL((head_kernel<T, NB, 1>), dim3(a.nblk), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
   }
   hipLaunchKernelGGL(argmax_final_kernel, dim3(c.n), dim3(1024), 0, st, a.cand_val, a.cand_idx, a.nblk, tokens_out, c);
 }

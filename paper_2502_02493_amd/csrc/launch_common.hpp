@@ -26,6 +26,28 @@ static inline size_t red_bytes(int nw, int rt) { return (size_t)(nw > 1 ? nw - 1
 // bf16 with more than 8 columns: hi and lo activation terms take a fragment each
 static inline bool two_fragments(int dtype, const Cols& c) { return dtype == 1 && 2 * c.n > kMaxCols; }
 
+static inline int cu_count() {
+  static const int n_cu = [] {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+    return n;
+  }();
+  return n_cu;
+}
+
+// Two-fragment passes: may the workgroups of a launch of n one-tile workgroups take two row tiles each
+// (every activation fragment load then serves twice the weights)?  Only where the halved launch does
+// not cost the busiest CU more tiles than before: 1024 -> 512 workgroups on 256 CUs stays at four
+// tiles per CU, 768 -> 384 would go from three to four (Qwen2-7B shape, 12-wide tree level: 3407 us
+// without pairing, 3434 us with every launch paired).
+static inline bool pair_tiles(int dtype, const Cols& c, int n) {
+  if (!two_fragments(dtype, c)) return false;
+  const int forced = env_int("EASYSPEC_PAIR_TILES", -1);  // tests (small models never fill a round): read at every call
+  if (forced >= 0) return forced != 0;
+  const int n_cu = cu_count();
+  return 2 * (((n + 1) / 2 + n_cu - 1) / n_cu) <= (n + n_cu - 1) / n_cu;
+}
+
 #define DISPATCH_TNB(dtype, two, ...)                                         \
   do {                                                                        \
     if ((dtype) == 1 && (two)) { typedef bf16_t T; constexpr int NB = 2; __VA_ARGS__; } \

@@ -102,8 +102,20 @@ def test_gate_up_weight_tiles_of_fewer_rows(oracle, gpu, monkeypatch, rows, dtyp
     the two-fragment kernel, whose workgroups hold two row tiles of each matrix: 79 and 69 tiles leave
     the last workgroup with one."""
     monkeypatch.setenv("EASYSPEC_TILE_ROWS", str(rows))
+    monkeypatch.setenv("EASYSPEC_PAIR_TILES", "1")  # the library pairs only launches that fill the CUs
     cfg = synth.model_shape("tiny", dtype=dtype)
     one_iteration(oracle, gpu, cfg, 560 + rows, [0, 1, 3, 4], 40, accept + 2, accept=accept)
+
+
+@pytest.mark.parametrize("shape", ["tiny", "tiny_qwen"])
+@pytest.mark.parametrize("pair", [0, 1])
+def test_two_fragment_passes_with_and_without_paired_tiles(oracle, gpu, monkeypatch, shape, pair):
+    """Passes of more than 8 columns (a 12-token calibration, bf16): every weight kernel with one row
+    tile per workgroup and with two (what the library takes where the halved launch still fills the
+    CUs: QKV and O of stacked sets, gate/up, LM head)."""
+    monkeypatch.setenv("EASYSPEC_PAIR_TILES", str(pair))
+    cfg = synth.model_shape(shape, dtype="bf16")
+    one_iteration(oracle, gpu, cfg, 590 + pair, [0, 1, 3, cfg["n_layers"]], 70, 13, accept=11)
 
 
 @pytest.mark.parametrize("rows", [8, 12, 16])
