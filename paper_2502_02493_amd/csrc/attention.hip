@@ -167,7 +167,7 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
 #pragma unroll
       for (int j = 0; j < N; ++j) {
         const int s = base + j * SPW + sub;
-        const bool valid = s < w1 && (!TREE || s < vbase || ((vmask >> (s - vbase)) & 1ull));
+        const bool valid = (int)(s < w1) & (int)(!TREE || (int)(s < vbase) | (int)((vmask >> ((s - vbase) & 63)) & 1ull));  // straight-line
         float kv[EPL];
         unpack<T>(kr[j], kv);
         float d[4];
@@ -216,7 +216,7 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
 #pragma unroll
     for (int j = 0; j < N; ++j) {
       const int s = base + j * SPW + sub;
-      const bool valid = s < w1 && (!TREE || s < vbase || ((vmask >> (s - vbase)) & 1ull));
+      const bool valid = (int)(s < w1) & (int)(!TREE || (int)(s < vbase) | (int)((vmask >> ((s - vbase) & 63)) & 1ull));  // straight-line
       float kv[EPL];
       unpack<T>(kr[j], kv);
 #pragma unroll
@@ -441,18 +441,20 @@ __global__ __launch_bounds__(64 * kMfmaAttnWaves) void attn_mfma_kernel(AttnArgs
   // 64 x PIECES 16-byte pieces.  The registers are free again once their contents sit in LDS, so
   // the next super tile is requested while the current one is still being worked on; the first
   // one before the queries are fetched.
-  const u32x4 zero = {0u, 0u, 0u, 0u};
+  // Loads are unconditional: a slot past the sub-chunk's end (only the last sub-chunk of the longest
+  // column has any: sub-chunks are multiples of 64 slots) re-reads the last row; its scores are masked
+  // below for every query row, so its probabilities are exact zeros.
   u32x4 kf[PIECES], vf[PIECES];
   auto request = [&](int base) {
 #pragma unroll
     for (int it = 0; it < PIECES; ++it) {
-      const int f = it * 64 + lane, sl = f / PIECES;
-      kf[it] = base + sl < ws1 ? __builtin_nontemporal_load(kc4 + (size_t)base * PIECES + f) : zero;
+      const int f = it * 64 + lane, sl = min(base + f / PIECES, ws1 - 1), piece = f % PIECES;
+      kf[it] = __builtin_nontemporal_load(kc4 + (size_t)sl * PIECES + piece);
     }
 #pragma unroll
     for (int it = 0; it < PIECES; ++it) {
-      const int f = it * 64 + lane, sl = f / PIECES;
-      vf[it] = base + sl < ws1 ? __builtin_nontemporal_load(vc + (size_t)base * PIECES + f) : zero;
+      const int f = it * 64 + lane, sl = min(base + f / PIECES, ws1 - 1), piece = f % PIECES;
+      vf[it] = __builtin_nontemporal_load(vc + (size_t)sl * PIECES + piece);
     }
   };
   request(ws0);
@@ -497,7 +499,8 @@ __global__ __launch_bounds__(64 * kMfmaAttnWaves) void attn_mfma_kernel(AttnArgs
 #pragma unroll
       for (int it = 0; it < PIECES; ++it) {
         const int f = it * 64 + lane, sl = f / PIECES, piece = f % PIECES;
-        if (((sl >> 2) & 3) == t) {  // slot sl belongs to tile t
+        // slot sl belongs to tile (sl / 4) % 4; with 16 pieces per row that is it % 4 for every lane
+        if (PIECES == 16 ? (it & 3) == t : ((sl >> 2) & 3) == t) {
           const int m = (sl >> 4) * 4 + (sl & 3);
           kt_lds[m * PIECES + (piece ^ (m & (PIECES - 1)))] = kf[it];
         }
@@ -514,7 +517,9 @@ __global__ __launch_bounds__(64 * kMfmaAttnWaves) void attn_mfma_kernel(AttnArgs
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int slot = base + q4 * 16 + t * 4 + i;
-        const bool valid = row_ok && slot < n_slots && (!TREE || slot < vbase || ((vmask >> (slot - vbase)) & 1ull));
+        // no short circuit: the shift amount is masked instead of guarded, so that this stays straight-line code
+        const bool seen = !TREE || (int)(slot < vbase) | (int)((vmask >> ((slot - vbase) & 63)) & 1ull);
+        const bool valid = (int)row_ok & (int)(slot < n_slots) & (int)seen;
         sc[t][i] = valid ? acc[i] * a.scale : -INFINITY;
       }
     }
