@@ -405,11 +405,6 @@ struct ColGroups {
 constexpr int kMfmaAttnWaves = 4;
 typedef short v4i16 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ bf16x8 pack_bf16x8(const uint32_t (&b)[8]) {
-  u32x4 v = {b[0] | (b[1] << 16), b[2] | (b[3] << 16), b[4] | (b[5] << 16), b[6] | (b[7] << 16)};
-  return __builtin_bit_cast(bf16x8, v);
-}
-
 template <int HD, bool TREE>
 __global__ __launch_bounds__(64 * kMfmaAttnWaves) void attn_mfma_kernel(AttnArgs a, Cols c, ColGroups cg, int G) {
   constexpr int KT = HD / 32, ET = HD / 16, PIECES = HD / 8;
@@ -465,15 +460,10 @@ __global__ __launch_bounds__(64 * kMfmaAttnWaves) void attn_mfma_kernel(AttnArgs
     const float* qp = a.Q + ((size_t)li * kMaxCols + col) * HQ + (kvh * G + g) * HD + q4 * 8;
 #pragma unroll
     for (int kt = 0; kt < KT; ++kt) {
-      uint32_t hb[8], lb[8];
+      float x[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float x = row_ok ? qp[kt * 32 + e] : 0.f;
-        hb[e] = float_to_bf16_bits(x);
-        lb[e] = float_to_bf16_bits(x - bf16_bits_to_float(hb[e]));
-      }
-      qh[kt] = pack_bf16x8(hb);
-      ql[kt] = pack_bf16x8(lb);
+      for (int e = 0; e < 8; ++e) x[e] = row_ok ? qp[kt * 32 + e] : 0.f;
+      split_bf16x8(x, qh[kt], ql[kt]);
     }
   }
 
@@ -536,22 +526,21 @@ __global__ __launch_bounds__(64 * kMfmaAttnWaves) void attn_mfma_kernel(AttnArgs
     const float alpha = __expf(m_run - m_ref);
     m_run = m_new;
     l_run *= alpha;
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {  // wave-uniform: once the running maxima have settled nothing is rescaled
 #pragma unroll
-    for (int et = 0; et < ET; ++et) o[et] *= alpha;
+      for (int et = 0; et < ET; ++et) o[et] *= alpha;
+    }
     // B operands of P.V: MFMA number h takes slots q4*16 + h*8 .. +8 of this lane = tiles 2h, 2h+1
     bf16x8 ph[2], pl[2];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      uint32_t hb[8], lb[8];
+      float pv[8];
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        const float pv = __expf(sc[2 * h + (j >> 2)][j & 3] - m_ref);
-        l_run += pv;
-        hb[j] = float_to_bf16_bits(pv);
-        lb[j] = float_to_bf16_bits(pv - bf16_bits_to_float(hb[j]));
+        pv[j] = __expf(sc[2 * h + (j >> 2)][j & 3] - m_ref);
+        l_run += pv[j];
       }
-      ph[h] = pack_bf16x8(hb);
-      pl[h] = pack_bf16x8(lb);
+      split_bf16x8(pv, ph[h], pl[h]);
     }
     __builtin_amdgcn_wave_barrier();
     // A operands: V^T row e = et*16 + lane%16, the 8 slots q4*16 + h*8 + j, by the LDS transposing
