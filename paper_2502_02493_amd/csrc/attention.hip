@@ -698,10 +698,10 @@ static bool attn_use_mfma(const Shape& s, const Cols& c, int n_set) {
     shared = shared || (i > 0 && c.seq[i] == c.seq[i - 1]);
     max_len = std::max(max_len, c.pos[i] + 1);
   }
-  // a launch over one layer with fewer than 6 columns keeps too few waves busy on the matrix cores (the
-  // partial buffers cap the sub-chunks at kMaxChunks): 4-token calibration at context 8192, 3835 us
-  // against 3614 us with the vector kernel; with 6 tokens 3939 against 3990 us
-  return shared && (long)n_set * c.n * max_len >= min_work && (n_set > 1 || c.n >= 6);
+  // a launch over one layer with fewer than 5 columns keeps too few waves busy on the matrix cores (the
+  // partial buffers cap the sub-chunks at kMaxChunks): 4-token calibration at context 8192, 3778 us
+  // against 3699 us with the vector kernel; with 5 tokens 3830 against 3872 us, with 6 3834 against 3999 us
+  return shared && (long)n_set * c.n * max_len >= min_work && (n_set > 1 || c.n >= 5);
 }
 
 // Runs of consecutive columns of one sequence, cut so that a group's query rows (columns x G
