@@ -3,6 +3,8 @@
 // how a launch cuts the contexts; and their launch wrappers.
 #include "launch_common.hpp"
 
+#include <limits.h>
+
 namespace es {
 
 // ------------------------------------------------------------------------------------------
@@ -416,8 +418,12 @@ __global__ __launch_bounds__(64 * kMfmaAttnWaves) void attn_mfma_kernel(AttnArgs
   const int r = lane & 15, q4 = lane >> 4;  // query row (MFMA column) and quarter / k-group
   const bool row_ok = r < cnt * G;
   const int col = first + (row_ok ? r / G : 0), g = row_ok ? r % G : 0;
-  int n_max = 0;  // slots the longest column of the group attends to
-  for (int i = 0; i < cnt; ++i) n_max = max(n_max, c.pos[first + i] + 1);
+  int n_max = 0;         // slots the longest column of the group attends to
+  int n_all = INT_MAX;   // slots below this one are visible to every column of the group
+  for (int i = 0; i < cnt; ++i) {
+    n_max = max(n_max, c.pos[first + i] + 1);
+    n_all = min(n_all, TREE ? min(c.pos[first + i] + 1, c.vis_base[first + i]) : c.pos[first + i] + 1);
+  }
   const int ws0 = chunk * a.CH;
   if (ws0 >= n_max) return;  // whole wave; nothing below synchronises across waves
   const int ws1 = min(ws0 + a.CH, n_max);
@@ -506,11 +512,16 @@ __global__ __launch_bounds__(64 * kMfmaAttnWaves) void attn_mfma_kernel(AttnArgs
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const int slot = base + q4 * 16 + t * 4 + i;
-        // no short circuit: the shift amount is masked instead of guarded, so that this stays straight-line code
-        const bool seen = !TREE || (int)(slot < vbase) | (int)((vmask >> ((slot - vbase) & 63)) & 1ull);
-        const bool valid = (int)row_ok & (int)(slot < n_slots) & (int)seen;
-        sc[t][i] = valid ? acc[i] * a.scale : -INFINITY;
+        const float v = acc[i] * a.scale;
+        if (base + 64 <= n_all) {  // wave-uniform: a super tile that every query row sees whole needs no mask
+          sc[t][i] = v;            // (padding rows get finite scores of a zero query; they are never stored)
+        } else {
+          const int slot = base + q4 * 16 + t * 4 + i;
+          // no short circuit: the shift amount is masked instead of guarded, so that this stays straight-line code
+          const bool seen = !TREE || (int)(slot < vbase) | (int)((vmask >> ((slot - vbase) & 63)) & 1ull);
+          const bool valid = (int)row_ok & (int)(slot < n_slots) & (int)seen;
+          sc[t][i] = valid ? v : -INFINITY;
+        }
       }
     }
     if (base + 64 < ws1) request(base + 64);  // both register sets are in LDS / consumed by now
