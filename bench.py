@@ -28,7 +28,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 # HBM KiB per launch of the dominant kernel (gate/up projection) from the rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs summarised in profiles/hbm_traffic_llama3_8b_ctx2048.md (scaled by a 1 GiB copy).
-MEASURED_TRAFFIC_KIB = {"llama3_8b_ctx2048": 230288.6}
+MEASURED_TRAFFIC_KIB = {"llama3_8b_ctx2048": 230288.8}
 
 
 def log(*a):
