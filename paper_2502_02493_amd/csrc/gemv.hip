@@ -11,7 +11,7 @@ namespace es {
 // pair = head * hd/2 + e, and packed as two matrices of (Hq + 2 Hkv) * hd/2 rows each (first and
 // second halves).  Unit of work: the same tile of R pairs of both, so that a pair sits in one
 // lane.  R is 16, or 12 where that fills the CUs better (qkv_tile_rows); a lane's four rows stay
-// inside one head because R and hd/2 are multiples of 4.  grid = k * ceil(pairs / R).
+// inside one head because R and hd/2 are multiples of 4.  grid = k * ceil(ceil(pairs / R) / TP).
 // ------------------------------------------------------------------------------------------
 struct QkvArgs {
   const u32x4* w;  // layer layer0
@@ -123,7 +123,7 @@ __global__ __launch_bounds__(TP == 1 ? 1024 : 512) void qkv_kernel(QkvArgs a, Co
 // launch (k > 1), or one down projection (k = 1).  Layer 0 of the launch updates the
 // residual: h = H + acc (+ Attnoutput of the next layer), writes H, the sum of squares of h
 // and T(h * gain_j) for the consumer(s) that come next; the other layers only store their
-// Attnoutput for later.  grid = k * d/16.
+// Attnoutput for later.  grid = k * ceil(d/16 / TP).
 // ------------------------------------------------------------------------------------------
 struct ProjArgs {
   const u32x4* w;
@@ -273,7 +273,7 @@ __global__ __launch_bounds__(1024) void proj_full_kernel(ProjFullArgs a, Cols c)
 // ------------------------------------------------------------------------------------------
 // Gate and up projections + SiLU(gate) * up of one layer, or of the k layers of a set each on
 // its own input (full-layer mode): layer li of the launch reads operand slot li of x with
-// partial sums slot li and writes operand slot li of act.  grid = k * F/16.
+// partial sums slot li and writes operand slot li of act.  grid = k * ceil(ceil(F / R) / TP).
 // ------------------------------------------------------------------------------------------
 struct GateUpArgs {
   const u32x4* wg;
@@ -345,7 +345,7 @@ __global__ __launch_bounds__(1024) void gateup_kernel(GateUpArgs a, Cols c) {
 }
 
 // ------------------------------------------------------------------------------------------
-// LM head: logits + per-workgroup argmax candidates (lowest index wins ties).  grid = ceil(V/16).
+// LM head: logits + argmax candidates per row tile (lowest index wins ties).  grid = ceil(ceil(V/16) / TP).
 // ------------------------------------------------------------------------------------------
 struct HeadArgs {
   const u32x4* w;
