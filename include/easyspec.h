@@ -106,7 +106,7 @@ void easyspec_destroy(easyspec_ctx *ctx);
  * Every pointer inside src is host|dev; the caller keeps src.  Synchronous. */
 int easyspec_load_weights(easyspec_ctx *ctx, const easyspec_weights *src);
 
-/* Layer-parallel strategy (Sec. 3.1.1: "a change in the configuration is enough").
+/* Layer-parallel strategy (Sec. 3.1.1: the strategy is a configuration choice, no retraining).
  * bounds (host): bounds[0] = 0 < bounds[1] < ... < bounds[n_sets] = n_layers; set j is the
  * layers [bounds[j], bounds[j+1]), at most EASYSPEC_MAX_SET of them.  Only fuzzy steps use it. */
 int easyspec_set_groups(easyspec_ctx *ctx, const int32_t *bounds, int32_t n_sets);

@@ -18,7 +18,7 @@
  * is carried as the vector x*g (rounded) and the scalar rsqrt(mean(x^2)+eps), and the scalar
  * multiplies the contraction's result.  Without rounding this is the same function.
  *
- * Model function (pre-norm decoder; the paper names only "attention layers", "MLP layers"
+ * Model function (pre-norm decoder; the paper names only the attention and MLP layers
  * and the normalisation before attention, App. E.1; the rest follows the benchmark shapes):
  *   RMSNorm(x; g) = x * rsqrt(mean(x^2) + eps) * g
  *   Attn_i(h) at position p = Wo * GQA(RoPE(Wq n + bq, p), K-cache incl. RoPE(Wk n + bk, p),
