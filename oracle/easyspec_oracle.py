@@ -44,6 +44,10 @@ def lib():
         vp, i32, dp, fp, ip = C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_float), C.POINTER(C.c_int32)
         L.eso_bf16_round.restype = C.c_double
         L.eso_bf16_round.argtypes = [C.c_double]
+        L.eso_bf16_pair_round.restype = C.c_double
+        L.eso_bf16_pair_round.argtypes = [C.c_double]
+        L.eso_model_set_rounding.restype = C.c_int
+        L.eso_model_set_rounding.argtypes = [vp, i32, i32]
         L.eso_matvec.argtypes = [vp, C.c_int, vp, C.c_double, C.c_int, C.c_int, dp, dp]
         L.eso_rmsnorm.argtypes = [dp, fp, C.c_int, C.c_double, dp]
         L.eso_rope.argtypes = [dp, C.c_int, C.c_int, C.c_double]
@@ -101,6 +105,14 @@ def _vp(a):
 
 def bf16_round(x: float) -> float:
     return lib().eso_bf16_round(float(x))
+
+
+def bf16_pair_round(x: float) -> float:
+    """x carried as two bf16 terms: bf16(x) + bf16(x - bf16(x))."""
+    return lib().eso_bf16_pair_round(float(x))
+
+
+ACT_PLAIN, ACT_SINGLE, ACT_PAIR = 0, 1, 2     # ESO_ACT_* of the C file
 
 
 def matvec(w: np.ndarray, x: np.ndarray, bias: np.ndarray | None = None, scale: float = 1.0) -> np.ndarray:
@@ -224,6 +236,14 @@ class Model:
                 vec(lw["g_attn"], d), vec(lw["g_mlp"], d))
         lib().eso_model_set_top(self._h, mat(weights["embed"], (v, d)), vec(weights["g_final"], d),
                                 mat(weights["lm_head"], (v, d)))
+
+    def set_rounding(self, act_mode: int, kv_bf16: bool):
+        """Where the model rounds: act_mode ACT_PLAIN (activations unrounded, RMSNorm as written: the plain
+        reference), ACT_SINGLE (one bf16 number) or ACT_PAIR (two bf16 terms, RMSNorm carried in two parts:
+        the HIP library's operand format); kv_bf16: cache entries rounded to bf16."""
+        if lib().eso_model_set_rounding(self._h, int(act_mode), int(bool(kv_bf16))) != 0:
+            raise ValueError("bad rounding mode")
+        return self
 
     def __del__(self):
         if getattr(self, "_h", None):
