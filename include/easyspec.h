@@ -179,10 +179,16 @@ int easyspec_calibrate(easyspec_ctx *ctx, const int32_t *tokens, const int32_t *
 /* Greedy acceptance (Alg. 3 with one-hot distributions): accept_len[b] = number of leading
  * positions where draft equals target_argmax; bonus[b] = target_argmax[b][accept_len[b]].
  *   draft [batch][gamma], target_argmax [batch][gamma+1], accept_len [batch], bonus [batch]
- * hip_stream == NULL: all four are host arrays and the call is a host loop.  Otherwise all four
- * are dev arrays and one small kernel is launched on that hipStream_t. */
+ * easyspec_greedy_accept: all four are dev arrays; one small kernel is launched on hip_stream (a
+ * hipStream_t, NULL = the null stream, as everywhere in this header) and nothing is synchronised,
+ * so the call is ordered with the draft steps that wrote `draft` on the same stream.
+ * EASYSPEC_EINVAL for NULL pointers, batch < 1, gamma < 0, or an accept_len that is not device
+ * memory (host arrays belong to the _host variant); EASYSPEC_EHIP without a HIP device.
+ * easyspec_greedy_accept_host: all four are host arrays; a plain host loop, no device needed. */
 int easyspec_greedy_accept(const int32_t *draft, const int32_t *target_argmax, int32_t batch, int32_t gamma,
                            int32_t *accept_len, int32_t *bonus, void *hip_stream);
+int easyspec_greedy_accept_host(const int32_t *draft, const int32_t *target_argmax, int32_t batch, int32_t gamma,
+                                int32_t *accept_len, int32_t *bonus);
 
 /* Acceptance by speculative sampling (Alg. 3; Sec. 2.1) of `batch` sequences, in double
  * precision on the device, with the random numbers supplied by the caller.

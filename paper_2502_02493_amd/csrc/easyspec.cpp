@@ -508,6 +508,13 @@ extern "C" int easyspec_calibrate(easyspec_ctx* ctx, const int32_t* tokens, cons
       ctx->fuzzy[q] = 0;
       ctx->tree[q].n = 0;
       ctx->precise[q] += n_tokens[q];
+static int check_greedy_args(const int32_t* draft, const int32_t* target, int32_t batch, int32_t gamma, int32_t* accept_len,
+                             int32_t* bonus) {
+  if (!target || !accept_len || !bonus || (gamma > 0 && !draft)) return fail(nullptr, EASYSPEC_EINVAL, "greedy_accept: NULL argument");
+  if (batch < 1 || gamma < 0) return fail(nullptr, EASYSPEC_EINVAL, "greedy_accept: batch must be >= 1 and gamma >= 0");
+  return EASYSPEC_OK;
+}
+
     }
   return EASYSPEC_OK;
 }
@@ -518,12 +525,24 @@ extern "C" int easyspec_calibrate(easyspec_ctx* ctx, const int32_t* tokens, cons
 
 extern "C" int easyspec_greedy_accept(const int32_t* draft, const int32_t* target, int32_t batch, int32_t gamma,
                                       int32_t* accept_len, int32_t* bonus, void* hip_stream) {
-  if (!draft || !target || !accept_len || !bonus) return fail(nullptr, EASYSPEC_EINVAL, "greedy_accept: NULL argument");
-  if (batch < 1 || gamma < 0) return fail(nullptr, EASYSPEC_EINVAL, "greedy_accept: batch must be >= 1 and gamma >= 0");
-  if (hip_stream) {
-    launch_accept(draft, target, batch, gamma, accept_len, bonus, (hipStream_t)hip_stream);
-    HIPCHK(nullptr, hipGetLastError());
-    return EASYSPEC_OK;
+  const int rc = check_greedy_args(draft, target, batch, gamma, accept_len, bonus);
+  if (rc != EASYSPEC_OK) return rc;
+  launch_accept(draft, target, batch, gamma, accept_len, bonus, (hipStream_t)hip_stream);
+  HIPCHK(nullptr, hipGetLastError());
+  return EASYSPEC_OK;
+}
+
+extern "C" int easyspec_greedy_accept_host(const int32_t* draft, const int32_t* target, int32_t batch, int32_t gamma,
+                                           int32_t* accept_len, int32_t* bonus) {
+  const int rc = check_greedy_args(draft, target, batch, gamma, accept_len, bonus);
+  if (rc != EASYSPEC_OK) return rc;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) return fail(nullptr, EASYSPEC_EHIP, "no HIP device available (this library has no CPU path)");
+  // a host array here would be written by the kernel through an address the device does not have
+  hipPointerAttribute_t attr;
+  if (hipPointerGetAttributes(&attr, accept_len) != hipSuccess || (attr.type != hipMemoryTypeDevice && attr.type != hipMemoryTypeManaged)) {
+    (void)hipGetLastError();
+    return fail(nullptr, EASYSPEC_EINVAL, "greedy_accept: accept_len is not device memory (host arrays: easyspec_greedy_accept_host)");
   }
   for (int b = 0; b < batch; ++b) {
     const int32_t* d = draft + (size_t)b * gamma;

@@ -75,16 +75,27 @@ def test_greedy_accept_host_path(oracle):
         d = np.array([p[0] for p in pairs], np.int32)
         t = np.array([p[1] for p in pairs], np.int32)
         acc, bonus = np.zeros(len(pairs), np.int32), np.zeros(len(pairs), np.int32)
-        es.easyspec_greedy_accept(d, t, len(pairs), gamma, acc, bonus, None)
+        es.easyspec_greedy_accept_host(d, t, len(pairs), gamma, acc, bonus)
         for i, (dd, tt) in enumerate(pairs):
             assert (int(acc[i]), int(bonus[i])) == oracle.greedy_accept(dd, tt)
     acc, bonus = np.zeros(2, np.int32), np.zeros(2, np.int32)
-    es.easyspec_greedy_accept(np.zeros(0, np.int32), np.array([[7], [9]], np.int32), 2, 0, acc, bonus, None)
+    es.easyspec_greedy_accept_host(np.zeros(0, np.int32), np.array([[7], [9]], np.int32), 2, 0, acc, bonus)
     assert list(acc) == [0, 0] and list(bonus) == [7, 9]
     with pytest.raises(es.EasySpecError):
-        es.easyspec_greedy_accept(None, np.zeros(2, np.int32), 1, 1, acc, bonus, None)
+        es.easyspec_greedy_accept_host(None, np.zeros(2, np.int32), 1, 1, acc, bonus)
     with pytest.raises(es.EasySpecError):
-        es.easyspec_greedy_accept(np.zeros(1, np.int32), np.zeros(2, np.int32), 0, 1, acc, bonus, None)
+        es.easyspec_greedy_accept_host(np.zeros(1, np.int32), np.zeros(2, np.int32), 0, 1, acc, bonus)
+
+
+def test_greedy_accept_device_entry_refuses_host_arrays():
+    """The device entry point never falls back to a host loop: host arrays (or no device at all) are an
+    error, whatever the stream handle is; the null stream is a stream like any other."""
+    acc, bonus = np.zeros(1, np.int32), np.zeros(1, np.int32)
+    for stream in (None, 0):
+        with pytest.raises(es.EasySpecError) as e:
+            es.easyspec_greedy_accept(np.zeros(1, np.int32), np.zeros(2, np.int32), 1, 1, acc, bonus, stream)
+        assert e.value.code in (es.EASYSPEC_EINVAL, es.EASYSPEC_EHIP)
+    assert list(acc) == [0] and list(bonus) == [0]
 
 
 def test_create_rejects_bad_shapes_before_touching_the_device():

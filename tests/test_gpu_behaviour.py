@@ -53,7 +53,7 @@ def test_lossless_greedy_loop_on_gpu(oracle, gpu, bounds):
             _, vl = b.calibrate({0: [last] + drafted}, all_rows=True)
             target = np.argmax(vl[0], axis=1).astype(np.int32)       # the verifier's greedy choices
             acc, bonus = np.zeros(1, np.int32), np.zeros(1, np.int32)
-            es.easyspec_greedy_accept(np.array(drafted, np.int32), target, 1, gamma, acc, bonus, None)
+            es.easyspec_greedy_accept_host(np.array(drafted, np.int32), target, 1, gamma, acc, bonus)
             m = int(acc[0])
             es.easyspec_truncate(b.ctx, 0, p0 + 1 + m)
             accepts.append(m)
@@ -87,7 +87,7 @@ def test_self_draft_accepts_everything_on_gpu(oracle, gpu):
             _, vl = b.calibrate({0: [last] + drafted}, all_rows=True)
             target = np.argmax(vl[0], axis=1).astype(np.int32)
             acc, bonus = np.zeros(1, np.int32), np.zeros(1, np.int32)
-            es.easyspec_greedy_accept(np.array(drafted, np.int32), target, 1, gamma, acc, bonus, None)
+            es.easyspec_greedy_accept_host(np.array(drafted, np.int32), target, 1, gamma, acc, bonus)
             assert int(acc[0]) == gamma
             es.easyspec_truncate(b.ctx, 0, p0 + 1 + gamma)
             calib, last = drafted + [int(bonus[0])], int(bonus[0])
@@ -206,18 +206,37 @@ def test_repeated_runs_are_bit_identical(gpu):
         assert np.array_equal(a, b)
 
 
-def test_greedy_accept_device_path(oracle, gpu):
+@pytest.mark.parametrize("which_stream", ["default", "side"])
+def test_greedy_accept_device_path(oracle, gpu, which_stream):
+    """The acceptance kernel on the default stream (handle 0) and on a second stream.  The outputs are
+    poisoned on the device beforehand and the inputs are produced by device work queued on the same
+    stream right before the call, so only a kernel ordered on that stream can give the right answer."""
     import torch
     import paper_2502_02493_amd as es
     dev = torch.device("cuda:0")
     gamma = 3
     pairs = list(itertools.product(itertools.product(range(3), repeat=gamma), itertools.product(range(3), repeat=gamma + 1)))
-    d = torch.tensor([p[0] for p in pairs], dtype=torch.int32, device=dev)
-    t = torch.tensor([p[1] for p in pairs], dtype=torch.int32, device=dev)
-    acc = torch.zeros(len(pairs), dtype=torch.int32, device=dev)
-    bonus = torch.zeros(len(pairs), dtype=torch.int32, device=dev)
-    es.easyspec_greedy_accept(d, t, len(pairs), gamma, acc, bonus, torch.cuda.current_stream().cuda_stream)
-    torch.cuda.synchronize()
+    d_host = torch.tensor([p[0] for p in pairs], dtype=torch.int32)
+    t_host = torch.tensor([p[1] for p in pairs], dtype=torch.int32)
+    stream = torch.cuda.current_stream() if which_stream == "default" else torch.cuda.Stream()
+    if which_stream == "default":
+        assert stream.cuda_stream == 0
+    with torch.cuda.stream(stream):
+        acc = torch.full((len(pairs),), -77, dtype=torch.int32, device=dev)
+        bonus = torch.full((len(pairs),), -77, dtype=torch.int32, device=dev)
+        # the inputs reach their final values through a chain of device work on this stream
+        big = torch.zeros(1 << 24, dtype=torch.int32, device=dev)
+        for _ in range(4):
+            big += 1
+        d = d_host.to(dev) + big[: d_host.numel()].view_as(d_host) - 4
+        t = t_host.to(dev) + big[: t_host.numel()].view_as(t_host) - 4
+        es.easyspec_greedy_accept(d, t, len(pairs), gamma, acc, bonus, stream.cuda_stream)
+        stream.synchronize()
     acc, bonus = acc.cpu().numpy(), bonus.cpu().numpy()
+    assert not np.any(acc == -77) and not np.any(bonus == -77)
     for i, (dd, tt) in enumerate(pairs):
         assert (int(acc[i]), int(bonus[i])) == oracle.greedy_accept(dd, tt)
+    # host arrays are refused, not looped over on the host
+    with pytest.raises(es.EasySpecError):
+        es.easyspec_greedy_accept(d_host.numpy(), t_host.numpy(), len(pairs), gamma, np.zeros(len(pairs), np.int32),
+                                  np.zeros(len(pairs), np.int32), stream.cuda_stream)
