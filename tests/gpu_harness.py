@@ -2,6 +2,8 @@
 logits and converts results to numpy.  Every computation goes through libeasyspec.so."""
 from __future__ import annotations
 
+import os
+
 import numpy as np
 import torch
 
@@ -9,10 +11,34 @@ import easyspec_synth as synth
 import paper_2502_02493_amd as es
 
 
+from tolerances import FULL_SIZE_TOL, MARGIN, PEAK_PER_TOL, PLAIN_TOL, TOL  # noqa: F401
+
+_LOG = os.environ.get("EASYSPEC_PARITY_LOG")
+
+
 def rel_l2(a, b):
     a = np.asarray(a, dtype=np.float64).ravel()
     b = np.asarray(b, dtype=np.float64).ravel()
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def peak_dev(a, b):
+    """Largest |a - b| in units of rms(b)."""
+    a = np.asarray(a, dtype=np.float64).ravel()
+    b = np.asarray(b, dtype=np.float64).ravel()
+    rms = max(float(np.linalg.norm(b)) / np.sqrt(b.size), 1e-300)
+    return float(np.max(np.abs(a - b))) / rms
+
+
+def assert_close(got, want, tol, what=""):
+    """rel-L2 below tol and no single element further than PEAK_PER_TOL * tol * rms(want) from the oracle."""
+    err, peak = rel_l2(got, want), peak_dev(got, want)
+    if _LOG:
+        with open(_LOG, "a") as f:
+            f.write(f"{err:.3e} {peak:.3e} {tol:.1e} {np.asarray(want).size} {os.environ.get('PYTEST_CURRENT_TEST', '?')} | {what}\n")
+    assert err < tol, f"{what}: rel-L2 {err:.3e} >= {tol:.1e}"
+    assert peak < PEAK_PER_TOL * tol, f"{what}: largest deviation {peak:.3e} rms >= {PEAK_PER_TOL * tol:.1e}"
+    return err
 
 
 class GpuDrafter:

@@ -1,19 +1,20 @@
 """GPU parity: the HIP path through the C ABI against the CPU oracle, element by element, on
-the same seeded inputs.  Tolerances: rel-L2 <= 1e-5 (fp32 models) / 2e-3 (bf16 models; the
-required bar is 2e-2, the two-term bf16 activations leave room for a ten times tighter one) on
-logits and hidden states; token ids and lengths exact (ids are compared wherever the oracle's
-top-1/top-2 logit gap exceeds the numerical noise floor, so that a genuine near-tie between
-two vocabulary entries cannot fail a correct kernel; the count of skipped comparisons is
-asserted to be small)."""
+the same seeded inputs.  Tolerances (tests/tolerances.py): rel-L2 <= 1e-5 (fp32 models) / 1e-3
+(bf16 models; the required bar is 2e-2, the two-term bf16 activations leave room for a tighter one)
+on logits and hidden states, with a bound on the largest single deviation beside it; against the
+plain oracle (no activation rounding) the required 2e-2; token ids and lengths exact (ids are compared
+wherever the oracle's top-1/top-2 logit gap exceeds the numerical noise floor, so that a genuine
+near-tie between two vocabulary entries cannot fail a correct kernel; the count of skipped
+comparisons is asserted to be small)."""
 import numpy as np
 import pytest
 
 import easyspec_synth as synth
 
+from tolerances import MARGIN, TOL
+
 pytestmark = pytest.mark.gpu
 
-TOL = {"fp32": 1e-5, "bf16": 2e-3}
-MARGIN = {"fp32": 1e-4, "bf16": 5e-3}    # in units of std(logits)
 
 
 @pytest.fixture(scope="module")
@@ -26,12 +27,13 @@ def gpu():
 
 
 class IdCheck:
-    def __init__(self, dtype):
+    def __init__(self, dtype, margin=None):
         self.dtype, self.checked, self.skipped = dtype, 0, 0
+        self.margin = MARGIN[dtype] if margin is None else margin
 
     def __call__(self, oracle, got_id, want_logits):
         want, margin = oracle.argmax(want_logits, with_margin=True)
-        if margin > MARGIN[self.dtype] * float(np.std(want_logits)):
+        if margin > self.margin * float(np.std(want_logits)):
             assert int(got_id) == want, (got_id, want, margin)
             self.checked += 1
         else:
@@ -42,6 +44,7 @@ class IdCheck:
 def kv_check(gpu, g, seq_o, b, n, tol):
     k, v = g.export_kv(b, n)
     # a bf16 cache may differ by one unit in the last place (2^-8 relative) on a few entries
+    tol = tol if tol < 1e-4 else max(tol, 2e-3)
     assert gpu.rel_l2(k, seq_o.K[:, :, :n]) < tol, "K cache"
     assert gpu.rel_l2(v, seq_o.V[:, :, :n]) < tol, "V cache"
     # per layer as well, so that one bad layer cannot hide in the norm of the others
@@ -50,23 +53,29 @@ def kv_check(gpu, g, seq_o, b, n, tol):
         assert gpu.rel_l2(v[l], seq_o.V[l, :, :n]) < 2 * tol, f"V cache layer {l}"
 
 
-def iteration_parity(oracle, gpu, cfg, seed, bounds, prompt_len, gamma, n_iters=2, max_ctx=None):
-    """Prefill, then n_iters x (gamma-1 fuzzy steps, calibration of m accepted tokens + bonus)."""
-    tol = TOL[cfg["dtype"]]
+def iteration_parity(oracle, gpu, cfg, seed, bounds, prompt_len, gamma, n_iters=2, max_ctx=None, plain=False):
+    """Prefill, then n_iters x (gamma-1 fuzzy steps, calibration of m accepted tokens + bonus).
+    plain: against the oracle with unrounded activations and RMSNorm as written (bf16 weights and cache
+    only), at the tolerance required of a bf16 model; ids then only where the oracle's top-2 gap is far
+    above that tolerance (the two sides do not decide in the same precision)."""
+    tol = gpu.PLAIN_TOL if plain else TOL[cfg["dtype"]]
     w = synth.make_weights(cfg, seed)
     max_ctx = max_ctx or (prompt_len + n_iters * (gamma + 2) + 8)
-    so = oracle.Sequence(oracle.Model(cfg, w, max_ctx))
+    model = oracle.Model(cfg, w, max_ctx)
+    if plain:
+        model.set_rounding(oracle.ACT_PLAIN, cfg["dtype"] == "bf16")
+    so = oracle.Sequence(model)
     g = gpu.GpuDrafter(cfg, w, max_batch=1, max_ctx=max_ctx, max_calib=16)
     g.set_groups(bounds)
-    ids = IdCheck(cfg["dtype"])
+    ids = IdCheck(cfg["dtype"], margin=0.3 if plain else None)
     try:
         prompt = synth.make_tokens(seed + 1, prompt_len, cfg["vocab"])
         want = so.calibrate(prompt, all_rows=True)
         nxt, got = g.prefill(0, prompt)
         assert got.shape == want.shape
-        assert gpu.rel_l2(got, want) < tol, "prefill logits"
+        gpu.assert_close(got, want, tol, "prefill logits")
         for r in range(prompt_len):
-            assert gpu.rel_l2(got[r], want[r]) < 4 * tol, f"prefill logits row {r}"
+            gpu.assert_close(got[r], want[r], 4 * tol, f"prefill logits row {r}")
         kv_check(gpu, g, so, 0, prompt_len, tol)
         tok = ids(oracle, nxt, want[-1])
         accept = synth.make_accept_lengths(seed + 2, n_iters, gamma - 1)
@@ -76,8 +85,8 @@ def iteration_parity(oracle, gpu, cfg, seed, bounds, prompt_len, gamma, n_iters=
             for _ in range(gamma - 1):
                 wl, wh = so.fuzzy_step(bounds, drafted[-1], want_hidden=True)
                 gt, gl = g.draft_step({0: drafted[-1]})
-                assert gpu.rel_l2(gl[0], wl) < tol, "fuzzy logits"
-                assert gpu.rel_l2(g.hidden()[0], wh) < tol, "fuzzy hidden state"
+                gpu.assert_close(gl[0], wl, tol, "fuzzy logits")
+                gpu.assert_close(g.hidden()[0], wh, tol, "fuzzy hidden state")
                 drafted.append(ids(oracle, gt[0], wl))
             p, f = g.lens()
             assert (p[0], f[0]) == (so.precise, so.fuzzy) == (so.precise, gamma - 1)
@@ -86,13 +95,14 @@ def iteration_parity(oracle, gpu, cfg, seed, bounds, prompt_len, gamma, n_iters=
             calib = drafted[:m] + [int(extra[it])]                   # accepted tokens + a "bonus" token
             wl, wh = so.calibrate(calib, all_rows=True, want_hidden=True)
             gt, gl = g.calibrate({0: calib}, all_rows=True)
-            assert gpu.rel_l2(gl[0], wl) < tol, "calibration logits"
-            assert gpu.rel_l2(g.hidden(), wh) < tol, "calibration hidden states"
+            gpu.assert_close(gl[0], wl, tol, "calibration logits")
+            gpu.assert_close(g.hidden(), wh, tol, "calibration hidden states")
             p, f = g.lens()
             assert (p[0], f[0]) == (so.precise, 0)
             kv_check(gpu, g, so, 0, so.precise, tol)
             tok = ids(oracle, gt[0], wl[-1])
-        assert ids.checked >= 3 and ids.skipped <= max(2, ids.checked // 4), (ids.checked, ids.skipped)
+        if not plain:
+            assert ids.checked >= 3 and ids.skipped <= max(2, ids.checked // 4), (ids.checked, ids.skipped)
     finally:
         g.close()
 
@@ -122,6 +132,14 @@ def test_tiny_qwen_shape(oracle, gpu, dtype):
 @pytest.mark.parametrize("bounds", [[0, 1, 3, 4], [0, 4]])
 def test_tiny_bf16(oracle, gpu, bounds):
     iteration_parity(oracle, gpu, synth.model_shape("tiny", dtype="bf16"), 300, bounds, 70, 4)
+
+
+@pytest.mark.parametrize("shape,bounds", [("tiny", [0, 1, 3, 4]), ("tiny", [0, 4]), ("tiny_qwen", [0, 1, 4, 5])])
+def test_tiny_bf16_against_plain_oracle(oracle, gpu, shape, bounds):
+    """The HIP path against an oracle that shares none of its numeric design: activations unrounded,
+    RMSNorm evaluated as written, only the weights and the cache in bf16.  rel-L2 <= 2e-2, the bar
+    required of a bf16 model, on prefill, fuzzy steps, calibrations, hidden states and the cache."""
+    iteration_parity(oracle, gpu, synth.model_shape(shape, dtype="bf16"), 310, bounds, 70, 4, plain=True)
 
 
 def test_ragged_tail_context(oracle, gpu):

@@ -61,18 +61,18 @@ def tree_parity(oracle, gpu, cfg, seed, bounds, prompt_len, widths, max_ctx=None
                 wl, wh = so.fuzzy_tree_step(bounds, toks, parents, want_hidden=True)
                 gt, gl = g.draft_tree_step({0: (toks, parents)})
                 assert gl[0].shape == wl.shape
-                assert gpu.rel_l2(gl[0], wl) < tol, "tree logits"
+                gpu.assert_close(gl[0], wl, tol, "tree logits")
                 for j in range(len(toks)):
-                    assert gpu.rel_l2(gl[0][j], wl[j]) < 4 * tol, f"tree logits node {j}"
+                    gpu.assert_close(gl[0][j], wl[j], 4 * tol, f"tree logits node {j}")
                     ids(oracle, gt[0][j], wl[j])
-                assert gpu.rel_l2(g.hidden(), wh) < tol, "tree hidden states"
+                gpu.assert_close(g.hidden(), wh, tol, "tree hidden states")
             p, f = g.lens()
             assert (p[0], f[0]) == (so.precise, so.fuzzy) == (P, total)
             kv_check(gpu, g, so, 0, P + total, tol)                       # every node's k, v included
             calib = [int(t) for t in synth.make_tokens(seed + 20 + it, 3, cfg["vocab"])]
             wl = so.calibrate(calib)
             gt, gl = g.calibrate({0: calib})
-            assert gpu.rel_l2(gl[0], wl) < tol, "calibration after a tree"
+            gpu.assert_close(gl[0], wl, tol, "calibration after a tree")
             P = so.precise
             kv_check(gpu, g, so, 0, P, tol)
         assert ids.checked >= total and ids.skipped <= max(2, ids.checked // 4), (ids.checked, ids.skipped)
@@ -146,7 +146,7 @@ def test_tree_two_sequences_ragged(oracle, gpu):
             gt, gl = g.draft_tree_step(call)
             for b, (toks, parents) in call.items():
                 wl = so[b].fuzzy_tree_step(bounds, toks, parents)
-                assert gpu.rel_l2(gl[b], wl) < tol, f"sequence {b}"
+                gpu.assert_close(gl[b], wl, tol, f"sequence {b}")
         p, f = g.lens()
         for b in (0, 1):
             assert (p[b], f[b]) == (so[b].precise, so[b].fuzzy)
