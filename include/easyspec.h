@@ -216,6 +216,20 @@ int easyspec_accept(const int32_t *draft, const float *draft_logits, const float
                     int32_t *accept_len, int32_t *bonus, void *workspace, void *hip_stream);
 int64_t easyspec_accept_workspace_bytes(int32_t batch, int32_t gamma, int32_t vocab); /* -1 for bad arguments */
 
+/* easyspec_accept for callers that cannot allocate device memory and have no workspace to hand in
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same
+ * arguments, same kernels and same results, but the workspace is the library's own fixed device
+ * array of easyspec_accept_static_max_bytes() bytes (8 MiB; every GPU the library runs on holds one
+ * until the process ends).  The call allocates and frees nothing.  EASYSPEC_ECAPACITY, with nothing
+ * launched, when easyspec_accept_workspace_bytes(batch, gamma, vocab) exceeds that size (about 8
+ * bytes per vocabulary entry and sequence: 6 sequences at a vocabulary of 152 064); other errors as
+ * easyspec_accept.  All calls on one GPU share the array, so two calls whose kernels can overlap
+ * (different streams, different threads) race: keep them on one stream, or order them yourself. */
+int easyspec_accept_static(const int32_t *draft, const float *draft_logits, const float *target_logits, const float *r,
+                           const float *u, int32_t batch, int32_t gamma, int32_t vocab, float temperature,
+                           int32_t *accept_len, int32_t *bonus, void *hip_stream);
+int64_t easyspec_accept_static_max_bytes(void);
+
 /* Host copies of the per-sequence lengths; each of precise, fuzzy: host [max_batch] or NULL. */
 int easyspec_get_lens(const easyspec_ctx *ctx, int32_t *precise, int32_t *fuzzy);
 

@@ -21,7 +21,7 @@ EASYSPEC_PARALLEL_ATTENTION, EASYSPEC_PARALLEL_FULL_LAYER = 0, 1
 
 EXPORTS = ["easyspec_create", "easyspec_destroy", "easyspec_load_weights", "easyspec_set_groups",
            "easyspec_default_groups", "easyspec_draft_step", "easyspec_calibrate", "easyspec_greedy_accept", "easyspec_greedy_accept_host",
-           "easyspec_accept", "easyspec_accept_workspace_bytes", "easyspec_draft_tree_step", "easyspec_set_parallel_mode", "easyspec_stream_read", "easyspec_stream_read_sink_floats", "easyspec_attention_cut",
+           "easyspec_accept", "easyspec_accept_workspace_bytes", "easyspec_accept_static", "easyspec_accept_static_max_bytes", "easyspec_draft_tree_step", "easyspec_set_parallel_mode", "easyspec_stream_read", "easyspec_stream_read_sink_floats", "easyspec_attention_cut",
            "easyspec_get_lens", "easyspec_truncate", "easyspec_kv_import", "easyspec_kv_export",
            "easyspec_get_hidden", "easyspec_step_bytes", "easyspec_profile_begin", "easyspec_profile_end",
            "easyspec_last_error"]
@@ -74,6 +74,9 @@ def load_library():
         L.easyspec_greedy_accept.argtypes = [vp, vp, i32, i32, vp, vp, vp]
         L.easyspec_greedy_accept_host.argtypes = [vp, vp, i32, i32, vp, vp]
         L.easyspec_accept.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, C.c_float, vp, vp, vp, vp]
+        L.easyspec_accept_static.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, C.c_float, vp, vp, vp]
+        L.easyspec_accept_static_max_bytes.argtypes = []
+        L.easyspec_accept_static_max_bytes.restype = C.c_int64
         L.easyspec_accept_workspace_bytes.argtypes = [i32, i32, i32]
         L.easyspec_accept_workspace_bytes.restype = C.c_int64
         L.easyspec_get_lens.argtypes = [vp, vp, vp]
@@ -200,6 +203,17 @@ def easyspec_greedy_accept_host(draft, target_argmax, batch, gamma, accept_len, 
 
                                           gamma, vocab, float(temperature), _ptr(accept_len), _ptr(bonus), _ptr(workspace),
                                           _ptr(hip_stream)), None)
+
+
+def easyspec_accept_static(draft, draft_logits, target_logits, r, u, batch, gamma, vocab, temperature, accept_len, bonus,
+                           hip_stream=None):
+    _check(load_library().easyspec_accept_static(_ptr(draft), _ptr(draft_logits), _ptr(target_logits), _ptr(r), _ptr(u), batch,
+                                                 gamma, vocab, float(temperature), _ptr(accept_len), _ptr(bonus),
+                                                 _ptr(hip_stream)), None)
+
+
+def easyspec_accept_static_max_bytes() -> int:
+    return int(load_library().easyspec_accept_static_max_bytes())
 
 
 def easyspec_accept_workspace_bytes(batch: int, gamma: int, vocab: int) -> int:

@@ -19,6 +19,8 @@
 //                              index order, then inside the chunk the draw lands in.
 #include "kernels.h"
 
+#include <mutex>
+
 namespace es {
 
 constexpr int kStatSlices = 8;     // workgroups per logit row in (1)
@@ -266,6 +268,39 @@ void launch_sample_accept(const int32_t* draft, const float* draft_logits, const
                      gamma, V, T, ws);
   hipLaunchKernelGGL(accept_draw_kernel, dim3(batch), dim3(kDrawThreads), 0, st, target_logits, u, gamma, V, T, ws, accept_len,
                      bonus);
+}
+
+// ------------------------------------------------------------------------------------------
+// The same three launches for callers that cannot allocate and bring no workspace: the
+// workspace is a file-scope device array.  Its name is a host-side stand-in, not a device
+// address: the address comes from hipGetSymbolAddress, once per device with that device
+// current (every GPU holds its own copy), and only that pointer is handed to kernels.
+// ------------------------------------------------------------------------------------------
+constexpr size_t kStaticWsDoubles = (size_t)1 << 20;  // 8 MiB per GPU, held until the process ends
+static __device__ __align__(256) double scratch[kStaticWsDoubles];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static double* g_scratch_ptr[kMaxDevices];  // per device, filled at the first call on it
+
+size_t sample_accept_static_capacity_bytes() { return kStaticWsDoubles * sizeof(double); }
+
+hipError_t sample_accept_static_workspace(double** out) {
+  *out = nullptr;
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    double* p = nullptr;
+    e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
 }
 
 }  // namespace es

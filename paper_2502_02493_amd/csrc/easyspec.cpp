@@ -560,18 +560,47 @@ extern "C" int64_t easyspec_accept_workspace_bytes(int32_t batch, int32_t gamma,
   return (int64_t)sample_accept_workspace_bytes(batch, gamma, vocab);
 }
 
-extern "C" int easyspec_accept(const int32_t* draft, const float* draft_logits, const float* target_logits, const float* r,
-                               const float* u, int32_t batch, int32_t gamma, int32_t vocab, float temperature,
-                               int32_t* accept_len, int32_t* bonus, void* workspace, void* hip_stream) {
-  if (!target_logits || !u || !accept_len || !bonus || !workspace) return fail(nullptr, EASYSPEC_EINVAL, "accept: NULL argument");
+static int check_accept_args(const int32_t* draft, const float* draft_logits, const float* target_logits, const float* r,
+                             const float* u, int32_t batch, int32_t gamma, int32_t vocab, float temperature, int32_t* accept_len,
+                             int32_t* bonus) {
+  if (!target_logits || !u || !accept_len || !bonus) return fail(nullptr, EASYSPEC_EINVAL, "accept: NULL argument");
   if (gamma > 0 && (!draft || !draft_logits || !r)) return fail(nullptr, EASYSPEC_EINVAL, "accept: NULL draft argument with gamma > 0");
   if (batch < 1 || batch > 65535 || gamma < 0 || gamma > 64 || vocab < 1)
     return fail(nullptr, EASYSPEC_EINVAL, "accept: need 1 <= batch <= 65535, 0 <= gamma <= 64, vocab >= 1");
   if (!(temperature > 0.f) || !(temperature < INFINITY)) return fail(nullptr, EASYSPEC_EINVAL, "accept: temperature must be positive and finite (use easyspec_greedy_accept at 0)");
   int ndev = 0;
   if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) return fail(nullptr, EASYSPEC_EHIP, "no HIP device available (this library has no CPU path)");
+  return EASYSPEC_OK;
+}
+
+extern "C" int easyspec_accept(const int32_t* draft, const float* draft_logits, const float* target_logits, const float* r,
+                               const float* u, int32_t batch, int32_t gamma, int32_t vocab, float temperature,
+                               int32_t* accept_len, int32_t* bonus, void* workspace, void* hip_stream) {
+  if (!workspace) return fail(nullptr, EASYSPEC_EINVAL, "accept: NULL argument");
+  const int rc = check_accept_args(draft, draft_logits, target_logits, r, u, batch, gamma, vocab, temperature, accept_len, bonus);
+  if (rc != EASYSPEC_OK) return rc;
   launch_sample_accept(draft, draft_logits, target_logits, r, u, batch, gamma, vocab, (double)temperature, (double*)workspace,
                        accept_len, bonus, (hipStream_t)hip_stream);
+  HIPCHK(nullptr, hipGetLastError());
+  return EASYSPEC_OK;
+}
+
+extern "C" int64_t easyspec_accept_static_max_bytes(void) { return (int64_t)sample_accept_static_capacity_bytes(); }
+
+extern "C" int easyspec_accept_static(const int32_t* draft, const float* draft_logits, const float* target_logits, const float* r,
+                                      const float* u, int32_t batch, int32_t gamma, int32_t vocab, float temperature,
+                                      int32_t* accept_len, int32_t* bonus, void* hip_stream) {
+  const int rc = check_accept_args(draft, draft_logits, target_logits, r, u, batch, gamma, vocab, temperature, accept_len, bonus);
+  if (rc != EASYSPEC_OK) return rc;
+  const size_t need = sample_accept_workspace_bytes(batch, gamma, vocab), have = sample_accept_static_capacity_bytes();
+  if (need > have)
+    return fail(nullptr, EASYSPEC_ECAPACITY, "accept_static: batch %d, gamma %d, vocab %d need %zu workspace bytes, the built-in workspace holds %zu (use easyspec_accept with a workspace of your own)",
+                batch, gamma, vocab, need, have);
+  double* ws = nullptr;
+  HIPCHK(nullptr, sample_accept_static_workspace(&ws));
+  // every workspace entry a call reads was written earlier in the same call, so nothing needs clearing
+  launch_sample_accept(draft, draft_logits, target_logits, r, u, batch, gamma, vocab, (double)temperature, ws, accept_len, bonus,
+                       (hipStream_t)hip_stream);
   HIPCHK(nullptr, hipGetLastError());
   return EASYSPEC_OK;
 }

@@ -117,6 +117,10 @@ size_t sample_accept_workspace_bytes(int batch, int gamma, int V);
 void launch_sample_accept(const int32_t* draft, const float* draft_logits, const float* target_logits, const float* r,
                           const float* u, int batch, int gamma, int V, double T, double* ws, int32_t* accept_len,
                           int32_t* bonus, hipStream_t st);
+// The library's own workspace for launch_sample_accept (a static device array, one copy per GPU): its
+// address on the current device (resolved at the first call there) and its size.  Allocates nothing.
+hipError_t sample_accept_static_workspace(double** out);
+size_t sample_accept_static_capacity_bytes();
 // Reads `bytes` (multiple of 16) of buf once; sink: stream_read_sink_floats() floats.
 void launch_stream_read(const void* buf, size_t bytes, float* sink, hipStream_t st);
 int stream_read_sink_floats();
