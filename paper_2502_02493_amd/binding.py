@@ -21,11 +21,11 @@ EASYSPEC_PARALLEL_ATTENTION, EASYSPEC_PARALLEL_FULL_LAYER = 0, 1
 
 EXPORTS = ["easyspec_create", "easyspec_destroy", "easyspec_load_weights", "easyspec_set_groups",
            "easyspec_default_groups", "easyspec_draft_step", "easyspec_calibrate", "easyspec_greedy_accept", "easyspec_greedy_accept_host",
-           "easyspec_accept", "easyspec_accept_workspace_bytes", "easyspec_accept_static", "easyspec_accept_static_max_bytes", "easyspec_draft_tree_step", "easyspec_set_parallel_mode", "easyspec_stream_read", "easyspec_stream_read_sink_floats", "easyspec_attention_cut",
+           "easyspec_accept", "easyspec_accept_workspace_bytes", "easyspec_accept_static", "easyspec_accept_static_max_bytes", "easyspec_draft_tree_step", "easyspec_set_parallel_mode", "easyspec_stream_read", "easyspec_stream_read_sink_floats", "easyspec_attention_cut", "easyspec_weight_walk",
            "easyspec_get_lens", "easyspec_truncate", "easyspec_kv_import", "easyspec_kv_export",
-           "easyspec_get_hidden", "easyspec_step_bytes", "easyspec_profile_begin", "easyspec_profile_end",
+           "easyspec_get_hidden", "easyspec_poison_workspaces", "easyspec_step_bytes", "easyspec_profile_begin", "easyspec_profile_end",
            "easyspec_last_error"]
-EASYSPEC_OP_QKV, EASYSPEC_OP_ATTN, EASYSPEC_OP_OPROJ, EASYSPEC_OP_GATEUP, EASYSPEC_OP_DOWN, EASYSPEC_OP_HEAD = range(6)
+EASYSPEC_OP_QKV, EASYSPEC_OP_ATTN, EASYSPEC_OP_OPROJ, EASYSPEC_OP_GATEUP, EASYSPEC_OP_DOWN, EASYSPEC_OP_HEAD, EASYSPEC_OP_ALL = range(7)
 
 
 class EasySpecError(RuntimeError):
@@ -85,12 +85,14 @@ def load_library():
         L.easyspec_kv_export.argtypes = [vp, i32, vp, vp, i32]
         L.easyspec_get_hidden.argtypes = [vp, vp, i32, C.POINTER(i32)]
         L.easyspec_step_bytes.argtypes = [vp]
+        L.easyspec_poison_workspaces.argtypes = [vp]
         L.easyspec_stream_read.argtypes = [vp, C.c_int64, vp, vp]
         L.easyspec_stream_read_sink_floats.argtypes = []
         L.easyspec_attention_cut.argtypes = [C.POINTER(easyspec_config), vp, i32, i32, vp, vp]
         L.easyspec_step_bytes.restype = C.c_int64
+        L.easyspec_weight_walk.argtypes = [C.POINTER(easyspec_config), i32, i32, i32, i32, vp]
         L.easyspec_profile_begin.argtypes = [vp, i32, i32]
-        L.easyspec_profile_end.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_float)]
+        L.easyspec_profile_end.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_float), vp]
         L.easyspec_last_error.argtypes = [vp]
         L.easyspec_last_error.restype = C.c_char_p
         _lib = L
@@ -193,14 +195,14 @@ def easyspec_greedy_accept(draft, target_argmax, batch, gamma, accept_len, bonus
                                                  _ptr(bonus), _ptr(hip_stream)), None)
 
 
-def easyspec_accept(draft, draft_logits, target_logits, r, u, batch, gamma, vocab, temperature, accept_len, bonus,
-                    workspace, hip_stream=None):
-    _check(load_library().easyspec_accept(_ptr(draft), _ptr(draft_logits), _ptr(target_logits), _ptr(r), _ptr(u), batch,
 def easyspec_greedy_accept_host(draft, target_argmax, batch, gamma, accept_len, bonus):
     _check(load_library().easyspec_greedy_accept_host(_ptr(draft), _ptr(target_argmax), batch, gamma, _ptr(accept_len),
                                                       _ptr(bonus)), None)
 
 
+def easyspec_accept(draft, draft_logits, target_logits, r, u, batch, gamma, vocab, temperature, accept_len, bonus,
+                    workspace, hip_stream=None):
+    _check(load_library().easyspec_accept(_ptr(draft), _ptr(draft_logits), _ptr(target_logits), _ptr(r), _ptr(u), batch,
                                           gamma, vocab, float(temperature), _ptr(accept_len), _ptr(bonus), _ptr(workspace),
                                           _ptr(hip_stream)), None)
 
@@ -240,6 +242,18 @@ def easyspec_attention_cut(cfg: easyspec_config, ctx_lens, n_layers_in_set: int,
     return rc, n_chunks, ranges
 
 
+EASYSPEC_WALK_FIELDS = 16
+WALK_NAMES = ("grid", "waves", "units_per_wg", "tile_rows", "fragments", "w_max", "w_pieces", "w_out_of_range", "x_max",
+              "x_slot_elems", "x_out_of_range", "tiles", "missed_tiles", "repeated_tiles", "reread_tiles", "uncovered_pieces")
+
+
+def easyspec_weight_walk(cfg: easyspec_config, op: int, n_cols: int, n_layers_in_set: int, full_layer: bool = False) -> dict:
+    rep = np.zeros(EASYSPEC_WALK_FIELDS, np.int64)
+    _check(load_library().easyspec_weight_walk(C.byref(cfg), int(op), int(n_cols), int(n_layers_in_set), int(bool(full_layer)),
+                                               _ptr(rep)), None)
+    return dict(zip(WALK_NAMES, (int(v) for v in rep)))
+
+
 def easyspec_get_lens(ctx, max_batch: int):
     p, f = np.zeros(max_batch, np.int32), np.zeros(max_batch, np.int32)
     _check(load_library().easyspec_get_lens(ctx, _ptr(p), _ptr(f)), ctx)
@@ -264,6 +278,10 @@ def easyspec_get_hidden(ctx, out, max_rows: int) -> int:
     return n.value
 
 
+def easyspec_poison_workspaces(ctx):
+    _check(load_library().easyspec_poison_workspaces(ctx), ctx)
+
+
 def easyspec_step_bytes(ctx) -> int:
     return int(load_library().easyspec_step_bytes(ctx))
 
@@ -272,10 +290,13 @@ def easyspec_profile_begin(ctx, op: int, max_launches: int):
     _check(load_library().easyspec_profile_begin(ctx, op, max_launches), ctx)
 
 
-def easyspec_profile_end(ctx):
-    """Returns (timed launches, total milliseconds)."""
+def easyspec_profile_end(ctx, per_launch=None):
+    """Returns (timed launches, total milliseconds); per_launch: a float32 numpy array of at least
+    max_launches entries that receives each launch's milliseconds."""
     n, ms = C.c_int32(0), C.c_float(0.0)
-    _check(load_library().easyspec_profile_end(ctx, C.byref(n), C.byref(ms)), ctx)
+    if per_launch is not None:
+        assert per_launch.dtype == np.float32
+    _check(load_library().easyspec_profile_end(ctx, C.byref(n), C.byref(ms), _ptr(per_launch)), ctx)
     return n.value, ms.value
 
 

@@ -683,11 +683,11 @@ static void launch_attn_g(int G, dim3 grid, int nwv, hipStream_t st, AttnArgs a,
   const size_t lds = (size_t)sets * G * (HD + 2) * sizeof(float);
   const dim3 blk(64 * nwv);
   switch (G) {
-    case 1: hipLaunchKernelGGL((attn_kernel<T, HD, 1, TREE>), grid, blk, lds, st, a, c); break;
-    case 2: hipLaunchKernelGGL((attn_kernel<T, HD, 2, TREE>), grid, blk, lds, st, a, c); break;
-    case 4: hipLaunchKernelGGL((attn_kernel<T, HD, 4, TREE>), grid, blk, lds, st, a, c); break;
-    case 7: hipLaunchKernelGGL((attn_kernel<T, HD, 7, TREE>), grid, blk, lds, st, a, c); break;
-    case 8: hipLaunchKernelGGL((attn_kernel<T, HD, 8, TREE>), grid, blk, lds, st, a, c); break;
+    case 1: ES_LAUNCH((attn_kernel<T, HD, 1, TREE>), grid, blk, lds, st, a, c); break;
+    case 2: ES_LAUNCH((attn_kernel<T, HD, 2, TREE>), grid, blk, lds, st, a, c); break;
+    case 4: ES_LAUNCH((attn_kernel<T, HD, 4, TREE>), grid, blk, lds, st, a, c); break;
+    case 7: ES_LAUNCH((attn_kernel<T, HD, 7, TREE>), grid, blk, lds, st, a, c); break;
+    case 8: ES_LAUNCH((attn_kernel<T, HD, 8, TREE>), grid, blk, lds, st, a, c); break;
     default: break;  // rejected at create
   }
 }
@@ -852,10 +852,10 @@ void launch_attn(const Shape& s, const Buffers& b, const Cols& c, int layer0, in
     const dim3 mg((n_chunks + kMfmaAttnWaves - 1) / kMfmaAttnWaves, s.Hkv, n_set * cg.n);
     const dim3 blk(64 * kMfmaAttnWaves);
     const size_t lds = (size_t)kMfmaAttnWaves * 80 * (s.hd / 8) * sizeof(u32x4);  // per wave a 64-slot V tile and a 16-slot K tile
-    if (s.hd == 128 && tree) hipLaunchKernelGGL((attn_mfma_kernel<128, true>), mg, blk, lds, st, a, c, cg, G);
-    else if (s.hd == 128) hipLaunchKernelGGL((attn_mfma_kernel<128, false>), mg, blk, lds, st, a, c, cg, G);
-    else if (tree) hipLaunchKernelGGL((attn_mfma_kernel<64, true>), mg, blk, lds, st, a, c, cg, G);
-    else hipLaunchKernelGGL((attn_mfma_kernel<64, false>), mg, blk, lds, st, a, c, cg, G);
+    if (s.hd == 128 && tree) ES_LAUNCH((attn_mfma_kernel<128, true>), mg, blk, lds, st, a, c, cg, G);
+    else if (s.hd == 128) ES_LAUNCH((attn_mfma_kernel<128, false>), mg, blk, lds, st, a, c, cg, G);
+    else if (tree) ES_LAUNCH((attn_mfma_kernel<64, true>), mg, blk, lds, st, a, c, cg, G);
+    else ES_LAUNCH((attn_mfma_kernel<64, false>), mg, blk, lds, st, a, c, cg, G);
   } else
   DISPATCH_T(s.dtype, {
     if (s.hd == 128 && tree) launch_attn_g<T, 128, true>(G, grid, nwv, st, a, c);
@@ -866,8 +866,8 @@ void launch_attn(const Shape& s, const Buffers& b, const Cols& c, int layer0, in
   if (n_chunks > 1) {
     const dim3 mgrid(n_set * c.n, s.Hkv);
     DISPATCH_T(s.dtype, {
-      if (s.hd == 128) hipLaunchKernelGGL((attn_merge_kernel<T, 128>), mgrid, dim3(256), 0, st, a, c);
-      else hipLaunchKernelGGL((attn_merge_kernel<T, 64>), mgrid, dim3(256), 0, st, a, c);
+      if (s.hd == 128) ES_LAUNCH((attn_merge_kernel<T, 128>), mgrid, dim3(256), 0, st, a, c);
+      else ES_LAUNCH((attn_merge_kernel<T, 64>), mgrid, dim3(256), 0, st, a, c);
     });
   }
 }

@@ -23,6 +23,7 @@
 // rsqrt(mean(h^2) + eps).  Both sides of the parity tests use this order of roundings.
 #pragma once
 #include "kernels.h"
+#include "tile_index.hpp"
 
 #include <algorithm>
 #include <type_traits>
@@ -52,39 +53,16 @@ struct Tr<bf16_t> {
   static constexpr int EPL = 8, KT = 32, PARTS = 2;
 };
 
-// Layout of an activation operand x[col][k] (col < 16, k < K) of a weight contraction, per
-// part (hi, lo).  It depends on the number of columns of the forward pass, which producer and
-// consumer both know:
-//   up to kPlainCols columns: plain rows, x[col][k] at col * K + k.  A wave's B fragments of one
-//     k-tile are then one 64-byte run per column: the fewest cache lines for one or two columns.
-//   more columns: tiles of KT consecutive k, inside a tile [k-group (4)][column (pitch)][EPL
-//     elements] — the order in which the lanes of a wave take their 16-byte fragments (lane =
-//     k-group * 16 + column) — so that the fragment loads of one k-tile and part are contiguous
-//     runs instead of one cache line per column (measured: 6-column calibration 7 % faster, 8-wide
-//     tree level 12 %; with one column the tiles would touch four times the lines of plain rows).
-//     The pitch follows the column count (xpitch): what these loads cost is the number of 128-byte
-//     lines a wave asks the L2 for, and a 4-column pass with a pitch of 16 touches four half-used
-//     lines per k-tile and part where a pitch of 4 touches two.
-constexpr int kPlainCols = 2;
-
-// 16-byte fragments per k-group of a tile: the column count rounded up to an even number (tiles
-// are then whole 128-byte lines), except that 7, 8, 15 and 16 columns keep 16, where packing
-// saves no line and costs the spread over 256-byte blocks
-__device__ __forceinline__ int xpitch(int ncols) {
-  const int even = (ncols + 1) & ~1;
-  return (even & 7) == 0 ? kMaxCols : even;
-}
+// Layout of an activation operand: see tile_index.hpp (xoff_elems), here by element type.
+static_assert(kOperandCols == kMaxCols, "operand slots hold kMaxCols columns");
 template <typename T>
 __device__ __forceinline__ size_t xoff(int ncols, int K, int col, int k) {
-  constexpr int EPL = Tr<T>::EPL, KT = Tr<T>::KT;
-  if (ncols <= kPlainCols) return (size_t)col * K + k;
-  const int pitch = xpitch(ncols);
-  return (size_t)(k / KT) * (pitch * KT) + (size_t)((k % KT) / EPL) * (pitch * EPL) + col * EPL + (k % EPL);
+  return xoff_elems(Tr<T>::EPL, ncols, K, col, k);
 }
 // u32x4 between the fragments of consecutive k-tiles
 template <typename T>
 __device__ __forceinline__ int xtile_stride(int ncols) {
-  return ncols <= kPlainCols ? 4 : 4 * xpitch(ncols);
+  return xtile_fragments(ncols);
 }
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
@@ -228,7 +206,7 @@ __device__ __forceinline__ bool folded(int ncols) {
 template <typename T, int RT, int NB>
 __device__ __forceinline__ void gemm_loop(const u32x4* const (&w)[RT], const u32x4* const (&xp)[NB], int xs, bool colok,
                                           int nkt, f32x4 (&acc)[RT], int w_lane, int w_stride) {
-  constexpr int U = 8 / RT;  // k-tiles per batch: 8 KB of weights in flight per wave
+  constexpr int U = batch_len(RT);  // k-tiles per batch: 8 KB of weights in flight per wave
   const int wave = threadIdx.x >> 6, NW = blockDim.x >> 6;
   // w_lane: the lane's 16-byte piece of a weight fragment, w_stride: pieces per fragment (lane and 64 for tiles of 16 rows)
   const u32x4* wp[RT];
@@ -236,17 +214,17 @@ __device__ __forceinline__ void gemm_loop(const u32x4* const (&w)[RT], const u32
   for (int r = 0; r < RT; ++r) wp[r] = w[r] + w_lane;
   const u32x4 zero = {0u, 0u, 0u, 0u};
   int kt = wave;
-  for (; kt + (U - 1) * NW < nkt; kt += U * NW) {
+  for (; batch_is_full(kt, U, NW, nkt); kt = next_batch(kt, U, NW)) {
     u32x4 a[RT][U], b[NB][U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
 #pragma unroll
-      for (int r = 0; r < RT; ++r) a[r][u] = __builtin_nontemporal_load(wp[r] + (size_t)(kt + u * NW) * w_stride);
+      for (int r = 0; r < RT; ++r) a[r][u] = __builtin_nontemporal_load(wp[r] + (size_t)batch_tile(kt, u, NW) * w_stride);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
 #pragma unroll
-      for (int q = 0; q < NB; ++q) b[q][u] = colok ? xp[q][(size_t)(kt + u * NW) * xs] : zero;
+      for (int q = 0; q < NB; ++q) b[q][u] = colok ? xp[q][(size_t)batch_tile(kt, u, NW) * xs] : zero;
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -263,15 +241,15 @@ __device__ __forceinline__ void gemm_loop(const u32x4* const (&w)[RT], const u32
     u32x4 a[RT][U], b[NB][U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const bool in = kt + u * NW < nkt;
+      const bool in = batch_tile(kt, u, NW) < nkt;
 #pragma unroll
-      for (int r = 0; r < RT; ++r) a[r][u] = in ? __builtin_nontemporal_load(wp[r] + (size_t)(kt + u * NW) * w_stride) : zero;
+      for (int r = 0; r < RT; ++r) a[r][u] = in ? __builtin_nontemporal_load(wp[r] + (size_t)batch_tile(kt, u, NW) * w_stride) : zero;
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const bool in = colok && kt + u * NW < nkt;
+      const bool in = colok && batch_tile(kt, u, NW) < nkt;
 #pragma unroll
-      for (int q = 0; q < NB; ++q) b[q][u] = in ? xp[q][(size_t)(kt + u * NW) * xs] : zero;
+      for (int q = 0; q < NB; ++q) b[q][u] = in ? xp[q][(size_t)batch_tile(kt, u, NW) * xs] : zero;
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -292,22 +270,18 @@ __device__ __forceinline__ void gemm_accumulate(const u32x4* const (&w)[RT], con
                                                 f32x4 (&acc)[RT], int w_lane = -1, int w_stride = 64) {
   constexpr int EPL = Tr<T>::EPL, KT = Tr<T>::KT, PARTS = Tr<T>::PARTS;
   const int lane = threadIdx.x & 63;
-  const int col = lane & 15, kg = lane >> 4;
   const int nkt = K / KT;
-  const size_t part = (size_t)kMaxCols * K;  // elements between the hi and lo arrays
   if (w_lane < 0) w_lane = lane;  // full tiles: fragment piece i belongs to lane i
   if (NB == 1) {
     // lane column c < ncols reads the hi term of column c, column ncols + c its lo term
-    const bool is_lo = PARTS == 2 && col >= ncols;
-    const int src = is_lo ? col - ncols : col;
-    const bool colok = src < ncols;
-    const u32x4* const xp[1] = {
-        reinterpret_cast<const u32x4*>(x + (is_lo ? part : 0) + xoff<T>(ncols, K, colok ? src : 0, kg * EPL))};
+    const long o = x_fragment_elems(EPL, PARTS, 1, ncols, K, lane, 0);
+    const bool colok = o >= 0;
+    const u32x4* const xp[1] = {reinterpret_cast<const u32x4*>(x + (colok ? o : 0))};
     gemm_loop<T, RT, 1>(w, xp, xtile_stride<T>(ncols), colok, nkt, acc, w_lane, w_stride);
   } else {
-    const bool colok = col < ncols;
-    const T* base = x + xoff<T>(ncols, K, colok ? col : 0, kg * EPL);
-    const u32x4* const xp[2] = {reinterpret_cast<const u32x4*>(base), reinterpret_cast<const u32x4*>(base + part)};
+    const long o0 = x_fragment_elems(EPL, PARTS, 2, ncols, K, lane, 0), o1 = x_fragment_elems(EPL, PARTS, 2, ncols, K, lane, 1);
+    const bool colok = o0 >= 0;
+    const u32x4* const xp[2] = {reinterpret_cast<const u32x4*>(x + (colok ? o0 : 0)), reinterpret_cast<const u32x4*>(x + (colok ? o1 : 0))};
     gemm_loop<T, RT, 2>(w, xp, xtile_stride<T>(ncols), colok, nkt, acc, w_lane, w_stride);
   }
 }

@@ -33,16 +33,18 @@ struct easyspec_ctx {
   std::vector<int32_t> bounds;  // current layer-parallel strategy
   std::vector<int32_t> single;  // every layer alone (Alg. 1 order)
   std::vector<void*> allocs;
+  std::vector<std::pair<void*, size_t>> work;  // the per-pass workspaces (easyspec_poison_workspaces)
   int32_t last_rows;
   int32_t parallel_mode;  // EASYSPEC_PARALLEL_*
   // per-kernel timing (easyspec_profile_*)
   int32_t prof_op;
-  size_t prof_used;
   std::vector<hipEvent_t> prof_ev;  // start/stop pairs
+  LaunchTimer timer;                // the pairs handed to the launches of the profiled kernel class
   std::string err;
 };
 
 static thread_local std::string g_err;
+thread_local es::LaunchTimer* es::g_launch_timer = nullptr;
 
 static int fail(easyspec_ctx* ctx, int code, const char* fmt, ...) {
   char buf[512];
@@ -77,6 +79,12 @@ static int dev_alloc(easyspec_ctx* ctx, void** p, size_t bytes) {
     int rc_ = dev_alloc(ctx, (void**)&(ptr), (size_t)(bytes));       \
     if (rc_ != EASYSPEC_OK) return rc_;                              \
   } while (0)
+// a workspace that every forward pass writes before it reads it
+#define ALLOC_WORK(ctx, ptr, bytes)                                  \
+  do {                                                               \
+    ALLOC(ctx, ptr, bytes);                                          \
+    (ctx)->work.emplace_back((void*)(ptr), (size_t)(bytes));         \
+  } while (0)
 
 static int check_config(const easyspec_config* c) {
   if (!c) return fail(nullptr, EASYSPEC_EINVAL, "config is NULL");
@@ -98,6 +106,15 @@ static int check_config(const easyspec_config* c) {
   return EASYSPEC_OK;
 }
 
+static void shape_of(const easyspec_config* cfg, Shape& s) {
+  memset(&s, 0, sizeof s);
+  s.dtype = cfg->dtype; s.L = cfg->n_layers; s.d = cfg->d_model; s.Hq = cfg->n_q_heads; s.Hkv = cfg->n_kv_heads;
+  s.hd = cfg->head_dim; s.F = cfg->d_ffn; s.V = cfg->vocab; s.HQ = s.Hq * s.hd; s.RQKV = (s.Hq + 2 * s.Hkv) * s.hd;
+  s.B = cfg->max_batch; s.max_ctx = cfg->max_ctx; s.eps = cfg->rms_eps; s.has_bias = cfg->qkv_bias ? 1 : 0;
+  s.R_ffn = tile_rows(s.F);
+  s.R_qkv = qkv_tile_rows(s.RQKV / 2);
+}
+
 extern "C" int easyspec_create(const easyspec_config* cfg, void* hip_stream, easyspec_ctx** out) {
   if (!out) return fail(nullptr, EASYSPEC_EINVAL, "out is NULL");
   *out = nullptr;
@@ -113,14 +130,10 @@ extern "C" int easyspec_create(const easyspec_config* cfg, void* hip_stream, eas
   ctx->weights_loaded = false;
   ctx->last_rows = 0;
   ctx->prof_op = -1;
-  ctx->prof_used = 0;
+  ctx->timer = LaunchTimer{nullptr, 0, 0};
   ctx->parallel_mode = EASYSPEC_PARALLEL_ATTENTION;
   Shape& s = ctx->s;
-  s.dtype = cfg->dtype; s.L = cfg->n_layers; s.d = cfg->d_model; s.Hq = cfg->n_q_heads; s.Hkv = cfg->n_kv_heads;
-  s.hd = cfg->head_dim; s.F = cfg->d_ffn; s.V = cfg->vocab; s.HQ = s.Hq * s.hd; s.RQKV = (s.Hq + 2 * s.Hkv) * s.hd;
-  s.B = cfg->max_batch; s.max_ctx = cfg->max_ctx; s.eps = cfg->rms_eps; s.has_bias = cfg->qkv_bias ? 1 : 0;
-  s.R_ffn = tile_rows(s.F);
-  s.R_qkv = qkv_tile_rows(s.RQKV / 2);
+  shape_of(cfg, s);
   ctx->precise.assign(s.B, 0);
   ctx->fuzzy.assign(s.B, 0);
   ctx->tree.assign(s.B, easyspec_ctx::Tree());
@@ -147,22 +160,22 @@ extern "C" int easyspec_create(const easyspec_config* cfg, void* hip_stream, eas
     const size_t kv_bytes = (size_t)s.L * s.B * s.Hkv * s.max_ctx * s.hd * es_;
     ALLOC(ctx, b.kc, kv_bytes);
     ALLOC(ctx, b.vc, kv_bytes);
-    ALLOC(ctx, b.H, (size_t)kMaxCols * s.d * sizeof(float));
-    ALLOC(ctx, b.ssp, (size_t)kMaxCols * (s.d / 16) * sizeof(float));
-    ALLOC(ctx, b.XA, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.d * act_);
-    ALLOC(ctx, b.ssp_set, (size_t)EASYSPEC_MAX_SET * kMaxCols * (s.d / 16) * sizeof(float));
-    ALLOC(ctx, b.XM, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.d * act_);
-    ALLOC(ctx, b.Q, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.HQ * sizeof(float));
-    ALLOC(ctx, b.AO, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.HQ * act_);
-    ALLOC(ctx, b.A, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.d * sizeof(float));
-    ALLOC(ctx, b.ACT, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.F * act_);
+    ALLOC_WORK(ctx, b.H, (size_t)kMaxCols * s.d * sizeof(float));
+    ALLOC_WORK(ctx, b.ssp, (size_t)kMaxCols * (s.d / 16) * sizeof(float));
+    ALLOC_WORK(ctx, b.XA, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.d * act_);
+    ALLOC_WORK(ctx, b.ssp_set, (size_t)EASYSPEC_MAX_SET * kMaxCols * (s.d / 16) * sizeof(float));
+    ALLOC_WORK(ctx, b.XM, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.d * act_);
+    ALLOC_WORK(ctx, b.Q, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.HQ * sizeof(float));
+    ALLOC_WORK(ctx, b.AO, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.HQ * act_);
+    ALLOC_WORK(ctx, b.A, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.d * sizeof(float));
+    ALLOC_WORK(ctx, b.ACT, (size_t)EASYSPEC_MAX_SET * kMaxCols * s.F * act_);
     const size_t prow = (size_t)EASYSPEC_MAX_SET * kMaxCols * s.Hq;
-    ALLOC(ctx, b.PO, prow * kMaxChunks * s.hd * sizeof(float));
-    ALLOC(ctx, b.PM, prow * kMaxChunks * sizeof(float));
-    ALLOC(ctx, b.PL, prow * kMaxChunks * sizeof(float));
+    ALLOC_WORK(ctx, b.PO, prow * kMaxChunks * s.hd * sizeof(float));
+    ALLOC_WORK(ctx, b.PM, prow * kMaxChunks * sizeof(float));
+    ALLOC_WORK(ctx, b.PL, prow * kMaxChunks * sizeof(float));
     const size_t nblk = (size_t)(s.V + 15) / 16;
-    ALLOC(ctx, b.amax_val, kMaxCols * nblk * sizeof(float));
-    ALLOC(ctx, b.amax_idx, kMaxCols * nblk * sizeof(int32_t));
+    ALLOC_WORK(ctx, b.amax_val, kMaxCols * nblk * sizeof(float));
+    ALLOC_WORK(ctx, b.amax_idx, kMaxCols * nblk * sizeof(int32_t));
     HIPCHK(ctx, hipMemsetAsync(b.kc, 0, kv_bytes, ctx->stream));
     HIPCHK(ctx, hipMemsetAsync(b.vc, 0, kv_bytes, ctx->stream));
 
@@ -324,19 +337,10 @@ extern "C" int easyspec_set_groups(easyspec_ctx* ctx, const int32_t* bounds, int
 // one forward pass over the columns `c` (launch sequence of Alg. 1 / Alg. 2)
 // ---------------------------------------------------------------------------------------------
 
-// Brackets the launches of one kernel class with an event pair while profiling is on.
+// While profiling is on, the launches of one kernel class made inside the scope take event pairs.
 struct ProfScope {
-  easyspec_ctx* ctx;
-  bool on;
-  ProfScope(easyspec_ctx* c, int op) : ctx(c), on(c->prof_op == op && c->prof_used + 2 <= c->prof_ev.size()) {
-    if (on) (void)hipEventRecord(ctx->prof_ev[ctx->prof_used], ctx->stream);
-  }
-  ~ProfScope() {
-    if (on) {
-      (void)hipEventRecord(ctx->prof_ev[ctx->prof_used + 1], ctx->stream);
-      ctx->prof_used += 2;
-    }
-  }
+  ProfScope(easyspec_ctx* c, int op) { g_launch_timer = (c->prof_op == op || c->prof_op == EASYSPEC_OP_ALL) ? &c->timer : nullptr; }
+  ~ProfScope() { g_launch_timer = nullptr; }
 };
 
 static int forward(easyspec_ctx* ctx, const Cols& c, const int32_t* tokens, const std::vector<int32_t>& bounds,
@@ -345,7 +349,7 @@ static int forward(easyspec_ctx* ctx, const Cols& c, const int32_t* tokens, cons
   const Buffers& b = ctx->b;
   hipStream_t st = ctx->stream;
   const int n_sets = (int)bounds.size() - 1;
-  launch_embed(s, b, c, tokens, 0, bounds[1] - bounds[0], st);
+  { ProfScope p(ctx, EASYSPEC_OP_ALL); launch_embed(s, b, c, tokens, 0, bounds[1] - bounds[0], st); }
   for (int j = 0; j < n_sets; ++j) {
     const int lo = bounds[j], hi = bounds[j + 1], k = hi - lo;
     const AttnCut cut = attn_cut(s, c, k);
@@ -508,13 +512,6 @@ extern "C" int easyspec_calibrate(easyspec_ctx* ctx, const int32_t* tokens, cons
       ctx->fuzzy[q] = 0;
       ctx->tree[q].n = 0;
       ctx->precise[q] += n_tokens[q];
-static int check_greedy_args(const int32_t* draft, const int32_t* target, int32_t batch, int32_t gamma, int32_t* accept_len,
-                             int32_t* bonus) {
-  if (!target || !accept_len || !bonus || (gamma > 0 && !draft)) return fail(nullptr, EASYSPEC_EINVAL, "greedy_accept: NULL argument");
-  if (batch < 1 || gamma < 0) return fail(nullptr, EASYSPEC_EINVAL, "greedy_accept: batch must be >= 1 and gamma >= 0");
-  return EASYSPEC_OK;
-}
-
     }
   return EASYSPEC_OK;
 }
@@ -523,17 +520,15 @@ static int check_greedy_args(const int32_t* draft, const int32_t* target, int32_
 // acceptance, lengths, cache access
 // ---------------------------------------------------------------------------------------------
 
-extern "C" int easyspec_greedy_accept(const int32_t* draft, const int32_t* target, int32_t batch, int32_t gamma,
-                                      int32_t* accept_len, int32_t* bonus, void* hip_stream) {
-  const int rc = check_greedy_args(draft, target, batch, gamma, accept_len, bonus);
-  if (rc != EASYSPEC_OK) return rc;
-  launch_accept(draft, target, batch, gamma, accept_len, bonus, (hipStream_t)hip_stream);
-  HIPCHK(nullptr, hipGetLastError());
+static int check_greedy_args(const int32_t* draft, const int32_t* target, int32_t batch, int32_t gamma, int32_t* accept_len,
+                             int32_t* bonus) {
+  if (!target || !accept_len || !bonus || (gamma > 0 && !draft)) return fail(nullptr, EASYSPEC_EINVAL, "greedy_accept: NULL argument");
+  if (batch < 1 || gamma < 0) return fail(nullptr, EASYSPEC_EINVAL, "greedy_accept: batch must be >= 1 and gamma >= 0");
   return EASYSPEC_OK;
 }
 
-extern "C" int easyspec_greedy_accept_host(const int32_t* draft, const int32_t* target, int32_t batch, int32_t gamma,
-                                           int32_t* accept_len, int32_t* bonus) {
+extern "C" int easyspec_greedy_accept(const int32_t* draft, const int32_t* target, int32_t batch, int32_t gamma,
+                                      int32_t* accept_len, int32_t* bonus, void* hip_stream) {
   const int rc = check_greedy_args(draft, target, batch, gamma, accept_len, bonus);
   if (rc != EASYSPEC_OK) return rc;
   int ndev = 0;
@@ -544,6 +539,15 @@ extern "C" int easyspec_greedy_accept_host(const int32_t* draft, const int32_t* 
     (void)hipGetLastError();
     return fail(nullptr, EASYSPEC_EINVAL, "greedy_accept: accept_len is not device memory (host arrays: easyspec_greedy_accept_host)");
   }
+  launch_accept(draft, target, batch, gamma, accept_len, bonus, (hipStream_t)hip_stream);
+  HIPCHK(nullptr, hipGetLastError());
+  return EASYSPEC_OK;
+}
+
+extern "C" int easyspec_greedy_accept_host(const int32_t* draft, const int32_t* target, int32_t batch, int32_t gamma,
+                                           int32_t* accept_len, int32_t* bonus) {
+  const int rc = check_greedy_args(draft, target, batch, gamma, accept_len, bonus);
+  if (rc != EASYSPEC_OK) return rc;
   for (int b = 0; b < batch; ++b) {
     const int32_t* d = draft + (size_t)b * gamma;
     const int32_t* t = target + (size_t)b * (gamma + 1);
@@ -686,9 +690,16 @@ extern "C" int easyspec_get_hidden(easyspec_ctx* ctx, float* out, int32_t max_ro
   return EASYSPEC_OK;
 }
 
+extern "C" int easyspec_poison_workspaces(easyspec_ctx* ctx) {
+  if (!ctx) return fail(nullptr, EASYSPEC_EINVAL, "ctx is NULL");
+  // all bits set: a NaN in float32 and in bf16, -1 as an index
+  for (const auto& w : ctx->work) HIPCHK(ctx, hipMemsetAsync(w.first, 0xFF, w.second, ctx->stream));
+  return EASYSPEC_OK;
+}
+
 extern "C" int easyspec_profile_begin(easyspec_ctx* ctx, int32_t op, int32_t max_launches) {
   if (!ctx) return fail(nullptr, EASYSPEC_EINVAL, "ctx is NULL");
-  if (op < EASYSPEC_OP_QKV || op > EASYSPEC_OP_HEAD) return fail(ctx, EASYSPEC_EINVAL, "profile_begin: unknown op %d", op);
+  if (op < EASYSPEC_OP_QKV || op > EASYSPEC_OP_ALL) return fail(ctx, EASYSPEC_EINVAL, "profile_begin: unknown op %d", op);
   if (max_launches < 1 || max_launches > (1 << 20)) return fail(ctx, EASYSPEC_EINVAL, "profile_begin: bad max_launches");
   if (ctx->prof_op >= 0) return fail(ctx, EASYSPEC_ESTATE, "profile_begin: already profiling");
   while (ctx->prof_ev.size() < (size_t)max_launches * 2) {
@@ -696,24 +707,25 @@ extern "C" int easyspec_profile_begin(easyspec_ctx* ctx, int32_t op, int32_t max
     HIPCHK(ctx, hipEventCreate(&e));
     ctx->prof_ev.push_back(e);
   }
-  ctx->prof_used = 0;
+  ctx->timer = LaunchTimer{ctx->prof_ev.data(), (size_t)max_launches * 2, 0};
   ctx->prof_op = op;
   return EASYSPEC_OK;
 }
 
-extern "C" int easyspec_profile_end(easyspec_ctx* ctx, int32_t* n_launches, float* total_ms) {
+extern "C" int easyspec_profile_end(easyspec_ctx* ctx, int32_t* n_launches, float* total_ms, float* launch_ms) {
   if (!ctx) return fail(nullptr, EASYSPEC_EINVAL, "ctx is NULL");
   if (!n_launches || !total_ms) return fail(ctx, EASYSPEC_EINVAL, "profile_end: NULL argument");
   if (ctx->prof_op < 0) return fail(ctx, EASYSPEC_ESTATE, "profile_end: not profiling");
   ctx->prof_op = -1;
   HIPCHK(ctx, hipStreamSynchronize(ctx->stream));
   float sum = 0.f;
-  for (size_t i = 0; i + 1 < ctx->prof_used; i += 2) {
+  for (size_t i = 0; i + 1 < ctx->timer.used; i += 2) {
     float ms = 0.f;
-    HIPCHK(ctx, hipEventElapsedTime(&ms, ctx->prof_ev[i], ctx->prof_ev[i + 1]));
+    HIPCHK(ctx, hipEventElapsedTime(&ms, ctx->timer.ev[i], ctx->timer.ev[i + 1]));
+    if (launch_ms) launch_ms[i / 2] = ms;
     sum += ms;
   }
-  *n_launches = (int32_t)(ctx->prof_used / 2);
+  *n_launches = (int32_t)(ctx->timer.used / 2);
   *total_ms = sum;
   return EASYSPEC_OK;
 }
@@ -768,6 +780,28 @@ extern "C" int easyspec_attention_cut(const easyspec_config* cfg, const int32_t*
       }
   }
   return nwv;
+}
+
+extern "C" int easyspec_weight_walk(const easyspec_config* cfg, int32_t op, int32_t n_cols, int32_t n_layers_in_set, int32_t full_layer,
+                                    int64_t* report) {
+  int rc = check_config(cfg);
+  if (rc != EASYSPEC_OK) return rc;
+  if (!report) return fail(nullptr, EASYSPEC_EINVAL, "weight_walk: NULL argument");
+  if (op != EASYSPEC_OP_QKV && op != EASYSPEC_OP_OPROJ && op != EASYSPEC_OP_GATEUP && op != EASYSPEC_OP_DOWN && op != EASYSPEC_OP_HEAD)
+    return fail(nullptr, EASYSPEC_EINVAL, "weight_walk: op %d streams no packed matrix", op);
+  if (n_cols < 1 || n_cols > kMaxCols) return fail(nullptr, EASYSPEC_EINVAL, "weight_walk: n_cols must be 1..%d", kMaxCols);
+  if (n_layers_in_set < 1 || n_layers_in_set > EASYSPEC_MAX_SET || n_layers_in_set > cfg->n_layers)
+    return fail(nullptr, EASYSPEC_EINVAL, "weight_walk: n_layers_in_set must be 1..%d and at most n_layers", EASYSPEC_MAX_SET);
+  Shape s;
+  shape_of(cfg, s);
+  const StreamPlan p = stream_plan(s, op, n_cols, n_layers_in_set, full_layer != 0);
+  StreamWalk w;
+  if (stream_walk(s, p, n_cols, &w) != 0) return fail(nullptr, EASYSPEC_EINVAL, "weight_walk: launch shape not walkable");
+  const int64_t out[EASYSPEC_WALK_FIELDS] = {p.grid, p.nw, p.TP, p.R, p.NB, w.w_max, w.w_pieces, w.w_out_of_range, w.x_max,
+                                             w.x_slot_elems, w.x_out_of_range, w.tiles, w.missed_tiles, w.repeated_tiles,
+                                             w.reread_tiles, w.uncovered_pieces};
+  memcpy(report, out, sizeof out);
+  return EASYSPEC_OK;
 }
 
 extern "C" int64_t easyspec_step_bytes(const easyspec_ctx* ctx) {

@@ -3,6 +3,12 @@
 // (tile layouts, the MFMA loop, wave reduction, split RMSNorm) is in device_common.hpp.
 #include "launch_common.hpp"
 
+#include <string.h>
+
+#include <vector>
+
+#include "../../include/easyspec.h"
+
 namespace es {
 
 // ------------------------------------------------------------------------------------------
@@ -35,15 +41,15 @@ __global__ __launch_bounds__(TP == 1 ? 1024 : 512) void qkv_kernel(QkvArgs a, Co
   const int KT = Tr<T>::KT;
   const int nkt = a.d / KT;
   const int half = a.hd / 2;
-  const int R = a.R, n_pairs = (a.Hq + 2 * a.Hkv) * half, units = (n_pairs + R - 1) / R, nwg = (units + TP - 1) / TP;
+  const int R = a.R, n_pairs = (a.Hq + 2 * a.Hkv) * half, units = ceil_div(n_pairs, R), nwg = ceil_div(units, TP);
   const int li = blockIdx.x / nwg, u0 = (blockIdx.x % nwg) * TP;
   const u32x4* wl = a.w + (size_t)li * a.w_layer_stride;
   const u32x4* w[2 * TP];
 #pragma unroll
   for (int p = 0; p < TP; ++p) {
-    const int u = min(u0 + p, units - 1);  // a missing last tile re-reads its neighbour (results dropped)
-    w[2 * p] = wl + (size_t)u * nkt * (4 * R);
-    w[2 * p + 1] = wl + (size_t)(units + u) * nkt * (4 * R);
+    const int u = clamped_unit(u0, p, units);  // a missing last tile re-reads its neighbour (results dropped)
+    w[2 * p] = wl + (size_t)u * row_tile_pieces(nkt, R);
+    w[2 * p + 1] = wl + (size_t)(units + u) * row_tile_pieces(nkt, R);
   }
   const T* x = reinterpret_cast<const T*>(a.x) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.d;
   // operands of the epilogue (wave 0 only) and of the norm scale are fetched before the weight
@@ -84,7 +90,7 @@ __global__ __launch_bounds__(TP == 1 ? 1024 : 512) void qkv_kernel(QkvArgs a, Co
   for (int p = 0; p < 2 * TP; ++p) acc[p] = f32x4{0.f, 0.f, 0.f, 0.f};
   // a tile of R < 16 pairs: the lanes of the missing rows re-read the last row (their results are dropped)
   const u32x4* const(&wc)[2 * TP] = w;
-  gemm_accumulate<T, 2 * TP, NB>(wc, x, a.d, c.n, acc, (lane >> 4) * R + min(lane & 15, R - 1), 4 * R);
+  gemm_accumulate<T, 2 * TP, NB>(wc, x, a.d, c.n, acc, lane_piece(lane, R), fragment_pieces(R));
   rstd_finish(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
   if (!reduce_waves<2 * TP>(acc, dyn_red)) return;
   fold_columns<T, 2 * TP>(acc, c.n);
@@ -144,12 +150,12 @@ template <typename T, int NB, int TP>
 __global__ __launch_bounds__(1024) void proj_resid_kernel(ProjArgs a, Cols c) {
   const int KT = Tr<T>::KT;
   const int nkt = a.K / KT;
-  const int ntile = a.d / 16, nwg = (ntile + TP - 1) / TP;
+  const int ntile = a.d / 16, nwg = ceil_div(ntile, TP);
   const int li = blockIdx.x / nwg, t0 = (blockIdx.x % nwg) * TP;
   const u32x4* w[TP];
 #pragma unroll
   for (int p = 0; p < TP; ++p)  // a missing last tile re-reads its neighbour (results dropped)
-    w[p] = a.w + (size_t)li * a.w_layer_stride + (size_t)min(t0 + p, ntile - 1) * nkt * 64;
+    w[p] = a.w + (size_t)li * a.w_layer_stride + (size_t)clamped_unit(t0, p, ntile) * row_tile_pieces(nkt, 16);
   const T* x = reinterpret_cast<const T*>(a.x) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.K;
   // residual-update operands (wave 0 of a layer-0 workgroup) are fetched before the weight stream
   const int lane = threadIdx.x & 63, col = lane & 15;
@@ -239,7 +245,7 @@ __global__ __launch_bounds__(1024) void proj_full_kernel(ProjFullArgs a, Cols c)
   const int n_sum = a.down ? a.k : 1;
   for (int j = 0; j < n_sum; ++j) {  // uniform over the workgroup
     const int l = li + j;
-    const u32x4* const w[1] = {a.w + (size_t)l * a.w_layer_stride + (size_t)t * nkt * 64};
+    const u32x4* const w[1] = {a.w + (size_t)l * a.w_layer_stride + (size_t)t * row_tile_pieces(nkt, 16)};
     gemm_accumulate<T, 1, NB>(w, reinterpret_cast<const T*>(a.x) + (size_t)l * Tr<T>::PARTS * kMaxCols * a.K, a.K, c.n, acc);
   }
   if (!reduce_waves<1>(acc, dyn_red)) return;
@@ -293,13 +299,13 @@ template <typename T, int NB, int TP>
 __global__ __launch_bounds__(1024) void gateup_kernel(GateUpArgs a, Cols c) {
   __shared__ float s_rstd[kMaxCols];
   const int nkt = a.d / Tr<T>::KT;
-  const int R = a.R, ntile = (a.F + R - 1) / R, nunit = (ntile + TP - 1) / TP;
+  const int R = a.R, ntile = ceil_div(a.F, R), nunit = ceil_div(ntile, TP);
   const int li = blockIdx.x / nunit, t0 = (blockIdx.x % nunit) * TP;
   const u32x4* w[2 * TP];
 #pragma unroll
   for (int p = 0; p < TP; ++p) {
-    const int t = min(t0 + p, ntile - 1);  // a missing last tile re-reads its neighbour (results dropped)
-    const size_t wl = (size_t)li * a.w_layer_stride + (size_t)t * nkt * (4 * R);
+    const int t = clamped_unit(t0, p, ntile);  // a missing last tile re-reads its neighbour (results dropped)
+    const size_t wl = (size_t)li * a.w_layer_stride + (size_t)t * row_tile_pieces(nkt, R);
     w[2 * p] = a.wg + wl;
     w[2 * p + 1] = a.wu + wl;
   }
@@ -310,10 +316,9 @@ __global__ __launch_bounds__(1024) void gateup_kernel(GateUpArgs a, Cols c) {
 #pragma unroll
   for (int p = 0; p < 2 * TP; ++p) acc[p] = f32x4{0.f, 0.f, 0.f, 0.f};
   // a tile of R < 16 rows: the lanes of the missing rows re-read the last row (their results are dropped)
-  const int m = threadIdx.x & 15, kg = (threadIdx.x & 63) >> 4;
   const u32x4* const(&wc)[2 * TP] = w;
   gemm_accumulate<T, 2 * TP, NB>(wc, reinterpret_cast<const T*>(a.x) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.d, a.d, c.n, acc,
-                                 kg * R + min(m, R - 1), 4 * R);
+                                 lane_piece(threadIdx.x & 63, R), fragment_pieces(R));
   rstd_finish(ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
   if (!reduce_waves<2 * TP>(acc, dyn_red)) return;
   fold_columns<T, 2 * TP>(acc, c.n);
@@ -368,7 +373,7 @@ __global__ __launch_bounds__(1024) void head_kernel(HeadArgs a, Cols c) {
   const int t0 = blockIdx.x * TP;
   const u32x4* w[TP];
 #pragma unroll
-  for (int p = 0; p < TP; ++p) w[p] = a.w + (size_t)min(t0 + p, a.nblk - 1) * nkt * 64;  // a missing tile re-reads the last one
+  for (int p = 0; p < TP; ++p) w[p] = a.w + (size_t)clamped_unit(t0, p, a.nblk) * row_tile_pieces(nkt, 16);  // a missing tile re-reads the last one
   RstdPre pre;
   rstd_issue(a.ssp, a.d / 16, c.n, pre);
   f32x4 acc[TP];
@@ -545,15 +550,160 @@ int qkv_tile_rows(int n_pairs) {
 
 void launch_embed(const Shape& s, const Buffers& b, const Cols& c, const int32_t* tokens, int layer0, int n_set,
                   hipStream_t st) {
-  DISPATCH_T(s.dtype, hipLaunchKernelGGL(embed_kernel<T>, dim3(c.n), dim3(1024), 0, st, (const T*)b.embed, tokens,
+  DISPATCH_T(s.dtype, ES_LAUNCH(embed_kernel<T>, dim3(c.n), dim3(1024), 0, st, (const T*)b.embed, tokens,
                                          b.g_attn + (size_t)layer0 * s.d, n_set, s.d, s.V, b.H, (T*)b.XA, b.ssp, c));
+}
+
+// ------------------------------------------------------------------------------------------
+// Launch shapes.  One function decides, per kernel class, how a launch cuts its packed matrices into
+// workgroups and waves; the launch wrappers below and the host-side walk of the weight stream
+// (stream_walk) both read it from there.
+// ------------------------------------------------------------------------------------------
+StreamPlan stream_plan(const Shape& s, int op, int ncols, int n_layers, bool full_layer) {
+  StreamPlan p;
+  memset(&p, 0, sizeof p);
+  p.op = op;
+  p.n_layers = n_layers;
+  p.R = 16;
+  p.n_mat = 1;
+  p.split_array = 0;
+  const int kt = s.dtype == 1 ? 32 : 16;
+  Cols c;
+  c.n = ncols;  // the only field the choices below read
+  p.NB = two_fragments(s.dtype, c) ? 2 : 1;
+  int dflt_nw = 8;
+  const char* env = "";
+  switch (op) {
+    case EASYSPEC_OP_QKV:
+      p.K = s.d; p.R = s.R_qkv; p.n_mat = 2; p.split_array = 0;  // both halves in one array: first halves, then second halves
+      p.units = ceil_div(s.RQKV / 2, p.R);
+      p.mat_pieces = tile_stride(s.RQKV / 2, s.d, s.dtype, p.R);
+      p.layer_pieces = 2 * p.mat_pieces;
+      dflt_nw = n_layers * p.units < 512 ? 8 : 4;  // few workgroups (a set of one layer): more waves per workgroup
+      env = "EASYSPEC_NW_QKV";
+      break;
+    case EASYSPEC_OP_OPROJ:
+      p.K = s.HQ;
+      p.units = s.d / 16;
+      p.mat_pieces = p.layer_pieces = tile_stride(s.d, s.HQ, s.dtype);
+      dflt_nw = n_layers * p.units < 512 ? 8 : 4;
+      env = "EASYSPEC_NW_O";
+      break;
+    case EASYSPEC_OP_GATEUP:
+      p.K = s.d; p.R = s.R_ffn; p.n_mat = 2; p.split_array = 1;  // gate and up: two arrays, same tiling
+      p.units = ceil_div(s.F, p.R);
+      p.mat_pieces = p.layer_pieces = tile_stride(s.F, s.d, s.dtype, p.R);
+      dflt_nw = 8;
+      env = "EASYSPEC_NW_GU";
+      break;
+    case EASYSPEC_OP_DOWN:
+      p.K = s.F;
+      p.units = s.d / 16;
+      p.mat_pieces = p.layer_pieces = tile_stride(s.d, s.F, s.dtype);
+      // Seven waves when that cuts K into whole batches of 8 tiles per wave (F = 14336: 8 batches each) and
+      // the pass has one activation fragment: measured 11 us per step faster than eight at the 8B shape
+      // (a wave's tiles are then 7 KB apart instead of a power of two); slower where K does not divide
+      // (Qwen2-7B's F = 18944) or with two fragments.
+      dflt_nw = (!full_layer && p.NB == 1 && (s.F / kt) % 56 == 0) ? 7 : 8;
+      env = "EASYSPEC_NW_DOWN";
+      p.n_layers = 1;  // one workgroup per row tile whatever the set size (full-layer mode sums the set's layers inside it)
+      break;
+    default:  // EASYSPEC_OP_HEAD
+      p.K = s.d;
+      p.units = (s.V + 15) / 16;
+      p.mat_pieces = p.layer_pieces = tile_stride(s.V, s.d, s.dtype);
+      p.n_layers = 1;
+      dflt_nw = 4;
+      env = "EASYSPEC_NW_HEAD";
+      break;
+  }
+  p.nkt = p.K / kt;
+  p.nw = pick_waves(dflt_nw, p.nkt, env);
+  // Two units per workgroup in two-fragment passes, where the halved launch still fills the CUs (the down
+  // projection's 256 workgroups never; the full-layer kernels have no such instantiation)
+  p.TP = 1;
+  if (op != EASYSPEC_OP_DOWN && !full_layer && pair_tiles(s.dtype, c, p.n_layers * p.units)) {
+    p.TP = 2;
+    if (op == EASYSPEC_OP_QKV && p.nw > 8) p.nw = 8;  // that instantiation is built for at most 8 waves
+  }
+  p.grid = p.n_layers * ceil_div(p.units, p.TP);
+  return p;
+}
+
+// Host model of one launch: every workgroup, wave and lane computes, through the index functions the
+// kernels use (tile_index.hpp), each 16-byte piece of weights and each activation fragment it would load.
+int stream_walk(const Shape& s, const StreamPlan& p, int ncols, StreamWalk* r) {
+  memset(r, 0, sizeof *r);
+  const int EPL = s.dtype == 1 ? 8 : 4, PARTS = s.dtype == 1 ? 2 : 1;
+  const int RT = p.n_mat * p.TP;       // row tiles a wave streams side by side
+  const int U = batch_len(RT);
+  if (U < 1) return -1;
+  const int nwg = ceil_div(p.units, p.TP);
+  r->w_pieces = (long long)p.n_layers * p.layer_pieces;
+  r->x_slot_elems = (long long)PARTS * kOperandCols * p.K;
+  r->tiles = (long long)p.n_layers * p.n_mat * p.units * p.nkt;
+  std::vector<unsigned char> seen((size_t)r->tiles, 0);
+  // the lanes of a wave must cover every piece of a fragment
+  {
+    std::vector<char> piece(fragment_pieces(p.R), 0);
+    for (int lane = 0; lane < 64; ++lane) {
+      const int q = lane_piece(lane, p.R);
+      if (q < 0 || q >= fragment_pieces(p.R)) return -1;
+      piece[q] = 1;
+    }
+    for (char c : piece) if (!c) ++r->uncovered_pieces;
+  }
+  for (int wg = 0; wg < p.grid; ++wg) {
+    const int li = wg / nwg, u0 = (wg % nwg) * p.TP;
+    for (int t = 0; t < p.TP; ++t) {
+      const int unit = clamped_unit(u0, t, p.units);
+      const bool reread = u0 + t >= p.units;
+      for (int m = 0; m < p.n_mat; ++m) {
+        // both halves of the QKV matrices share one array (second halves after the first); gate and up are two arrays
+        const long long base = (long long)li * p.layer_pieces + (long long)((p.split_array ? 0 : m * p.units) + unit) * row_tile_pieces(p.nkt, p.R);
+        for (int wave = 0; wave < p.nw; ++wave) {
+          auto visit = [&](int tile) {
+            for (int lane = 0; lane < 64; ++lane) {
+              const long long idx = base + lane_piece(lane, p.R) + (long long)tile * fragment_pieces(p.R);
+              if (idx > r->w_max) r->w_max = idx;
+              if (idx < 0 || idx >= r->w_pieces) ++r->w_out_of_range;
+              if (m == 0 && t == 0) {  // the activation fragments do not depend on the row tile
+                for (int q = 0; q < p.NB; ++q) {
+                  const long o = x_fragment_elems(EPL, PARTS, p.NB, ncols, p.K, lane, q);
+                  if (o < 0) continue;
+                  const long long last = o + (long long)tile * xtile_fragments(ncols) * EPL + EPL - 1;
+                  if (last > r->x_max) r->x_max = last;
+                  if (last >= r->x_slot_elems) ++r->x_out_of_range;
+                }
+              }
+            }
+            if (tile < 0 || tile >= p.nkt) { ++r->w_out_of_range; return; }
+            if (reread) { ++r->reread_tiles; return; }
+            unsigned char& n = seen[(((size_t)li * p.n_mat + m) * p.units + unit) * p.nkt + tile];
+            if (n < 255) ++n;
+          };
+          int kt = wave;
+          for (; batch_is_full(kt, U, p.nw, p.nkt); kt = next_batch(kt, U, p.nw))
+            for (int u = 0; u < U; ++u) visit(batch_tile(kt, u, p.nw));
+          if (kt < p.nkt)
+            for (int u = 0; u < U; ++u)
+              if (batch_tile(kt, u, p.nw) < p.nkt) visit(batch_tile(kt, u, p.nw));
+        }
+      }
+    }
+  }
+  for (unsigned char n : seen) {
+    if (n == 0) ++r->missed_tiles;
+    if (n > 1) ++r->repeated_tiles;
+  }
+  return 0;
 }
 
 void launch_qkv(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st) {
   QkvArgs a;
-  const size_t stride = 2 * tile_stride(s.RQKV / 2, s.d, s.dtype, s.R_qkv);  // first halves, second halves
-  a.w = (const u32x4*)b.wqkv + (size_t)layer0 * stride;
-  a.w_layer_stride = stride;
+  const StreamPlan p = stream_plan(s, EASYSPEC_OP_QKV, c.n, n_set, false);
+  a.w = (const u32x4*)b.wqkv + (size_t)layer0 * p.layer_pieces;
+  a.w_layer_stride = p.layer_pieces;
   a.x = b.XA;
   a.ssp = b.ssp;
   a.bias = s.has_bias ? b.bqkv + (size_t)layer0 * s.RQKV : nullptr;
@@ -562,29 +712,22 @@ void launch_qkv(const Shape& s, const Buffers& b, const Cols& c, int layer0, int
   a.kc = b.kc;
   a.vc = b.vc;
   a.layer0 = layer0; a.d = s.d; a.Hq = s.Hq; a.Hkv = s.Hkv; a.hd = s.hd; a.B = s.B; a.max_ctx = s.max_ctx;
-  a.R = s.R_qkv;
+  a.R = p.R;
   a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
-  const int units = (s.RQKV / 2 + s.R_qkv - 1) / s.R_qkv;
-  const int grid = n_set * units;
-  const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
-  // few workgroups (a set of one layer): more waves per workgroup
-  const int nw = pick_waves(grid < 512 ? 8 : 4, nkt, "EASYSPEC_NW_QKV");
-  if (pair_tiles(s.dtype, c, grid)) {
+  if (p.TP == 2) {
     // two tiles per workgroup share every fragment load (12-wide tree level 3292 -> 3282 us)
-    const int grid2 = n_set * ((units + 1) / 2);
-    const int nw2 = nw > 8 ? 8 : nw;  // the instantiation is built for at most 8 waves
-    hipLaunchKernelGGL((qkv_kernel<bf16_t, 2, 2>), dim3(grid2), dim3(64 * nw2), red_bytes(nw2, 4), st, a, c);
+    ES_LAUNCH((qkv_kernel<bf16_t, 2, 2>), dim3(p.grid), dim3(64 * p.nw), red_bytes(p.nw, 4), st, a, c);
     return;
   }
-  DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
-               hipLaunchKernelGGL((qkv_kernel<T, NB, 1>), dim3(grid), dim3(64 * nw), red_bytes(nw, 2), st, a, c));
+  DISPATCH_TNB(s.dtype, p.NB == 2,
+               ES_LAUNCH((qkv_kernel<T, NB, 1>), dim3(p.grid), dim3(64 * p.nw), red_bytes(p.nw, 2), st, a, c));
 }
 
 void launch_oproj(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st) {
   ProjArgs a;
-  const size_t stride = tile_stride(s.d, s.HQ, s.dtype);
-  a.w = (const u32x4*)b.wo + (size_t)layer0 * stride;
-  a.w_layer_stride = stride;
+  const StreamPlan p = stream_plan(s, EASYSPEC_OP_OPROJ, c.n, n_set, false);
+  a.w = (const u32x4*)b.wo + (size_t)layer0 * p.layer_pieces;
+  a.w_layer_stride = p.layer_pieces;
   a.x = b.AO;
   a.K = s.HQ; a.d = s.d;
   a.H = b.H; a.A = b.A; a.a_add = -1;
@@ -592,70 +735,53 @@ void launch_oproj(const Shape& s, const Buffers& b, const Cols& c, int layer0, i
   a.n_gain = 1;
   a.xout = b.XM;
   a.ssp = b.ssp;
-  const int grid = n_set * (s.d / 16);
-  const int nkt = s.HQ / (s.dtype == 1 ? 32 : 16);
-  const int nw = pick_waves(grid < 512 ? 8 : 4, nkt, "EASYSPEC_NW_O");
-  if (pair_tiles(s.dtype, c, grid)) {
+  if (p.TP == 2) {
     // two row tiles per workgroup share every fragment load (12-wide tree level 3284 -> 3259 us)
-    const int grid2 = n_set * ((s.d / 16 + 1) / 2);
-    hipLaunchKernelGGL((proj_resid_kernel<bf16_t, 2, 2>), dim3(grid2), dim3(64 * nw), red_bytes(nw, 2), st, a, c);
+    ES_LAUNCH((proj_resid_kernel<bf16_t, 2, 2>), dim3(p.grid), dim3(64 * p.nw), red_bytes(p.nw, 2), st, a, c);
     return;
   }
-  DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
-               hipLaunchKernelGGL((proj_resid_kernel<T, NB, 1>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+  DISPATCH_TNB(s.dtype, p.NB == 2,
+               ES_LAUNCH((proj_resid_kernel<T, NB, 1>), dim3(p.grid), dim3(64 * p.nw), red_bytes(p.nw, 1), st, a, c));
 }
 
 void launch_gateup(const Shape& s, const Buffers& b, const Cols& c, int layer, int n_layers, const float* ssp, hipStream_t st) {
   GateUpArgs a;
-  const size_t stride = tile_stride(s.F, s.d, s.dtype, s.R_ffn);
-  a.wg = (const u32x4*)b.wg + (size_t)layer * stride;
-  a.wu = (const u32x4*)b.wu + (size_t)layer * stride;
-  a.w_layer_stride = stride;
-  a.x = b.XM; a.ssp = ssp; a.act = b.ACT; a.d = s.d; a.F = s.F; a.R = s.R_ffn;
+  const StreamPlan p = stream_plan(s, EASYSPEC_OP_GATEUP, c.n, n_layers, false);
+  a.wg = (const u32x4*)b.wg + (size_t)layer * p.layer_pieces;
+  a.wu = (const u32x4*)b.wu + (size_t)layer * p.layer_pieces;
+  a.w_layer_stride = p.layer_pieces;
+  a.x = b.XM; a.ssp = ssp; a.act = b.ACT; a.d = s.d; a.F = s.F; a.R = p.R;
   a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
-  const int ntile = (s.F + s.R_ffn - 1) / s.R_ffn;
-  const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
-  const int nw = pick_waves(8, nkt, "EASYSPEC_NW_GU");
-  if (pair_tiles(s.dtype, c, n_layers * ntile)) {
+  if (p.TP == 2) {
     // two fragments per k-tile: two row tiles of each matrix per workgroup, so that four MFMA row tiles
     // share every fragment load (measured: 12-wide tree level 3402 -> 3322 us; with one fragment the
     // larger workgroups lose: 6-token calibration 3377 -> 3411 us, draft step 2676 -> 2731 us)
-    const int grid = n_layers * ((ntile + 1) / 2);
-    hipLaunchKernelGGL((gateup_kernel<bf16_t, 2, 2>), dim3(grid), dim3(64 * nw), red_bytes(nw, 4), st, a, c);
+    ES_LAUNCH((gateup_kernel<bf16_t, 2, 2>), dim3(p.grid), dim3(64 * p.nw), red_bytes(p.nw, 4), st, a, c);
     return;
   }
-  const int grid = n_layers * ntile;
-  DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
-               hipLaunchKernelGGL((gateup_kernel<T, NB, 1>), dim3(grid), dim3(64 * nw), red_bytes(nw, 2), st, a, c));
+  DISPATCH_TNB(s.dtype, p.NB == 2,
+               ES_LAUNCH((gateup_kernel<T, NB, 1>), dim3(p.grid), dim3(64 * p.nw), red_bytes(p.nw, 2), st, a, c));
 }
 
 void launch_down(const Shape& s, const Buffers& b, const Cols& c, int layer, int a_next, const float* gain, int n_gain,
                  void* xout, hipStream_t st) {
   ProjArgs a;
-  const size_t stride = tile_stride(s.d, s.F, s.dtype);
-  a.w = (const u32x4*)b.wd + (size_t)layer * stride;
-  a.w_layer_stride = stride;
+  const StreamPlan p = stream_plan(s, EASYSPEC_OP_DOWN, c.n, 1, false);
+  a.w = (const u32x4*)b.wd + (size_t)layer * p.layer_pieces;
+  a.w_layer_stride = p.layer_pieces;
   a.x = b.ACT;
   a.K = s.F; a.d = s.d;
   a.H = b.H; a.A = b.A; a.a_add = a_next;
   a.gain = gain; a.n_gain = n_gain; a.xout = xout; a.ssp = b.ssp;
-  const int grid = s.d / 16;
-  const int nkt = s.F / (s.dtype == 1 ? 32 : 16);
-  // Seven waves when that cuts K into whole batches of 8 tiles per wave (F = 14336: 8 batches each) and
-  // the pass has one activation fragment: measured 11 us per step faster than eight at the 8B shape
-  // (a wave's tiles are then 7 KB apart instead of a power of two); slower where K does not divide
-  // (Qwen2-7B's F = 18944) or with two fragments.
-  const bool seven = !two_fragments(s.dtype, c) && nkt % 56 == 0;
-  const int nw = pick_waves(seven ? 7 : 8, nkt, "EASYSPEC_NW_DOWN");
-  DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
-               hipLaunchKernelGGL((proj_resid_kernel<T, NB, 1>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+  DISPATCH_TNB(s.dtype, p.NB == 2,
+               ES_LAUNCH((proj_resid_kernel<T, NB, 1>), dim3(p.grid), dim3(64 * p.nw), red_bytes(p.nw, 1), st, a, c));
 }
 
 void launch_oproj_full(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st) {
   ProjFullArgs a;
-  const size_t stride = tile_stride(s.d, s.HQ, s.dtype);
-  a.w = (const u32x4*)b.wo + (size_t)layer0 * stride;
-  a.w_layer_stride = stride;
+  const StreamPlan p = stream_plan(s, EASYSPEC_OP_OPROJ, c.n, n_set, true);
+  a.w = (const u32x4*)b.wo + (size_t)layer0 * p.layer_pieces;
+  a.w_layer_stride = p.layer_pieces;
   a.x = b.AO;
   a.K = s.HQ; a.d = s.d; a.k = n_set; a.down = 0;
   a.H = b.H; a.A = b.A;
@@ -663,46 +789,39 @@ void launch_oproj_full(const Shape& s, const Buffers& b, const Cols& c, int laye
   a.n_gain = 0;
   a.xout = b.XM;
   a.ssp = b.ssp_set;
-  const int grid = n_set * (s.d / 16);
-  const int nkt = s.HQ / (s.dtype == 1 ? 32 : 16);
-  const int nw = pick_waves(grid < 512 ? 8 : 4, nkt, "EASYSPEC_NW_O");
-  DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
-               hipLaunchKernelGGL((proj_full_kernel<T, NB>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+  DISPATCH_TNB(s.dtype, p.NB == 2,
+               ES_LAUNCH((proj_full_kernel<T, NB>), dim3(p.grid), dim3(64 * p.nw), red_bytes(p.nw, 1), st, a, c));
 }
 
 void launch_down_full(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, const float* gain, int n_gain,
                       void* xout, hipStream_t st) {
   ProjFullArgs a;
-  const size_t stride = tile_stride(s.d, s.F, s.dtype);
-  a.w = (const u32x4*)b.wd + (size_t)layer0 * stride;
-  a.w_layer_stride = stride;
+  const StreamPlan p = stream_plan(s, EASYSPEC_OP_DOWN, c.n, n_set, true);
+  a.w = (const u32x4*)b.wd + (size_t)layer0 * p.layer_pieces;
+  a.w_layer_stride = p.layer_pieces;
   a.x = b.ACT;
   a.K = s.F; a.d = s.d; a.k = n_set; a.down = 1;
   a.H = b.H; a.A = b.A;
   a.gain = gain; a.n_gain = n_gain; a.xout = xout; a.ssp = b.ssp;
-  const int grid = s.d / 16;
-  const int nkt = s.F / (s.dtype == 1 ? 32 : 16);
-  const int nw = pick_waves(8, nkt, "EASYSPEC_NW_DOWN");
-  DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
-               hipLaunchKernelGGL((proj_full_kernel<T, NB>), dim3(grid), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+  DISPATCH_TNB(s.dtype, p.NB == 2,
+               ES_LAUNCH((proj_full_kernel<T, NB>), dim3(p.grid), dim3(64 * p.nw), red_bytes(p.nw, 1), st, a, c));
 }
 
 void launch_head(const Shape& s, const Buffers& b, const Cols& c, float* logits_out, int32_t* tokens_out, hipStream_t st) {
   HeadArgs a;
+  const StreamPlan p = stream_plan(s, EASYSPEC_OP_HEAD, c.n, 1, false);
   a.w = (const u32x4*)b.wlm; a.x = b.XA; a.ssp = b.ssp; a.logits = logits_out;
   a.cand_val = b.amax_val; a.cand_idx = b.amax_idx;
-  a.d = s.d; a.V = s.V; a.nblk = (s.V + 15) / 16;
+  a.d = s.d; a.V = s.V; a.nblk = p.units;
   a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
-  const int nkt = s.d / (s.dtype == 1 ? 32 : 16);
-  const int nw = pick_waves(4, nkt, "EASYSPEC_NW_HEAD");
-  if (pair_tiles(s.dtype, c, a.nblk)) {
+  if (p.TP == 2) {
     // two row tiles per workgroup share every fragment load (12-wide tree level 3309 -> 3276 us; four: the same)
-    hipLaunchKernelGGL((head_kernel<bf16_t, 2, 2>), dim3((a.nblk + 1) / 2), dim3(64 * nw), red_bytes(nw, 2), st, a, c);
+    ES_LAUNCH((head_kernel<bf16_t, 2, 2>), dim3(p.grid), dim3(64 * p.nw), red_bytes(p.nw, 2), st, a, c);
   } else {
-    DISPATCH_TNB(s.dtype, two_fragments(s.dtype, c),
-                 hipLaunchKernelGGL((head_kernel<T, NB, 1>), dim3(a.nblk), dim3(64 * nw), red_bytes(nw, 1), st, a, c));
+    DISPATCH_TNB(s.dtype, p.NB == 2,
+                 ES_LAUNCH((head_kernel<T, NB, 1>), dim3(p.grid), dim3(64 * p.nw), red_bytes(p.nw, 1), st, a, c));
   }
-  hipLaunchKernelGGL(argmax_final_kernel, dim3(c.n), dim3(1024), 0, st, a.cand_val, a.cand_idx, a.nblk, tokens_out, c);
+  ES_LAUNCH(argmax_final_kernel, dim3(c.n), dim3(1024), 0, st, a.cand_val, a.cand_idx, a.nblk, tokens_out, c);
 }
 
 }  // namespace es

@@ -67,6 +67,43 @@ struct Buffers {
   int32_t *amax_idx;
 };
 
+// Per-launch timing (easyspec_profile_*): while a timer is installed for the calling thread, every kernel
+// launch of the forward pass binds the next start / stop event pair to its own dispatch, so that the pair's
+// elapsed time is the kernel's begin-to-end time as a kernel trace reports it (no stream markers between).
+struct LaunchTimer {
+  hipEvent_t* ev;  // start / stop pairs
+  size_t cap, used;
+};
+extern thread_local LaunchTimer* g_launch_timer;
+
+// How one launch of a weight-streaming kernel class (EASYSPEC_OP_QKV, _OPROJ, _GATEUP, _DOWN, _HEAD) cuts its
+// packed matrices: decided in one place (stream_plan) for the launch wrappers and for stream_walk.
+struct StreamPlan {
+  int op;
+  int n_mat;        // packed matrices a unit reads side by side: QKV 2 (first and second rotary halves), gate/up 2, else 1
+  int split_array;  // 1: the n_mat matrices are separate arrays of the same tiling (gate, up); 0: one array, one after the other
+  int units;        // units per layer: row tiles, or tiles of rotation pairs
+  int TP;           // units per workgroup
+  int R;            // rows per tile
+  int K, nkt;       // contraction length, k-tiles
+  int nw;           // waves per workgroup
+  int NB;           // activation fragments per k-tile
+  int n_layers;     // layers the grid spans
+  int grid;
+  size_t mat_pieces;    // 16-byte pieces of one packed matrix of one layer
+  size_t layer_pieces;  // pieces from one layer to the next inside an array
+};
+StreamPlan stream_plan(const Shape& s, int op, int ncols, int n_layers, bool full_layer);
+// What a host walk of the launch found: the highest piece index against the pieces the launch's layers
+// hold, the highest activation element against an operand slot, k-tiles never read, read twice (apart
+// from the deliberate re-reads of a missing last unit), and fragment pieces no lane takes.
+struct StreamWalk {
+  long long w_max, w_pieces, w_out_of_range;
+  long long x_max, x_slot_elems, x_out_of_range;
+  long long tiles, missed_tiles, repeated_tiles, reread_tiles, uncovered_pieces;
+};
+int stream_walk(const Shape& s, const StreamPlan& p, int ncols, StreamWalk* r);
+
 // Launch wrappers (all asynchronous on `st`).
 // Packed matrices: row tiles of R <= 16 rows (see repack_kernel).
 int tile_rows(int rows);

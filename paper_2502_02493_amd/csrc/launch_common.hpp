@@ -2,6 +2,7 @@
 #pragma once
 #include "device_common.hpp"
 
+#include <hip/hip_ext.h>
 #include <stdlib.h>
 
 namespace es {
@@ -20,6 +21,18 @@ static inline int pick_waves(int dflt, int nkt, const char* env) {
   while (nw > 1 && nkt / nw < 8) nw /= 2;
   return nw;
 }
+
+// Every launch of the forward pass goes through here; see LaunchTimer.
+#define ES_LAUNCH(kernel, grid, block, lds, st, ...)                                                              \
+  do {                                                                                                            \
+    es::LaunchTimer* t_ = es::g_launch_timer;                                                                     \
+    if (t_ && t_->used + 2 <= t_->cap) {                                                                          \
+      hipExtLaunchKernelGGL(kernel, grid, block, lds, st, t_->ev[t_->used], t_->ev[t_->used + 1], 0, __VA_ARGS__); \
+      t_->used += 2;                                                                                              \
+    } else {                                                                                                      \
+      hipLaunchKernelGGL(kernel, grid, block, lds, st, __VA_ARGS__);                                              \
+    }                                                                                                             \
+  } while (0)
 
 static inline size_t red_bytes(int nw, int rt) { return (size_t)(nw > 1 ? nw - 1 : 0) * rt * 64 * sizeof(f32x4); }
 

@@ -30,7 +30,9 @@ def test_header_constants_match_binding():
     for name in ("EASYSPEC_OK", "EASYSPEC_EINVAL", "EASYSPEC_ECAPACITY", "EASYSPEC_ESTATE", "EASYSPEC_EHIP",
                  "EASYSPEC_DTYPE_F32", "EASYSPEC_DTYPE_BF16", "EASYSPEC_POLICY_ALIGNED", "EASYSPEC_POLICY_PACKED",
                  "EASYSPEC_MAX_BATCH", "EASYSPEC_MAX_CALIB_TOKENS", "EASYSPEC_MAX_SET", "EASYSPEC_OP_QKV",
-                 "EASYSPEC_OP_ATTN", "EASYSPEC_OP_OPROJ", "EASYSPEC_OP_GATEUP", "EASYSPEC_OP_DOWN", "EASYSPEC_OP_HEAD"):
+                 "EASYSPEC_OP_ATTN", "EASYSPEC_OP_OPROJ", "EASYSPEC_OP_GATEUP", "EASYSPEC_OP_DOWN", "EASYSPEC_OP_HEAD", "EASYSPEC_OP_ALL",
+                 "EASYSPEC_MAX_TREE_WIDTH", "EASYSPEC_MAX_TREE_NODES", "EASYSPEC_MAX_CHUNKS", "EASYSPEC_PARALLEL_ATTENTION",
+                 "EASYSPEC_PARALLEL_FULL_LAYER"):
         m = re.search(rf"#define\s+{name}\s+\(?(-?\d+)\)?", header)
         assert m, name
         assert int(m.group(1)) == getattr(es.binding, name), name
@@ -226,3 +228,90 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode != 0
     assert "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+# ---------------------------------------------------------------------------- the weight stream's index arithmetic
+
+WEIGHT_OPS = ("EASYSPEC_OP_QKV", "EASYSPEC_OP_OPROJ", "EASYSPEC_OP_GATEUP", "EASYSPEC_OP_DOWN", "EASYSPEC_OP_HEAD")
+
+
+def check_walk(cfg, op, n_cols, k, full=False):
+    """Every piece a launch reads lies inside the packed matrices of its layers, reaches their last piece, and
+    every k-tile of every row tile is read exactly once (a missing last unit of a two-unit workgroup is
+    re-read on purpose); every activation fragment lies inside its operand slot."""
+    r = es.easyspec_weight_walk(cfg, getattr(es, op), n_cols, k, full)
+    what = (op, n_cols, k, full, r)
+    assert r["w_out_of_range"] == 0 and 0 <= r["w_max"] == r["w_pieces"] - 1, what
+    assert r["x_out_of_range"] == 0 and 0 <= r["x_max"] < r["x_slot_elems"], what
+    assert r["missed_tiles"] == 0 and r["repeated_tiles"] == 0 and r["uncovered_pieces"] == 0, what
+    if r["units_per_wg"] == 1:
+        assert r["reread_tiles"] == 0, what
+    assert r["grid"] >= 1 and 1 <= r["waves"] <= 16 and r["fragments"] == (2 if cfg.dtype == es.EASYSPEC_DTYPE_BF16 and n_cols > 8 else 1), what
+    return r
+
+
+@pytest.mark.parametrize("shape,dtype", [("tiny", "fp32"), ("tiny", "bf16"), ("tiny_qwen", "fp32"), ("tiny_qwen", "bf16")])
+def test_weight_stream_index_arithmetic_small_shapes(monkeypatch, shape, dtype):
+    """Host walk of every weight-streaming launch shape of the small models: all column counts, set sizes,
+    both parallel modes, forced wave counts (including counts that do not divide K), forced tile heights and
+    forced two-unit workgroups.  A wrong tile-to-wave assignment (a skipped or doubled k-tile), a wrong clamp
+    of the last unit or a lane piece outside its fragment shows up here, on the CPU, before any launch."""
+    base = synth.model_shape(shape, dtype=dtype)
+    cfg = es.make_config(base, 2, 128, 16)
+    n = 0
+    for op in WEIGHT_OPS:
+        for n_cols in range(1, 17):
+            for k in (1, 2, 3, base["n_layers"]):
+                check_walk(cfg, op, n_cols, k)
+                n += 1
+                if op in ("EASYSPEC_OP_OPROJ", "EASYSPEC_OP_GATEUP", "EASYSPEC_OP_DOWN"):
+                    check_walk(cfg, op, n_cols, k, full=True)
+    assert n == 5 * 16 * 4
+    for env in ("EASYSPEC_NW_QKV", "EASYSPEC_NW_O", "EASYSPEC_NW_GU", "EASYSPEC_NW_DOWN", "EASYSPEC_NW_HEAD"):
+        for nw in (1, 2, 3, 5, 6, 7, 8, 11, 16):
+            monkeypatch.setenv(env, str(nw))
+            for op in WEIGHT_OPS:
+                for n_cols in (1, 5, 12):
+                    check_walk(cfg, op, n_cols, 2)
+        monkeypatch.delenv(env)
+    for pair in ("0", "1"):
+        monkeypatch.setenv("EASYSPEC_PAIR_TILES", pair)
+        for rows in (13, 14, 15, 16):
+            monkeypatch.setenv("EASYSPEC_TILE_ROWS", str(rows))
+            for qrows in (8, 12, 16):
+                monkeypatch.setenv("EASYSPEC_QKV_TILE_ROWS", str(qrows))
+                for op in WEIGHT_OPS:
+                    for n_cols in (1, 9, 16):
+                        r = check_walk(cfg, op, n_cols, 3)
+                        if dtype == "bf16" and n_cols > 8 and op != "EASYSPEC_OP_DOWN":
+                            assert r["units_per_wg"] == (2 if pair == "1" else 1)
+
+
+@pytest.mark.parametrize("shape", ["llama3_8b", "qwen2_7b"])
+def test_weight_stream_index_arithmetic_benchmark_shapes(shape):
+    """The same walk at the two benchmark shapes with the launch shapes the library picks there (14-row gate/up
+    tiles and 12-pair QKV tiles at the 8B width, seven waves in the down projection, two-unit workgroups in
+    two-fragment passes where they fill the CUs), for the set sizes of the benchmark strategies."""
+    base = synth.model_shape(shape)
+    cfg = es.make_config(base, 4, 32768, 16)
+    seen_two_units = False
+    for op in WEIGHT_OPS:
+        for n_cols, k in ((1, 1), (1, 3), (1, 4), (1, 7), (4, 4), (6, 1), (9, 1), (12, 4), (16, 8)):
+            r = check_walk(cfg, op, n_cols, k)
+            seen_two_units = seen_two_units or r["units_per_wg"] == 2
+    assert seen_two_units
+    r = check_walk(cfg, "EASYSPEC_OP_DOWN", 1, 1)
+    assert r["waves"] == (7 if shape == "llama3_8b" else 8) and r["grid"] == base["d_model"] // 16
+    r = check_walk(cfg, "EASYSPEC_OP_GATEUP", 1, 1)
+    assert r["tile_rows"] == (14 if shape == "llama3_8b" else 16)
+    for op in ("EASYSPEC_OP_OPROJ", "EASYSPEC_OP_GATEUP", "EASYSPEC_OP_DOWN"):
+        check_walk(cfg, op, 1, 4, full=True)
+
+
+def test_weight_walk_rejects_bad_arguments():
+    cfg = es.make_config(synth.model_shape("tiny"), 1, 64, 16)
+    for args in ((es.EASYSPEC_OP_ATTN, 1, 1), (es.EASYSPEC_OP_QKV, 0, 1), (es.EASYSPEC_OP_QKV, 17, 1), (es.EASYSPEC_OP_QKV, 1, 0),
+                 (es.EASYSPEC_OP_QKV, 1, 9), (es.EASYSPEC_OP_QKV, 1, 5), (es.EASYSPEC_OP_ALL, 1, 1)):
+        with pytest.raises(es.EasySpecError) as e:
+            es.easyspec_weight_walk(cfg, *args)
+        assert e.value.code == es.EASYSPEC_EINVAL

@@ -187,6 +187,92 @@ def test_dropped_fuzzy_slots_are_never_read(gpu, dtype):
     assert np.array_equal(a1, b1) and np.array_equal(a2, b2)
 
 
+@pytest.mark.parametrize("shape,dtype,bounds", [("tiny", "fp32", [0, 1, 3, 4]), ("tiny", "bf16", [0, 4]),
+                                                ("tiny_qwen", "bf16", [0, 1, 4, 5])])
+def test_workspaces_hold_nothing_between_calls(gpu, monkeypatch, shape, dtype, bounds):
+    """Every workspace between the kernels of a pass (residual stream, norm operands and partial sums,
+    queries, attention outputs, split-KV partials, parked Attnoutputs, MLP activations, argmax candidates)
+    is filled with NaN before every call: logits, drafted ids and the cache keep every bit.  Covers
+    prefill in chunks, split-KV attention with a merge (context beyond one chunk), chain steps, a tree
+    level on the vector kernel and on the matrix cores, a two-fragment calibration, and the full-layer mode."""
+    import paper_2502_02493_amd as es
+    cfg = synth.model_shape(shape, dtype=dtype)
+    w = synth.make_weights(cfg, 650)
+    toks = [int(t) for t in synth.make_tokens(651, 400, cfg["vocab"])]
+
+    def run(poison):
+        g = gpu.GpuDrafter(cfg, w, 2, 512, 16)
+        outs = []
+
+        def p():
+            if poison:
+                es.easyspec_poison_workspaces(g.ctx)
+
+        try:
+            g.set_groups(bounds)
+            for i in range(0, 320, 16):                                   # 320 slots: past the single-chunk limit
+                p(); _, l = g.calibrate({0: toks[i:i + 16]})
+            outs.append(l[0])
+            p(); _, l = g.calibrate({1: toks[320:331]}); outs.append(l[1])   # 11 columns: two activation fragments (bf16)
+            for t in toks[331:334]:
+                p(); tk, l = g.draft_step({0: t, 1: t + 1 if t + 1 < cfg["vocab"] else 0}); outs += [tk.copy(), l]
+            p(); _, l = g.calibrate({0: toks[334:337]}); outs.append(l[0])
+            p(); tk, l = g.draft_tree_step({0: (toks[337:341], [-1, -1, -1, -1])}); outs += [tk[0], l[0]]
+            p(); tk, l = g.draft_tree_step({0: (toks[341:347], [0, 0, 1, 2, 3, 3])}); outs += [tk[0], l[0]]
+            g.set_full_layer(True)
+            p(); _, l = g.calibrate({0: toks[347:349], 1: toks[349:350]}); outs += [l[0], l[1]]
+            p(); tk, l = g.draft_step({0: toks[350], 1: toks[351]}); outs += [tk.copy(), l]
+            k, v = g.export_kv(0, int(g.lens()[0][0]) + int(g.lens()[1][0]))
+            outs += [k, v]
+            return outs
+        finally:
+            g.close()
+
+    a = run(False)
+    for mfma in ("1", "2"):                                               # 2: every multi-column launch on the matrix cores (bf16)
+        monkeypatch.setenv("EASYSPEC_ATTN_MFMA", mfma)
+        ref = a if mfma == "1" else run(False)
+        b = run(True)
+        assert len(ref) == len(b)
+        for x, y in zip(ref, b):
+            assert np.all(np.isfinite(np.asarray(y, dtype=np.float64)))
+            assert np.array_equal(x, y)
+
+
+def test_per_launch_timing_counts_every_launch(gpu):
+    """easyspec_profile_*: every launch of the profiled kernel class carries its own event pair; the count is
+    the launch count the set table implies and every duration is a plausible kernel time."""
+    import paper_2502_02493_amd as es
+    cfg = synth.model_shape("tiny")
+    w = synth.make_weights(cfg, 660)
+    g = gpu.GpuDrafter(cfg, w, 1, 600, 16)
+    try:
+        g.set_groups([0, 1, 3, 4])
+        toks = [int(t) for t in synth.make_tokens(661, 330, cfg["vocab"])]
+        for i in range(0, 320, 16):
+            g.calibrate({0: toks[i:i + 16]})
+        _, ref = g.draft_step({0: toks[320]})
+        es.easyspec_truncate(g.ctx, 0, 320)
+        want = {es.EASYSPEC_OP_QKV: 3, es.EASYSPEC_OP_ATTN: 6, es.EASYSPEC_OP_OPROJ: 3, es.EASYSPEC_OP_GATEUP: 4,
+                es.EASYSPEC_OP_DOWN: 4, es.EASYSPEC_OP_HEAD: 2}             # 3 sets, 4 layers; attention = partial + merge
+        for op, n_want in want.items():
+            per = np.full(16, -1.0, np.float32)
+            es.easyspec_profile_begin(g.ctx, op, 16)
+            _, got = g.draft_step({0: toks[320]})
+            n, total = es.easyspec_profile_end(g.ctx, per)
+            es.easyspec_truncate(g.ctx, 0, 320)
+            assert n == n_want, (op, n)
+            assert np.all(per[:n] > 0.0005) and np.all(per[:n] < 1.0) and np.all(per[n:] == -1.0), per    # 0.5 us ... 1 ms
+            assert abs(float(per[:n].sum()) - total) < 1e-3 * total + 1e-6
+            assert np.array_equal(got, ref)                                 # timing changes no result
+        es.easyspec_profile_begin(g.ctx, es.EASYSPEC_OP_GATEUP, 2)          # fewer pairs than launches: the rest runs untimed
+        g.draft_step({0: toks[320]})
+        n, _ = es.easyspec_profile_end(g.ctx)
+        assert n == 2
+    finally:
+        g.close()
+
+
 def test_repeated_runs_are_bit_identical(gpu):
     """Fixed summation orders everywhere: the same calls give the same bits."""
     cfg = synth.model_shape("tiny_qwen", dtype="bf16")
