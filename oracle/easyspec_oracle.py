@@ -40,7 +40,8 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        L = C.CDLL(build())
+        # EASYSPEC_ORACLE_LIB: another build of the same source (the sanitizer build of tests/test_oracle_sanitized.py)
+        L = C.CDLL(os.environ.get("EASYSPEC_ORACLE_LIB") or build())
         vp, i32, dp, fp, ip = C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_float), C.POINTER(C.c_int32)
         L.eso_bf16_round.restype = C.c_double
         L.eso_bf16_round.argtypes = [C.c_double]
