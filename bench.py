@@ -164,61 +164,46 @@ class Loop:
                           "tokens_drawn": "uniform 1..%d" % self.M if self.draw_calib else "fixed", "bytes": calib_bytes,
                           "hbm_frac": round(calib_bytes / (calib_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}}
 
-    def event_cost(self, reps=4):
-        """What binding a start and a stop event to a dispatch adds to the duration it then reports.  The kernels
-        of a draft step depend on each other and run back to back (a kernel trace shows no gaps), so their
-        durations add up to the step's duration; the event-bound durations of the same launches add up to
-        more, by a fixed cost per launch.  Returns (microseconds per launch, launches per step)."""
-        es, env = self.env.es, self.env
-        ev = env.events(2)
-        wall = 0.0
+    def timed(self, what, reps):
+        """Every kernel of `reps` x (the draft steps of an iteration | a calibration) with a start and a stop event
+        bound to its dispatch, as a kernel trace times them.  Returns (microseconds per launch, kernel class per
+        launch, calls): calls = draft steps or calibrations covered."""
+        es = self.env.es
+        cap = reps * 4096
+        ms, op = np.zeros(cap, np.float32), np.zeros(cap, np.int32)
+        us_all, op_all = [], []
         for _ in range(reps):
-            self.calibrate()
-            ev[0].record()
-            self.steps()
-            ev[1].record()
-            env.torch.cuda.synchronize()
-            wall += ev[0].elapsed_time(ev[1])
-        n_tot, ms_tot = 0, 0.0
-        for _ in range(reps):
-            self.calibrate()
+            if what == "step":
+                self.calibrate()
+            else:
+                self.reset()
             es.easyspec_profile_begin(self.ctx, es.EASYSPEC_OP_ALL, 4096)
-            self.steps()
-            n, ms = es.easyspec_profile_end(self.ctx)
-            n_tot, ms_tot = n_tot + n, ms_tot + ms
-        return 1e3 * (ms_tot - wall) / max(n_tot, 1), n_tot / (reps * (self.gamma - 1))
+            if what == "step":
+                self.steps()
+            else:
+                self.calibrate()
+            n, _ = es.easyspec_profile_end(self.ctx, ms, op)
+            us_all.append(1e3 * ms[:n].astype(np.float64))
+            op_all.append(op[:n].copy())
+        return np.concatenate(us_all), np.concatenate(op_all), reps * ((self.gamma - 1) if what == "step" else 1)
 
-    def kernel_table(self, cost_us, reps=3):
-        """Per kernel class: launches, microseconds (each kernel's own begin-to-end time from events bound to its
-        dispatch, less the events' own cost per launch) and algorithmic bytes per draft step and per calibration,
-        with the share of the HBM roofline."""
-        es, env = self.env.es, self.env
+    def kernel_table(self, reps=3):
+        """Per kernel class: launches, microseconds (each kernel's own begin-to-end time) and algorithmic bytes per
+        draft step and per calibration, with the share of the HBM roofline; and how the kernels' durations add up
+        against the duration of the whole call (dependent kernels run back to back)."""
+        env = self.env
         step_bytes, _, _ = self.bytes()
         weights = op_bytes(self.cfg, 0)
-        kv = step_bytes - sum(weights.values())
-        per = op_bytes(self.cfg, kv)
-        table = {}
-        for name in OPS:
-            row = {}
-            for what in ("per_step", "per_calibration"):
-                n_tot, ms_tot = 0, 0.0
-                for _ in range(reps):
-                    if what == "per_step":
-                        self.calibrate()
-                    else:
-                        self.reset()
-                    es.easyspec_profile_begin(self.ctx, env.op_id[name], 4096)
-                    if what == "per_step":
-                        self.steps()
-                    else:
-                        self.calibrate()
-                    n, ms = es.easyspec_profile_end(self.ctx)
-                    n_tot, ms_tot = n_tot + n, ms_tot + ms
-                calls = reps * ((self.gamma - 1) if what == "per_step" else 1)
-                us = (1e3 * ms_tot - cost_us * n_tot) / calls
-                row[what] = {"launches": round(n_tot / calls, 1), "us": round(us, 1), "bytes": per[name],
-                             "hbm_frac": round(per[name] / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
-            table[name] = row
+        per = op_bytes(self.cfg, step_bytes - sum(weights.values()))
+        table = {name: {} for name in OPS}
+        for what, key in (("step", "per_step"), ("calibration", "per_calibration")):
+            us, op, calls = self.timed(what, reps)
+            for name in OPS:
+                sel = op == env.op_id[name]
+                t = float(us[sel].sum()) / calls
+                table[name][key] = {"launches": round(int(sel.sum()) / calls, 1), "us": round(t, 1), "bytes": per[name],
+                                    "hbm_frac": round(per[name] / (t * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
+            table["all_kernels_" + key] = {"launches": round(len(us) / calls, 1), "sum_us": round(float(us.sum()) / calls, 1)}
         return table
 
 
@@ -347,19 +332,21 @@ def main():
     e = 2 if cfg["dtype"] == "bf16" else 4
     gu_bytes = 2 * cfg["d_ffn"] * cfg["d_model"] * e
 
-    # Dominant kernel (gate/up projection: 2*F*d weights per launch): every launch of the same iterations again
-    # with a start and a stop event bound to its dispatch, i.e. the kernel's own begin-to-end time.
-    n_launch = args.steps * gamma * cfg["n_layers"]
-    per_launch = np.zeros(n_launch, np.float32)
-    es.easyspec_profile_begin(ctx, es.EASYSPEC_OP_GATEUP, n_launch)
+    # Dominant kernel (gate/up projection: 2*F*d weights per launch): the same iterations again with a start and a
+    # stop event bound to every kernel's dispatch (what a kernel trace does); its launches are those of class GATEUP.
+    per_iter = 4096
+    ms, op = np.zeros(per_iter, np.float32), np.zeros(per_iter, np.int32)
+    gu_us = []
     for _ in range(args.steps):
+        es.easyspec_profile_begin(ctx, es.EASYSPEC_OP_ALL, per_iter)
         loop.iteration()
-    n_timed, total_ms = es.easyspec_profile_end(ctx, per_launch)
-    cost_us, launches_timed_per_step = loop.event_cost()
-    gu_raw_ms = total_ms / max(n_timed, 1)
-    gu_ms = gu_raw_ms - 1e-3 * cost_us
+        n, _ = es.easyspec_profile_end(ctx, ms, op)
+        gu_us.append(1e3 * ms[:n][op[:n] == es.EASYSPEC_OP_GATEUP].astype(np.float64))
+    gu_us = np.concatenate(gu_us)
+    n_timed = int(gu_us.size)
+    gu_ms = 1e-3 * float(gu_us.mean())
     gu_gbs = gu_bytes / (gu_ms * 1e-3) / 1e9
-    kernels = loop.kernel_table(cost_us)
+    kernels = loop.kernel_table()
 
     # what a kernel that only reads reaches on this device (same loads as the weight stream), 4 GiB per pass
     probe = torch.empty(1 << 30, dtype=torch.int32, device=dev)
@@ -395,15 +382,10 @@ def main():
                      "traffic": traffic_kib * 1024 if traffic_kib else None,
                      "traffic_source": "profiles/hbm_traffic_llama3_8b_ctx2048.md (rocprofv3 --pmc runs of this workload; a committed figure, not a reading of this run)" if traffic_kib else None,
                      "bytes_per_launch": int(gu_bytes), "avg_launch_us": round(1e3 * gu_ms, 2),
-                     "event_bound_avg_us": round(1e3 * gu_raw_ms, 2), "event_cost_us_per_launch": round(cost_us, 3),
-                     "event_bound_median_us": round(1e3 * float(np.median(per_launch[:n_timed])), 2) if n_timed else None,
-                     "event_bound_min_us": round(1e3 * float(np.min(per_launch[:n_timed])), 2) if n_timed else None,
-                     "frac_from_event_bound_avg": round(gu_bytes / (gu_raw_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                     "timing": "a start and a stop event bound to each launch's own dispatch (kernel begin to end), over the launches of "
-                               "the timed iterations (calibrations and draft steps); avg_launch_us = that average less what the events "
-                               "themselves add per launch, measured in this run as (sum of the event-bound durations of a draft "
-                               "step's %d back-to-back launches - the step's duration) / launches; profiles/kernel_stats_llama3_8b_ctx2048.md "
-                               "holds the kernel trace of the same iterations" % round(launches_timed_per_step),
+                     "median_launch_us": round(float(np.median(gu_us)), 2), "min_launch_us": round(float(gu_us.min()), 2),
+                     "timing": "a start and a stop HIP event bound to the dispatch of every kernel of the timed iterations "
+                               "(calibrations and draft steps), as a kernel trace times them; no correction applied; "
+                               "profiles/kernel_stats_llama3_8b_ctx2048.md holds the rocprofv3 kernel trace of the same command",
                      "launches_timed": n_timed, "stream_read_gbs": round(stream_gbs, 1),
                      "frac_of_stream_read": round(gu_gbs / stream_gbs, 4)},
         "kernels": kernels,

@@ -305,12 +305,14 @@ int easyspec_weight_walk(const easyspec_config *cfg, int32_t op, int32_t n_cols,
 /* Per-kernel timing for roofline reports.  Between profile_begin and profile_end every kernel
  * launch of the class `op` made by draft steps and calibrations carries a start and a stop HIP
  * event bound to its own dispatch (at most max_launches launches; later ones run untimed), so a
- * pair's elapsed time is that kernel's begin-to-end time, the figure a kernel trace reports.
+ * pair's elapsed time is that kernel's begin-to-end time.  With EASYSPEC_OP_ALL every launch of
+ * the forward pass is timed, which is what a kernel trace does and gives the figures that compare
+ * with one (a timed kernel that follows an untimed one also counts part of its predecessor's tail).
  * profile_end synchronises the stream and returns the number of timed launches, the sum of their
- * durations in milliseconds and, if launch_ms is not NULL (host, max_launches floats), each
- * launch's duration in launch order.  A class with two kernels per use (attention: partial +
- * merge; head: logits + argmax) counts each kernel as a launch.  Not meant to stay on in
- * production. */
+ * durations in milliseconds and, where launch_ms / launch_op are not NULL (host, max_launches
+ * entries each), every launch's duration and kernel class in launch order (the embedding gather
+ * reports EASYSPEC_OP_ALL).  A class with two kernels per use (attention: partial + merge; head:
+ * logits + argmax) counts each kernel as a launch.  Not meant to stay on in production. */
 #define EASYSPEC_OP_QKV 0    /* stacked QKV projection + rotary + cache write */
 #define EASYSPEC_OP_ATTN 1   /* split-KV decode attention (partial + merge kernels together) */
 #define EASYSPEC_OP_OPROJ 2  /* stacked O projection */
@@ -319,7 +321,7 @@ int easyspec_weight_walk(const easyspec_config *cfg, int32_t op, int32_t n_cols,
 #define EASYSPEC_OP_HEAD 5   /* LM head + argmax (both kernels together) */
 #define EASYSPEC_OP_ALL 6    /* every kernel of the forward pass, the embedding gather included */
 int easyspec_profile_begin(easyspec_ctx *ctx, int32_t op, int32_t max_launches);
-int easyspec_profile_end(easyspec_ctx *ctx, int32_t *n_launches, float *total_ms, float *launch_ms);
+int easyspec_profile_end(easyspec_ctx *ctx, int32_t *n_launches, float *total_ms, float *launch_ms, int32_t *launch_op);
 
 /* Message of the last failed call on ctx (ctx == NULL: of the last failed easyspec_create or
  * context-free call on this thread).  Never NULL. */

@@ -92,7 +92,7 @@ def load_library():
         L.easyspec_step_bytes.restype = C.c_int64
         L.easyspec_weight_walk.argtypes = [C.POINTER(easyspec_config), i32, i32, i32, i32, vp]
         L.easyspec_profile_begin.argtypes = [vp, i32, i32]
-        L.easyspec_profile_end.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_float), vp]
+        L.easyspec_profile_end.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_float), vp, vp]
         L.easyspec_last_error.argtypes = [vp]
         L.easyspec_last_error.restype = C.c_char_p
         _lib = L
@@ -290,13 +290,13 @@ def easyspec_profile_begin(ctx, op: int, max_launches: int):
     _check(load_library().easyspec_profile_begin(ctx, op, max_launches), ctx)
 
 
-def easyspec_profile_end(ctx, per_launch=None):
-    """Returns (timed launches, total milliseconds); per_launch: a float32 numpy array of at least
-    max_launches entries that receives each launch's milliseconds."""
+def easyspec_profile_end(ctx, per_launch=None, per_launch_op=None):
+    """Returns (timed launches, total milliseconds); per_launch / per_launch_op: float32 / int32 numpy arrays of
+    at least max_launches entries that receive each launch's milliseconds and kernel class."""
     n, ms = C.c_int32(0), C.c_float(0.0)
-    if per_launch is not None:
-        assert per_launch.dtype == np.float32
-    _check(load_library().easyspec_profile_end(ctx, C.byref(n), C.byref(ms), _ptr(per_launch)), ctx)
+    assert per_launch is None or per_launch.dtype == np.float32
+    assert per_launch_op is None or per_launch_op.dtype == np.int32
+    _check(load_library().easyspec_profile_end(ctx, C.byref(n), C.byref(ms), _ptr(per_launch), _ptr(per_launch_op)), ctx)
     return n.value, ms.value
 
 

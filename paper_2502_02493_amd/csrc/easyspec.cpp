@@ -39,6 +39,7 @@ struct easyspec_ctx {
   // per-kernel timing (easyspec_profile_*)
   int32_t prof_op;
   std::vector<hipEvent_t> prof_ev;  // start/stop pairs
+  std::vector<int8_t> prof_op_of;   // kernel class of the launch that took pair i
   LaunchTimer timer;                // the pairs handed to the launches of the profiled kernel class
   std::string err;
 };
@@ -130,7 +131,7 @@ extern "C" int easyspec_create(const easyspec_config* cfg, void* hip_stream, eas
   ctx->weights_loaded = false;
   ctx->last_rows = 0;
   ctx->prof_op = -1;
-  ctx->timer = LaunchTimer{nullptr, 0, 0};
+  ctx->timer = LaunchTimer{nullptr, nullptr, 0, 0, 0};
   ctx->parallel_mode = EASYSPEC_PARALLEL_ATTENTION;
   Shape& s = ctx->s;
   shape_of(cfg, s);
@@ -339,7 +340,10 @@ extern "C" int easyspec_set_groups(easyspec_ctx* ctx, const int32_t* bounds, int
 
 // While profiling is on, the launches of one kernel class made inside the scope take event pairs.
 struct ProfScope {
-  ProfScope(easyspec_ctx* c, int op) { g_launch_timer = (c->prof_op == op || c->prof_op == EASYSPEC_OP_ALL) ? &c->timer : nullptr; }
+  ProfScope(easyspec_ctx* c, int op) {
+    g_launch_timer = (c->prof_op == op || c->prof_op == EASYSPEC_OP_ALL) ? &c->timer : nullptr;
+    c->timer.cur_op = op;
+  }
   ~ProfScope() { g_launch_timer = nullptr; }
 };
 
@@ -707,12 +711,13 @@ extern "C" int easyspec_profile_begin(easyspec_ctx* ctx, int32_t op, int32_t max
     HIPCHK(ctx, hipEventCreate(&e));
     ctx->prof_ev.push_back(e);
   }
-  ctx->timer = LaunchTimer{ctx->prof_ev.data(), (size_t)max_launches * 2, 0};
+  if (ctx->prof_op_of.size() < (size_t)max_launches) ctx->prof_op_of.resize((size_t)max_launches);
+  ctx->timer = LaunchTimer{ctx->prof_ev.data(), ctx->prof_op_of.data(), (size_t)max_launches * 2, 0, 0};
   ctx->prof_op = op;
   return EASYSPEC_OK;
 }
 
-extern "C" int easyspec_profile_end(easyspec_ctx* ctx, int32_t* n_launches, float* total_ms, float* launch_ms) {
+extern "C" int easyspec_profile_end(easyspec_ctx* ctx, int32_t* n_launches, float* total_ms, float* launch_ms, int32_t* launch_op) {
   if (!ctx) return fail(nullptr, EASYSPEC_EINVAL, "ctx is NULL");
   if (!n_launches || !total_ms) return fail(ctx, EASYSPEC_EINVAL, "profile_end: NULL argument");
   if (ctx->prof_op < 0) return fail(ctx, EASYSPEC_ESTATE, "profile_end: not profiling");
@@ -723,6 +728,7 @@ extern "C" int easyspec_profile_end(easyspec_ctx* ctx, int32_t* n_launches, floa
     float ms = 0.f;
     HIPCHK(ctx, hipEventElapsedTime(&ms, ctx->timer.ev[i], ctx->timer.ev[i + 1]));
     if (launch_ms) launch_ms[i / 2] = ms;
+    if (launch_op) launch_op[i / 2] = ctx->timer.op[i / 2];
     sum += ms;
   }
   *n_launches = (int32_t)(ctx->timer.used / 2);

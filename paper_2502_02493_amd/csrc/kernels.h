@@ -71,8 +71,10 @@ struct Buffers {
 // launch of the forward pass binds the next start / stop event pair to its own dispatch, so that the pair's
 // elapsed time is the kernel's begin-to-end time as a kernel trace reports it (no stream markers between).
 struct LaunchTimer {
-  hipEvent_t* ev;  // start / stop pairs
+  hipEvent_t* ev;   // start / stop pairs
+  int8_t* op;       // kernel class of the launch that took pair i (EASYSPEC_OP_*), one entry per pair
   size_t cap, used;
+  int cur_op;       // class of the launches made right now
 };
 extern thread_local LaunchTimer* g_launch_timer;
 

@@ -28,6 +28,7 @@ static inline int pick_waves(int dflt, int nkt, const char* env) {
     es::LaunchTimer* t_ = es::g_launch_timer;                                                                     \
     if (t_ && t_->used + 2 <= t_->cap) {                                                                          \
       hipExtLaunchKernelGGL(kernel, grid, block, lds, st, t_->ev[t_->used], t_->ev[t_->used + 1], 0, __VA_ARGS__); \
+      t_->op[t_->used / 2] = (int8_t)t_->cur_op;                                                                  \
       t_->used += 2;                                                                                              \
     } else {                                                                                                      \
       hipLaunchKernelGGL(kernel, grid, block, lds, st, __VA_ARGS__);                                              \

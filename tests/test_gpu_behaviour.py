@@ -265,6 +265,17 @@ def test_per_launch_timing_counts_every_launch(gpu):
             assert np.all(per[:n] > 0.0005) and np.all(per[:n] < 1.0) and np.all(per[n:] == -1.0), per    # 0.5 us ... 1 ms
             assert abs(float(per[:n].sum()) - total) < 1e-3 * total + 1e-6
             assert np.array_equal(got, ref)                                 # timing changes no result
+        # every kernel of the pass, with its class, in launch order: embed; per set QKV, attention, merge, O, then
+        # gate/up and down per layer; head and argmax
+        per, ops = np.zeros(64, np.float32), np.full(64, -1, np.int32)
+        es.easyspec_profile_begin(g.ctx, es.EASYSPEC_OP_ALL, 64)
+        _, got = g.draft_step({0: toks[320]})
+        n, total = es.easyspec_profile_end(g.ctx, per, ops)
+        es.easyspec_truncate(g.ctx, 0, 320)
+        Q, A, O, G, D, H, E = (es.EASYSPEC_OP_QKV, es.EASYSPEC_OP_ATTN, es.EASYSPEC_OP_OPROJ, es.EASYSPEC_OP_GATEUP,
+                               es.EASYSPEC_OP_DOWN, es.EASYSPEC_OP_HEAD, es.EASYSPEC_OP_ALL)
+        assert list(ops[:n]) == [E, Q, A, A, O, G, D, Q, A, A, O, G, D, G, D, Q, A, A, O, G, D, H, H]
+        assert np.all(per[:n] > 0.0005) and np.array_equal(got, ref)
         es.easyspec_profile_begin(g.ctx, es.EASYSPEC_OP_GATEUP, 2)          # fewer pairs than launches: the rest runs untimed
         g.draft_step({0: toks[320]})
         n, _ = es.easyspec_profile_end(g.ctx)
