@@ -267,6 +267,55 @@ def test_batch16_ragged_contexts(oracle, gpu, dtype):
         g.close()
 
 
+@pytest.mark.parametrize("shape,dtype", [("tiny", "fp32"), ("tiny", "bf16"), ("tiny_qwen", "bf16")])
+def test_maximum_context_filled_to_the_last_slot(oracle, gpu, shape, dtype):
+    """The library's largest context (65 536 slots: 64 split-KV chunks of 1024) on small models: a synthetic prefix,
+    a 9-token calibration, fuzzy steps, a 4-wide tree level whose last node takes slot 65 535, then every further
+    call is refused with ECAPACITY and leaves the lengths alone."""
+    import paper_2502_02493_amd as es
+    cfg = synth.model_shape(shape, dtype=dtype)
+    w = synth.make_weights(cfg, 540)
+    max_ctx, tol = 65536, TOL[dtype]
+    bounds = groups(es, cfg, 2, "packed")
+    so = oracle.Sequence(oracle.Model(cfg, w, max_ctx))
+    g = gpu.GpuDrafter(cfg, w, max_batch=1, max_ctx=max_ctx, max_calib=16)
+    try:
+        g.set_groups(bounds)
+        n0 = max_ctx - 9 - 3 - 4
+        k, v = synth.make_kv_prefix(cfg, 541, n0)
+        so.import_kv(k, v); g.import_kv(0, k, v)
+        toks = [int(t) for t in synth.make_tokens(542, 32, cfg["vocab"])]
+        wl = so.calibrate(toks[:9], all_rows=True)
+        _, gl = g.calibrate({0: toks[:9]}, all_rows=True)
+        gpu.assert_close(gl[0], wl, tol, "9-token calibration behind 65 520 slots")
+        # the calibration again after a chain of fuzzy steps was dropped
+        for t in toks[9:12]:
+            gpu.assert_close(g.draft_step({0: t})[1][0], so.fuzzy_step(bounds, t), tol, "fuzzy step")
+        es.easyspec_truncate(g.ctx, 0, n0 + 9); so.set_lens(n0 + 9, 0)
+        for t in toks[12:15]:
+            gpu.assert_close(g.draft_step({0: t})[1][0], so.fuzzy_step(bounds, t), tol, "fuzzy step")
+        es.easyspec_truncate(g.ctx, 0, n0 + 9); so.set_lens(n0 + 9, 0)
+        wl = so.calibrate(toks[15:18], all_rows=True)
+        _, gl = g.calibrate({0: toks[15:18]}, all_rows=True)
+        gpu.assert_close(gl[0], wl, tol, "3-token calibration")
+        wl = so.fuzzy_tree_step(bounds, toks[18:22], [-1, -1, -1, -1])
+        _, gl = g.draft_tree_step({0: (toks[18:22], [-1, -1, -1, -1])})
+        gpu.assert_close(gl[0], wl, tol, "tree level that fills the context")
+        p, f = g.lens()
+        assert int(p[0]) + int(f[0]) == max_ctx == so.precise + so.fuzzy
+        for call in (lambda: g.draft_tree_step({0: ([1], [0])}), lambda: g.calibrate({0: toks[:5]})):
+            with pytest.raises(es.EasySpecError) as e:
+                call()
+            assert e.value.code == es.EASYSPEC_ECAPACITY
+        p2, f2 = g.lens()
+        assert (int(p2[0]), int(f2[0])) == (int(p[0]), int(f[0]))
+        gk, gv = g.export_kv(0, max_ctx)
+        assert gpu.rel_l2(gk[:, :, n0:], so.K[:, :, n0:]) < (4e-3 if dtype == "bf16" else tol)
+        assert gpu.rel_l2(gv[:, :, n0:], so.V[:, :, n0:]) < (4e-3 if dtype == "bf16" else tol)
+    finally:
+        g.close()
+
+
 _FULL = {}
 
 
