@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM KiB per launch of the dominant kernel (gate/up projection) from the rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs summarised in profiles/hbm_traffic_llama3_8b_ctx2048.md (scaled by a 1 GiB copy).  A
 # committed figure, not a reading of the run it is printed in.
-COMMITTED_TRAFFIC_KIB = {"llama3_8b_ctx2048": 230288.8}
+COMMITTED_TRAFFIC_KIB = {"llama3_8b_ctx2048": 230061.3}
 OPS = ("qkv", "attn", "oproj", "gateup", "down", "head")
 
 
