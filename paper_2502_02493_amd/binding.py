@@ -1,5 +1,5 @@
 """ctypes binding of libeasyspec.so: one Python function per C entry point of
-include/easyspec.h, same names, argument marshalling only.  Nothing is computed here and there
+include/easyspec.h and include/easyspec_instrument.h, same names, argument marshalling only.  Nothing is computed here and there
 is no fallback: if the library is missing or no GPU is usable the calls raise."""
 from __future__ import annotations
 

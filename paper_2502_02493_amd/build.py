@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libeasyspec.so")
 SOURCES = ["easyspec.cpp", "gemv.hip", "attention.hip", "util.hip", "accept.hip"]
 HEADERS = [os.path.join(CSRC, "kernels.h"), os.path.join(CSRC, "device_common.hpp"), os.path.join(CSRC, "launch_common.hpp"), os.path.join(CSRC, "tile_index.hpp"),
-           os.path.join(HERE, "..", "include", "easyspec.h")]
+           os.path.join(HERE, "..", "include", "easyspec.h"), os.path.join(HERE, "..", "include", "easyspec_instrument.h")]
 
 # -packed-fp32-ops off: the compiler must not form packed fp32 VALU instructions.
 HIPCC_FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -2,6 +2,7 @@
 // precise / fuzzy length state machine, weight repacking, and the launch sequence of one
 // forward pass.  All arithmetic of the method runs in the kernels of gemv.hip, attention.hip and accept.hip.
 #include "../../include/easyspec.h"
+#include "../../include/easyspec_instrument.h"
 
 #include <math.h>
 #include <stdarg.h>

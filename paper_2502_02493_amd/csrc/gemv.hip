@@ -7,7 +7,7 @@
 
 #include <vector>
 
-#include "../../include/easyspec.h"
+#include "../../include/easyspec_instrument.h"
 
 namespace es {
 

@@ -14,8 +14,13 @@ import paper_2502_02493_amd as es
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
+def _headers():
+    inc = os.path.join(ROOT, "include")
+    return "\n".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
+
+
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "easyspec.h")).read()
+    header = _headers()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(easyspec_[a-z_]+)\s*\(", header))
     assert declared, "no declarations found"
@@ -26,7 +31,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_header_constants_match_binding():
-    header = open(os.path.join(ROOT, "include", "easyspec.h")).read()
+    header = _headers()
     for name in ("EASYSPEC_OK", "EASYSPEC_EINVAL", "EASYSPEC_ECAPACITY", "EASYSPEC_ESTATE", "EASYSPEC_EHIP",
                  "EASYSPEC_DTYPE_F32", "EASYSPEC_DTYPE_BF16", "EASYSPEC_POLICY_ALIGNED", "EASYSPEC_POLICY_PACKED",
                  "EASYSPEC_MAX_BATCH", "EASYSPEC_MAX_CALIB_TOKENS", "EASYSPEC_MAX_SET", "EASYSPEC_OP_QKV",
@@ -36,6 +41,17 @@ def test_header_constants_match_binding():
         m = re.search(rf"#define\s+{name}\s+\(?(-?\d+)\)?", header)
         assert m, name
         assert int(m.group(1)) == getattr(es.binding, name), name
+
+
+def test_method_header_declares_no_instrumentation():
+    """easyspec.h is the boundary of the method; timing, probes, host models and poisoning live in
+    easyspec_instrument.h."""
+    core = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "easyspec.h")).read(), flags=re.S)
+    for name in ("easyspec_profile_begin", "easyspec_profile_end", "easyspec_stream_read", "easyspec_attention_cut",
+                 "easyspec_weight_walk", "easyspec_poison_workspaces"):
+        assert name not in core, name
+    for name in ("easyspec_draft_step", "easyspec_calibrate", "easyspec_greedy_accept", "easyspec_accept", "easyspec_draft_tree_step"):
+        assert name in core, name
 
 
 def test_default_groups_matches_paper_table_and_oracle(oracle):
