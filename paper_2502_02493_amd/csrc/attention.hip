@@ -17,6 +17,9 @@ namespace es {
 // leave registers, since K and V fragments of a slot sit in the same lanes.  The four waves'
 // states are combined through LDS; if the context has more than one chunk the workgroup
 // writes a partial (max, sum, accumulator) per head and attn_merge_kernel combines the chunks.
+// For bf16 caches with 128-element heads and four to eight query heads per KV head the scores come
+// from the matrix cores instead (K rows staged through the wave's own LDS into MFMA A fragments,
+// the queries as two bf16 terms): the vector ALUs keep the softmax of one head per lane and P.V.
 // ------------------------------------------------------------------------------------------
 struct AttnArgs {
   const float* Q;
@@ -124,15 +127,40 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
 
   float q[G][EPL], acc[G][EPL], m_run[G], l_run[G];
   // one head per lane (see the batch code): running maximum and sum of that head only
-  constexpr bool kHeadPerLane = G == 4 && LPS == 16;
+  // ... and, for bf16 caches and four to eight query heads per KV head, the scores themselves from the
+  // matrix cores: a tile of 16 slots x 32 elements of K is the A operand, the queries (two bf16 terms,
+  // hi and lo, one product each) the B operand with the heads repeated over the 16 columns.  With four
+  // heads lane l receives the score of head 2 (l & 1) + ((l >> 1) & 1), the head the vector path leaves
+  // there, and probabilities travel as quad broadcasts; with more, lane l has head l % 8 and the
+  // probabilities of a batch go through a few hundred bytes of the wave's LDS, where every lane of a
+  // slot's row reads all heads' values back (same address for the whole row: a broadcast).
+  constexpr bool kScoresByMfma = LPS == 16 && G >= 4 && std::is_same<T, bf16_t>::value;
+  constexpr bool kHeadPerLane = (G == 4 && LPS == 16) || kScoresByMfma;
+  constexpr bool kQuadHeads = G == 4;
+  constexpr int QKT = kScoresByMfma ? HD / 32 : 1;
+  // per slot row (sub): 8 heads x 8 probabilities, 8 rescale factors, 4 floats of padding (bank spread)
+  constexpr int kShareRow = 76;
+  bf16x8 qh[QKT], ql[QKT];
   float m1 = -INFINITY, l1 = 0.f;
   const bool odd1 = lane & 1, odd2 = lane & 2;
+  const int head_l = kQuadHeads ? 2 * (lane & 1) + ((lane >> 1) & 1) : min(lane & 7, G - 1);  // this lane's head
+  if constexpr (kScoresByMfma) {
+    const int h = head_l;
+    const float* qp = a.Q + ((size_t)li * kMaxCols + col) * HQ + (kvh * G + h) * HD + (lane >> 4) * 8;
+#pragma unroll
+    for (int kt = 0; kt < QKT; ++kt) {
+      float x[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x[e] = qp[kt * 32 + e];
+      split_bf16x8(x, qh[kt], ql[kt]);
+    }
+  }
 #pragma unroll
   for (int g = 0; g < G; ++g) {
     const float* qp = a.Q + ((size_t)li * kMaxCols + col) * HQ + (kvh * G + g) * HD + e0;
 #pragma unroll
     for (int j = 0; j < EPL; ++j) {
-      q[g][j] = qp[j];
+      if constexpr (!kScoresByMfma) q[g][j] = qp[j];
       acc[g][j] = 0.f;
     }
     m_run[g] = -INFINITY;
@@ -146,18 +174,44 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
   // below): unconditional loads, no branch per load.
   int w0, w1;
   wave_range(s0, s1, Geo::UNIT, wave, NWV, w0, w1);
-  auto process = [&](auto n_loads, int base) {
-    constexpr int N = decltype(n_loads)::value;
-    u32x4 kr[N], vr[N];
+  auto fetch_k = [&](auto n_loads, int base, u32x4* kr) {
 #pragma unroll
-    for (int j = 0; j < N; ++j) {
+    for (int j = 0; j < decltype(n_loads)::value; ++j) {
       const int s = min(base + j * SPW + sub, w1 - 1);
       kr[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kb + ((uint32_t)s * ROW_BYTES + lane_byte)));
     }
+  };
+  auto fetch_v = [&](auto n_loads, int base, u32x4* vr) {
 #pragma unroll
-    for (int j = 0; j < N; ++j) {
+    for (int j = 0; j < decltype(n_loads)::value; ++j) {
       const int s = min(base + j * SPW + sub, w1 - 1);
       vr[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vb + ((uint32_t)s * ROW_BYTES + lane_byte)));
+    }
+  };
+  // One batch: kr, vr hold its K and V rows.  `staged` runs once the K registers are free again (matrix-core
+  // scores only: the rows sit in LDS by then), which is where the next batch is requested.
+  auto consume = [&](auto n_loads, int base, u32x4* kr, const u32x4* vr, auto&& staged) {
+    constexpr int N = decltype(n_loads)::value;
+    // K for the matrix cores: tile t holds 16 slots; A row r = lane % 16 carries slot
+    // (r % 4) * 4 + r / 4 of the tile, so that the score of the slot this lane's V load j = 4 t + i
+    // brings (slot 4 i + sub of the tile) comes out in this lane, element i of the tile's result.
+    // The rows are loaded whole (coalesced, as for the vector products) and turned into A fragments
+    // through the wave's own 8 KB of LDS, the 16-byte pieces of slot row s XORed by s % 16 so that
+    // neither the row-wise stores nor the fragment reads meet a bank twice.
+    constexpr int NT = kScoresByMfma ? (N + 3) / 4 : 1;
+    u32x4 ka[NT][QKT];
+    if constexpr (kScoresByMfma) {
+      u32x4* stage = reinterpret_cast<u32x4*>(dyn_f) + wave * (IT * SPW * LPS);
+      const int piece = lane % LPS, r = lane & 15, slot_r = (r & 3) * 4 + (r >> 2);
+#pragma unroll
+      for (int j = 0; j < N; ++j) stage[(j * SPW + sub) * LPS + (piece ^ ((j * SPW + sub) & 15))] = kr[j];
+      __builtin_amdgcn_wave_barrier();  // LDS operations of one wave execute in order: no wait is needed
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int kt = 0; kt < QKT; ++kt) ka[t][kt] = stage[(t * 16 + slot_r) * LPS + ((kt * 4 + (lane >> 4)) ^ slot_r)];
+      __builtin_amdgcn_wave_barrier();  // the reads are issued before the next batch's stores
+      staged();
     }
     if constexpr (kHeadPerLane) {
       // Four query heads over a 16-lane row: instead of four row-wide sums per slot, the lanes
@@ -166,25 +220,42 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
       // (one head) and the probability of head g comes back to the row's other lanes as a
       // quad broadcast on its way into the P.V products.
       float sc1[N];
+      f32x4 st[NT];
+      if constexpr (kScoresByMfma) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          f32x4 s_hi = {0.f, 0.f, 0.f, 0.f}, s_lo = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int kt = 0; kt < QKT; ++kt) {
+            s_hi = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[t][kt]), qh[kt], s_hi, 0, 0, 0);
+            s_lo = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[t][kt]), ql[kt], s_lo, 0, 0, 0);
+          }
+          st[t] = s_hi + s_lo;
+        }
+      }
 #pragma unroll
       for (int j = 0; j < N; ++j) {
         const int s = base + j * SPW + sub;
         const bool valid = (int)(s < w1) & (int)(!TREE || (int)(s < vbase) | (int)((vmask >> ((s - vbase) & 63)) & 1ull));  // straight-line
-        float kv[EPL];
-        unpack<T>(kr[j], kv);
-        float d[4];
+        if constexpr (kScoresByMfma) {
+          sc1[j] = valid ? st[j / 4][j % 4] * a.scale : -INFINITY;
+        } else {
+          float kv[EPL];
+          unpack<T>(kr[j], kv);
+          float d[4];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          d[g] = 0.f;
+          for (int g = 0; g < 4; ++g) {
+            d[g] = 0.f;
 #pragma unroll
-          for (int e = 0; e < EPL; ++e) d[g] += q[g][e] * kv[e];
+            for (int e = 0; e < EPL; ++e) d[g] += q[g][e] * kv[e];
+          }
+          const float t0 = (odd1 ? d[2] : d[0]) + dpp_f32<0xB1>(odd1 ? d[0] : d[2]);  // lane ^ 1
+          const float t1 = (odd1 ? d[3] : d[1]) + dpp_f32<0xB1>(odd1 ? d[1] : d[3]);
+          float v = (odd2 ? t1 : t0) + dpp_f32<0x4E>(odd2 ? t0 : t1);                  // lane ^ 2
+          v += dpp_f32<0x124>(v);  // row_ror:4
+          v += dpp_f32<0x128>(v);  // row_ror:8
+          sc1[j] = valid ? v * a.scale : -INFINITY;
         }
-        const float t0 = (odd1 ? d[2] : d[0]) + dpp_f32<0xB1>(odd1 ? d[0] : d[2]);  // lane ^ 1
-        const float t1 = (odd1 ? d[3] : d[1]) + dpp_f32<0xB1>(odd1 ? d[1] : d[3]);
-        float v = (odd2 ? t1 : t0) + dpp_f32<0x4E>(odd2 ? t0 : t1);                  // lane ^ 2
-        v += dpp_f32<0x124>(v);  // row_ror:4
-        v += dpp_f32<0x128>(v);  // row_ror:8
-        sc1[j] = valid ? v * a.scale : -INFINITY;
       }
       float bm = sc1[0];
 #pragma unroll
@@ -194,23 +265,68 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
       const float alpha = __expf(m1 - m_ref);
       m1 = m_new;
       l1 *= alpha;
-      const float al[4] = {dpp_f32<0x00>(alpha), dpp_f32<0xAA>(alpha), dpp_f32<0x55>(alpha), dpp_f32<0xFF>(alpha)};
-#pragma unroll
-      for (int g = 0; g < 4; ++g)
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[g][e] *= al[g];
-#pragma unroll
-      for (int j = 0; j < N; ++j) {
-        float vv[EPL];
-        unpack<T>(vr[j], vv);
-        const float p = __expf(sc1[j] - m_ref);  // 0 for slots past the end or masked
-        l1 += p;
-        // head g sits in quad lane 0, 2, 1, 3 for g = 0 .. 3
-        const float pg[4] = {dpp_f32<0x00>(p), dpp_f32<0xAA>(p), dpp_f32<0x55>(p), dpp_f32<0xFF>(p)};
+      if constexpr (kQuadHeads) {
+        const float al[4] = {dpp_f32<0x00>(alpha), dpp_f32<0xAA>(alpha), dpp_f32<0x55>(alpha), dpp_f32<0xFF>(alpha)};
 #pragma unroll
         for (int g = 0; g < 4; ++g)
 #pragma unroll
-          for (int e = 0; e < EPL; ++e) acc[g][e] += pg[g] * vv[e];
+          for (int e = 0; e < EPL; ++e) acc[g][e] *= al[g];
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+          float vv[EPL];
+          unpack<T>(vr[j], vv);
+          const float p = __expf(sc1[j] - m_ref);  // 0 for slots past the end or masked
+          l1 += p;
+          // head g sits in quad lane 0, 2, 1, 3 for g = 0 .. 3
+          const float pg[4] = {dpp_f32<0x00>(p), dpp_f32<0xAA>(p), dpp_f32<0x55>(p), dpp_f32<0xFF>(p)};
+#pragma unroll
+          for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[g][e] += pg[g] * vv[e];
+        }
+      } else {
+        // lanes 0..7 of a slot row put their head's probabilities and rescale factor into the wave's LDS
+        // (the K tiles are in registers by now); every lane then reads all heads' values of its row
+        constexpr int NP = (N + 3) / 4;  // 16-byte pieces of probabilities per head
+        float* share = dyn_f + wave * (IT * SPW * LPS * 4) + sub * kShareRow;
+        float pj[4 * NP];
+#pragma unroll
+        for (int j = 0; j < 4 * NP; ++j) {
+          pj[j] = j < N ? __expf(sc1[j < N ? j : 0] - m_ref) : 0.f;  // 0 for slots past the end or masked
+          l1 += pj[j];
+        }
+        if ((lane & 8) == 0) {
+#pragma unroll
+          for (int q4 = 0; q4 < NP; ++q4)
+            *reinterpret_cast<f32x4*>(share + (lane & 7) * 8 + 4 * q4) = f32x4{pj[4 * q4], pj[4 * q4 + 1], pj[4 * q4 + 2], pj[4 * q4 + 3]};
+          share[64 + (lane & 7)] = alpha;
+        }
+        __builtin_amdgcn_wave_barrier();  // LDS operations of one wave execute in order
+        const f32x4 al0 = *reinterpret_cast<const f32x4*>(share + 64), al1 = *reinterpret_cast<const f32x4*>(share + 68);
+        const float al[8] = {al0[0], al0[1], al0[2], al0[3], al1[0], al1[1], al1[2], al1[3]};
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) acc[g][e] *= al[g];
+#pragma unroll
+        for (int q4 = 0; q4 < NP; ++q4) {  // four slots' probabilities of every head at a time (registers)
+          f32x4 pg[G];
+#pragma unroll
+          for (int g = 0; g < G; ++g) pg[g] = *reinterpret_cast<const f32x4*>(share + g * 8 + 4 * q4);
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj) {
+            const int j = 4 * q4 + jj;
+            if (j < N) {
+              float vv[EPL];
+              unpack<T>(vr[j], vv);
+#pragma unroll
+              for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc[g][e] += pg[g][jj] * vv[e];
+            }
+          }
+        }
+        __builtin_amdgcn_wave_barrier();  // the reads are issued before the next batch's K rows overwrite the place
       }
       return;
     }
@@ -261,11 +377,58 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
       }
     }
   };
+  auto process = [&](auto n_loads, int base) {
+    u32x4 kr[decltype(n_loads)::value], vr[decltype(n_loads)::value];
+    fetch_k(n_loads, base, kr);
+    fetch_v(n_loads, base, vr);
+    consume(n_loads, base, kr, vr, [] {});
+  };
   int base = w0;  // wave-uniform, like the loop conditions
-  for (; w1 - base > 2 * Geo::UNIT; base += Geo::WAVE_SLOTS) process(std::integral_constant<int, IT>{}, base);
+  constexpr std::integral_constant<int, IT> kFull{};
+  auto full_batch_at = [&](int b) { return w1 - b > 2 * Geo::UNIT; };
+  if constexpr (kScoresByMfma && kQuadHeads) {  // (more heads: no registers left for a second set of V rows)
+    // With the scores on the matrix cores the vector arithmetic of a batch no longer hides the
+    // latency of the next one's loads behind other waves' work, so a wave keeps two batches in
+    // flight: K of the next batch goes into the registers the staging has just freed, V into a
+    // second set of registers.  The request is unconditional, like the loads themselves: past the
+    // wave's share it re-reads the last row.
+    if (full_batch_at(base)) {
+      u32x4 kr[IT], vr[IT], vn[IT];
+      fetch_k(kFull, base, kr);
+      fetch_v(kFull, base, vr);
+      for (;;) {
+        const int next = base + Geo::WAVE_SLOTS;
+        consume(kFull, base, kr, vr, [&] {
+          fetch_k(kFull, next, kr);
+          fetch_v(kFull, next, vn);
+          asm volatile("" ::: "memory");  // the requests stay here: the compiler would sink them to their first use
+        });
+        base = next;
+        if (!full_batch_at(base)) break;
+#pragma unroll
+        for (int j = 0; j < IT; ++j) vr[j] = vn[j];
+      }
+    }
+  } else {
+    for (; full_batch_at(base); base += Geo::WAVE_SLOTS) process(kFull, base);
+  }
   for (; base < w1; base += Geo::UNIT) process(std::integral_constant<int, kAttnSmallIT>{}, base);
 
-  if constexpr (kHeadPerLane) {  // back to every lane holding all four heads' maximum and sum
+  if constexpr (kHeadPerLane && !kQuadHeads) {  // back to every lane holding all heads' maximum and sum: through LDS
+    float* share = dyn_f + wave * (IT * SPW * LPS * 4) + sub * kShareRow;
+    if ((lane & 8) == 0) {
+      share[lane & 7] = m1;
+      share[8 + (lane & 7)] = l1;
+    }
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      m_run[g] = share[g];
+      l_run[g] = share[8 + g];
+    }
+  }
+  if constexpr (kScoresByMfma) __syncthreads();  // the combination below reuses the LDS the K tiles went through
+  if constexpr (kHeadPerLane && kQuadHeads) {  // back to every lane holding all four heads' maximum and sum
     const float mm[4] = {dpp_f32<0x00>(m1), dpp_f32<0xAA>(m1), dpp_f32<0x55>(m1), dpp_f32<0xFF>(m1)};
     const float ll[4] = {dpp_f32<0x00>(l1), dpp_f32<0xAA>(l1), dpp_f32<0x55>(l1), dpp_f32<0xFF>(l1)};
 #pragma unroll
@@ -605,72 +768,55 @@ __global__ __launch_bounds__(64 * kMfmaAttnWaves) void attn_mfma_kernel(AttnArgs
   }
 }
 
-// Merge the chunk partials of one (layer, column, KV head): all G query heads, chunks in
-// order.  Runs as its own launch: the kernel boundary is what makes the partials written by
-// workgroups on other XCDs visible (a device-scope fence inside the attention kernel costs an
-// L2 write-back per workgroup and was measured several times slower).  Columns whose context
-// fits one chunk were finished by attn_kernel.  grid = (k * columns, Hkv), block = 256.
+// Merge the chunk partials of one (layer, column, query head), chunks in order.  Runs as its own
+// launch: the kernel boundary is what makes the partials written by workgroups on other XCDs
+// visible (a device-scope fence inside the attention kernel costs an L2 write-back per workgroup
+// and was measured several times slower).  Columns whose context fits one chunk were finished by
+// attn_kernel.  grid = (k * columns, Hq), block = HD: one thread per output element, one small
+// workgroup per head, so that the launch is as wide as the partials allow and costs one memory
+// latency whatever the number of heads that share a KV head.
 template <typename T, int HD>
-__global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, Cols c) {
-  __shared__ float s_w[8][kMaxChunks];  // per head: exp(m_chunk - m) ; chunk count <= 64 = one lane each
-  __shared__ float s_l[8];
-  const int li = blockIdx.x / c.n, col = blockIdx.x % c.n, kvh = blockIdx.y, tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+__global__ __launch_bounds__(HD) void attn_merge_kernel(AttnArgs a, Cols c) {
+  __shared__ float s_w[kMaxChunks];   // exp(m_chunk - m); chunk count <= 64 = one lane each
+  __shared__ float s_lw[kMaxChunks];  // the chunk's sum on the common reference
+  const int li = blockIdx.x / c.n, col = blockIdx.x % c.n, head = blockIdx.y, e = threadIdx.x;
   const int n_slots = c.pos[col] + 1;
   int nch, s0_unused, s1_unused;
   chunk_range(a, n_slots, AttnGeom<T, HD>::UNIT, 0, nch, s0_unused, s1_unused);
   if (nch == 1) return;
-  const int G = a.Hq / a.Hkv, HQ = a.Hq * HD;
-  const size_t arow = (size_t)li * kMaxCols + col;
-  // every load of the kernel is issued up front: the first 16 chunk partials of this thread's
-  // output elements (all of them for contexts up to 16 chunks) together with the chunk maxima
-  // and sums, so that the kernel costs one memory latency, not three
-  constexpr int EPT = (8 * HD + 255) / 256;  // output elements per thread, at most (G <= 8)
-  float pv[EPT][16];
+  const int HQ = a.Hq * HD;
+  const size_t row = ((size_t)li * kMaxCols + col) * a.Hq + head;
+  // every load is issued up front: the first 16 chunk partials of this thread's output element (all
+  // of them for contexts up to 16 chunks) together with the chunk maxima and sums
+  const float* po = a.PO + row * kMaxChunks * HD + e;
+  float pv[16];
 #pragma unroll
-  for (int k = 0; k < EPT; ++k) {
-    const int idx = tid + 256 * k;
-    const int g = idx / HD, e = idx % HD;
-    const float* po = a.PO + (arow * a.Hq + kvh * G + g) * kMaxChunks * HD + e;
-#pragma unroll
-    for (int u = 0; u < 16; ++u) pv[k][u] = (idx < G * HD && u < nch) ? po[(size_t)u * HD] : 0.f;
-  }
-  for (int g = wave; g < G; g += 4) {  // one wave per head, one lane per chunk
-    const size_t row = arow * a.Hq + kvh * G + g;
-    const float pm = lane < nch ? a.PM[row * kMaxChunks + lane] : -INFINITY;
-    const float pl = lane < nch ? a.PL[row * kMaxChunks + lane] : 0.f;
+  for (int u = 0; u < 16; ++u) pv[u] = u < nch ? po[(size_t)u * HD] : 0.f;
+  if (e < 64) {  // the first wave: one lane per chunk
+    const float pm = e < nch ? a.PM[row * kMaxChunks + e] : -INFINITY;
+    const float pl = e < nch ? a.PL[row * kMaxChunks + e] : 0.f;
     float m = pm;
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
     const float wgt = __expf(pm - m);
-    s_w[g][lane] = wgt;
-    // sum in chunk order so that the result does not depend on the reduction tree
-    const float l = pl * wgt;
-    float tot = 0.f;
-    for (int ch = 0; ch < nch; ++ch) tot += __shfl(l, ch, 64);
-    if (lane == 0) s_l[g] = tot;
+    s_w[e] = wgt;
+    s_lw[e] = pl * wgt;
   }
   __syncthreads();
+  float tot = 0.f;  // in chunk order so that the result does not depend on a reduction tree
+  for (int ch = 0; ch < nch; ++ch) tot += s_lw[ch];
+  float o = 0.f;
 #pragma unroll
-  for (int k = 0; k < EPT; ++k) {
-    const int idx = tid + 256 * k;
-    if (idx >= G * HD) break;
-    const int g = idx / HD, e = idx % HD;
-    const int head = kvh * G + g;
-    const float* po = a.PO + (arow * a.Hq + head) * kMaxChunks * HD + e;
-    float o = 0.f;
+  for (int u = 0; u < 16; ++u) o += pv[u] * (u < nch ? s_w[u] : 0.f);
+  for (int c0 = 16; c0 < nch; c0 += 8) {
+    float pw[8];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) o += pv[k][u] * (u < nch ? s_w[g][u] : 0.f);
-    for (int c0 = 16; c0 < nch; c0 += 8) {
-      float pw[8];
+    for (int u = 0; u < 8; ++u) pw[u] = c0 + u < nch ? po[(size_t)(c0 + u) * HD] : 0.f;  // independent loads
 #pragma unroll
-      for (int u = 0; u < 8; ++u) pw[u] = c0 + u < nch ? po[(size_t)(c0 + u) * HD] : 0.f;  // independent loads
-#pragma unroll
-      for (int u = 0; u < 8; ++u) o += pw[u] * (c0 + u < nch ? s_w[g][c0 + u] : 0.f);
-    }
-    store_act1<T>(reinterpret_cast<T*>(a.AO) + (size_t)li * Tr<T>::PARTS * kMaxCols * HQ + xoff<T>(c.n, HQ, col, head * HD + e),
-                  (size_t)kMaxCols * HQ, o / s_l[g]);
+    for (int u = 0; u < 8; ++u) o += pw[u] * (c0 + u < nch ? s_w[c0 + u] : 0.f);
   }
+  store_act1<T>(reinterpret_cast<T*>(a.AO) + (size_t)li * Tr<T>::PARTS * kMaxCols * HQ + xoff<T>(c.n, HQ, col, head * HD + e),
+                (size_t)kMaxCols * HQ, o / tot);
 }
 
 template <typename T, int HD, bool TREE>
@@ -680,7 +826,10 @@ static void launch_attn_g(int G, dim3 grid, int nwv, hipStream_t st, AttnArgs a,
   const int groups = nwv * AttnGeom<T, HD>::SPW;
   a.direct = (size_t)groups * G * (HD + 2) * sizeof(float) <= 65536 ? 1 : 0;
   const int sets = a.direct ? groups : nwv;
-  const size_t lds = (size_t)sets * G * (HD + 2) * sizeof(float);
+  size_t lds = (size_t)sets * G * (HD + 2) * sizeof(float);
+  // scores from the matrix cores (four query heads per KV head, bf16 caches): 8 KB per wave for the K tiles
+  if (G >= 4 && AttnGeom<T, HD>::LPS == 16 && std::is_same<T, bf16_t>::value)
+    lds = std::max(lds, (size_t)nwv * kAttnIT * AttnGeom<T, HD>::SPW * HD * sizeof(T));
   const dim3 blk(64 * nwv);
   switch (G) {
     case 1: ES_LAUNCH((attn_kernel<T, HD, 1, TREE>), grid, blk, lds, st, a, c); break;
@@ -864,10 +1013,10 @@ void launch_attn(const Shape& s, const Buffers& b, const Cols& c, int layer0, in
     else launch_attn_g<T, 64, false>(G, grid, nwv, st, a, c);
   });
   if (n_chunks > 1) {
-    const dim3 mgrid(n_set * c.n, s.Hkv);
+    const dim3 mgrid(n_set * c.n, s.Hq);
     DISPATCH_T(s.dtype, {
-      if (s.hd == 128) ES_LAUNCH((attn_merge_kernel<T, 128>), mgrid, dim3(256), 0, st, a, c);
-      else ES_LAUNCH((attn_merge_kernel<T, 64>), mgrid, dim3(256), 0, st, a, c);
+      if (s.hd == 128) ES_LAUNCH((attn_merge_kernel<T, 128>), mgrid, dim3(128), 0, st, a, c);
+      else ES_LAUNCH((attn_merge_kernel<T, 64>), mgrid, dim3(64), 0, st, a, c);
     });
   }
 }
