@@ -390,13 +390,12 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
     // With the scores on the matrix cores the vector arithmetic of a batch no longer hides the
     // latency of the next one's loads behind other waves' work, so a wave keeps two batches in
     // flight: K of the next batch goes into the registers the staging has just freed, V into a
-    // second set of registers.  The request is unconditional, like the loads themselves: past the
-    // wave's share it re-reads the last row.
+    // second set of registers.
     if (full_batch_at(base)) {
       u32x4 kr[IT], vr[IT], vn[IT];
       fetch_k(kFull, base, kr);
       fetch_v(kFull, base, vr);
-      for (;;) {
+      while (full_batch_at(base + Geo::WAVE_SLOTS)) {  // another full batch follows: request it, work on this one
         const int next = base + Geo::WAVE_SLOTS;
         consume(kFull, base, kr, vr, [&] {
           fetch_k(kFull, next, kr);
@@ -404,10 +403,11 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
           asm volatile("" ::: "memory");  // the requests stay here: the compiler would sink them to their first use
         });
         base = next;
-        if (!full_batch_at(base)) break;
 #pragma unroll
         for (int j = 0; j < IT; ++j) vr[j] = vn[j];
       }
+      consume(kFull, base, kr, vr, [] {});  // the wave's last full batch
+      base += Geo::WAVE_SLOTS;
     }
   } else {
     for (; full_batch_at(base); base += Geo::WAVE_SLOTS) process(kFull, base);
