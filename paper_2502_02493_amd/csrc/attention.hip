@@ -144,17 +144,20 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
   float m1 = -INFINITY, l1 = 0.f;
   const bool odd1 = lane & 1, odd2 = lane & 2;
   const int head_l = kQuadHeads ? 2 * (lane & 1) + ((lane >> 1) & 1) : min(lane & 7, G - 1);  // this lane's head
+  // the lane's B fragments of the queries: requested here, split into their two bf16 terms only after the
+  // wave's first K and V rows have been requested too (split_q), so that the two latencies overlap
+  float q_raw[QKT][8];
   if constexpr (kScoresByMfma) {
-    const int h = head_l;
-    const float* qp = a.Q + ((size_t)li * kMaxCols + col) * HQ + (kvh * G + h) * HD + (lane >> 4) * 8;
+    const float* qp = a.Q + ((size_t)li * kMaxCols + col) * HQ + (kvh * G + head_l) * HD + (lane >> 4) * 8;
 #pragma unroll
-    for (int kt = 0; kt < QKT; ++kt) {
-      float x[8];
+    for (int kt = 0; kt < QKT; ++kt)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) x[e] = qp[kt * 32 + e];
-      split_bf16x8(x, qh[kt], ql[kt]);
-    }
+      for (int e = 0; e < 8; ++e) q_raw[kt][e] = qp[kt * 32 + e];
   }
+  auto split_q = [&] {
+#pragma unroll
+    for (int kt = 0; kt < QKT; ++kt) split_bf16x8(q_raw[kt], qh[kt], ql[kt]);
+  };
 #pragma unroll
   for (int g = 0; g < G; ++g) {
     const float* qp = a.Q + ((size_t)li * kMaxCols + col) * HQ + (kvh * G + g) * HD + e0;
@@ -386,32 +389,37 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
   int base = w0;  // wave-uniform, like the loop conditions
   constexpr std::integral_constant<int, IT> kFull{};
   auto full_batch_at = [&](int b) { return w1 - b > 2 * Geo::UNIT; };
-  if constexpr (kScoresByMfma && kQuadHeads) {  // (more heads: no registers left for a second set of V rows)
-    // With the scores on the matrix cores the vector arithmetic of a batch no longer hides the
-    // latency of the next one's loads behind other waves' work, so a wave keeps two batches in
-    // flight: K of the next batch goes into the registers the staging has just freed, V into a
-    // second set of registers.
+  if constexpr (kScoresByMfma) {
     if (full_batch_at(base)) {
-      u32x4 kr[IT], vr[IT], vn[IT];
+      u32x4 kr[IT], vr[IT];
       fetch_k(kFull, base, kr);
       fetch_v(kFull, base, vr);
-      while (full_batch_at(base + Geo::WAVE_SLOTS)) {  // another full batch follows: request it, work on this one
-        const int next = base + Geo::WAVE_SLOTS;
-        consume(kFull, base, kr, vr, [&] {
-          fetch_k(kFull, next, kr);
-          fetch_v(kFull, next, vn);
-          asm volatile("" ::: "memory");  // the requests stay here: the compiler would sink them to their first use
-        });
-        base = next;
+      split_q();
+      if constexpr (kQuadHeads) {
+        // With the scores on the matrix cores the vector arithmetic of a batch no longer hides the
+        // latency of the next one's loads behind other waves' work, so a wave keeps two batches in
+        // flight: K of the next batch goes into the registers the staging has just freed, V into a
+        // second set of registers.  (More heads: no registers left for that set.)
+        u32x4 vn[IT];
+        while (full_batch_at(base + Geo::WAVE_SLOTS)) {  // another full batch follows: request it, work on this one
+          const int next = base + Geo::WAVE_SLOTS;
+          consume(kFull, base, kr, vr, [&] {
+            fetch_k(kFull, next, kr);
+            fetch_v(kFull, next, vn);
+            asm volatile("" ::: "memory");  // the requests stay here: the compiler would sink them to their first use
+          });
+          base = next;
 #pragma unroll
-        for (int j = 0; j < IT; ++j) vr[j] = vn[j];
+          for (int j = 0; j < IT; ++j) vr[j] = vn[j];
+        }
       }
-      consume(kFull, base, kr, vr, [] {});  // the wave's last full batch
+      consume(kFull, base, kr, vr, [] {});  // four heads: the wave's last full batch
       base += Geo::WAVE_SLOTS;
+    } else {
+      split_q();
     }
-  } else {
-    for (; full_batch_at(base); base += Geo::WAVE_SLOTS) process(kFull, base);
   }
+  for (; full_batch_at(base); base += Geo::WAVE_SLOTS) process(kFull, base);
   for (; base < w1; base += Geo::UNIT) process(std::integral_constant<int, kAttnSmallIT>{}, base);
 
   if constexpr (kHeadPerLane && !kQuadHeads) {  // back to every lane holding all heads' maximum and sum: through LDS
