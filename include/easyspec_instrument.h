@@ -61,6 +61,19 @@ int easyspec_attention_cut(const easyspec_config *cfg, const int32_t *ctx_lens, 
 int easyspec_weight_walk(const easyspec_config *cfg, int32_t op, int32_t n_cols, int32_t n_layers_in_set, int32_t full_layer,
                          int64_t *report);
 
+/* Host model of how the vector attention kernel, where it takes its scores from the matrix cores (bf16
+ * caches, head_dim 128, 4 to 8 query heads per KV head), passes a batch of n_loads x 4 K rows (n_loads = 2:
+ * a short step, 8: a full batch) through a wave's LDS into MFMA A fragments, evaluated with the kernel's own
+ * index functions for all 64 lanes.  Host arithmetic only.  report (host, EASYSPEC_STAGE_FIELDS entries):
+ *   [0] 16-byte pieces stored, [1] distinct places they take, [2] highest place + 1, [3] places a wave owns,
+ *   [4] fragment pieces fetched from rows of the batch, [5] of those, fetches that do not return the piece
+ *   (slot, 32-element k-tile, k-group) the MFMA operand needs there, [6] fetches from rows the batch does not
+ *   have (their scores are never used), [7] (lane, load) pairs whose score would come out in another lane or
+ *   element than the one that holds the slot's V row, [8] pairs of lanes of one quarter-wave that meet in one
+ *   16-byte bank group, stores and fetches together. */
+#define EASYSPEC_STAGE_FIELDS 9
+int easyspec_attention_stage_walk(int32_t n_loads, int64_t *report);
+
 /* Per-kernel timing for roofline reports.  Between profile_begin and profile_end every kernel
  * launch of the class `op` made by draft steps and calibrations carries a start and a stop HIP
  * event bound to its own dispatch (at most max_launches launches; later ones run untimed), so a

@@ -21,7 +21,7 @@ EASYSPEC_PARALLEL_ATTENTION, EASYSPEC_PARALLEL_FULL_LAYER = 0, 1
 
 EXPORTS = ["easyspec_create", "easyspec_destroy", "easyspec_load_weights", "easyspec_set_groups",
            "easyspec_default_groups", "easyspec_draft_step", "easyspec_calibrate", "easyspec_greedy_accept", "easyspec_greedy_accept_host",
-           "easyspec_accept", "easyspec_accept_workspace_bytes", "easyspec_accept_static", "easyspec_accept_static_max_bytes", "easyspec_draft_tree_step", "easyspec_set_parallel_mode", "easyspec_stream_read", "easyspec_stream_read_sink_floats", "easyspec_attention_cut", "easyspec_weight_walk",
+           "easyspec_accept", "easyspec_accept_workspace_bytes", "easyspec_accept_static", "easyspec_accept_static_max_bytes", "easyspec_draft_tree_step", "easyspec_set_parallel_mode", "easyspec_stream_read", "easyspec_stream_read_sink_floats", "easyspec_attention_cut", "easyspec_weight_walk", "easyspec_attention_stage_walk",
            "easyspec_get_lens", "easyspec_truncate", "easyspec_kv_import", "easyspec_kv_export",
            "easyspec_get_hidden", "easyspec_poison_workspaces", "easyspec_step_bytes", "easyspec_profile_begin", "easyspec_profile_end",
            "easyspec_last_error"]
@@ -91,6 +91,7 @@ def load_library():
         L.easyspec_attention_cut.argtypes = [C.POINTER(easyspec_config), vp, i32, i32, vp, vp]
         L.easyspec_step_bytes.restype = C.c_int64
         L.easyspec_weight_walk.argtypes = [C.POINTER(easyspec_config), i32, i32, i32, i32, vp]
+        L.easyspec_attention_stage_walk.argtypes = [i32, vp]
         L.easyspec_profile_begin.argtypes = [vp, i32, i32]
         L.easyspec_profile_end.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_float), vp, vp]
         L.easyspec_last_error.argtypes = [vp]
@@ -252,6 +253,17 @@ def easyspec_weight_walk(cfg: easyspec_config, op: int, n_cols: int, n_layers_in
     _check(load_library().easyspec_weight_walk(C.byref(cfg), int(op), int(n_cols), int(n_layers_in_set), int(bool(full_layer)),
                                                _ptr(rep)), None)
     return dict(zip(WALK_NAMES, (int(v) for v in rep)))
+
+
+EASYSPEC_STAGE_FIELDS = 9
+STAGE_NAMES = ("stored", "distinct_places", "highest_place", "places", "fetched", "wrong_piece", "unused_rows", "misplaced_scores",
+               "bank_conflicts")
+
+
+def easyspec_attention_stage_walk(n_loads: int) -> dict:
+    rep = np.zeros(EASYSPEC_STAGE_FIELDS, np.int64)
+    _check(load_library().easyspec_attention_stage_walk(int(n_loads), _ptr(rep)), None)
+    return dict(zip(STAGE_NAMES, (int(v) for v in rep)))
 
 
 def easyspec_get_lens(ctx, max_batch: int):

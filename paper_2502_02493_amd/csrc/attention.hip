@@ -205,14 +205,13 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a, Cols c) {
     u32x4 ka[NT][QKT];
     if constexpr (kScoresByMfma) {
       u32x4* stage = reinterpret_cast<u32x4*>(dyn_f) + wave * (IT * SPW * LPS);
-      const int piece = lane % LPS, r = lane & 15, slot_r = (r & 3) * 4 + (r >> 2);
 #pragma unroll
-      for (int j = 0; j < N; ++j) stage[(j * SPW + sub) * LPS + (piece ^ ((j * SPW + sub) & 15))] = kr[j];
+      for (int j = 0; j < N; ++j) stage[stage_store_piece(lane, j)] = kr[j];
       __builtin_amdgcn_wave_barrier();  // LDS operations of one wave execute in order: no wait is needed
 #pragma unroll
       for (int t = 0; t < NT; ++t)
 #pragma unroll
-        for (int kt = 0; kt < QKT; ++kt) ka[t][kt] = stage[(t * 16 + slot_r) * LPS + ((kt * 4 + (lane >> 4)) ^ slot_r)];
+        for (int kt = 0; kt < QKT; ++kt) ka[t][kt] = stage[stage_fetch_piece(lane, t, kt)];
       __builtin_amdgcn_wave_barrier();  // the reads are issued before the next batch's stores
       staged();
     }

@@ -10,10 +10,12 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <string>
 #include <vector>
 
 #include "kernels.h"
+#include "tile_index.hpp"
 
 using namespace es;
 
@@ -787,6 +789,65 @@ extern "C" int easyspec_attention_cut(const easyspec_config* cfg, const int32_t*
       }
   }
   return nwv;
+}
+
+extern "C" int easyspec_attention_stage_walk(int32_t n_loads, int64_t* report) {
+  if (!report) return fail(nullptr, EASYSPEC_EINVAL, "attention_stage_walk: NULL report");
+  if (n_loads != 2 && n_loads != 8) return fail(nullptr, EASYSPEC_EINVAL, "attention_stage_walk: n_loads must be 2 or 8");
+  constexpr int kPlaces = 32 * kStageRowPieces;  // 32 rows of 16 pieces = the 8 KB a wave owns
+  int held_slot[kPlaces], held_piece[kPlaces], stores_at[kPlaces];
+  for (int i = 0; i < kPlaces; ++i) held_slot[i] = held_piece[i] = -1, stores_at[i] = 0;
+  int64_t* r = report;
+  for (int i = 0; i < EASYSPEC_STAGE_FIELDS; ++i) r[i] = 0;
+  r[3] = kPlaces;
+  auto quarter_conflicts = [&](const int (&place)[64]) {
+    int64_t n = 0;
+    for (int q = 0; q < 4; ++q)
+      for (int a = 0; a < 16; ++a)
+        for (int b = a + 1; b < 16; ++b) n += (place[16 * q + a] & 15) == (place[16 * q + b] & 15);
+    return n;
+  };
+  for (int j = 0; j < n_loads; ++j) {
+    int place[64];
+    for (int lane = 0; lane < 64; ++lane) {
+      const int at = stage_store_piece(lane, j);
+      place[lane] = at;
+      ++r[0];
+      if (at < 0 || at >= kPlaces) return fail(nullptr, EASYSPEC_EINVAL, "attention_stage_walk: store outside the stage");
+      if (stores_at[at]++ == 0) ++r[1];
+      held_slot[at] = 4 * j + (lane >> 4);
+      held_piece[at] = lane & 15;
+      r[2] = std::max<int64_t>(r[2], at + 1);
+    }
+    r[8] += quarter_conflicts(place);
+  }
+  const int n_tiles = (n_loads + 3) / 4;
+  for (int t = 0; t < n_tiles; ++t)
+    for (int kt = 0; kt < 4; ++kt) {
+      int place[64];
+      for (int lane = 0; lane < 64; ++lane) {
+        const int at = stage_fetch_piece(lane, t, kt);
+        place[lane] = at;
+        if (at < 0 || at >= kPlaces) return fail(nullptr, EASYSPEC_EINVAL, "attention_stage_walk: fetch outside the stage");
+        const int want_slot = t * 16 + stage_tile_slot(lane), want_piece = 4 * kt + (lane >> 4);
+        if (want_slot >= 4 * n_loads) {
+          ++r[6];
+          continue;
+        }
+        ++r[4];
+        r[5] += held_slot[at] != want_slot || held_piece[at] != want_piece;
+      }
+      r[8] += quarter_conflicts(place);
+    }
+  for (int j = 0; j < n_loads; ++j)
+    for (int lane = 0; lane < 64; ++lane) {
+      const int t = j / 4, i = j % 4;
+      // element i of the lane's MFMA result is A row 4 (lane / 16) + i, fed by the lanes whose lane % 16 is that row
+      const int a_row = 4 * (lane >> 4) + i;
+      const int slot_of_row = t * 16 + stage_tile_slot(a_row);
+      r[7] += slot_of_row != 4 * j + (lane >> 4) || score_slot_in_batch(lane, t, i) != 4 * j + (lane >> 4);
+    }
+  return EASYSPEC_OK;
 }
 
 extern "C" int easyspec_weight_walk(const easyspec_config* cfg, int32_t op, int32_t n_cols, int32_t n_layers_in_set, int32_t full_layer,

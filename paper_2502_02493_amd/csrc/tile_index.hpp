@@ -90,4 +90,28 @@ ES_HD constexpr long x_fragment_elems(int EPL, int PARTS, int NB, int ncols, int
   return (q ? part : 0) + (long)xoff_elems(EPL, ncols, K, col, kg * EPL);
 }
 
+
+// ------------------------------------------------------------------------------------------
+// Vector attention with scores from the matrix cores (bf16 caches, 16 lanes per K row): how a batch of
+// K rows passes through a wave's own LDS into MFMA A fragments, and where a slot's score comes out.
+// A batch is `loads` loads of 4 slots (lane = sub * 16 + piece: slot 4 j + sub of the batch, 16-byte piece
+// `piece` of its row); the stage holds up to 32 rows of 16 pieces.
+// ------------------------------------------------------------------------------------------
+constexpr int kStageRowPieces = 16;
+// where load j of `lane` is stored: row = the slot's number in the batch, the pieces of a row XORed by its number
+ES_HD constexpr int stage_store_piece(int lane, int j) {
+  const int row = 4 * j + (lane >> 4);
+  return row * kStageRowPieces + ((lane & 15) ^ (row & 15));
+}
+// Tile t of 16 slots: A row r = lane % 16 carries slot (r % 4) * 4 + r / 4 of the tile, k-group lane / 16 of
+// k-tile kt its piece 4 kt + lane / 16: the stage index that lane reads for (t, kt)
+ES_HD constexpr int stage_tile_slot(int lane) { return ((lane & 15) & 3) * 4 + ((lane & 15) >> 2); }
+ES_HD constexpr int stage_fetch_piece(int lane, int t, int kt) {
+  const int slot = stage_tile_slot(lane);
+  return (t * 16 + slot) * kStageRowPieces + ((4 * kt + (lane >> 4)) ^ slot);
+}
+// The MFMA result of tile t holds, in element i of lane (lane / 16, any column), the score of A row 4 (lane / 16) + i,
+// which by stage_tile_slot is slot 4 i + lane / 16 of the tile: the slot of the batch whose V row load 4 t + i brings to the lane.
+ES_HD constexpr int score_slot_in_batch(int lane, int t, int i) { return t * 16 + 4 * i + (lane >> 4); }
+
 }  // namespace es

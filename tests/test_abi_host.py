@@ -331,3 +331,25 @@ def test_weight_walk_rejects_bad_arguments():
         with pytest.raises(es.EasySpecError) as e:
             es.easyspec_weight_walk(cfg, *args)
         assert e.value.code == es.EASYSPEC_EINVAL
+
+
+def test_attention_stage_walk_delivers_every_k_piece_to_its_mfma_operand():
+    """The passage of a batch of K rows through a wave's LDS into MFMA A fragments (vector attention with scores
+    from the matrix cores), walked on the host with the kernel's own index functions: every stored piece has a
+    place of its own inside the wave's 8 KB, every fetch returns the piece its operand position needs, the score
+    of a slot comes out where that slot's V row sits, and no quarter-wave meets a bank group twice."""
+    import paper_2502_02493_amd as es
+    for n_loads in (2, 8):
+        rep = es.easyspec_attention_stage_walk(n_loads)
+        assert rep["stored"] == rep["distinct_places"] == 64 * n_loads
+        assert rep["highest_place"] <= rep["places"] == 512
+        tiles = (n_loads + 3) // 4
+        assert rep["fetched"] + rep["unused_rows"] == 64 * 4 * tiles
+        assert rep["fetched"] == 16 * n_loads * 4          # every piece of every row of the batch, once
+        assert rep["wrong_piece"] == 0
+        assert rep["misplaced_scores"] == 0
+        assert rep["bank_conflicts"] == 0
+    for bad in (0, 1, 4, 16):
+        with pytest.raises(es.EasySpecError) as e:
+            es.easyspec_attention_stage_walk(bad)
+        assert e.value.code == es.EASYSPEC_EINVAL
