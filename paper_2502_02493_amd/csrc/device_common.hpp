@@ -203,9 +203,12 @@ __device__ __forceinline__ bool folded(int ncols) {
   return Tr<T>::PARTS == 2 && 2 * ncols <= kMaxCols;
 }
 
-template <typename T, int RT, int NB>
-__device__ __forceinline__ void gemm_loop(const u32x4* const (&w)[RT], const u32x4* const (&xp)[NB], int xs, bool colok,
-                                          int nkt, f32x4 (&acc)[RT], int w_lane, int w_stride) {
+// NP = forward passes served by one launch (1, or 2: a calibration of more columns than one pass holds runs
+// its passes two at a time).  Every weight fragment a wave loads is then used for both passes' columns: the
+// passes have their own activation operands, accumulators and epilogues, the weights leave HBM once.
+template <typename T, int RT, int NB, int NP>
+__device__ __forceinline__ void gemm_loop(const u32x4* const (&w)[RT], const u32x4* const (&xp)[NP][NB], int xs, bool colok,
+                                          int nkt, f32x4 (&acc)[NP][RT], int w_lane, int w_stride) {
   constexpr int U = batch_len(RT);  // k-tiles per batch: 8 KB of weights in flight per wave
   const int wave = threadIdx.x >> 6, NW = blockDim.x >> 6;
   // w_lane: the lane's 16-byte piece of a weight fragment, w_stride: pieces per fragment (lane and 64 for tiles of 16 rows)
@@ -215,30 +218,34 @@ __device__ __forceinline__ void gemm_loop(const u32x4* const (&w)[RT], const u32
   const u32x4 zero = {0u, 0u, 0u, 0u};
   int kt = wave;
   for (; batch_is_full(kt, U, NW, nkt); kt = next_batch(kt, U, NW)) {
-    u32x4 a[RT][U], b[NB][U];
+    u32x4 a[RT][U], b[NP][NB][U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
 #pragma unroll
       for (int r = 0; r < RT; ++r) a[r][u] = __builtin_nontemporal_load(wp[r] + (size_t)batch_tile(kt, u, NW) * w_stride);
     }
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
+    for (int p = 0; p < NP; ++p)
 #pragma unroll
-      for (int q = 0; q < NB; ++q) b[q][u] = colok ? xp[q][(size_t)batch_tile(kt, u, NW) * xs] : zero;
-    }
+      for (int u = 0; u < U; ++u) {
+#pragma unroll
+        for (int q = 0; q < NB; ++q) b[p][q][u] = colok ? xp[p][q][(size_t)batch_tile(kt, u, NW) * xs] : zero;
+      }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
 #pragma unroll
       for (int r = 0; r < RT; ++r) {
 #pragma unroll
-        for (int q = 0; q < NB; ++q) mma<T>(acc[r], a[r][u], b[q][u]);
+        for (int p = 0; p < NP; ++p)
+#pragma unroll
+          for (int q = 0; q < NB; ++q) mma<T>(acc[p][r], a[r][u], b[p][q][u]);
       }
     }
   }
   if (kt < nkt) {
     // last, partial batch: same shape with the loads past the end switched off (wave-uniform), so
     // that the remaining tiles are still fetched together instead of one latency at a time
-    u32x4 a[RT][U], b[NB][U];
+    u32x4 a[RT][U], b[NP][NB][U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const bool in = batch_tile(kt, u, NW) < nkt;
@@ -246,17 +253,21 @@ __device__ __forceinline__ void gemm_loop(const u32x4* const (&w)[RT], const u32
       for (int r = 0; r < RT; ++r) a[r][u] = in ? __builtin_nontemporal_load(wp[r] + (size_t)batch_tile(kt, u, NW) * w_stride) : zero;
     }
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const bool in = colok && batch_tile(kt, u, NW) < nkt;
+    for (int p = 0; p < NP; ++p)
 #pragma unroll
-      for (int q = 0; q < NB; ++q) b[q][u] = in ? xp[q][(size_t)batch_tile(kt, u, NW) * xs] : zero;
-    }
+      for (int u = 0; u < U; ++u) {
+        const bool in = colok && batch_tile(kt, u, NW) < nkt;
+#pragma unroll
+        for (int q = 0; q < NB; ++q) b[p][q][u] = in ? xp[p][q][(size_t)batch_tile(kt, u, NW) * xs] : zero;
+      }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
 #pragma unroll
       for (int r = 0; r < RT; ++r) {
 #pragma unroll
-        for (int q = 0; q < NB; ++q) mma<T>(acc[r], a[r][u], b[q][u]);
+        for (int p = 0; p < NP; ++p)
+#pragma unroll
+          for (int q = 0; q < NB; ++q) mma<T>(acc[p][r], a[r][u], b[p][q][u]);
       }
     }
   }
@@ -264,26 +275,34 @@ __device__ __forceinline__ void gemm_loop(const u32x4* const (&w)[RT], const u32
 
 // NB is chosen by the host per launch: 1 when the activations have one term (fp32) or the
 // columns fold (at most 8), else 2.  Separate instantiations keep the common one-fragment path
-// free of the second path's registers.
-template <typename T, int RT, int NB>
-__device__ __forceinline__ void gemm_accumulate(const u32x4* const (&w)[RT], const T* __restrict__ x, int K, int ncols,
-                                                f32x4 (&acc)[RT], int w_lane = -1, int w_stride = 64) {
+// free of the second path's registers.  x[p]: the operand of pass p (all passes have ncols columns).
+template <typename T, int RT, int NB, int NP>
+__device__ __forceinline__ void gemm_accumulate(const u32x4* const (&w)[RT], const T* const (&x)[NP], int K, int ncols,
+                                                f32x4 (&acc)[NP][RT], int w_lane = -1, int w_stride = 64) {
   constexpr int EPL = Tr<T>::EPL, KT = Tr<T>::KT, PARTS = Tr<T>::PARTS;
   const int lane = threadIdx.x & 63;
   const int nkt = K / KT;
   if (w_lane < 0) w_lane = lane;  // full tiles: fragment piece i belongs to lane i
-  if (NB == 1) {
-    // lane column c < ncols reads the hi term of column c, column ncols + c its lo term
-    const long o = x_fragment_elems(EPL, PARTS, 1, ncols, K, lane, 0);
-    const bool colok = o >= 0;
-    const u32x4* const xp[1] = {reinterpret_cast<const u32x4*>(x + (colok ? o : 0))};
-    gemm_loop<T, RT, 1>(w, xp, xtile_stride<T>(ncols), colok, nkt, acc, w_lane, w_stride);
-  } else {
-    const long o0 = x_fragment_elems(EPL, PARTS, 2, ncols, K, lane, 0), o1 = x_fragment_elems(EPL, PARTS, 2, ncols, K, lane, 1);
-    const bool colok = o0 >= 0;
-    const u32x4* const xp[2] = {reinterpret_cast<const u32x4*>(x + (colok ? o0 : 0)), reinterpret_cast<const u32x4*>(x + (colok ? o1 : 0))};
-    gemm_loop<T, RT, 2>(w, xp, xtile_stride<T>(ncols), colok, nkt, acc, w_lane, w_stride);
-  }
+  // NB == 1: lane column c < ncols reads the hi term of column c, column ncols + c its lo term
+  long o[NB];
+#pragma unroll
+  for (int q = 0; q < NB; ++q) o[q] = x_fragment_elems(EPL, PARTS, NB, ncols, K, lane, q);
+  const bool colok = o[0] >= 0;
+  const u32x4* xp[NP][NB];
+#pragma unroll
+  for (int p = 0; p < NP; ++p)
+#pragma unroll
+    for (int q = 0; q < NB; ++q) xp[p][q] = reinterpret_cast<const u32x4*>(x[p] + (colok ? o[q] : 0));
+  const u32x4* const(&xc)[NP][NB] = xp;
+  gemm_loop<T, RT, NB, NP>(w, xc, xtile_stride<T>(ncols), colok, nkt, acc, w_lane, w_stride);
+}
+
+// one pass
+template <typename T, int RT, int NB>
+__device__ __forceinline__ void gemm_accumulate(const u32x4* const (&w)[RT], const T* __restrict__ x, int K, int ncols,
+                                                f32x4 (&acc)[RT], int w_lane = -1, int w_stride = 64) {
+  const T* const xs[1] = {x};
+  gemm_accumulate<T, RT, NB, 1>(w, xs, K, ncols, reinterpret_cast<f32x4(&)[1][RT]>(acc), w_lane, w_stride);
 }
 
 // After reduce_waves, in the wave that holds the totals: add the lo-term columns onto the
@@ -379,5 +398,20 @@ __device__ __forceinline__ void rstd_finish(const float* __restrict__ ssp, int n
 }
 
 extern __shared__ f32x4 dyn_red[];
+
+// Kernel argument of a launch that serves two passes: their arguments and columns side by side.  Those kernels
+// are compiled for workgroups of at most kTwinThreads threads (room for 256 registers per lane).
+constexpr int kTwinThreads = 512;
+template <typename Args>
+struct Twin {
+  Args a[2];
+  Cols c[2];
+};
+// pass p's piece of the reduction buffer ((NW - 1) * RT * 64 f32x4 each)
+template <int RT>
+__device__ __forceinline__ f32x4* red_of_pass(int p) {
+  const int NW = blockDim.x >> 6;
+  return dyn_red + (size_t)p * (NW > 1 ? NW - 1 : 0) * RT * 64;
+}
 
 }  // namespace es

@@ -23,6 +23,9 @@ struct easyspec_ctx {
   easyspec_config cfg;
   Shape s;
   Buffers b;
+  Buffers b2;      // a second set of per-pass workspaces (same weights and caches): the second of two passes run together
+  bool has_b2;
+  const float* last_H;  // residual rows of the most recent pass
   hipStream_t stream;
   bool weights_loaded;
   std::vector<int32_t> precise, fuzzy;
@@ -133,6 +136,8 @@ extern "C" int easyspec_create(const easyspec_config* cfg, void* hip_stream, eas
   ctx->stream = (hipStream_t)hip_stream;
   ctx->weights_loaded = false;
   ctx->last_rows = 0;
+  ctx->last_H = nullptr;
+  ctx->has_b2 = false;
   ctx->prof_op = -1;
   ctx->timer = LaunchTimer{nullptr, nullptr, 0, 0, 0};
   ctx->parallel_mode = EASYSPEC_PARALLEL_ATTENTION;
@@ -180,6 +185,28 @@ extern "C" int easyspec_create(const easyspec_config* cfg, void* hip_stream, eas
     const size_t nblk = (size_t)(s.V + 15) / 16;
     ALLOC_WORK(ctx, b.amax_val, kMaxCols * nblk * sizeof(float));
     ALLOC_WORK(ctx, b.amax_idx, kMaxCols * nblk * sizeof(int32_t));
+    // A calibration of more columns than one pass holds runs its passes two at a time (the weight kernels serve
+    // both from one read of the weights): the second pass of a pair works in a workspace set of its own.
+    Buffers& b2 = ctx->b2;
+    b2 = b;
+    ctx->has_b2 = (long)s.B * cfg->max_calib_tokens > kMaxCols;
+    if (ctx->has_b2) {
+      ALLOC_WORK(ctx, b2.H, (size_t)kMaxCols * s.d * sizeof(float));
+      ALLOC_WORK(ctx, b2.ssp, (size_t)kMaxCols * (s.d / 16) * sizeof(float));
+      ALLOC_WORK(ctx, b2.XA, (size_t)kMaxCols * s.d * act_);
+      ALLOC_WORK(ctx, b2.XM, (size_t)kMaxCols * s.d * act_);
+      ALLOC_WORK(ctx, b2.Q, (size_t)kMaxCols * s.HQ * sizeof(float));
+      ALLOC_WORK(ctx, b2.AO, (size_t)kMaxCols * s.HQ * act_);
+      ALLOC_WORK(ctx, b2.A, (size_t)kMaxCols * s.d * sizeof(float));
+      ALLOC_WORK(ctx, b2.ACT, (size_t)kMaxCols * s.F * act_);
+      const size_t prow2 = (size_t)kMaxCols * s.Hq;  // calibrations go layer by layer: one layer's worth of each
+      ALLOC_WORK(ctx, b2.PO, prow2 * kMaxChunks * s.hd * sizeof(float));
+      ALLOC_WORK(ctx, b2.PM, prow2 * kMaxChunks * sizeof(float));
+      ALLOC_WORK(ctx, b2.PL, prow2 * kMaxChunks * sizeof(float));
+      ALLOC_WORK(ctx, b2.amax_val, kMaxCols * nblk * sizeof(float));
+      ALLOC_WORK(ctx, b2.amax_idx, kMaxCols * nblk * sizeof(int32_t));
+      b2.ssp_set = nullptr;  // full-layer mode never runs two passes together
+    }
     HIPCHK(ctx, hipMemsetAsync(b.kc, 0, kv_bytes, ctx->stream));
     HIPCHK(ctx, hipMemsetAsync(b.vc, 0, kv_bytes, ctx->stream));
 
@@ -350,19 +377,26 @@ struct ProfScope {
   ~ProfScope() { g_launch_timer = nullptr; }
 };
 
+// c2: a second pass of as many columns run together with the first (sets of one layer only: a calibration); the
+// weight kernels then serve both passes in one launch each, embedding, attention and argmax run per pass.
 static int forward(easyspec_ctx* ctx, const Cols& c, const int32_t* tokens, const std::vector<int32_t>& bounds,
-                   bool full_layer, float* logits_out, int32_t* tokens_out) {
+                   bool full_layer, float* logits_out, int32_t* tokens_out, const Cols* c2 = nullptr) {
   const Shape& s = ctx->s;
   const Buffers& b = ctx->b;
+  const Buffers* b2 = c2 ? &ctx->b2 : nullptr;
   hipStream_t st = ctx->stream;
   const int n_sets = (int)bounds.size() - 1;
+  if (c2 && (full_layer || !ctx->has_b2 || c2->n != c.n || n_sets != s.L))
+    return fail(ctx, EASYSPEC_EINVAL, "internal: two passes together need equal column counts and sets of one layer");
   { ProfScope p(ctx, EASYSPEC_OP_ALL); launch_embed(s, b, c, tokens, 0, bounds[1] - bounds[0], st); }
+  if (c2) { ProfScope p(ctx, EASYSPEC_OP_ALL); launch_embed(s, *b2, *c2, tokens, 0, 1, st); }
   for (int j = 0; j < n_sets; ++j) {
     const int lo = bounds[j], hi = bounds[j + 1], k = hi - lo;
     const AttnCut cut = attn_cut(s, c, k);
     // every attention layer of the set reads the hidden state that enters the set
-    { ProfScope p(ctx, EASYSPEC_OP_QKV); launch_qkv(s, b, c, lo, k, st); }
+    { ProfScope p(ctx, EASYSPEC_OP_QKV); launch_qkv(s, b, c, lo, k, st, b2, c2); }
     { ProfScope p(ctx, EASYSPEC_OP_ATTN); launch_attn(s, b, c, lo, k, cut, st); }
+    if (c2) { ProfScope p(ctx, EASYSPEC_OP_ATTN); launch_attn(s, *b2, *c2, lo, k, attn_cut(s, *c2, k), st); }
     if (full_layer && k > 1) {
       // App. B ablation: the MLPs of the set also work from the set's input, each behind its own
       // layer's attention; one launch per operation for the whole set
@@ -373,23 +407,24 @@ static int forward(easyspec_ctx* ctx, const Cols& c, const int32_t* tokens, cons
       else launch_down_full(s, b, c, lo, k, b.g_final, 1, b.XA, st);
       continue;
     }
-    { ProfScope p(ctx, EASYSPEC_OP_OPROJ); launch_oproj(s, b, c, lo, k, st); }
+    { ProfScope p(ctx, EASYSPEC_OP_OPROJ); launch_oproj(s, b, c, lo, k, st, b2, c2); }
     // the MLPs run in layer order on the running residual
     for (int i = lo; i < hi; ++i) {
-      { ProfScope p(ctx, EASYSPEC_OP_GATEUP); launch_gateup(s, b, c, i, 1, b.ssp, st); }
+      { ProfScope p(ctx, EASYSPEC_OP_GATEUP); launch_gateup(s, b, c, i, 1, b.ssp, st, b2, c2, c2 ? b2->ssp : nullptr); }
       ProfScope p(ctx, EASYSPEC_OP_DOWN);
       if (i + 1 < hi) {
-        launch_down(s, b, c, i, i + 1 - lo, b.g_mlp + (size_t)(i + 1) * s.d, 1, b.XM, st);
+        launch_down(s, b, c, i, i + 1 - lo, b.g_mlp + (size_t)(i + 1) * s.d, 1, b.XM, st, b2, c2, c2 ? b2->XM : nullptr);
       } else if (hi < s.L) {
-        launch_down(s, b, c, i, -1, b.g_attn + (size_t)hi * s.d, bounds[j + 2] - hi, b.XA, st);
+        launch_down(s, b, c, i, -1, b.g_attn + (size_t)hi * s.d, bounds[j + 2] - hi, b.XA, st, b2, c2, c2 ? b2->XA : nullptr);
       } else {
-        launch_down(s, b, c, i, -1, b.g_final, 1, b.XA, st);
+        launch_down(s, b, c, i, -1, b.g_final, 1, b.XA, st, b2, c2, c2 ? b2->XA : nullptr);
       }
     }
   }
-  { ProfScope p(ctx, EASYSPEC_OP_HEAD); launch_head(s, b, c, logits_out, tokens_out, st); }
+  { ProfScope p(ctx, EASYSPEC_OP_HEAD); launch_head(s, b, c, logits_out, tokens_out, st, b2, c2); }
   HIPCHK(ctx, hipGetLastError());
-  ctx->last_rows = c.n;
+  ctx->last_rows = c2 ? c2->n : c.n;
+  ctx->last_H = c2 ? b2->H : b.H;
   return EASYSPEC_OK;
 }
 
@@ -490,8 +525,15 @@ extern "C" int easyspec_calibrate(easyspec_ctx* ctx, const int32_t* tokens, cons
     total += n;
   }
   if (total == 0) return fail(ctx, EASYSPEC_EINVAL, "calibrate: no tokens");
-  // passes of at most 16 columns; a sequence's tokens stay together
+  // passes of at most 16 columns; a sequence's tokens stay together.  Two consecutive passes of equal column
+  // counts run together, so that the weights are read once for both.
   int b = 0;
+  Cols held;  // a pass waiting for a partner
+  memset(&held, 0, sizeof held);
+  bool holding = false;
+  const char* pair_env = getenv("EASYSPEC_PAIR_PASSES");  // tests: 0 = one pass at a time; read at every call
+  const bool pair_passes = !pair_env || atoi(pair_env) != 0;
+  auto run = [&](const Cols& c, const Cols* partner) { return forward(ctx, c, tokens, ctx->single, false, logits_out, next_token_out, partner); };
   while (b < s.B) {
     Cols c;
     memset(&c, 0, sizeof c);
@@ -511,7 +553,25 @@ extern "C" int easyspec_calibrate(easyspec_ctx* ctx, const int32_t* tokens, cons
       ++b;
     }
     if (c.n == 0) continue;
-    const int rc = forward(ctx, c, tokens, ctx->single, false, logits_out, next_token_out);
+    int rc = EASYSPEC_OK;
+    if (holding && held.n == c.n) {
+      rc = run(held, &c);
+      holding = false;
+    } else {
+      if (holding) rc = run(held, nullptr);
+      const bool more = b < s.B;  // sequences left: a partner may follow
+      if (rc == EASYSPEC_OK && more && pair_passes && ctx->has_b2 && twin_passes_fit(s, c.n)) {
+        held = c;
+        holding = true;
+      } else if (rc == EASYSPEC_OK) {
+        holding = false;
+        rc = run(c, nullptr);
+      }
+    }
+    if (rc != EASYSPEC_OK) return rc;
+  }
+  if (holding) {
+    const int rc = run(held, nullptr);
     if (rc != EASYSPEC_OK) return rc;
   }
   for (int q = 0; q < s.B; ++q)
@@ -692,7 +752,7 @@ extern "C" int easyspec_get_hidden(easyspec_ctx* ctx, float* out, int32_t max_ro
   if (!out || !n_rows) return fail(ctx, EASYSPEC_EINVAL, "get_hidden: NULL argument");
   if (ctx->last_rows == 0) return fail(ctx, EASYSPEC_ESTATE, "get_hidden: no forward has run");
   if (max_rows < ctx->last_rows) return fail(ctx, EASYSPEC_ECAPACITY, "get_hidden: %d rows needed", ctx->last_rows);
-  HIPCHK(ctx, hipMemcpyAsync(out, ctx->b.H, (size_t)ctx->last_rows * ctx->s.d * sizeof(float), hipMemcpyDeviceToDevice, ctx->stream));
+  HIPCHK(ctx, hipMemcpyAsync(out, ctx->last_H, (size_t)ctx->last_rows * ctx->s.d * sizeof(float), hipMemcpyDeviceToDevice, ctx->stream));
   *n_rows = ctx->last_rows;
   return EASYSPEC_OK;
 }

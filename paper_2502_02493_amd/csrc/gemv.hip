@@ -35,9 +35,12 @@ struct QkvArgs {
 };
 
 // TP: tiles of R pairs per workgroup (two where a pass loads two fragments per k-tile, as for gate/up)
-template <typename T, int NB, int TP>
-__global__ __launch_bounds__(TP == 1 ? 1024 : 512) void qkv_kernel(QkvArgs a, Cols c) {
-  __shared__ float s_rstd[kMaxCols];
+// NP passes (of equal column counts) are served from one read of the weights.
+template <typename T, int NB, int TP, int NP>
+__device__ __forceinline__ void qkv_body(const QkvArgs* const (&ap)[NP], const Cols* const (&cp)[NP]) {
+  __shared__ float s_rstd[NP][kMaxCols];
+  const QkvArgs& a = *ap[0];  // what the passes share: weights, bias, rotary table, caches, shape
+  const int ncols = cp[0]->n;
   const int KT = Tr<T>::KT;
   const int nkt = a.d / KT;
   const int half = a.hd / 2;
@@ -51,17 +54,15 @@ __global__ __launch_bounds__(TP == 1 ? 1024 : 512) void qkv_kernel(QkvArgs a, Co
     w[2 * p] = wl + (size_t)u * row_tile_pieces(nkt, R);
     w[2 * p + 1] = wl + (size_t)(units + u) * row_tile_pieces(nkt, R);
   }
-  const T* x = reinterpret_cast<const T*>(a.x) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.d;
   // operands of the epilogue (wave 0 only) and of the norm scale are fetched before the weight
   // stream starts, so that their latency does not sit in the tail of the kernel
   const int lane = threadIdx.x & 63, col = lane & 15;
   const int row0 = (lane >> 4) * 4;  // of the tile
   const int RQKV = (a.Hq + 2 * a.Hkv) * a.hd;
-  const bool col_ok = threadIdx.x < 64 && col < c.n;
-  const int pos = col_ok ? c.pos[col] : 0, seq = col_ok ? c.seq[col] : 0;
+  const bool col_ok = threadIdx.x < 64 && col < ncols;
   bool rows_ok[TP];
   int head[TP], e0[TP];
-  f32x4 b_lo[TP], b_hi[TP], cs01[TP], cs23[TP];
+  f32x4 b_lo[TP], b_hi[TP];
 #pragma unroll
   for (int p = 0; p < TP; ++p) {
     const int pair0 = (u0 + p) * R + row0;  // first of the lane's four pairs
@@ -69,59 +70,92 @@ __global__ __launch_bounds__(TP == 1 ? 1024 : 512) void qkv_kernel(QkvArgs a, Co
     head[p] = rows_ok[p] ? pair0 / half : 0;
     e0[p] = rows_ok[p] ? pair0 % half : 0;  // element inside the head, < hd/2
     b_lo[p] = b_hi[p] = f32x4{0.f, 0.f, 0.f, 0.f};
-    cs01[p] = cs23[p] = f32x4{1.f, 0.f, 1.f, 0.f};
-    if (col_ok && rows_ok[p]) {
-      if (a.bias) {
-        b_lo[p] = *reinterpret_cast<const f32x4*>(a.bias + (size_t)li * RQKV + head[p] * a.hd + e0[p]);
-        b_hi[p] = *reinterpret_cast<const f32x4*>(a.bias + (size_t)li * RQKV + head[p] * a.hd + e0[p] + half);
-      }
-      if (head[p] < a.Hq + a.Hkv) {
-        const f32x4* rp = reinterpret_cast<const f32x4*>(a.rope + (size_t)c.rope_pos[col] * half + e0[p]);  // 4 x (cos, sin)
-        cs01[p] = rp[0];
-        cs23[p] = rp[1];
-      }
+    if (col_ok && rows_ok[p] && a.bias) {
+      b_lo[p] = *reinterpret_cast<const f32x4*>(a.bias + (size_t)li * RQKV + head[p] * a.hd + e0[p]);
+      b_hi[p] = *reinterpret_cast<const f32x4*>(a.bias + (size_t)li * RQKV + head[p] * a.hd + e0[p] + half);
     }
   }
-  RstdPre pre;
-  rstd_issue(a.ssp, a.d / 16, c.n, pre);
-
-  f32x4 acc[2 * TP];
+  int pos[NP], seq[NP];
+  f32x4 cs01[NP][TP], cs23[NP][TP];
+  const T* x[NP];
+  RstdPre pre[NP];
+  f32x4 acc[NP][2 * TP];
 #pragma unroll
-  for (int p = 0; p < 2 * TP; ++p) acc[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int q = 0; q < NP; ++q) {
+    const Cols& c = *cp[q];
+    pos[q] = col_ok ? c.pos[col] : 0;
+    seq[q] = col_ok ? c.seq[col] : 0;
+#pragma unroll
+    for (int p = 0; p < TP; ++p) {
+      cs01[q][p] = cs23[q][p] = f32x4{1.f, 0.f, 1.f, 0.f};
+      if (col_ok && rows_ok[p] && head[p] < a.Hq + a.Hkv) {
+        const f32x4* rp = reinterpret_cast<const f32x4*>(a.rope + (size_t)c.rope_pos[col] * half + e0[p]);  // 4 x (cos, sin)
+        cs01[q][p] = rp[0];
+        cs23[q][p] = rp[1];
+      }
+    }
+    x[q] = reinterpret_cast<const T*>(ap[q]->x) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.d;
+    rstd_issue(ap[q]->ssp, a.d / 16, ncols, pre[q]);
+#pragma unroll
+    for (int p = 0; p < 2 * TP; ++p) acc[q][p] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
   // a tile of R < 16 pairs: the lanes of the missing rows re-read the last row (their results are dropped)
   const u32x4* const(&wc)[2 * TP] = w;
-  gemm_accumulate<T, 2 * TP, NB>(wc, x, a.d, c.n, acc, lane_piece(lane, R), fragment_pieces(R));
-  rstd_finish(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
-  if (!reduce_waves<2 * TP>(acc, dyn_red)) return;
-  fold_columns<T, 2 * TP>(acc, c.n);
+  const T* const(&xc)[NP] = x;
+  gemm_accumulate<T, 2 * TP, NB, NP>(wc, xc, a.d, ncols, acc, lane_piece(lane, R), fragment_pieces(R));
+  bool mine = false;
+#pragma unroll
+  for (int q = 0; q < NP; ++q) {
+    rstd_finish(ap[q]->ssp, a.d / 16, ncols, a.inv_d, a.eps, pre[q], s_rstd[q]);
+    mine = reduce_waves<2 * TP>(acc[q], red_of_pass<2 * TP>(q));
+  }
+  if (!mine) return;
+#pragma unroll
+  for (int q = 0; q < NP; ++q) fold_columns<T, 2 * TP>(acc[q], ncols);  // all 64 lanes
 
-  if (col >= c.n) return;
-  const float r = s_rstd[col];
+  if (col >= ncols) return;
 #pragma unroll
-  for (int p = 0; p < TP; ++p) {
-    if (!rows_ok[p]) continue;
-    const float cosv[4] = {cs01[p][0], cs01[p][2], cs23[p][0], cs23[p][2]}, sinv[4] = {cs01[p][1], cs01[p][3], cs23[p][1], cs23[p][3]};
-    float lo[4], hi[4];
+  for (int q = 0; q < NP; ++q) {
+    const float r = s_rstd[q][col];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      // identity rotation (cos 1, sin 0) for the V rows; bias 0 without bias
-      const float v0 = acc[2 * p][i] * r + b_lo[p][i], v1 = acc[2 * p + 1][i] * r + b_hi[p][i];
-      lo[i] = v0 * cosv[i] - v1 * sinv[i];
-      hi[i] = v1 * cosv[i] + v0 * sinv[i];
-    }
-    if (head[p] < a.Hq) {
-      float* q = a.q + ((size_t)li * kMaxCols + col) * (a.Hq * a.hd) + head[p] * a.hd + e0[p];
-      store4<float>(q, lo[0], lo[1], lo[2], lo[3]);
-      store4<float>(q + half, hi[0], hi[1], hi[2], hi[3]);
-    } else {
-      const bool is_k = head[p] < a.Hq + a.Hkv;
-      const int kvh = is_k ? head[p] - a.Hq : head[p] - a.Hq - a.Hkv;
-      T* base = reinterpret_cast<T*>(is_k ? a.kc : a.vc);
-      T* row = base + ((((size_t)(a.layer0 + li) * a.B + seq) * a.Hkv + kvh) * a.max_ctx + pos) * a.hd + e0[p];
-      store4<T>(row, lo[0], lo[1], lo[2], lo[3]);
-      store4<T>(row + half, hi[0], hi[1], hi[2], hi[3]);
+    for (int p = 0; p < TP; ++p) {
+      if (!rows_ok[p]) continue;
+      const float cosv[4] = {cs01[q][p][0], cs01[q][p][2], cs23[q][p][0], cs23[q][p][2]},
+                  sinv[4] = {cs01[q][p][1], cs01[q][p][3], cs23[q][p][1], cs23[q][p][3]};
+      float lo[4], hi[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        // identity rotation (cos 1, sin 0) for the V rows; bias 0 without bias
+        const float v0 = acc[q][2 * p][i] * r + b_lo[p][i], v1 = acc[q][2 * p + 1][i] * r + b_hi[p][i];
+        lo[i] = v0 * cosv[i] - v1 * sinv[i];
+        hi[i] = v1 * cosv[i] + v0 * sinv[i];
+      }
+      if (head[p] < a.Hq) {
+        float* qo = ap[q]->q + ((size_t)li * kMaxCols + col) * (a.Hq * a.hd) + head[p] * a.hd + e0[p];
+        store4<float>(qo, lo[0], lo[1], lo[2], lo[3]);
+        store4<float>(qo + half, hi[0], hi[1], hi[2], hi[3]);
+      } else {
+        const bool is_k = head[p] < a.Hq + a.Hkv;
+        const int kvh = is_k ? head[p] - a.Hq : head[p] - a.Hq - a.Hkv;
+        T* base = reinterpret_cast<T*>(is_k ? a.kc : a.vc);
+        T* row = base + ((((size_t)(a.layer0 + li) * a.B + seq[q]) * a.Hkv + kvh) * a.max_ctx + pos[q]) * a.hd + e0[p];
+        store4<T>(row, lo[0], lo[1], lo[2], lo[3]);
+        store4<T>(row + half, hi[0], hi[1], hi[2], hi[3]);
+      }
     }
   }
+}
+template <typename T, int NB, int TP>
+__global__ __launch_bounds__(TP == 1 ? 1024 : 512) void qkv_kernel(QkvArgs a, Cols c) {
+  const QkvArgs* const ap[1] = {&a};
+  const Cols* const cp[1] = {&c};
+  qkv_body<T, NB, TP, 1>(ap, cp);
+}
+template <typename T, int NB, int TP>
+__global__ __launch_bounds__(kTwinThreads) void qkv_twin_kernel(Twin<QkvArgs> t) {
+  const QkvArgs* const ap[2] = {&t.a[0], &t.a[1]};
+  const Cols* const cp[2] = {&t.c[0], &t.c[1]};
+  qkv_body<T, NB, TP, 2>(ap, cp);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -146,8 +180,11 @@ struct ProjArgs {
 };
 
 // TP: row tiles per workgroup (two for the stacked O launches of two-fragment passes, as for gate/up)
-template <typename T, int NB, int TP>
-__global__ __launch_bounds__(1024) void proj_resid_kernel(ProjArgs a, Cols c) {
+// NP passes (of equal column counts) are served from one read of the weights.
+template <typename T, int NB, int TP, int NP>
+__device__ __forceinline__ void proj_resid_body(const ProjArgs* const (&ap)[NP], const Cols* const (&cp)[NP]) {
+  const ProjArgs& a = *ap[0];  // what the passes share: weights, gains, shape, a_add, n_gain
+  const int ncols = cp[0]->n;
   const int KT = Tr<T>::KT;
   const int nkt = a.K / KT;
   const int ntile = a.d / 16, nwg = ceil_div(ntile, TP);
@@ -156,56 +193,83 @@ __global__ __launch_bounds__(1024) void proj_resid_kernel(ProjArgs a, Cols c) {
 #pragma unroll
   for (int p = 0; p < TP; ++p)  // a missing last tile re-reads its neighbour (results dropped)
     w[p] = a.w + (size_t)li * a.w_layer_stride + (size_t)clamped_unit(t0, p, ntile) * row_tile_pieces(nkt, 16);
-  const T* x = reinterpret_cast<const T*>(a.x) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.K;
   // residual-update operands (wave 0 of a layer-0 workgroup) are fetched before the weight stream
   const int lane = threadIdx.x & 63, col = lane & 15;
-  const bool ok = col < c.n;
-  f32x4 h_in[TP], a_in[TP], g_in[TP];
+  const bool ok = col < ncols;
+  const T* x[NP];
+  f32x4 h_in[NP][TP], a_in[NP][TP], g_in[TP], acc[NP][TP];
 #pragma unroll
   for (int p = 0; p < TP; ++p) {
-    h_in[p] = a_in[p] = g_in[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+    g_in[p] = f32x4{0.f, 0.f, 0.f, 0.f};
     const int r0 = (t0 + p) * 16 + (lane >> 4) * 4;
-    if (threadIdx.x < 64 && li == 0 && ok && t0 + p < ntile) {
-      h_in[p] = *reinterpret_cast<const f32x4*>(a.H + (size_t)col * a.d + r0);
-      if (a.a_add >= 0) a_in[p] = *reinterpret_cast<const f32x4*>(a.A + ((size_t)a.a_add * kMaxCols + col) * a.d + r0);
-      g_in[p] = *reinterpret_cast<const f32x4*>(a.gain + r0);
+    if (threadIdx.x < 64 && li == 0 && ok && t0 + p < ntile) g_in[p] = *reinterpret_cast<const f32x4*>(a.gain + r0);
+  }
+#pragma unroll
+  for (int q = 0; q < NP; ++q) {
+    x[q] = reinterpret_cast<const T*>(ap[q]->x) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.K;
+#pragma unroll
+    for (int p = 0; p < TP; ++p) {
+      h_in[q][p] = a_in[q][p] = acc[q][p] = f32x4{0.f, 0.f, 0.f, 0.f};
+      const int r0 = (t0 + p) * 16 + (lane >> 4) * 4;
+      if (threadIdx.x < 64 && li == 0 && ok && t0 + p < ntile) {
+        h_in[q][p] = *reinterpret_cast<const f32x4*>(ap[q]->H + (size_t)col * a.d + r0);
+        if (a.a_add >= 0) a_in[q][p] = *reinterpret_cast<const f32x4*>(ap[q]->A + ((size_t)a.a_add * kMaxCols + col) * a.d + r0);
+      }
     }
   }
-  f32x4 acc[TP];
-#pragma unroll
-  for (int p = 0; p < TP; ++p) acc[p] = f32x4{0.f, 0.f, 0.f, 0.f};
   const u32x4* const(&wc)[TP] = w;
-  gemm_accumulate<T, TP, NB>(wc, x, a.K, c.n, acc);
-  if (!reduce_waves<TP>(acc, dyn_red)) return;
-  fold_columns<T, TP>(acc, c.n);
+  const T* const(&xc)[NP] = x;
+  gemm_accumulate<T, TP, NB, NP>(wc, xc, a.K, ncols, acc);
+  bool mine = false;
+#pragma unroll
+  for (int q = 0; q < NP; ++q) mine = reduce_waves<TP>(acc[q], red_of_pass<TP>(q));
+  if (!mine) return;
+#pragma unroll
+  for (int q = 0; q < NP; ++q) fold_columns<T, TP>(acc[q], ncols);  // all 64 lanes
 
 #pragma unroll
-  for (int p = 0; p < TP; ++p) {
-    const int t = t0 + p;
-    if (t >= ntile) break;
-    const int r0 = t * 16 + (lane >> 4) * 4;
-    if (li > 0) {
-      if (ok) store4<float>(a.A + ((size_t)li * kMaxCols + col) * a.d + r0, acc[p][0], acc[p][1], acc[p][2], acc[p][3]);
-      continue;
-    }
-    float ss = 0.f;
-    if (ok) {
-      float* hp = a.H + (size_t)col * a.d + r0;
-      f32x4 h = h_in[p];
-      h += acc[p];
-      if (a.a_add >= 0) h += a_in[p];
-      *reinterpret_cast<f32x4*>(hp) = h;
-      for (int j = 0; j < a.n_gain; ++j) {
-        const f32x4 g = j == 0 ? g_in[p] : *reinterpret_cast<const f32x4*>(a.gain + (size_t)j * a.d + r0);
-        T* xo = reinterpret_cast<T*>(a.xout) + (size_t)j * Tr<T>::PARTS * kMaxCols * a.d + xoff<T>(c.n, a.d, col, r0);
-        store_act4<T>(xo, (size_t)kMaxCols * a.d, h[0] * g[0], h[1] * g[1], h[2] * g[2], h[3] * g[3]);
+  for (int q = 0; q < NP; ++q) {
+    const ProjArgs& aq = *ap[q];
+#pragma unroll
+    for (int p = 0; p < TP; ++p) {
+      const int t = t0 + p;
+      if (t >= ntile) break;
+      const int r0 = t * 16 + (lane >> 4) * 4;
+      if (li > 0) {
+        if (ok) store4<float>(aq.A + ((size_t)li * kMaxCols + col) * a.d + r0, acc[q][p][0], acc[q][p][1], acc[q][p][2], acc[q][p][3]);
+        continue;
       }
-      ss = h[0] * h[0] + h[1] * h[1] + h[2] * h[2] + h[3] * h[3];
+      float ss = 0.f;
+      if (ok) {
+        float* hp = aq.H + (size_t)col * a.d + r0;
+        f32x4 h = h_in[q][p];
+        h += acc[q][p];
+        if (a.a_add >= 0) h += a_in[q][p];
+        *reinterpret_cast<f32x4*>(hp) = h;
+        for (int j = 0; j < a.n_gain; ++j) {
+          const f32x4 g = j == 0 ? g_in[p] : *reinterpret_cast<const f32x4*>(a.gain + (size_t)j * a.d + r0);
+          T* xo = reinterpret_cast<T*>(aq.xout) + (size_t)j * Tr<T>::PARTS * kMaxCols * a.d + xoff<T>(ncols, a.d, col, r0);
+          store_act4<T>(xo, (size_t)kMaxCols * a.d, h[0] * g[0], h[1] * g[1], h[2] * g[2], h[3] * g[3]);
+        }
+        ss = h[0] * h[0] + h[1] * h[1] + h[2] * h[2] + h[3] * h[3];
+      }
+      ss += __shfl_xor(ss, 16, 64);
+      ss += __shfl_xor(ss, 32, 64);
+      if (ok && lane < 16) aq.ssp[col * ntile + t] = ss;
     }
-    ss += __shfl_xor(ss, 16, 64);
-    ss += __shfl_xor(ss, 32, 64);
-    if (ok && lane < 16) a.ssp[col * ntile + t] = ss;
   }
+}
+template <typename T, int NB, int TP>
+__global__ __launch_bounds__(1024) void proj_resid_kernel(ProjArgs a, Cols c) {
+  const ProjArgs* const ap[1] = {&a};
+  const Cols* const cp[1] = {&c};
+  proj_resid_body<T, NB, TP, 1>(ap, cp);
+}
+template <typename T, int NB, int TP>
+__global__ __launch_bounds__(kTwinThreads) void proj_resid_twin_kernel(Twin<ProjArgs> t) {
+  const ProjArgs* const ap[2] = {&t.a[0], &t.a[1]};
+  const Cols* const cp[2] = {&t.c[0], &t.c[1]};
+  proj_resid_body<T, NB, TP, 2>(ap, cp);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -295,9 +359,12 @@ struct GateUpArgs {
 
 // TP: row tiles of each matrix per workgroup.  Two (four MFMA row tiles share every activation
 // fragment) halve the fragment loads per weight byte, which is what passes of many columns pay for.
-template <typename T, int NB, int TP>
-__global__ __launch_bounds__(1024) void gateup_kernel(GateUpArgs a, Cols c) {
-  __shared__ float s_rstd[kMaxCols];
+// NP passes (of equal column counts) are served from one read of the weights.
+template <typename T, int NB, int TP, int NP>
+__device__ __forceinline__ void gateup_body(const GateUpArgs* const (&ap)[NP], const Cols* const (&cp)[NP]) {
+  __shared__ float s_rstd[NP][kMaxCols];
+  const GateUpArgs& a = *ap[0];  // what the passes share: weights and shape
+  const int ncols = cp[0]->n;
   const int nkt = a.d / Tr<T>::KT;
   const int R = a.R, ntile = ceil_div(a.F, R), nunit = ceil_div(ntile, TP);
   const int li = blockIdx.x / nunit, t0 = (blockIdx.x % nunit) * TP;
@@ -309,44 +376,71 @@ __global__ __launch_bounds__(1024) void gateup_kernel(GateUpArgs a, Cols c) {
     w[2 * p] = a.wg + wl;
     w[2 * p + 1] = a.wu + wl;
   }
-  const float* ssp = a.ssp + (size_t)li * kMaxCols * (a.d / 16);
-  RstdPre pre;
-  rstd_issue(ssp, a.d / 16, c.n, pre);
-  f32x4 acc[2 * TP];
+  const float* ssp[NP];
+  const T* x[NP];
+  RstdPre pre[NP];
+  f32x4 acc[NP][2 * TP];
 #pragma unroll
-  for (int p = 0; p < 2 * TP; ++p) acc[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int q = 0; q < NP; ++q) {
+    ssp[q] = ap[q]->ssp + (size_t)li * kMaxCols * (a.d / 16);
+    x[q] = reinterpret_cast<const T*>(ap[q]->x) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.d;
+    rstd_issue(ssp[q], a.d / 16, ncols, pre[q]);
+#pragma unroll
+    for (int p = 0; p < 2 * TP; ++p) acc[q][p] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
   // a tile of R < 16 rows: the lanes of the missing rows re-read the last row (their results are dropped)
   const u32x4* const(&wc)[2 * TP] = w;
-  gemm_accumulate<T, 2 * TP, NB>(wc, reinterpret_cast<const T*>(a.x) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.d, a.d, c.n, acc,
-                                 lane_piece(threadIdx.x & 63, R), fragment_pieces(R));
-  rstd_finish(ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
-  if (!reduce_waves<2 * TP>(acc, dyn_red)) return;
-  fold_columns<T, 2 * TP>(acc, c.n);
+  const T* const(&xc)[NP] = x;
+  gemm_accumulate<T, 2 * TP, NB, NP>(wc, xc, a.d, ncols, acc, lane_piece(threadIdx.x & 63, R), fragment_pieces(R));
+  bool mine = false;
+#pragma unroll
+  for (int q = 0; q < NP; ++q) {
+    rstd_finish(ssp[q], a.d / 16, ncols, a.inv_d, a.eps, pre[q], s_rstd[q]);
+    mine = reduce_waves<2 * TP>(acc[q], red_of_pass<2 * TP>(q));
+  }
+  if (!mine) return;
+#pragma unroll
+  for (int q = 0; q < NP; ++q) fold_columns<T, 2 * TP>(acc[q], ncols);  // all 64 lanes
   const int lane = threadIdx.x & 63, col = lane & 15;
-  if (col >= c.n) return;
-  const float r = s_rstd[col];
-  T* dst = reinterpret_cast<T*>(a.act) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.F;
+  if (col >= ncols) return;
   const int row0 = (lane >> 4) * 4;  // of the tile
 #pragma unroll
-  for (int p = 0; p < TP; ++p) {
-    const int t = t0 + p;
-    if (t >= ntile) break;
-    float o[4];
+  for (int q = 0; q < NP; ++q) {
+    const float r = s_rstd[q][col];
+    T* dst = reinterpret_cast<T*>(ap[q]->act) + (size_t)li * Tr<T>::PARTS * kMaxCols * a.F;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const float g = acc[2 * p][i] * r, u = acc[2 * p + 1][i] * r;
-      o[i] = (g / (1.0f + expf(-g))) * u;
-    }
-    if (R == 16) {
-      store_act4<T>(dst + xoff<T>(c.n, a.F, col, t * 16 + row0), (size_t)kMaxCols * a.F, o[0], o[1], o[2], o[3]);
-    } else {
+    for (int p = 0; p < TP; ++p) {
+      const int t = t0 + p;
+      if (t >= ntile) break;
+      float o[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const int f = t * R + row0 + i;
-        if (row0 + i < R && f < a.F) store_act1<T>(dst + xoff<T>(c.n, a.F, col, f), (size_t)kMaxCols * a.F, o[i]);
+        const float g = acc[q][2 * p][i] * r, u = acc[q][2 * p + 1][i] * r;
+        o[i] = (g / (1.0f + expf(-g))) * u;
+      }
+      if (R == 16) {
+        store_act4<T>(dst + xoff<T>(ncols, a.F, col, t * 16 + row0), (size_t)kMaxCols * a.F, o[0], o[1], o[2], o[3]);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int f = t * R + row0 + i;
+          if (row0 + i < R && f < a.F) store_act1<T>(dst + xoff<T>(ncols, a.F, col, f), (size_t)kMaxCols * a.F, o[i]);
+        }
       }
     }
   }
+}
+template <typename T, int NB, int TP>
+__global__ __launch_bounds__(1024) void gateup_kernel(GateUpArgs a, Cols c) {
+  const GateUpArgs* const ap[1] = {&a};
+  const Cols* const cp[1] = {&c};
+  gateup_body<T, NB, TP, 1>(ap, cp);
+}
+template <typename T, int NB, int TP>
+__global__ __launch_bounds__(kTwinThreads) void gateup_twin_kernel(Twin<GateUpArgs> t) {
+  const GateUpArgs* const ap[2] = {&t.a[0], &t.a[1]};
+  const Cols* const cp[2] = {&t.c[0], &t.c[1]};
+  gateup_body<T, NB, TP, 2>(ap, cp);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -366,54 +460,86 @@ struct HeadArgs {
 __device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
 
 // TP: row tiles per workgroup (as for gate/up: more than one where a pass loads two fragments per k-tile)
-template <typename T, int NB, int TP>
-__global__ __launch_bounds__(1024) void head_kernel(HeadArgs a, Cols c) {
-  __shared__ float s_rstd[kMaxCols];
+// NP passes (of equal column counts) are served from one read of the weights.
+template <typename T, int NB, int TP, int NP>
+__device__ __forceinline__ void head_body(const HeadArgs* const (&ap)[NP], const Cols* const (&cp)[NP]) {
+  __shared__ float s_rstd[NP][kMaxCols];
+  const HeadArgs& a = *ap[0];  // what the passes share: weights, shape, the logits array
+  const int ncols = cp[0]->n;
   const int nkt = a.d / Tr<T>::KT;
   const int t0 = blockIdx.x * TP;
   const u32x4* w[TP];
 #pragma unroll
   for (int p = 0; p < TP; ++p) w[p] = a.w + (size_t)clamped_unit(t0, p, a.nblk) * row_tile_pieces(nkt, 16);  // a missing tile re-reads the last one
-  RstdPre pre;
-  rstd_issue(a.ssp, a.d / 16, c.n, pre);
-  f32x4 acc[TP];
+  const T* x[NP];
+  RstdPre pre[NP];
+  f32x4 acc[NP][TP];
 #pragma unroll
-  for (int p = 0; p < TP; ++p) acc[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int q = 0; q < NP; ++q) {
+    x[q] = reinterpret_cast<const T*>(ap[q]->x);
+    rstd_issue(ap[q]->ssp, a.d / 16, ncols, pre[q]);
+#pragma unroll
+    for (int p = 0; p < TP; ++p) acc[q][p] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
   const u32x4* const(&wc)[TP] = w;
-  gemm_accumulate<T, TP, NB>(wc, reinterpret_cast<const T*>(a.x), a.d, c.n, acc);
-  rstd_finish(a.ssp, a.d / 16, c.n, a.inv_d, a.eps, pre, s_rstd);
-  if (!reduce_waves<TP>(acc, dyn_red)) return;
-  fold_columns<T, TP>(acc, c.n);
+  const T* const(&xc)[NP] = x;
+  gemm_accumulate<T, TP, NB, NP>(wc, xc, a.d, ncols, acc);
+  bool mine = false;
+#pragma unroll
+  for (int q = 0; q < NP; ++q) {
+    rstd_finish(ap[q]->ssp, a.d / 16, ncols, a.inv_d, a.eps, pre[q], s_rstd[q]);
+    mine = reduce_waves<TP>(acc[q], red_of_pass<TP>(q));
+  }
+  if (!mine) return;
+#pragma unroll
+  for (int q = 0; q < NP; ++q) fold_columns<T, TP>(acc[q], ncols);  // all 64 lanes
   const int lane = threadIdx.x & 63, col = lane & 15;
-  const bool ok = col < c.n;
-  const float r = ok ? s_rstd[col] : 0.f;
+  const bool ok = col < ncols;
 #pragma unroll
-  for (int p = 0; p < TP; ++p) {
-    const int t = t0 + p;
-    if (t >= a.nblk) break;
-    const int r0 = t * 16 + (lane >> 4) * 4;
-    float bv = -INFINITY;
-    int bi = 0x7FFFFFFF;
+  for (int q = 0; q < NP; ++q) {
+    const HeadArgs& aq = *ap[q];
+    const Cols& c = *cp[q];
+    const float r = ok ? s_rstd[q][col] : 0.f;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row = r0 + i;
-      const float v = acc[p][i] * r;
-      if (ok && row < a.V) {
-        if (a.logits && c.logit_row[col] >= 0) a.logits[(size_t)c.logit_row[col] * a.V + row] = v;
-        if (better(v, row, bv, bi)) { bv = v; bi = row; }
+    for (int p = 0; p < TP; ++p) {
+      const int t = t0 + p;
+      if (t >= a.nblk) break;
+      const int r0 = t * 16 + (lane >> 4) * 4;
+      float bv = -INFINITY;
+      int bi = 0x7FFFFFFF;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = r0 + i;
+        const float v = acc[q][p][i] * r;
+        if (ok && row < a.V) {
+          if (aq.logits && c.logit_row[col] >= 0) aq.logits[(size_t)c.logit_row[col] * a.V + row] = v;
+          if (better(v, row, bv, bi)) { bv = v; bi = row; }
+        }
+      }
+#pragma unroll
+      for (int off = 16; off <= 32; off <<= 1) {
+        const float ov = __shfl_xor(bv, off, 64);
+        const int oi = __shfl_xor(bi, off, 64);
+        if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+      }
+      if (ok && lane < 16) {
+        aq.cand_val[(size_t)col * a.nblk + t] = bv;
+        aq.cand_idx[(size_t)col * a.nblk + t] = bi;
       }
     }
-#pragma unroll
-    for (int off = 16; off <= 32; off <<= 1) {
-      const float ov = __shfl_xor(bv, off, 64);
-      const int oi = __shfl_xor(bi, off, 64);
-      if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-    }
-    if (ok && lane < 16) {
-      a.cand_val[(size_t)col * a.nblk + t] = bv;
-      a.cand_idx[(size_t)col * a.nblk + t] = bi;
-    }
   }
+}
+template <typename T, int NB, int TP>
+__global__ __launch_bounds__(1024) void head_kernel(HeadArgs a, Cols c) {
+  const HeadArgs* const ap[1] = {&a};
+  const Cols* const cp[1] = {&c};
+  head_body<T, NB, TP, 1>(ap, cp);
+}
+template <typename T, int NB, int TP>
+__global__ __launch_bounds__(kTwinThreads) void head_twin_kernel(Twin<HeadArgs> t) {
+  const HeadArgs* const ap[2] = {&t.a[0], &t.a[1]};
+  const Cols* const cp[2] = {&t.c[0], &t.c[1]};
+  head_body<T, NB, TP, 2>(ap, cp);
 }
 
 __global__ __launch_bounds__(1024) void argmax_final_kernel(const float* cand_val, const int32_t* cand_idx, int nblk,
@@ -699,82 +825,123 @@ int stream_walk(const Shape& s, const StreamPlan& p, int ncols, StreamWalk* r) {
   return 0;
 }
 
-void launch_qkv(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st) {
-  QkvArgs a;
+// Two passes of n_cols columns each can share their launches if no weight kernel's workgroup exceeds what the
+// two-pass kernels are compiled for (twice the accumulators and activation fragments per wave).
+bool twin_passes_fit(const Shape& s, int n_cols) {
+  static const int ops[] = {EASYSPEC_OP_QKV, EASYSPEC_OP_OPROJ, EASYSPEC_OP_GATEUP, EASYSPEC_OP_DOWN, EASYSPEC_OP_HEAD};
+  for (int op : ops)
+    if (64 * stream_plan(s, op, n_cols, 1, false).nw > kTwinThreads) return false;
+  return true;
+}
+
+// One pass, or (c2 given) two passes of equal column counts in one launch of the same shape, with a reduction
+// buffer for each pass.
+#define ES_LAUNCH_PASSES(K1, K2, grid, nw, lds, st, a, c, a2, c2)                     \
+  do {                                                                                \
+    if (c2) {                                                                         \
+      Twin<std::decay_t<decltype(a)>> tw;                                             \
+      tw.a[0] = a; tw.a[1] = a2; tw.c[0] = c; tw.c[1] = *(c2);                        \
+      ES_LAUNCH(K2, dim3(grid), dim3(64 * (nw)), 2 * (lds), st, tw);                  \
+    } else {                                                                          \
+      ES_LAUNCH(K1, dim3(grid), dim3(64 * (nw)), lds, st, a, c);                      \
+    }                                                                                 \
+  } while (0)
+
+void launch_qkv(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st, const Buffers* b2,
+                const Cols* c2) {
   const StreamPlan p = stream_plan(s, EASYSPEC_OP_QKV, c.n, n_set, false);
-  a.w = (const u32x4*)b.wqkv + (size_t)layer0 * p.layer_pieces;
-  a.w_layer_stride = p.layer_pieces;
-  a.x = b.XA;
-  a.ssp = b.ssp;
-  a.bias = s.has_bias ? b.bqkv + (size_t)layer0 * s.RQKV : nullptr;
-  a.rope = b.rope;
-  a.q = b.Q;
-  a.kc = b.kc;
-  a.vc = b.vc;
-  a.layer0 = layer0; a.d = s.d; a.Hq = s.Hq; a.Hkv = s.Hkv; a.hd = s.hd; a.B = s.B; a.max_ctx = s.max_ctx;
-  a.R = p.R;
-  a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
+  auto args = [&](const Buffers& w) {
+    QkvArgs a;
+    a.w = (const u32x4*)w.wqkv + (size_t)layer0 * p.layer_pieces;
+    a.w_layer_stride = p.layer_pieces;
+    a.x = w.XA;
+    a.ssp = w.ssp;
+    a.bias = s.has_bias ? w.bqkv + (size_t)layer0 * s.RQKV : nullptr;
+    a.rope = w.rope;
+    a.q = w.Q;
+    a.kc = w.kc;
+    a.vc = w.vc;
+    a.layer0 = layer0; a.d = s.d; a.Hq = s.Hq; a.Hkv = s.Hkv; a.hd = s.hd; a.B = s.B; a.max_ctx = s.max_ctx;
+    a.R = p.R;
+    a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
+    return a;
+  };
+  const QkvArgs a = args(b), a2 = args(b2 ? *b2 : b);
   if (p.TP == 2) {
     // two tiles per workgroup share every fragment load (12-wide tree level 3292 -> 3282 us)
-    ES_LAUNCH((qkv_kernel<bf16_t, 2, 2>), dim3(p.grid), dim3(64 * p.nw), red_bytes(p.nw, 4), st, a, c);
+    ES_LAUNCH_PASSES((qkv_kernel<bf16_t, 2, 2>), (qkv_twin_kernel<bf16_t, 2, 2>), p.grid, p.nw, red_bytes(p.nw, 4), st, a, c, a2, c2);
     return;
   }
   DISPATCH_TNB(s.dtype, p.NB == 2,
-               ES_LAUNCH((qkv_kernel<T, NB, 1>), dim3(p.grid), dim3(64 * p.nw), red_bytes(p.nw, 2), st, a, c));
+               ES_LAUNCH_PASSES((qkv_kernel<T, NB, 1>), (qkv_twin_kernel<T, NB, 1>), p.grid, p.nw, red_bytes(p.nw, 2), st, a, c, a2, c2));
 }
 
-void launch_oproj(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st) {
-  ProjArgs a;
+void launch_oproj(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st, const Buffers* b2,
+                  const Cols* c2) {
   const StreamPlan p = stream_plan(s, EASYSPEC_OP_OPROJ, c.n, n_set, false);
-  a.w = (const u32x4*)b.wo + (size_t)layer0 * p.layer_pieces;
-  a.w_layer_stride = p.layer_pieces;
-  a.x = b.AO;
-  a.K = s.HQ; a.d = s.d;
-  a.H = b.H; a.A = b.A; a.a_add = -1;
-  a.gain = b.g_mlp + (size_t)layer0 * s.d;
-  a.n_gain = 1;
-  a.xout = b.XM;
-  a.ssp = b.ssp;
+  auto args = [&](const Buffers& w) {
+    ProjArgs a;
+    a.w = (const u32x4*)w.wo + (size_t)layer0 * p.layer_pieces;
+    a.w_layer_stride = p.layer_pieces;
+    a.x = w.AO;
+    a.K = s.HQ; a.d = s.d;
+    a.H = w.H; a.A = w.A; a.a_add = -1;
+    a.gain = w.g_mlp + (size_t)layer0 * s.d;
+    a.n_gain = 1;
+    a.xout = w.XM;
+    a.ssp = w.ssp;
+    return a;
+  };
+  const ProjArgs a = args(b), a2 = args(b2 ? *b2 : b);
   if (p.TP == 2) {
     // two row tiles per workgroup share every fragment load (12-wide tree level 3284 -> 3259 us)
-    ES_LAUNCH((proj_resid_kernel<bf16_t, 2, 2>), dim3(p.grid), dim3(64 * p.nw), red_bytes(p.nw, 2), st, a, c);
+    ES_LAUNCH_PASSES((proj_resid_kernel<bf16_t, 2, 2>), (proj_resid_twin_kernel<bf16_t, 2, 2>), p.grid, p.nw, red_bytes(p.nw, 2), st, a, c, a2, c2);
     return;
   }
   DISPATCH_TNB(s.dtype, p.NB == 2,
-               ES_LAUNCH((proj_resid_kernel<T, NB, 1>), dim3(p.grid), dim3(64 * p.nw), red_bytes(p.nw, 1), st, a, c));
+               ES_LAUNCH_PASSES((proj_resid_kernel<T, NB, 1>), (proj_resid_twin_kernel<T, NB, 1>), p.grid, p.nw, red_bytes(p.nw, 1), st, a, c, a2, c2));
 }
 
-void launch_gateup(const Shape& s, const Buffers& b, const Cols& c, int layer, int n_layers, const float* ssp, hipStream_t st) {
-  GateUpArgs a;
+void launch_gateup(const Shape& s, const Buffers& b, const Cols& c, int layer, int n_layers, const float* ssp, hipStream_t st,
+                   const Buffers* b2, const Cols* c2, const float* ssp2) {
   const StreamPlan p = stream_plan(s, EASYSPEC_OP_GATEUP, c.n, n_layers, false);
-  a.wg = (const u32x4*)b.wg + (size_t)layer * p.layer_pieces;
-  a.wu = (const u32x4*)b.wu + (size_t)layer * p.layer_pieces;
-  a.w_layer_stride = p.layer_pieces;
-  a.x = b.XM; a.ssp = ssp; a.act = b.ACT; a.d = s.d; a.F = s.F; a.R = p.R;
-  a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
+  auto args = [&](const Buffers& w, const float* sums) {
+    GateUpArgs a;
+    a.wg = (const u32x4*)w.wg + (size_t)layer * p.layer_pieces;
+    a.wu = (const u32x4*)w.wu + (size_t)layer * p.layer_pieces;
+    a.w_layer_stride = p.layer_pieces;
+    a.x = w.XM; a.ssp = sums; a.act = w.ACT; a.d = s.d; a.F = s.F; a.R = p.R;
+    a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
+    return a;
+  };
+  const GateUpArgs a = args(b, ssp), a2 = args(b2 ? *b2 : b, b2 ? ssp2 : ssp);
   if (p.TP == 2) {
     // two fragments per k-tile: two row tiles of each matrix per workgroup, so that four MFMA row tiles
     // share every fragment load (measured: 12-wide tree level 3402 -> 3322 us; with one fragment the
     // larger workgroups lose: 6-token calibration 3377 -> 3411 us, draft step 2676 -> 2731 us)
-    ES_LAUNCH((gateup_kernel<bf16_t, 2, 2>), dim3(p.grid), dim3(64 * p.nw), red_bytes(p.nw, 4), st, a, c);
+    ES_LAUNCH_PASSES((gateup_kernel<bf16_t, 2, 2>), (gateup_twin_kernel<bf16_t, 2, 2>), p.grid, p.nw, red_bytes(p.nw, 4), st, a, c, a2, c2);
     return;
   }
   DISPATCH_TNB(s.dtype, p.NB == 2,
-               ES_LAUNCH((gateup_kernel<T, NB, 1>), dim3(p.grid), dim3(64 * p.nw), red_bytes(p.nw, 2), st, a, c));
+               ES_LAUNCH_PASSES((gateup_kernel<T, NB, 1>), (gateup_twin_kernel<T, NB, 1>), p.grid, p.nw, red_bytes(p.nw, 2), st, a, c, a2, c2));
 }
 
 void launch_down(const Shape& s, const Buffers& b, const Cols& c, int layer, int a_next, const float* gain, int n_gain,
-                 void* xout, hipStream_t st) {
-  ProjArgs a;
+                 void* xout, hipStream_t st, const Buffers* b2, const Cols* c2, void* xout2) {
   const StreamPlan p = stream_plan(s, EASYSPEC_OP_DOWN, c.n, 1, false);
-  a.w = (const u32x4*)b.wd + (size_t)layer * p.layer_pieces;
-  a.w_layer_stride = p.layer_pieces;
-  a.x = b.ACT;
-  a.K = s.F; a.d = s.d;
-  a.H = b.H; a.A = b.A; a.a_add = a_next;
-  a.gain = gain; a.n_gain = n_gain; a.xout = xout; a.ssp = b.ssp;
+  auto args = [&](const Buffers& w, void* out) {
+    ProjArgs a;
+    a.w = (const u32x4*)w.wd + (size_t)layer * p.layer_pieces;
+    a.w_layer_stride = p.layer_pieces;
+    a.x = w.ACT;
+    a.K = s.F; a.d = s.d;
+    a.H = w.H; a.A = w.A; a.a_add = a_next;
+    a.gain = gain; a.n_gain = n_gain; a.xout = out; a.ssp = w.ssp;
+    return a;
+  };
+  const ProjArgs a = args(b, xout), a2 = args(b2 ? *b2 : b, b2 ? xout2 : xout);
   DISPATCH_TNB(s.dtype, p.NB == 2,
-               ES_LAUNCH((proj_resid_kernel<T, NB, 1>), dim3(p.grid), dim3(64 * p.nw), red_bytes(p.nw, 1), st, a, c));
+               ES_LAUNCH_PASSES((proj_resid_kernel<T, NB, 1>), (proj_resid_twin_kernel<T, NB, 1>), p.grid, p.nw, red_bytes(p.nw, 1), st, a, c, a2, c2));
 }
 
 void launch_oproj_full(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st) {
@@ -807,21 +974,27 @@ void launch_down_full(const Shape& s, const Buffers& b, const Cols& c, int layer
                ES_LAUNCH((proj_full_kernel<T, NB>), dim3(p.grid), dim3(64 * p.nw), red_bytes(p.nw, 1), st, a, c));
 }
 
-void launch_head(const Shape& s, const Buffers& b, const Cols& c, float* logits_out, int32_t* tokens_out, hipStream_t st) {
-  HeadArgs a;
+void launch_head(const Shape& s, const Buffers& b, const Cols& c, float* logits_out, int32_t* tokens_out, hipStream_t st,
+                 const Buffers* b2, const Cols* c2) {
   const StreamPlan p = stream_plan(s, EASYSPEC_OP_HEAD, c.n, 1, false);
-  a.w = (const u32x4*)b.wlm; a.x = b.XA; a.ssp = b.ssp; a.logits = logits_out;
-  a.cand_val = b.amax_val; a.cand_idx = b.amax_idx;
-  a.d = s.d; a.V = s.V; a.nblk = p.units;
-  a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
+  auto args = [&](const Buffers& w) {
+    HeadArgs a;
+    a.w = (const u32x4*)w.wlm; a.x = w.XA; a.ssp = w.ssp; a.logits = logits_out;
+    a.cand_val = w.amax_val; a.cand_idx = w.amax_idx;
+    a.d = s.d; a.V = s.V; a.nblk = p.units;
+    a.inv_d = 1.0f / (float)s.d; a.eps = s.eps;
+    return a;
+  };
+  const HeadArgs a = args(b), a2 = args(b2 ? *b2 : b);
   if (p.TP == 2) {
     // two row tiles per workgroup share every fragment load (12-wide tree level 3309 -> 3276 us; four: the same)
-    ES_LAUNCH((head_kernel<bf16_t, 2, 2>), dim3(p.grid), dim3(64 * p.nw), red_bytes(p.nw, 2), st, a, c);
+    ES_LAUNCH_PASSES((head_kernel<bf16_t, 2, 2>), (head_twin_kernel<bf16_t, 2, 2>), p.grid, p.nw, red_bytes(p.nw, 2), st, a, c, a2, c2);
   } else {
     DISPATCH_TNB(s.dtype, p.NB == 2,
-                 ES_LAUNCH((head_kernel<T, NB, 1>), dim3(p.grid), dim3(64 * p.nw), red_bytes(p.nw, 1), st, a, c));
+                 ES_LAUNCH_PASSES((head_kernel<T, NB, 1>), (head_twin_kernel<T, NB, 1>), p.grid, p.nw, red_bytes(p.nw, 1), st, a, c, a2, c2));
   }
   ES_LAUNCH(argmax_final_kernel, dim3(c.n), dim3(1024), 0, st, a.cand_val, a.cand_idx, a.nblk, tokens_out, c);
+  if (c2) ES_LAUNCH(argmax_final_kernel, dim3(c2->n), dim3(1024), 0, st, a2.cand_val, a2.cand_idx, a2.nblk, tokens_out, *c2);
 }
 
 }  // namespace es

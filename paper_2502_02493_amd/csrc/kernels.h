@@ -115,7 +115,12 @@ size_t packed_bytes(int dtype, int rows, int K, int R);
 void launch_repack(int dtype, const void* src, void* dst, int rows, int K, int R, int half, int row_add, hipStream_t st);
 void launch_embed(const Shape& s, const Buffers& b, const Cols& c, const int32_t* tokens, int layer0, int n_set,
                   hipStream_t st);
-void launch_qkv(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st);
+// The weight kernels take an optional second pass (b2, c2: its workspaces and columns, c2->n == c.n): one launch then
+// serves both passes, every wave using each weight fragment it loads for both passes' columns
+// (twin_passes_fit(): whether the launch shapes of passes of n_cols columns allow it).
+bool twin_passes_fit(const Shape& s, int n_cols);
+void launch_qkv(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st,
+                const Buffers* b2 = nullptr, const Cols* c2 = nullptr);
 // How an attention launch over n_set layers cuts the contexts of these columns into split-KV chunks.
 struct AttnCut {
   bool mfma;     // the matrix-core kernel takes the launch (groups of columns of one sequence)
@@ -132,10 +137,12 @@ int attn_waves(const AttnCut& cut);
 void attn_ranges(const Shape& s, const AttnCut& cut, int n_slots, int chunk, int wave, int* nch, int* w0, int* w1);
 void launch_attn(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, const AttnCut& cut, hipStream_t st);
 // O projection of the set's layers; the first layer's result goes straight into the residual.
-void launch_oproj(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st);
+void launch_oproj(const Shape& s, const Buffers& b, const Cols& c, int layer0, int n_set, hipStream_t st,
+                  const Buffers* b2 = nullptr, const Cols* c2 = nullptr);
 // Gate/up of n_layers consecutive layers, layer i on operand slot i of XM with partial sums slot i
 // of ssp ([n_layers][16][d/16]) into operand slot i of ACT.  n_layers = 1 outside full-layer mode.
-void launch_gateup(const Shape& s, const Buffers& b, const Cols& c, int layer, int n_layers, const float* ssp, hipStream_t st);
+void launch_gateup(const Shape& s, const Buffers& b, const Cols& c, int layer, int n_layers, const float* ssp, hipStream_t st,
+                   const Buffers* b2 = nullptr, const Cols* c2 = nullptr, const float* ssp2 = nullptr);
 // Full-layer-parallel mode (App. B ablation), per set: the O projections (every layer parks its
 // Attnoutput and writes its own MLP's input into XM / ssp_set) and the down projections (summed
 // over the set's layers and added to the residual together with the Attnoutputs).
@@ -146,9 +153,10 @@ void launch_down_full(const Shape& s, const Buffers& b, const Cols& c, int layer
 // -1.  The normed-input vectors for what comes next are written with gains
 // gain[0..n_gain) (stride d) into xout (stride 16*d elements of T).
 void launch_down(const Shape& s, const Buffers& b, const Cols& c, int layer, int a_next, const float* gain,
-                 int n_gain, void* xout, hipStream_t st);
+                 int n_gain, void* xout, hipStream_t st, const Buffers* b2 = nullptr, const Cols* c2 = nullptr,
+                 void* xout2 = nullptr);
 void launch_head(const Shape& s, const Buffers& b, const Cols& c, float* logits_out, int32_t* tokens_out,
-                 hipStream_t st);
+                 hipStream_t st, const Buffers* b2 = nullptr, const Cols* c2 = nullptr);
 void launch_accept(const int32_t* draft, const int32_t* target, int batch, int gamma, int32_t* accept_len,
                    int32_t* bonus, hipStream_t st);
 // Acceptance by speculative sampling; ws: sample_accept_workspace_bytes() of scratch.
