@@ -175,7 +175,12 @@ int easyspec_draft_tree_step(easyspec_ctx *ctx, const int32_t *tokens_in, const 
  *                  logits_rows = 1 -> [max_batch][max_calib_tokens][vocab] (every token)
  * For each such sequence: fuzzy[b] = 0 (all fuzzy slots dropped, accepted or not); layers run
  * in order over the n tokens at positions precise[b] .. precise[b]+n-1, causal among themselves;
- * their k, v overwrite those slots; precise[b] += n. */
+ * their k, v overwrite those slots; precise[b] += n.
+ * A forward pass holds up to 16 token columns.  The sequences are taken in index order and packed into
+ * passes, a sequence's tokens staying together; two consecutive passes of equal column counts run
+ * together, each weight matrix being read once for both (so 4 sequences x 6 tokens cost one read of the
+ * weights, not two); other passes run one after the other.  The results do not depend on the packing
+ * beyond the last bits of fp32 arithmetic. */
 int easyspec_calibrate(easyspec_ctx *ctx, const int32_t *tokens, const int32_t *n_tokens,
                        int32_t *next_token_out, float *logits_out, int32_t logits_rows);
 
