@@ -115,3 +115,9 @@ def test_8b_layer_shape_reduced_depth(oracle, gpu, monkeypatch):
     """The 8B layer shape (real tile counts, wave counts and seven-wave down projection) at 3 layers: 4 x 6 tokens."""
     cfg = synth.model_shape("llama3_8b", n_layers=3, vocab=4096)
     run_case(oracle, gpu, monkeypatch, cfg, 1150, [300, 40, 700, 129], [6, 6, 6, 6], 6, pairs=1)
+
+
+def test_four_passes_two_pairs(oracle, gpu, monkeypatch):
+    """8 x 8 tokens: four passes of 16 columns, run as two pairs one after the other (the second pair reuses both
+    workspace sets)."""
+    run_case(oracle, gpu, monkeypatch, synth.model_shape("tiny", dtype="bf16"), 1160, [12, 70, 257, 3, 129, 64, 300, 31], [8] * 8, 8, pairs=2)
